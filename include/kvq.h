@@ -1,0 +1,195 @@
+/*
+ * kvq - low-bit KV-cache decode attention with outlier-token tracing, for gfx950.
+ *
+ * C ABI of the hot path of "KV Cache Quantization with Outlier Tokens Tracing"
+ * (OTT).  All pointers named "device" are HIP device pointers owned by the
+ * caller; the library never allocates, frees or keeps a pointer after a call
+ * returns, enqueues all work on the caller's stream and never synchronises.
+ * `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *
+ * Cache shape follows the paper's [num_layers, batch_size, num_heads,
+ * sequence_length, head_dim] (Introduction).  A "unit" is one (layer, batch,
+ * kv head); unit index u = (layer * batch + b) * kv_heads + h.  Every buffer
+ * below is a dense array whose leading dimension is the unit.  Sequence
+ * lengths are uniform over the batch.
+ *
+ * Return value of every call: 0 (KVQ_OK) or a negative kvq_status.  Arguments
+ * are validated on the host before anything is launched, so an error return
+ * means no device work was enqueued.  Data-dependent events (the auxiliary
+ * pool filling up) are not errors: they set `frozen[u]` on the device.
+ */
+#ifndef KVQ_H
+#define KVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum kvq_status {
+  KVQ_OK = 0,
+  KVQ_ERR_INVALID_ARG = -1, /* null pointer, out-of-range or inconsistent argument        */
+  KVQ_ERR_UNSUPPORTED = -2, /* meaningful for the method but not built (e.g. head_dim 64) */
+  KVQ_ERR_WORKSPACE = -3,   /* workspace smaller than kvq_query_sizes reports             */
+  KVQ_ERR_LAUNCH = -4       /* the HIP runtime refused a launch                           */
+} kvq_status;
+
+/* Hyper-parameters in the paper's notation (Experiments, "Details"): bit width b,
+ * group size G, residual length R, outlier_num N, size of the additional pool A. */
+typedef struct kvq_config {
+  int32_t layers;
+  int32_t batch;
+  int32_t q_heads;        /* multiple of kv_heads; q_heads / kv_heads in {1,2,4,8}            */
+  int32_t kv_heads;
+  int32_t head_dim;       /* 128                                                              */
+  int32_t max_seq;        /* token capacity of the quantized cache; multiple of group_k       */
+  int32_t bits;           /* b: 2 or 4                                                        */
+  int32_t group_k;        /* G: tokens per Key group and quantization cadence: 32, 64 or 128  */
+  int32_t group_v;        /* channels per Value group: 32, 64 or 128                          */
+  int32_t residual;       /* R >= 0: recent tokens kept in full precision                     */
+  int32_t outlier_budget; /* N >= 0 per unit; 0 disables tracing (the paper's layers 0 and 1) */
+  int32_t aux_capacity;   /* A >= 0: slots for tokens evicted from the outlier pool           */
+} kvq_config;
+
+/* Sizes (bytes unless said otherwise) of every caller-allocated buffer. */
+typedef struct kvq_sizes {
+  int64_t units;            /* layers * batch * kv_heads                                      */
+  int64_t res_rows;         /* rows per unit of the residual ring: G * ceil((R + G) / G)      */
+  int64_t pool_slots;       /* N + A: slots [0,N) outlier pool, [N,N+A) auxiliary pool        */
+  int64_t k_codes_bytes;    /* [units][max_seq/32][512*bits] packed Key codes                 */
+  int64_t k_meta_bytes;     /* [units][max_seq/G][head_dim] u32 = fp16 step | fp16 zero << 16 */
+  int64_t v_codes_bytes;    /* [units][max_seq/32][512*bits] packed Value codes               */
+  int64_t v_meta_bytes;     /* [units][max_seq][head_dim/group_v] u32, same packing           */
+  int64_t mask_bytes;       /* [units][max_seq/32] u32, bit t%32 set: token lives in a pool   */
+  int64_t res_bytes;        /* each of k_res, v_res: [units][res_rows][head_dim] fp16         */
+  int64_t pool_rows_bytes;  /* each of pool_k, pool_v: [units][pool_slots][head_dim] fp16     */
+  int64_t pool_idx_bytes;   /* [units][pool_slots] int32 token index                          */
+  int64_t pool_score_bytes; /* [units][pool_slots] fp64 L1 score                              */
+  int64_t counter_bytes;    /* each of pool_count, aux_count, frozen: [units] int32           */
+  int64_t selected_bytes;   /* [batch*kv_heads][G] uint8, one layer                           */
+  int64_t workspace_bytes;  /* decode-attention workspace for one layer                       */
+} kvq_sizes;
+
+/*
+ * Quantized cache (device).  Packed format.  Codes are stored in blocks of 32 tokens x 128
+ * channels = 512*bits bytes, block i of a unit holding tokens 32i .. 32i+31.  A block is
+ * 64 "lanes" of 8 "fields" of 8 codes.  Code x = 2v + e (v in 0..3, e in 0..1) of field f
+ * of lane l sits in a little-endian u32 word at
+ *     bits = 2:  bit 16e + 2(4(f&1) + v)  of the word at byte  16 l + 4 (f>>1)
+ *     bits = 4:  bit 16e + 4v             of the word at byte  1024 (f>>2) + 16 l + 4 (f&3)
+ * Key block:   token t = 16 th + m, channel c = 32 cb + 8 r + x  ->  lane 16 r + m, field 4 th + cb.
+ * Value block: channel c = 16 ct + n, token t = 8 r + x          ->  lane 16 r + n, field ct.
+ * (A lane's 16 bytes are what one wavefront lane loads with one dwordx4; a field is one
+ * lane's share of a 16x16x32 matrix-core operand.)
+ * k_meta[u][group][c] and v_meta[u][token][c / group_v] are u32 = fp16 step | fp16 zero << 16;
+ * the dequantized value is zero + code * step.  mask[u][block] bit t%32 is set when token
+ * 32*block + t was selected as an outlier (it then lives in the outlier or auxiliary pool and
+ * its codes are placeholders).
+ */
+typedef struct kvq_qcache {
+  void* k_codes;
+  void* k_meta;
+  void* v_codes;
+  void* v_meta;
+  void* mask;
+} kvq_qcache;
+
+/* Outlier pool and auxiliary pool (device).  Occupied slots are [0, pool_count[u]) and
+ * [N, N + aux_count[u]).  Must be zero-initialised (counts and frozen) by the caller. */
+typedef struct kvq_pool {
+  void* pool_k;
+  void* pool_v;
+  int32_t* pool_idx;
+  double* pool_score;
+  int32_t* pool_count;
+  int32_t* aux_count;
+  int32_t* frozen;
+} kvq_pool;
+
+/* Full-precision residual ring (device): res_rows rows per unit; the live rows are
+ * res_start, res_start+1, ... (mod res_rows), oldest first. */
+typedef struct kvq_residual {
+  void* k_res;
+  void* v_res;
+} kvq_residual;
+
+/* Fill `out` with the buffer sizes for `cfg`.  Host only. */
+int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out);
+
+/*
+ * Append the new token's Key and Value (K = K_<n || K_n, V likewise: Background,
+ * decoding phase) of one layer to the residual ring.
+ *   k_new, v_new : device fp16 [batch][kv_heads][head_dim]
+ *   res_start    : ring row of the oldest live token, in [0, res_rows)
+ *   n_res        : live rows before the append, in [0, res_rows)
+ * Writes ring row (res_start + n_res) mod res_rows of every unit of `layer`.
+ */
+int32_t kvq_append_residual(const kvq_config* cfg, int32_t layer, const void* k_new, const void* v_new,
+                            kvq_residual res, int32_t res_start, int32_t n_res, void* stream);
+
+/*
+ * Outlier-token competition for one group of G tokens of one layer (Method,
+ * "Quantization"; Appendix "Competition Mechanism"): score each token by the L1
+ * norm of its Key, rank pool and group together (score, then token index,
+ * ascending), keep the N smallest as the new pool, move members that fall out to
+ * the auxiliary pool; if those do not fit, set frozen[u] and change nothing else.
+ *   group_index  : index of the group in the sequence; its tokens are
+ *                  group_index*G .. group_index*G + G - 1; must be < max_seq / G
+ *   k_group, v_group : device fp16; unit (b,h) of this layer has its G rows of head_dim
+ *                  contiguous at element offset (b*kv_heads + h) * unit_stride
+ *   unit_stride  : in fp16 elements, >= G * head_dim, multiple of 8; k_group and v_group
+ *                  16-byte aligned
+ *   pool         : updated in place (rows are bit-exact copies of the group's rows)
+ *   selected     : device uint8 [batch*kv_heads][G], out: 1 = token entered the pool now
+ */
+int32_t kvq_trace_outliers(const kvq_config* cfg, int32_t layer, int32_t group_index, const void* k_group,
+                           const void* v_group, int64_t unit_stride, kvq_pool pool, uint8_t* selected,
+                           void* stream);
+
+/*
+ * Quantize one group of G tokens of one layer and store it as group `group_index`
+ * of the quantized cache: rows flagged in `selected` are first replaced by the
+ * per-channel mean of the group (Method, "Quantization"), then Keys are quantized
+ * channel-wise over the G tokens and Values token-wise over group_v channels with
+ * Eq. 2 (step = (max - min) / (2^b - 1) stored in fp16, zero = min, round to
+ * nearest), packed, and the mask words of the group are written.
+ *   k_group, v_group, unit_stride : as in kvq_trace_outliers (read only)
+ *   selected     : device uint8 [batch*kv_heads][G] or NULL (= none selected)
+ */
+int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_index, const void* k_group,
+                           const void* v_group, int64_t unit_stride, const uint8_t* selected,
+                           kvq_qcache qcache, void* stream);
+
+/*
+ * Decode-step attention of one layer (Eq. 1) over the three cache kinds (Method,
+ * "Decoding"): the first n_quant tokens from the quantized cache, except those
+ * whose mask bit is set, which come from the outlier / auxiliary pool in full
+ * precision; then the n_res residual tokens in full precision.  One softmax over
+ * all of them, scale 1/sqrt(head_dim).  Query head j reads kv head j / (q_heads /
+ * kv_heads).
+ *   q        : device fp16 [batch][q_heads][head_dim]
+ *   n_quant  : multiple of G, <= max_seq
+ *   res_start, n_res : live part of the residual ring, n_res <= res_rows;
+ *              n_quant + n_res >= 1
+ *   out      : device fp16 [batch][q_heads][head_dim]
+ *   workspace: device scratch of at least kvq_sizes.workspace_bytes, 256-byte aligned;
+ *              contents need not be preserved between calls; two calls that overlap in
+ *              time must not share it
+ */
+int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qcache,
+                             int32_t n_quant, kvq_residual res, int32_t res_start, int32_t n_res,
+                             kvq_pool pool, void* out, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/* Static string for a kvq_status value. */
+const char* kvq_status_string(int32_t status);
+
+/* Library version, for the binding's load check. */
+int32_t kvq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVQ_H */

@@ -1,0 +1,13 @@
+"""MI355X-native low-bit KV-cache decode attention with outlier-token tracing.
+
+The computation lives in libkvq.so (HIP, gfx950; sources under csrc/); this
+package is its Python binding.
+"""
+from . import binding
+from .binding import (KvqError, kvq_append_residual, kvq_config, kvq_decode_attention, kvq_pool, kvq_qcache,
+                      kvq_quantize_group, kvq_query_sizes, kvq_residual, kvq_sizes, kvq_trace_outliers,
+                      kvq_version, load_library, status_string)
+
+__all__ = ["binding", "KvqError", "kvq_append_residual", "kvq_config", "kvq_decode_attention", "kvq_pool",
+           "kvq_qcache", "kvq_quantize_group", "kvq_query_sizes", "kvq_residual", "kvq_sizes",
+           "kvq_trace_outliers", "kvq_version", "load_library", "status_string"]

@@ -1,0 +1,148 @@
+"""Thin ctypes binding of libkvq.so: argument marshalling only.
+
+Every function has the name and the argument order of its C entry point (see
+include/kvq.h).  Tensors are torch CUDA tensors used as raw device memory; no
+arithmetic of the method happens here.  The library must have been built
+(`python -m paper_2505_10938_amd.build` or `__graft_entry__.build()`); a missing
+library is an error, there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libkvq.so")
+
+KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH = 0, -1, -2, -3, -4
+
+EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
+           "kvq_decode_attention", "kvq_status_string", "kvq_version"]
+
+
+class kvq_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("layers", "batch", "q_heads", "kv_heads", "head_dim", "max_seq", "bits", "group_k",
+                 "group_v", "residual", "outlier_budget", "aux_capacity")]
+
+
+class kvq_sizes(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in
+                ("units", "res_rows", "pool_slots", "k_codes_bytes", "k_meta_bytes", "v_codes_bytes",
+                 "v_meta_bytes", "mask_bytes", "res_bytes", "pool_rows_bytes", "pool_idx_bytes",
+                 "pool_score_bytes", "counter_bytes", "selected_bytes", "workspace_bytes")]
+
+
+class kvq_qcache(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_meta", "v_codes", "v_meta", "mask")]
+
+
+class kvq_pool(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("pool_k", "pool_v", "pool_idx", "pool_score", "pool_count", "aux_count", "frozen")]
+
+
+class kvq_residual(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("k_res", "v_res")]
+
+
+class KvqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load libkvq.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2505_10938_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    i32, i64, vp = C.c_int32, C.c_int64, C.c_void_p
+    cfgp = C.POINTER(kvq_config)
+    lib.kvq_version.restype = i32
+    lib.kvq_status_string.restype = C.c_char_p
+    lib.kvq_status_string.argtypes = [i32]
+    lib.kvq_query_sizes.restype = i32
+    lib.kvq_query_sizes.argtypes = [cfgp, C.POINTER(kvq_sizes)]
+    lib.kvq_append_residual.restype = i32
+    lib.kvq_append_residual.argtypes = [cfgp, i32, vp, vp, kvq_residual, i32, i32, vp]
+    lib.kvq_trace_outliers.restype = i32
+    lib.kvq_trace_outliers.argtypes = [cfgp, i32, i32, vp, vp, i64, kvq_pool, vp, vp]
+    lib.kvq_quantize_group.restype = i32
+    lib.kvq_quantize_group.argtypes = [cfgp, i32, i32, vp, vp, i64, vp, kvq_qcache, vp]
+    lib.kvq_decode_attention.restype = i32
+    lib.kvq_decode_attention.argtypes = [cfgp, i32, vp, kvq_qcache, i32, kvq_residual, i32, i32, kvq_pool,
+                                         vp, vp, C.c_size_t, vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(x):
+    """Device (or null) pointer of a torch tensor / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def status_string(status: int) -> str:
+    return load_library().kvq_status_string(status).decode()
+
+
+def kvq_version() -> int:
+    return load_library().kvq_version()
+
+
+def kvq_query_sizes(cfg: kvq_config) -> kvq_sizes:
+    out = kvq_sizes()
+    st = load_library().kvq_query_sizes(C.byref(cfg), C.byref(out))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_query_sizes")
+    return out
+
+
+def kvq_append_residual(cfg, layer, k_new, v_new, res: kvq_residual, res_start, n_res, stream=None):
+    st = load_library().kvq_append_residual(C.byref(cfg), layer, _ptr(k_new), _ptr(v_new), res, res_start, n_res,
+                                            _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_append_residual")
+
+
+def kvq_trace_outliers(cfg, layer, group_index, k_group, v_group, unit_stride, pool: kvq_pool, selected,
+                       stream=None):
+    st = load_library().kvq_trace_outliers(C.byref(cfg), layer, group_index, _ptr(k_group), _ptr(v_group),
+                                           unit_stride, pool, _ptr(selected), _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_trace_outliers")
+
+
+def kvq_quantize_group(cfg, layer, group_index, k_group, v_group, unit_stride, selected, qcache: kvq_qcache,
+                       stream=None):
+    st = load_library().kvq_quantize_group(C.byref(cfg), layer, group_index, _ptr(k_group), _ptr(v_group),
+                                           unit_stride, _ptr(selected), qcache, _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_quantize_group")
+
+
+def kvq_decode_attention(cfg, layer, q, qcache: kvq_qcache, n_quant, res: kvq_residual, res_start, n_res,
+                         pool: kvq_pool, out, workspace, workspace_bytes, stream=None):
+    st = load_library().kvq_decode_attention(C.byref(cfg), layer, _ptr(q), qcache, n_quant, res, res_start, n_res,
+                                             pool, _ptr(out), _ptr(workspace), workspace_bytes, _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_decode_attention")

@@ -1,0 +1,116 @@
+"""Device buffers of one KV cache and the host-side schedule that drives the library.
+
+Allocation (torch tensors as raw device memory) and the "quantize every G steps"
+schedule (Method, "Quantization") live here; every computation is a call into
+libkvq.so through `binding`.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+def make_config(layers, batch, q_heads, kv_heads, max_seq, bits=2, group_k=32, group_v=32, residual=128,
+                outlier_budget=8, aux_capacity=32, head_dim=128) -> B.kvq_config:
+    return B.kvq_config(layers, batch, q_heads, kv_heads, head_dim, max_seq, bits, group_k, group_v, residual,
+                        outlier_budget, aux_capacity)
+
+
+class KVCache:
+    """All caller-owned buffers of kvq for one configuration, on one device."""
+
+    def __init__(self, cfg: B.kvq_config, device="cuda:0"):
+        self.cfg = cfg
+        self.sizes = sz = B.kvq_query_sizes(cfg)
+        dev = torch.device(device)
+        self.device = dev
+
+        def raw(nbytes):
+            return torch.zeros(max(int(nbytes), 16), dtype=torch.uint8, device=dev)
+
+        self.k_codes, self.k_meta = raw(sz.k_codes_bytes), raw(sz.k_meta_bytes)
+        self.v_codes, self.v_meta = raw(sz.v_codes_bytes), raw(sz.v_meta_bytes)
+        self.mask = raw(sz.mask_bytes)
+        self.k_res, self.v_res = raw(sz.res_bytes), raw(sz.res_bytes)
+        self.pool_k, self.pool_v = raw(sz.pool_rows_bytes), raw(sz.pool_rows_bytes)
+        self.pool_idx, self.pool_score = raw(sz.pool_idx_bytes), raw(sz.pool_score_bytes)
+        self.pool_count, self.aux_count, self.frozen = (raw(sz.counter_bytes) for _ in range(3))
+        self.selected = raw(sz.selected_bytes)
+        self.workspace = raw(sz.workspace_bytes)
+        self.qcache = B.kvq_qcache(*(t.data_ptr() for t in (self.k_codes, self.k_meta, self.v_codes, self.v_meta,
+                                                            self.mask)))
+        self.pool = B.kvq_pool(*(t.data_ptr() for t in (self.pool_k, self.pool_v, self.pool_idx, self.pool_score,
+                                                        self.pool_count, self.aux_count, self.frozen)))
+        self.res = B.kvq_residual(self.k_res.data_ptr(), self.v_res.data_ptr())
+        # per-layer schedule state (uniform over the batch)
+        self.n_quant = [0] * cfg.layers
+        self.res_start = [0] * cfg.layers
+        self.n_res = [0] * cfg.layers
+
+    # ---- views for tests / loaders -------------------------------------------------------------
+    @property
+    def units_per_layer(self):
+        return self.cfg.batch * self.cfg.kv_heads
+
+    def res_view(self, which="k"):
+        t = self.k_res if which == "k" else self.v_res
+        return t.view(torch.float16).view(self.sizes.units, self.sizes.res_rows, self.cfg.head_dim)
+
+    def _group_ptrs(self, layer, row0):
+        hd = self.cfg.head_dim
+        unit0 = layer * self.units_per_layer
+        off = (unit0 * self.sizes.res_rows + row0) * hd * 2
+        return self.k_res.data_ptr() + off, self.v_res.data_ptr() + off, self.sizes.res_rows * hd
+
+    # ---- the schedule --------------------------------------------------------------------------------
+    def append(self, layer, k_new, v_new, stream=None, trace=True):
+        """Append one token (fp16 [batch, kv_heads, head_dim] each); when the ring holds R + G
+        tokens, trace and quantize the oldest G.  Returns True if a group was quantized."""
+        cfg = self.cfg
+        B.kvq_append_residual(cfg, layer, k_new, v_new, self.res, self.res_start[layer], self.n_res[layer], stream)
+        self.n_res[layer] += 1
+        if self.n_res[layer] == cfg.residual + cfg.group_k:
+            self.quantize_oldest(layer, stream, trace)
+            return True
+        return False
+
+    def quantize_oldest(self, layer, stream=None, trace=True):
+        cfg = self.cfg
+        G = cfg.group_k
+        assert self.n_res[layer] >= G and self.n_quant[layer] + G <= cfg.max_seq
+        gi = self.n_quant[layer] // G
+        kp, vp, stride = self._group_ptrs(layer, self.res_start[layer])
+        sel = None
+        if trace and cfg.outlier_budget > 0:
+            B.kvq_trace_outliers(cfg, layer, gi, kp, vp, stride, self.pool, self.selected, stream)
+            sel = self.selected
+        B.kvq_quantize_group(cfg, layer, gi, kp, vp, stride, sel, self.qcache, stream)
+        self.n_quant[layer] += G
+        self.n_res[layer] -= G
+        self.res_start[layer] = (self.res_start[layer] + G) % self.sizes.res_rows
+
+    def load_residual(self, layer, k_rows, v_rows):
+        """Bulk-load rows (fp16 [batch, kv_heads, n, head_dim]) into an empty ring (test / benchmark
+        set-up: a plain device copy, equivalent to n appends)."""
+        n = k_rows.shape[2]
+        rows = self.sizes.res_rows
+        assert self.n_res[layer] == 0 and n <= rows
+        u0, u1 = layer * self.units_per_layer, (layer + 1) * self.units_per_layer
+        s = self.res_start[layer]
+        first = min(n, rows - s)                      # the ring may wrap
+        for view, src in ((self.res_view("k"), k_rows), (self.res_view("v"), v_rows)):
+            src = src.reshape(-1, n, self.cfg.head_dim)
+            view[u0:u1, s:s + first] = src[:, :first]
+            if first < n:
+                view[u0:u1, 0:n - first] = src[:, first:]
+        self.n_res[layer] = n
+
+    def decode(self, layer, q, out=None, stream=None):
+        """Attention output (fp16 [batch, q_heads, head_dim]) of one decode step."""
+        if out is None:
+            out = torch.empty_like(q)
+        B.kvq_decode_attention(self.cfg, layer, q, self.qcache, self.n_quant[layer], self.res,
+                               self.res_start[layer], self.n_res[layer], self.pool, out, self.workspace,
+                               self.workspace.numel(), stream)
+        return out

@@ -1,0 +1,198 @@
+// Host side of the C ABI: argument validation, buffer sizes, launches.
+#include "kvq_common.h"
+
+namespace {
+
+using kvq::Dims;
+
+int32_t check_config(const kvq_config* c) {
+  if (!c) return KVQ_ERR_INVALID_ARG;
+  if (c->layers < 1 || c->batch < 1 || c->kv_heads < 1 || c->q_heads < 1) return KVQ_ERR_INVALID_ARG;
+  if (c->q_heads % c->kv_heads != 0) return KVQ_ERR_INVALID_ARG;
+  if (c->bits != 2 && c->bits != 4) return KVQ_ERR_INVALID_ARG;
+  if (c->group_k != 32 && c->group_k != 64 && c->group_k != 128) return KVQ_ERR_INVALID_ARG;
+  if (c->head_dim < 32 || c->head_dim % 32 != 0) return KVQ_ERR_INVALID_ARG;
+  if (c->group_v != 32 && c->group_v != 64 && c->group_v != 128) return KVQ_ERR_INVALID_ARG;
+  if (c->head_dim % c->group_v != 0) return KVQ_ERR_INVALID_ARG;
+  if (c->max_seq < c->group_k || c->max_seq % c->group_k != 0) return KVQ_ERR_INVALID_ARG;
+  if (c->residual < 0 || c->outlier_budget < 0 || c->aux_capacity < 0) return KVQ_ERR_INVALID_ARG;
+  if (c->residual > (1 << 20) || c->max_seq > (1 << 24)) return KVQ_ERR_INVALID_ARG;
+  if (c->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;
+  const int g = c->q_heads / c->kv_heads;
+  if (g != 1 && g != 2 && g != 4 && g != 8) return KVQ_ERR_UNSUPPORTED;
+  if (c->outlier_budget > 64 || c->aux_capacity > 64) return KVQ_ERR_UNSUPPORTED;
+  return KVQ_OK;
+}
+
+int64_t res_rows_of(const kvq_config* c) {
+  const int64_t G = c->group_k;
+  return G * ((c->residual + G + G - 1) / G);
+}
+
+int32_t decode_chunks_q(int32_t n_quant) { return (n_quant + kvq::kChunkTokens - 1) / kvq::kChunkTokens; }
+int32_t decode_chunks_fp(int64_t rows) { return (int32_t)((rows + kvq::kFpChunkRows - 1) / kvq::kFpChunkRows); }
+
+Dims make_dims(const kvq_config* c, int32_t layer) {
+  Dims d;
+  d.batch = c->batch;
+  d.q_heads = c->q_heads;
+  d.kv_heads = c->kv_heads;
+  d.g = c->q_heads / c->kv_heads;
+  d.bits = c->bits;
+  d.G = c->group_k;
+  d.Gv = c->group_v;
+  d.N = c->outlier_budget;
+  d.A = c->aux_capacity;
+  d.max_seq = c->max_seq;
+  d.res_rows = (int32_t)res_rows_of(c);
+  d.pool_slots = c->outlier_budget + c->aux_capacity;
+  d.units_per_layer = c->batch * c->kv_heads;
+  d.unit0 = (int64_t)layer * d.units_per_layer;
+  d.block_bytes = 512 * c->bits;
+  d.blocks_per_unit = c->max_seq / kvq::kBlockTokens;
+  d.groups_per_unit = c->max_seq / c->group_k;
+  d.vgroups = c->head_dim / c->group_v;
+  return d;
+}
+
+int32_t from_hip(hipError_t e) { return e == hipSuccess ? KVQ_OK : KVQ_ERR_LAUNCH; }
+
+}  // namespace
+
+extern "C" {
+
+int32_t kvq_version(void) { return 1; }
+
+const char* kvq_status_string(int32_t status) {
+  switch (status) {
+    case KVQ_OK: return "ok";
+    case KVQ_ERR_INVALID_ARG: return "invalid argument";
+    case KVQ_ERR_UNSUPPORTED: return "configuration not supported by this build";
+    case KVQ_ERR_WORKSPACE: return "workspace too small";
+    case KVQ_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out) {
+  if (!out) return KVQ_ERR_INVALID_ARG;
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  const int64_t units = (int64_t)cfg->layers * cfg->batch * cfg->kv_heads;
+  const int64_t upl = (int64_t)cfg->batch * cfg->kv_heads;
+  const int64_t hd = cfg->head_dim;
+  const int64_t slots = (int64_t)cfg->outlier_budget + cfg->aux_capacity;
+  const int64_t g = cfg->q_heads / cfg->kv_heads;
+  out->units = units;
+  out->res_rows = res_rows_of(cfg);
+  out->pool_slots = slots;
+  out->k_codes_bytes = units * (cfg->max_seq / 32) * 512 * cfg->bits;
+  out->k_meta_bytes = units * (cfg->max_seq / cfg->group_k) * hd * 4;
+  out->v_codes_bytes = out->k_codes_bytes;
+  out->v_meta_bytes = units * cfg->max_seq * (hd / cfg->group_v) * 4;
+  out->mask_bytes = units * (cfg->max_seq / 32) * 4;
+  out->res_bytes = units * out->res_rows * hd * 2;
+  out->pool_rows_bytes = units * slots * hd * 2;
+  out->pool_idx_bytes = units * slots * 4;
+  out->pool_score_bytes = units * slots * 8;
+  out->counter_bytes = units * 4;
+  out->selected_bytes = upl * cfg->group_k;
+  const int64_t chunks = decode_chunks_q(cfg->max_seq) + decode_chunks_fp(out->res_rows + slots);
+  out->workspace_bytes = upl * chunks * g * (hd + 2) * 4;
+  return KVQ_OK;
+}
+
+int32_t kvq_append_residual(const kvq_config* cfg, int32_t layer, const void* k_new, const void* v_new,
+                            kvq_residual res, int32_t res_start, int32_t n_res, void* stream) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
+  if (!k_new || !v_new || !res.k_res || !res.v_res) return KVQ_ERR_INVALID_ARG;
+  const int32_t rows = (int32_t)res_rows_of(cfg);
+  if (res_start < 0 || res_start >= rows || n_res < 0 || n_res >= rows) return KVQ_ERR_INVALID_ARG;
+  const Dims d = make_dims(cfg, layer);
+  return from_hip(kvq::launch_append(d, (const __half*)k_new, (const __half*)v_new, (__half*)res.k_res,
+                                     (__half*)res.v_res, (res_start + n_res) % rows, (hipStream_t)stream));
+}
+
+int32_t kvq_trace_outliers(const kvq_config* cfg, int32_t layer, int32_t group_index, const void* k_group,
+                           const void* v_group, int64_t unit_stride, kvq_pool pool, uint8_t* selected,
+                           void* stream) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
+  if (group_index < 0 || group_index >= cfg->max_seq / cfg->group_k) return KVQ_ERR_INVALID_ARG;
+  if (!k_group || !v_group || !selected) return KVQ_ERR_INVALID_ARG;
+  if (unit_stride < (int64_t)cfg->group_k * cfg->head_dim || unit_stride % 8 != 0) return KVQ_ERR_INVALID_ARG;
+  if ((((uintptr_t)k_group) | ((uintptr_t)v_group)) & 15) return KVQ_ERR_INVALID_ARG;
+  if (!pool.pool_count || !pool.aux_count || !pool.frozen) return KVQ_ERR_INVALID_ARG;
+  if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v || !pool.pool_idx || !pool.pool_score))
+    return KVQ_ERR_INVALID_ARG;
+  const Dims d = make_dims(cfg, layer);
+  return from_hip(kvq::launch_trace(d, group_index, (const __half*)k_group, (const __half*)v_group, unit_stride,
+                                    pool, selected, (hipStream_t)stream));
+}
+
+int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_index, const void* k_group,
+                           const void* v_group, int64_t unit_stride, const uint8_t* selected, kvq_qcache qc,
+                           void* stream) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
+  if (group_index < 0 || group_index >= cfg->max_seq / cfg->group_k) return KVQ_ERR_INVALID_ARG;
+  if (!k_group || !v_group) return KVQ_ERR_INVALID_ARG;
+  if (unit_stride < (int64_t)cfg->group_k * cfg->head_dim || unit_stride % 8 != 0) return KVQ_ERR_INVALID_ARG;
+  if ((((uintptr_t)k_group) | ((uintptr_t)v_group)) & 15) return KVQ_ERR_INVALID_ARG;
+  if (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask) return KVQ_ERR_INVALID_ARG;
+  const Dims d = make_dims(cfg, layer);
+  return from_hip(kvq::launch_quantize(d, group_index, (const __half*)k_group, (const __half*)v_group,
+                                       unit_stride, selected, qc, (hipStream_t)stream));
+}
+
+int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc, int32_t n_quant,
+                             kvq_residual res, int32_t res_start, int32_t n_res, kvq_pool pool, void* out,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
+  if (!q || !out) return KVQ_ERR_INVALID_ARG;
+  if (n_quant < 0 || n_quant > cfg->max_seq || n_quant % cfg->group_k != 0) return KVQ_ERR_INVALID_ARG;
+  const int32_t rows = (int32_t)res_rows_of(cfg);
+  if (n_res < 0 || n_res > rows || res_start < 0 || res_start >= rows) return KVQ_ERR_INVALID_ARG;
+  if (n_quant + n_res < 1) return KVQ_ERR_INVALID_ARG;
+  if (n_quant > 0 && (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask))
+    return KVQ_ERR_INVALID_ARG;
+  if (n_res > 0 && (!res.k_res || !res.v_res)) return KVQ_ERR_INVALID_ARG;
+  if (!pool.pool_count || !pool.aux_count) return KVQ_ERR_INVALID_ARG;
+  if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v)) return KVQ_ERR_INVALID_ARG;
+  kvq_sizes sz;
+  kvq_query_sizes(cfg, &sz);
+  if (!workspace || ((uintptr_t)workspace & 255) != 0) return KVQ_ERR_WORKSPACE;
+  if ((int64_t)workspace_bytes < sz.workspace_bytes) return KVQ_ERR_WORKSPACE;
+
+  kvq::DecodeArgs a;
+  a.d = make_dims(cfg, layer);
+  a.q = (const __half*)q;
+  a.k_codes = (const uint8_t*)qc.k_codes;
+  a.k_meta = (const uint32_t*)qc.k_meta;
+  a.v_codes = (const uint8_t*)qc.v_codes;
+  a.v_meta = (const uint32_t*)qc.v_meta;
+  a.mask = (const uint32_t*)qc.mask;
+  a.k_res = (const __half*)res.k_res;
+  a.v_res = (const __half*)res.v_res;
+  a.pool_k = (const __half*)pool.pool_k;
+  a.pool_v = (const __half*)pool.pool_v;
+  a.pool_count = pool.pool_count;
+  a.aux_count = pool.aux_count;
+  a.out = (__half*)out;
+  a.partials = (float*)workspace;
+  a.n_quant = n_quant;
+  a.res_start = res_start;
+  a.n_res = n_res;
+  a.chunks_q = decode_chunks_q(n_quant);
+  a.chunks_fp = decode_chunks_fp((int64_t)n_res + a.d.pool_slots);
+  if (a.chunks_fp < 1) a.chunks_fp = 1;
+  return from_hip(kvq::launch_decode(a, (hipStream_t)stream));
+}
+
+}  // extern "C"

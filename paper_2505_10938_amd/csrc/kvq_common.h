@@ -1,0 +1,83 @@
+// Internal declarations shared by the host entry points and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "kvq.h"
+
+namespace kvq {
+
+constexpr int kHeadDim = 128;      // the only head size built
+constexpr int kBlockTokens = 32;   // tokens per packed block
+constexpr int kChunkTokens = 512;  // quantized tokens per decode workgroup
+constexpr int kFpChunkRows = 64;   // full-precision rows per decode workgroup
+constexpr float kNegBig = -1.0e30f;
+
+// Everything a kernel needs to find a unit's data, derived once on the host.
+struct Dims {
+  int32_t batch, q_heads, kv_heads, g;       // g = q_heads / kv_heads
+  int32_t bits, G, Gv, N, A;
+  int32_t max_seq, res_rows, pool_slots;
+  int32_t units_per_layer;                    // batch * kv_heads
+  int64_t unit0;                              // first unit of the layer being processed
+  int32_t block_bytes;                        // 512 * bits
+  int32_t blocks_per_unit;                    // max_seq / 32
+  int32_t groups_per_unit;                    // max_seq / G
+  int32_t vgroups;                            // head_dim / Gv
+};
+
+struct DecodeArgs {
+  Dims d;
+  const __half* q;
+  const uint8_t* k_codes;
+  const uint32_t* k_meta;
+  const uint8_t* v_codes;
+  const uint32_t* v_meta;
+  const uint32_t* mask;
+  const __half* k_res;
+  const __half* v_res;
+  const __half* pool_k;
+  const __half* pool_v;
+  const int32_t* pool_count;
+  const int32_t* aux_count;
+  __half* out;
+  float* partials;      // [units_per_layer][n_chunks][g][head_dim + 2]
+  int32_t n_quant, res_start, n_res;
+  int32_t chunks_q;     // workgroups over the quantized segment
+  int32_t chunks_fp;    // workgroups over the residual + pool rows
+};
+
+hipError_t launch_append(const Dims& d, const __half* k_new, const __half* v_new, __half* k_res, __half* v_res,
+                         int32_t row, hipStream_t s);
+hipError_t launch_trace(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
+                        int64_t unit_stride, const kvq_pool& pool, uint8_t* selected, hipStream_t s);
+hipError_t launch_quantize(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
+                           int64_t unit_stride, const uint8_t* selected, const kvq_qcache& qc, hipStream_t s);
+hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
+
+// ---- packed layout ---------------------------------------------------------------------------
+// Byte offset (inside a block) of the u32 word that holds field f of lane l, and the bit
+// offset of code x = 2v + e inside that word.
+__host__ __device__ inline int word_byte(int bits, int lane, int f) {
+  return bits == 2 ? 16 * lane + 4 * (f >> 1) : 1024 * (f >> 2) + 16 * lane + 4 * (f & 3);
+}
+__host__ __device__ inline int code_bit(int bits, int f, int x) {
+  const int v = x >> 1, e = x & 1;
+  return bits == 2 ? 16 * e + 2 * (4 * (f & 1) + v) : 16 * e + 4 * v;
+}
+// Key block: (token t in 0..31, channel c) -> (lane, field, x)
+__host__ __device__ inline void k_pos(int t, int c, int& lane, int& f, int& x) {
+  lane = 16 * ((c & 31) >> 3) + (t & 15);
+  f = 4 * (t >> 4) + (c >> 5);
+  x = c & 7;
+}
+// Value block: (token t in 0..31, channel c) -> (lane, field, x)
+__host__ __device__ inline void v_pos(int t, int c, int& lane, int& f, int& x) {
+  lane = 16 * (t >> 3) + (c & 15);
+  f = c >> 4;
+  x = t & 7;
+}
+
+}  // namespace kvq

@@ -1,0 +1,101 @@
+"""Shared set-up for the GPU parity tests: build the same cache with the oracle (CPU) and
+with the library (GPU) from the same seeded inputs, and compare them."""
+from __future__ import annotations
+
+import numpy as np
+
+import kvq_synth as S
+from oracle import kvq_oracle as O
+
+
+def oracle_states(w: S.Workload, K: np.ndarray, V: np.ndarray, n_quant: int):
+    """K, V: fp16 [batch, kv_heads, n, hd] of one layer.  Streams the first n_quant tokens of
+    every unit through the oracle group by group.  Returns a flat list of UnitState."""
+    states = []
+    G = w.group_k
+    for b in range(w.batch):
+        for h in range(w.kv_heads):
+            st = O.UnitState(w.head_dim, w.bits, G, w.group_v, w.outlier_budget, w.aux_capacity)
+            for i in range(n_quant // G):
+                st.append_group(K[b, h, i * G:(i + 1) * G], V[b, h, i * G:(i + 1) * G])
+            states.append(st)
+    return states
+
+
+def gpu_cache(w: S.Workload, K: np.ndarray, V: np.ndarray, n_quant: int, n_res: int, layer: int = 0,
+              max_seq: int | None = None, cache=None):
+    """Same stream through the library: groups are placed in the ring and quantized one by
+    one, then the n_res residual rows are loaded."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    G = w.group_k
+    if cache is None:
+        ms = max_seq or max(G, ((n_quant + G - 1) // G) * G)
+        cfg = KC.make_config(w.layers, w.batch, w.q_heads, w.kv_heads, ms, w.bits, G, w.group_v, w.residual,
+                             w.outlier_budget, w.aux_capacity, w.head_dim)
+        cache = KC.KVCache(cfg)
+    Kd = torch.from_numpy(K).cuda()
+    Vd = torch.from_numpy(V).cuda()
+    for i in range(n_quant // G):
+        cache.load_residual(layer, Kd[:, :, i * G:(i + 1) * G], Vd[:, :, i * G:(i + 1) * G])
+        cache.quantize_oldest(layer)
+    if n_res:
+        cache.load_residual(layer, Kd[:, :, n_quant:n_quant + n_res], Vd[:, :, n_quant:n_quant + n_res])
+    torch.cuda.synchronize()
+    return cache
+
+
+def compare_state(cache, states, w: S.Workload, n_quant: int, layer: int = 0):
+    """Bit-exact comparison of packed codes, steps/zeros, mask words, pool / auxiliary sets
+    (token index, score, K and V rows) and the frozen flag, unit by unit."""
+    cfg, sz = cache.cfg, cache.sizes
+    upl = w.batch * w.kv_heads
+    u0 = layer * upl
+    nb = n_quant // 32
+    ng = n_quant // w.group_k
+    bb = 512 * w.bits
+    kc = cache.k_codes.cpu().numpy().reshape(sz.units, cfg.max_seq // 32, bb)
+    vc = cache.v_codes.cpu().numpy().reshape(sz.units, cfg.max_seq // 32, bb)
+    km = cache.k_meta.cpu().numpy().view(np.uint32).reshape(sz.units, cfg.max_seq // w.group_k, w.head_dim)
+    vm = cache.v_meta.cpu().numpy().view(np.uint32).reshape(sz.units, cfg.max_seq, w.head_dim // w.group_v)
+    mk = cache.mask.cpu().numpy().view(np.uint32).reshape(sz.units, cfg.max_seq // 32)
+    slots = sz.pool_slots
+    pk = cache.pool_k.cpu().numpy().view(np.uint16)[:sz.units * slots * w.head_dim].reshape(sz.units, slots, w.head_dim)
+    pv = cache.pool_v.cpu().numpy().view(np.uint16)[:sz.units * slots * w.head_dim].reshape(sz.units, slots, w.head_dim)
+    pidx = cache.pool_idx.cpu().numpy().view(np.int32)[:sz.units * slots].reshape(sz.units, slots)
+    psc = cache.pool_score.cpu().numpy().view(np.float64)[:sz.units * slots].reshape(sz.units, slots)
+    pcnt = cache.pool_count.cpu().numpy().view(np.int32)[:sz.units]
+    acnt = cache.aux_count.cpu().numpy().view(np.int32)[:sz.units]
+    frz = cache.frozen.cpu().numpy().view(np.int32)[:sz.units]
+    N = w.outlier_budget
+    for i, st in enumerate(states):
+        u = u0 + i
+        ref = O.packed_unit(st)
+        assert np.array_equal(km[u, :ng], ref["k_meta"]), f"k_meta unit {i}"
+        assert np.array_equal(vm[u, :n_quant], ref["v_meta"]), f"v_meta unit {i}"
+        assert np.array_equal(kc[u, :nb], ref["k_codes"]), f"k_codes unit {i}"
+        assert np.array_equal(vc[u, :nb], ref["v_codes"]), f"v_codes unit {i}"
+        assert np.array_equal(mk[u, :nb], ref["mask"]), f"mask unit {i}"
+        assert bool(frz[u]) == st.frozen, f"frozen unit {i}"
+        assert pcnt[u] == len(st.pool) and acnt[u] == len(st.aux), f"pool counts unit {i}"
+        for name, members, lo, cnt in (("pool", st.pool, 0, pcnt[u]), ("aux", st.aux, N, acnt[u])):
+            got = sorted(range(lo, lo + cnt), key=lambda s: pidx[u, s])
+            want = sorted(members, key=lambda m: m["idx"])
+            assert [int(pidx[u, s]) for s in got] == [m["idx"] for m in want], f"{name} index set unit {i}"
+            for s, m in zip(got, want):
+                assert psc[u, s] == m["score"], f"{name} score unit {i}"
+                assert np.array_equal(pk[u, s], m["k"].view(np.uint16)), f"{name} K row unit {i}"
+                assert np.array_equal(pv[u, s], m["v"].view(np.uint16)), f"{name} V row unit {i}"
+
+
+def oracle_attention(w: S.Workload, states, Q: np.ndarray, K: np.ndarray, V: np.ndarray, n_quant: int, n_res: int):
+    """fp64 [batch, q_heads, hd] reference outputs of one decode step."""
+    g = w.q_heads // w.kv_heads
+    out = np.zeros((w.batch, w.q_heads, w.head_dim))
+    for b in range(w.batch):
+        for h in range(w.kv_heads):
+            st = states[b * w.kv_heads + h]
+            o, _ = O.decode_attention(Q[b, h * g:(h + 1) * g], st, K[b, h, n_quant:n_quant + n_res],
+                                      V[b, h, n_quant:n_quant + n_res])
+            out[b, h * g:(h + 1) * g] = o
+    return out

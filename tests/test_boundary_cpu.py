@@ -1,0 +1,97 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, reports
+buffer sizes, and rejects bad arguments on the host before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2505_10938_amd as P
+from paper_2505_10938_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def cfg(**kw):
+    base = dict(layers=1, batch=2, q_heads=8, kv_heads=2, head_dim=128, max_seq=1024, bits=2, group_k=32,
+                group_v=32, residual=128, outlier_budget=8, aux_capacity=32)
+    base.update(kw)
+    return P.kvq_config(**base)
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "kvq.h")).read()
+    declared = set(re.findall(r"\b(kvq_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    lib = P.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert P.kvq_version() >= 1
+    assert P.status_string(0) == "ok" and "workspace" in P.status_string(B.KVQ_ERR_WORKSPACE)
+
+
+def test_sizes():
+    s = P.kvq_query_sizes(cfg())
+    assert s.units == 4 and s.res_rows == 160 and s.pool_slots == 40
+    assert s.k_codes_bytes == 4 * 1024 // 32 * 1024          # 2 bits: 1 KiB per 32-token block
+    assert s.k_meta_bytes == 4 * (1024 // 32) * 128 * 4
+    assert s.v_meta_bytes == 4 * 1024 * 4 * 4
+    # bytes per quantized token per unit: 96 at 2-bit, G=32, Gv=32
+    per_tok = (s.k_codes_bytes + s.v_codes_bytes + s.k_meta_bytes + s.v_meta_bytes) / (4 * 1024)
+    assert per_tok == 96
+    s4 = P.kvq_query_sizes(cfg(bits=4))
+    assert (s4.k_codes_bytes + s4.v_codes_bytes + s4.k_meta_bytes + s4.v_meta_bytes) / (4 * 1024) == 160
+    # residual ring is a whole number of groups: R=32, G=128 -> 256 rows
+    assert P.kvq_query_sizes(cfg(group_k=128, residual=32, max_seq=1024)).res_rows == 256
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(bits=3), B.KVQ_ERR_INVALID_ARG),
+    (dict(group_k=48), B.KVQ_ERR_INVALID_ARG),
+    (dict(group_v=16), B.KVQ_ERR_INVALID_ARG),
+    (dict(max_seq=1000), B.KVQ_ERR_INVALID_ARG),
+    (dict(q_heads=7), B.KVQ_ERR_INVALID_ARG),
+    (dict(residual=-1), B.KVQ_ERR_INVALID_ARG),
+    (dict(head_dim=64, group_v=32), B.KVQ_ERR_UNSUPPORTED),
+    (dict(q_heads=6, kv_heads=2), B.KVQ_ERR_UNSUPPORTED),
+    (dict(outlier_budget=100), B.KVQ_ERR_UNSUPPORTED),
+])
+def test_bad_config(kw, status):
+    with pytest.raises(P.KvqError) as e:
+        P.kvq_query_sizes(cfg(**kw))
+    assert e.value.status == status
+
+
+def test_bad_call_arguments_rejected_before_launch():
+    lib = P.load_library()
+    c = cfg()
+    qc = B.kvq_qcache(256, 256, 256, 256, 256)
+    pool = B.kvq_pool(256, 256, 256, 256, 256, 256, 256)
+    res = B.kvq_residual(256, 256)
+    ws = P.kvq_query_sizes(c).workspace_bytes
+    dec = lambda **k: lib.kvq_decode_attention(C.byref(c), k.get("layer", 0), k.get("q", 256), qc,
+                                               k.get("n_quant", 64), res, k.get("res_start", 0),
+                                               k.get("n_res", 10), pool, k.get("out", 256), k.get("ws", 512),
+                                               k.get("wsb", ws), None)
+    assert dec(layer=1) == B.KVQ_ERR_INVALID_ARG
+    assert dec(q=None) == B.KVQ_ERR_INVALID_ARG
+    assert dec(n_quant=33) == B.KVQ_ERR_INVALID_ARG
+    assert dec(n_quant=2048) == B.KVQ_ERR_INVALID_ARG
+    assert dec(n_res=161) == B.KVQ_ERR_INVALID_ARG
+    assert dec(n_quant=0, n_res=0) == B.KVQ_ERR_INVALID_ARG
+    assert dec(wsb=ws - 1) == B.KVQ_ERR_WORKSPACE
+    assert dec(ws=None) == B.KVQ_ERR_WORKSPACE
+    assert dec(ws=520) == B.KVQ_ERR_WORKSPACE                # not 256-byte aligned
+    tr = lambda **k: lib.kvq_trace_outliers(C.byref(c), 0, k.get("gi", 0), k.get("kg", 256), 256,
+                                            k.get("stride", 32 * 128), pool, k.get("sel", 256), None)
+    assert tr(gi=32) == B.KVQ_ERR_INVALID_ARG
+    assert tr(stride=100) == B.KVQ_ERR_INVALID_ARG
+    assert tr(kg=258) == B.KVQ_ERR_INVALID_ARG
+    assert tr(sel=None) == B.KVQ_ERR_INVALID_ARG
+    qz = lambda **k: lib.kvq_quantize_group(C.byref(c), 0, k.get("gi", 0), k.get("kg", 256), 256, 32 * 128, None,
+                                            k.get("qc", qc), None)
+    assert qz(gi=-1) == B.KVQ_ERR_INVALID_ARG
+    assert qz(qc=B.kvq_qcache(256, 0, 256, 256, 256)) == B.KVQ_ERR_INVALID_ARG
+    ap = lambda **k: lib.kvq_append_residual(C.byref(c), 0, 256, 256, res, k.get("start", 0), k.get("n", 0), None)
+    assert ap(start=160) == B.KVQ_ERR_INVALID_ARG
+    assert ap(n=160) == B.KVQ_ERR_INVALID_ARG

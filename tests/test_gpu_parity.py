@@ -1,0 +1,79 @@
+"""GPU parity: the HIP path against the CPU oracle on the same seeded inputs, through the
+C ABI.  Packed codes, steps/zeros, mask words, outlier/auxiliary sets: bit-exact.  Attention
+output: max abs error <= 2e-3 against the oracle's fp64 result (fp16 output, fp32
+accumulation on the GPU)."""
+import numpy as np
+import pytest
+
+import kvq_synth as S
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+ATT_TOL = 2e-3
+
+
+def run_case(w: S.Workload, regimes=("peaky", "diffuse")):
+    import torch
+    K, V = S.layer_kv(w, 0)
+    nq, nr = w.n_quant, w.n_res
+    states = H.oracle_states(w, K, V, nq)
+    cache = H.gpu_cache(w, K, V, nq, nr)
+    H.compare_state(cache, states, w, nq)
+    errs = {}
+    for regime in regimes:
+        Q = S.layer_queries(w, 0, 0, regime)
+        ref = H.oracle_attention(w, states, Q, K, V, nq, nr)
+        out = cache.decode(0, torch.from_numpy(Q).cuda())
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all()
+        errs[regime] = float(np.abs(got - ref).max())
+        assert errs[regime] <= ATT_TOL, (regime, errs)
+    return errs
+
+
+def small(name, **kw):
+    base = dict(layers=1, batch=2, q_heads=2, kv_heads=2, context=1024 + 77)
+    base.update(kw)
+    return S.Workload(name, **base)
+
+
+def test_config1_small_mha():
+    run_case(S.WORKLOADS["small_mha_1k"])
+
+
+@pytest.mark.parametrize("g", [1, 2, 4, 8])
+def test_gqa_ratios(g):
+    run_case(small(f"g{g}", q_heads=2 * g, context=1500))
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("G,Gv,R,N", [(32, 32, 128, 8), (64, 64, 32, 3), (128, 128, 32, 3), (32, 128, 0, 4)])
+def test_hyper_parameter_grid(bits, G, Gv, R, N):
+    run_case(small(f"b{bits}G{G}", bits=bits, group_k=G, group_v=Gv, residual=R, outlier_budget=N, q_heads=4,
+                   context=1024 + 200))
+
+
+def test_budget_zero_plain_group_quantization():
+    run_case(small("n0", outlier_budget=0))
+
+
+def test_short_sequence_nothing_quantized():
+    w = small("short", context=100)
+    assert w.n_quant == 0
+    run_case(w)
+
+
+def test_single_token():
+    run_case(small("one", context=1))
+
+
+def test_warmup_and_freeze_budget_equals_group():
+    # N = G = 32 with many outlier tokens: the first group is all outliers, evictions fill the
+    # auxiliary pool and tracing stops early
+    w = small("freeze", outlier_budget=32, aux_capacity=32, rho=0.05, context=2048 + 128)
+    K, V = S.layer_kv(w, 0)
+    states = H.oracle_states(w, K, V, w.n_quant)
+    assert any(st.frozen for st in states)
+    run_case(w)
