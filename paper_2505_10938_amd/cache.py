@@ -114,3 +114,17 @@ class KVCache:
                                self.res_start[layer], self.n_res[layer], self.pool, out, self.workspace,
                                self.workspace.numel(), stream)
         return out
+
+    def clone(self):
+        """A second cache with the same contents in its own device memory."""
+        other = KVCache.__new__(KVCache)
+        other.cfg, other.sizes, other.device = self.cfg, self.sizes, self.device
+        names = ("k_codes", "k_meta", "v_codes", "v_meta", "mask", "k_res", "v_res", "pool_k", "pool_v",
+                 "pool_idx", "pool_score", "pool_count", "aux_count", "frozen", "selected", "workspace")
+        for n in names:
+            setattr(other, n, getattr(self, n).clone())
+        other.qcache = B.kvq_qcache(*(getattr(other, n).data_ptr() for n in names[:5]))
+        other.pool = B.kvq_pool(*(getattr(other, n).data_ptr() for n in names[7:14]))
+        other.res = B.kvq_residual(other.k_res.data_ptr(), other.v_res.data_ptr())
+        other.n_quant, other.res_start, other.n_res = list(self.n_quant), list(self.res_start), list(self.n_res)
+        return other
