@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--workload", default="llama2_7b_4k")
     ap.add_argument("--cpu-units", type=int, default=16, help="units of the workload the oracle is timed on")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--decode-only", type=int, default=0, metavar="N",
+                    help="profiling aid: after set-up run N decode-attention launches over the cache copies and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -80,6 +82,16 @@ def main():
     outs = [torch.empty_like(qd) for _ in range(n_inst)]
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
+
+    if args.decode_only:
+        for c in inst:                                        # bring every copy to the post-step state
+            c.append(0, k_new, v_new)
+        torch.cuda.synchronize()
+        for i in range(args.decode_only):
+            inst[i % n_inst].decode(0, qd, outs[i % n_inst])
+        torch.cuda.synchronize()
+        print(json.dumps({"decode_only_launches": args.decode_only, "workload": w.name}))
+        return
 
     def step(c, out):
         quantized = c.append(0, k_new, v_new)                 # fills the ring -> trace + quantize
