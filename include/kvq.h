@@ -59,9 +59,9 @@ typedef struct kvq_sizes {
   int64_t res_rows;         /* rows per unit of the residual ring: G * ceil((R + G) / G)      */
   int64_t pool_slots;       /* N + A: slots [0,N) outlier pool, [N,N+A) auxiliary pool        */
   int64_t k_codes_bytes;    /* [units][max_seq/32][512*bits] packed Key codes                 */
-  int64_t k_meta_bytes;     /* [units][max_seq/G][head_dim] u32 = fp16 step | fp16 zero << 16 */
+  int64_t k_meta_bytes;     /* [units][max_seq/G][2][head_dim] fp16: steps, zeros              */
   int64_t v_codes_bytes;    /* [units][max_seq/32][512*bits] packed Value codes               */
-  int64_t v_meta_bytes;     /* [units][max_seq][head_dim/group_v] u32, same packing           */
+  int64_t v_meta_bytes;     /* [units][max_seq/32][128*NV bytes] fp16 steps, zeros (see below) */
   int64_t mask_bytes;       /* [units][max_seq/32] u32, bit t%32 set: token lives in a pool   */
   int64_t res_bytes;        /* each of k_res, v_res: [units][res_rows][head_dim] fp16         */
   int64_t pool_rows_bytes;  /* each of pool_k, pool_v: [units][pool_slots][head_dim] fp16     */
@@ -83,8 +83,12 @@ typedef struct kvq_sizes {
  * Value block: channel c = 16 ct + n, token t = 8 r + x          ->  lane 16 r + n, field ct.
  * (A lane's 16 bytes are what one wavefront lane loads with one dwordx4; a field is one
  * lane's share of a 16x16x32 matrix-core operand.)
- * k_meta[u][group][c] and v_meta[u][token][c / group_v] are u32 = fp16 step | fp16 zero << 16;
- * the dequantized value is zero + code * step.  mask[u][block] bit t%32 is set when token
+ * Steps and zeros are fp16; the dequantized value is zero + code * step.
+ *   k_meta[u][group]  (512 bytes): step[128 channels], then zero[128 channels].
+ *   v_meta[u][block]  (128*NV bytes, NV = head_dim / group_v): step[16 token pairs][NV][2], i.e.
+ *                     the step of token 2p+e and value group j at index (p*NV + j)*2 + e; then
+ *                     zero[NV][32 tokens].
+ * mask[u][block] bit t%32 is set when token
  * 32*block + t was selected as an outlier (it then lives in the outlier or auxiliary pool and
  * its codes are placeholders).
  */

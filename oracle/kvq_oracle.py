@@ -262,6 +262,8 @@ def decode_attention(q_heads: np.ndarray, state: UnitState, k_res: np.ndarray, v
 # and the lane's words live at byte  half*1024 + lane*16 + 4*word.
 # K block: token t = 16*th + m, channel c = 32*cb + 8*r + x -> lane 16*r + m, field 4*th + cb.
 # V block: channel c = 16*ct + n, token t = 8*r + x        -> lane 16*r + n, field ct.
+# Meta (fp16): Key group = step[128] then zero[128]; Value block = step[16 pairs][NV][2] then
+# zero[NV][32 tokens].
 
 def _pack_fields(fields: np.ndarray, bits: int) -> np.ndarray:
     """fields: u8 [64 lanes, 8 fields, 8 codes] -> packed block bytes (u8 [512*bits])."""
@@ -303,11 +305,23 @@ def pack_v_block(codes: np.ndarray, bits: int) -> np.ndarray:
     return _pack_fields(fields, bits)
 
 
-def pack_meta(step: np.ndarray, zero: np.ndarray) -> np.ndarray:
-    """(step, zero) fp16 pairs -> u32, step in the low half."""
-    s = np.ascontiguousarray(step).view(np.uint16).astype(np.uint32)
-    z = np.ascontiguousarray(zero).view(np.uint16).astype(np.uint32)
-    return s | (z << np.uint32(16))
+def pack_k_meta(step: np.ndarray, zero: np.ndarray) -> np.ndarray:
+    """Key meta of the groups of one unit: fp16 [groups, 2, 128] = steps, then zeros."""
+    return np.stack([step, zero], axis=1).astype(np.float16)
+
+
+def pack_v_meta(step: np.ndarray, zero: np.ndarray) -> np.ndarray:
+    """Value meta of one unit, per 32-token block: fp16 step[16 pairs][NV][2] (token 2p+e,
+    value group j at (p*NV + j)*2 + e) followed by fp16 zero[NV][32 tokens].
+    step, zero: fp16 [n tokens, NV]; returns fp16 [n/32, 64*NV]."""
+    n, nv = step.shape
+    out = np.zeros((n // 32, 64 * nv), np.float16)
+    for blk in range(n // 32):
+        for t in range(32):
+            for j in range(nv):
+                out[blk, ((t >> 1) * nv + j) * 2 + (t & 1)] = step[32 * blk + t, j]
+                out[blk, 32 * nv + j * 32 + t] = zero[32 * blk + t, j]
+    return out
 
 
 def mask_words(masked: np.ndarray) -> np.ndarray:
@@ -324,6 +338,6 @@ def packed_unit(state: UnitState):
     vc = np.stack([pack_v_block(state.v_codes[32 * i:32 * i + 32], state.bits) for i in range(nb)]) \
         if nb else np.zeros((0, 512 * state.bits), np.uint8)
     return dict(k_codes=kc, v_codes=vc,
-                k_meta=pack_meta(state.k_step, state.k_zero),
-                v_meta=pack_meta(state.v_step, state.v_zero),
+                k_meta=pack_k_meta(state.k_step, state.k_zero),
+                v_meta=pack_v_meta(state.v_step, state.v_zero),
                 mask=mask_words(state.masked))

@@ -17,6 +17,7 @@ int32_t check_config(const kvq_config* c) {
   if (c->max_seq < c->group_k || c->max_seq % c->group_k != 0) return KVQ_ERR_INVALID_ARG;
   if (c->residual < 0 || c->outlier_budget < 0 || c->aux_capacity < 0) return KVQ_ERR_INVALID_ARG;
   if (c->residual > (1 << 20) || c->max_seq > (1 << 24)) return KVQ_ERR_INVALID_ARG;
+  if (c->batch > 65535 || c->kv_heads > 65535) return KVQ_ERR_INVALID_ARG;   // grid y/z limits
   if (c->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;
   const int g = c->q_heads / c->kv_heads;
   if (g != 1 && g != 2 && g != 4 && g != 8) return KVQ_ERR_UNSUPPORTED;
@@ -52,6 +53,7 @@ Dims make_dims(const kvq_config* c, int32_t layer) {
   d.blocks_per_unit = c->max_seq / kvq::kBlockTokens;
   d.groups_per_unit = c->max_seq / c->group_k;
   d.vgroups = c->head_dim / c->group_v;
+  d.bpg_shift = c->group_k == 32 ? 0 : (c->group_k == 64 ? 1 : 2);
   return d;
 }
 

@@ -26,6 +26,7 @@ struct Dims {
   int32_t blocks_per_unit;                    // max_seq / 32
   int32_t groups_per_unit;                    // max_seq / G
   int32_t vgroups;                            // head_dim / Gv
+  int32_t bpg_shift;                          // log2(G / 32): blocks per Key group
 };
 
 struct DecodeArgs {

@@ -111,7 +111,10 @@ __global__ void __launch_bounds__(256) quantize_kernel(Dims d, int32_t group_ind
     const __half st = step_of(mn, mx, BITS);
     const uint32_t m = (uint32_t)__half_as_ushort(st) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
     skm[c] = m;
-    k_meta[(u * d.groups_per_unit + group_index) * kHeadDim + c] = m;
+    // global layout of a group's Key meta: fp16 step[128], then fp16 zero[128]
+    __half* gm = (__half*)(k_meta + (u * d.groups_per_unit + group_index) * kHeadDim);
+    gm[c] = st;
+    gm[kHeadDim + c] = __float2half_rn(mn);
   } else {
     const int nvg = G * d.vgroups;
     for (int i = tid - 128; i < nvg; i += 128) {
@@ -126,7 +129,13 @@ __global__ void __launch_bounds__(256) quantize_kernel(Dims d, int32_t group_ind
       const __half st = step_of(mn, mx, BITS);
       const uint32_t m = (uint32_t)__half_as_ushort(st) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
       svm[i] = m;
-      v_meta[(u * d.max_seq + (int64_t)group_index * G + t) * d.vgroups + j] = m;
+      // global layout of a 32-token block's Value meta (NV = value groups per token):
+      // fp16 step[16 token pairs][NV][2], then fp16 zero[NV][32 tokens]
+      const int64_t tok = (int64_t)group_index * G + t;
+      const int tb = (int)(tok & 31);
+      __half* gm = (__half*)(v_meta + (u * d.blocks_per_unit + (tok >> 5)) * 32 * d.vgroups);
+      gm[((tb >> 1) * d.vgroups + j) * 2 + (tb & 1)] = st;
+      gm[32 * d.vgroups + j * 32 + tb] = __float2half_rn(mn);
     }
   }
   __syncthreads();

@@ -56,8 +56,9 @@ def compare_state(cache, states, w: S.Workload, n_quant: int, layer: int = 0):
     bb = 512 * w.bits
     kc = cache.k_codes.cpu().numpy().reshape(sz.units, cfg.max_seq // 32, bb)
     vc = cache.v_codes.cpu().numpy().reshape(sz.units, cfg.max_seq // 32, bb)
-    km = cache.k_meta.cpu().numpy().view(np.uint32).reshape(sz.units, cfg.max_seq // w.group_k, w.head_dim)
-    vm = cache.v_meta.cpu().numpy().view(np.uint32).reshape(sz.units, cfg.max_seq, w.head_dim // w.group_v)
+    nv = w.head_dim // w.group_v
+    km = cache.k_meta.cpu().numpy().view(np.uint16).reshape(sz.units, cfg.max_seq // w.group_k, 2, w.head_dim)
+    vm = cache.v_meta.cpu().numpy().view(np.uint16).reshape(sz.units, cfg.max_seq // 32, 64 * nv)
     mk = cache.mask.cpu().numpy().view(np.uint32).reshape(sz.units, cfg.max_seq // 32)
     slots = sz.pool_slots
     pk = cache.pool_k.cpu().numpy().view(np.uint16)[:sz.units * slots * w.head_dim].reshape(sz.units, slots, w.head_dim)
@@ -71,8 +72,8 @@ def compare_state(cache, states, w: S.Workload, n_quant: int, layer: int = 0):
     for i, st in enumerate(states):
         u = u0 + i
         ref = O.packed_unit(st)
-        assert np.array_equal(km[u, :ng], ref["k_meta"]), f"k_meta unit {i}"
-        assert np.array_equal(vm[u, :n_quant], ref["v_meta"]), f"v_meta unit {i}"
+        assert np.array_equal(km[u, :ng], ref["k_meta"].view(np.uint16)), f"k_meta unit {i}"
+        assert np.array_equal(vm[u, :nb], ref["v_meta"].view(np.uint16)), f"v_meta unit {i}"
         assert np.array_equal(kc[u, :nb], ref["k_codes"]), f"k_codes unit {i}"
         assert np.array_equal(vc[u, :nb], ref["v_codes"]), f"v_codes unit {i}"
         assert np.array_equal(mk[u, :nb], ref["mask"]), f"mask unit {i}"

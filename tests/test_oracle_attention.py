@@ -157,8 +157,15 @@ def test_packer_against_hand_computed_positions_and_bijection():
                     one = np.zeros((32, 128), np.uint8); one[t, c] = codes[t, c]
                     acc_one = fn(one, bits)
                     assert np.array_equal(acc_one & packed, acc_one)
-    # meta and mask words
-    m = O.pack_meta(np.array([1.0, 2.0], np.float16), np.array([-1.0, 0.5], np.float16))
-    assert m.tolist() == [0x3C00 | (0xBC00 << 16), 0x4000 | (0x3800 << 16)]
+    # meta planes and mask words
+    km = O.pack_k_meta(np.arange(256, dtype=np.float16).reshape(2, 128), -np.arange(256, dtype=np.float16).reshape(2, 128))
+    assert km.shape == (2, 2, 128) and km[1, 0, 5] == 133 and km[1, 1, 5] == -133
+    st = np.arange(64 * 4, dtype=np.float16).reshape(64, 4)          # step of token t, group j = 4t + j
+    vm = O.pack_v_meta(st, -st)
+    assert vm.shape == (2, 256)
+    assert vm[0, 0] == 0 and vm[0, 1] == 4 and vm[0, 2] == 1 and vm[0, 3] == 5      # pair 0: (t0,j0),(t1,j0),(t0,j1),(t1,j1)
+    assert vm[0, (3 * 4 + 2) * 2 + 1] == 4 * 7 + 2                                    # token 7 = pair 3, e = 1, group 2
+    assert vm[0, 128 + 2 * 32 + 7] == -(4 * 7 + 2)                                    # zero[j=2][t=7]
+    assert vm[1, 128 + 3 * 32 + 31] == -(4 * 63 + 3)
     mk = np.zeros(64, bool); mk[0] = mk[33] = mk[63] = True
     assert O.mask_words(mk).tolist() == [1, (1 << 1) | (1 << 31)]
