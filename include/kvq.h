@@ -87,7 +87,7 @@ typedef struct kvq_sizes {
  *   k_meta[u][group]  (512 bytes): step[128 channels], then zero[128 channels].
  *   v_meta[u][block]  (128*NV bytes, NV = head_dim / group_v): step[16 token pairs][NV][2], i.e.
  *                     the step of token 2p+e and value group j at index (p*NV + j)*2 + e; then
- *                     zero[NV][32 tokens].
+ *                     zero[16 token pairs][NV][2], indexed the same way.
  * mask[u][block] bit t%32 is set when token
  * 32*block + t was selected as an outlier (it then lives in the outlier or auxiliary pool and
  * its codes are placeholders).
@@ -178,9 +178,10 @@ int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_i
  *   res_start, n_res : live part of the residual ring, n_res <= res_rows;
  *              n_quant + n_res >= 1
  *   out      : device fp16 [batch][q_heads][head_dim]
- *   workspace: device scratch of at least kvq_sizes.workspace_bytes, 256-byte aligned;
- *              contents need not be preserved between calls; two calls that overlap in
- *              time must not share it
+ *   workspace: device scratch of at least kvq_sizes.workspace_bytes, 256-byte aligned.  It must
+ *              be zero-filled once before its first use; every call leaves the part it relies on
+ *              (per-unit arrival counters) zero again, so it can be reused call after call.  Two
+ *              calls that overlap in time must not share it
  */
 int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qcache,
                              int32_t n_quant, kvq_residual res, int32_t res_start, int32_t n_res,

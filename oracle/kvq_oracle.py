@@ -263,7 +263,7 @@ def decode_attention(q_heads: np.ndarray, state: UnitState, k_res: np.ndarray, v
 # K block: token t = 16*th + m, channel c = 32*cb + 8*r + x -> lane 16*r + m, field 4*th + cb.
 # V block: channel c = 16*ct + n, token t = 8*r + x        -> lane 16*r + n, field ct.
 # Meta (fp16): Key group = step[128] then zero[128]; Value block = step[16 pairs][NV][2] then
-# zero[NV][32 tokens].
+# zero[16 pairs][NV][2].
 
 def _pack_fields(fields: np.ndarray, bits: int) -> np.ndarray:
     """fields: u8 [64 lanes, 8 fields, 8 codes] -> packed block bytes (u8 [512*bits])."""
@@ -312,7 +312,7 @@ def pack_k_meta(step: np.ndarray, zero: np.ndarray) -> np.ndarray:
 
 def pack_v_meta(step: np.ndarray, zero: np.ndarray) -> np.ndarray:
     """Value meta of one unit, per 32-token block: fp16 step[16 pairs][NV][2] (token 2p+e,
-    value group j at (p*NV + j)*2 + e) followed by fp16 zero[NV][32 tokens].
+    value group j at (p*NV + j)*2 + e) followed by fp16 zero[16 pairs][NV][2], same indexing.
     step, zero: fp16 [n tokens, NV]; returns fp16 [n/32, 64*NV]."""
     n, nv = step.shape
     out = np.zeros((n // 32, 64 * nv), np.float16)
@@ -320,7 +320,7 @@ def pack_v_meta(step: np.ndarray, zero: np.ndarray) -> np.ndarray:
         for t in range(32):
             for j in range(nv):
                 out[blk, ((t >> 1) * nv + j) * 2 + (t & 1)] = step[32 * blk + t, j]
-                out[blk, 32 * nv + j * 32 + t] = zero[32 * blk + t, j]
+                out[blk, 32 * nv + ((t >> 1) * nv + j) * 2 + (t & 1)] = zero[32 * blk + t, j]
     return out
 
 

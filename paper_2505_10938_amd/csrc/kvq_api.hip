@@ -30,8 +30,30 @@ int64_t res_rows_of(const kvq_config* c) {
   return G * ((c->residual + G + G - 1) / G);
 }
 
-int32_t decode_chunks_q(int32_t n_quant) { return (n_quant + kvq::kChunkTokens - 1) / kvq::kChunkTokens; }
-int32_t decode_chunks_fp(int64_t rows) { return (int32_t)((rows + kvq::kFpChunkRows - 1) / kvq::kFpChunkRows); }
+// Split of one unit's decode work over workgroups.  Quantized tokens go in mini-chunks of 128
+// (one wavefront each at a time); a workgroup gets at least 4 of them when there are that many.
+struct Split {
+  int32_t splits_q, mc_per_split, splits_fp;
+};
+Split decode_split(int64_t units_per_layer, int32_t n_quant, int64_t fp_rows) {
+  Split s;
+  const int32_t mc = (n_quant + kvq::kMiniChunk - 1) / kvq::kMiniChunk;
+  if (mc == 0) {
+    s.splits_q = 0;
+    s.mc_per_split = 0;
+  } else {
+    int64_t want = (kvq::kTargetWorkgroups + units_per_layer - 1) / units_per_layer;
+    const int64_t cap = (mc + 3) / 4;
+    if (want > cap) want = cap;
+    if (want < 1) want = 1;
+    s.mc_per_split = (int32_t)((mc + want - 1) / want);
+    s.splits_q = (mc + s.mc_per_split - 1) / s.mc_per_split;
+  }
+  s.splits_fp = (int32_t)((fp_rows + kvq::kFpChunkRows - 1) / kvq::kFpChunkRows);
+  if (s.splits_fp < 1) s.splits_fp = 1;
+  return s;
+}
+constexpr int64_t kCounterBytes(int64_t upl) { return ((upl * 4 + 255) / 256) * 256; }
 
 Dims make_dims(const kvq_config* c, int32_t layer) {
   Dims d;
@@ -99,8 +121,13 @@ int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out) {
   out->pool_score_bytes = units * slots * 8;
   out->counter_bytes = units * 4;
   out->selected_bytes = upl * cfg->group_k;
-  const int64_t chunks = decode_chunks_q(cfg->max_seq) + decode_chunks_fp(out->res_rows + slots);
-  out->workspace_bytes = upl * chunks * g * (hd + 2) * 4;
+  // worst case over n_quant <= max_seq: the split count never exceeds this one
+  int64_t sq_max = (kvq::kTargetWorkgroups + upl - 1) / upl;
+  const int64_t mc_max = (cfg->max_seq + kvq::kMiniChunk - 1) / kvq::kMiniChunk;
+  if (sq_max > (mc_max + 3) / 4) sq_max = (mc_max + 3) / 4;
+  if (sq_max < 1) sq_max = 1;
+  const int64_t sfp_max = (out->res_rows + slots + kvq::kFpChunkRows - 1) / kvq::kFpChunkRows;
+  out->workspace_bytes = kCounterBytes(upl) + upl * (sq_max + sfp_max) * g * (hd + 2) * 4;
   return KVQ_OK;
 }
 
@@ -187,13 +214,15 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
   a.pool_count = pool.pool_count;
   a.aux_count = pool.aux_count;
   a.out = (__half*)out;
-  a.partials = (float*)workspace;
+  a.counters = (int32_t*)workspace;
+  a.partials = (float*)((unsigned char*)workspace + kCounterBytes(a.d.units_per_layer));
   a.n_quant = n_quant;
   a.res_start = res_start;
   a.n_res = n_res;
-  a.chunks_q = decode_chunks_q(n_quant);
-  a.chunks_fp = decode_chunks_fp((int64_t)n_res + a.d.pool_slots);
-  if (a.chunks_fp < 1) a.chunks_fp = 1;
+  const Split sp = decode_split(a.d.units_per_layer, n_quant, (int64_t)n_res + a.d.pool_slots);
+  a.splits_q = sp.splits_q;
+  a.mc_per_split = sp.mc_per_split;
+  a.splits_fp = sp.splits_fp;
   return from_hip(kvq::launch_decode(a, (hipStream_t)stream));
 }
 

@@ -11,7 +11,8 @@ namespace kvq {
 
 constexpr int kHeadDim = 128;      // the only head size built
 constexpr int kBlockTokens = 32;   // tokens per packed block
-constexpr int kChunkTokens = 512;  // quantized tokens per decode workgroup
+constexpr int kMiniChunk = 128;     // quantized tokens one wavefront handles at a time
+constexpr int kTargetWorkgroups = 768;  // decode workgroups wanted in flight (3 per compute unit)
 constexpr int kFpChunkRows = 64;   // full-precision rows per decode workgroup
 constexpr float kNegBig = -1.0e30f;
 
@@ -44,10 +45,12 @@ struct DecodeArgs {
   const int32_t* pool_count;
   const int32_t* aux_count;
   __half* out;
-  float* partials;      // [units_per_layer][n_chunks][g][head_dim + 2]
+  float* partials;      // [units_per_layer][splits_q + splits_fp][g][head_dim + 2]
+  int32_t* counters;    // [units_per_layer], zero on entry and on exit
   int32_t n_quant, res_start, n_res;
-  int32_t chunks_q;     // workgroups over the quantized segment
-  int32_t chunks_fp;    // workgroups over the residual + pool rows
+  int32_t splits_q;     // workgroups per unit over the quantized segment
+  int32_t mc_per_split; // 128-token mini-chunks per such workgroup
+  int32_t splits_fp;    // workgroups per unit over the residual + pool rows
 };
 
 hipError_t launch_append(const Dims& d, const __half* k_new, const __half* v_new, __half* k_res, __half* v_res,

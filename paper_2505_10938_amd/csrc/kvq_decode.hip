@@ -1,19 +1,21 @@
 // Decode-step attention (Eq. 1) over the quantized cache, the residual ring and the outlier
-// pools, for gfx950.
+// pools, for gfx950.  One kernel launch per call.
 //
-// Work split: grid = (chunks, kv heads, batch).  A quantized chunk is 512 tokens = 16 packed
-// blocks; each of the 4 wavefronts of a workgroup owns 4 blocks (128 tokens) and produces its
-// own (max, sum, weighted values); the 4 results are merged through LDS and written as one
-// partial per (unit, chunk).  Full-precision chunks (64 rows of residual / pool / auxiliary
-// pool) produce partials of the same form.  A second small kernel merges the partials.
+// Work split: grid = (splits, kv heads, batch).  The quantized tokens of a unit are cut into
+// mini-chunks of 128 tokens (4 packed blocks).  A "quantized" workgroup owns a contiguous range
+// of mini-chunks; its 4 wavefronts take them round-robin, each keeping a running (max, sum,
+// weighted values) and loading its next mini-chunk into registers while it computes the current
+// one.  "Full-precision" workgroups take 64 rows of residual / pool / auxiliary pool each.  Every
+// workgroup merges its 4 wavefronts through LDS into one partial; the last workgroup of a unit to
+// arrive (per-unit counter) merges the partials and writes the fp16 output.
 //
 // Arithmetic: every contraction runs on the matrix cores (v_mfma_f32_16x16x32_f16).
 //  * q.K^T:  A = q * step, split in fp16 hi + lo rows (two matrix rows per query head, so the
 //            split costs no extra instruction), B = the packed codes themselves.
 //  * P.V:    A = p * step (hi + lo rows), B = the packed codes.
 //  * zero points: sum_c q_c z_c (one scalar per group and head) is A = q (hi/lo) times B = the
-//            fp16 zero plane of the group; sum_t p_t z_t (one scalar per head and value group)
-//            and sum_t p_t are A = p (hi/lo) times B = [zero plane | ones].
+//            fp16 zeros of the group; sum_t p_t z_t (one scalar per head and value group) and
+//            sum_t p_t are A = p (hi/lo) times B = [zeros | ones].
 // A packed code becomes an fp16 operand with ONE `and`: masked in place, a 2-bit code at bits
 // [2v, 2v+2) of a half-word is the fp16 subnormal code * 2^(2v-24) (the matrix cores take
 // subnormal inputs exactly), and the factor 2^(-2v) is folded into the other operand.
@@ -83,17 +85,16 @@ __device__ inline int pair_pos(int v) { return BITS == 2 ? 2 * v : 4 * (v & 1); 
 
 // One matrix-core operand (8 fp16 = 4 dwords) from field f of a lane's packed words.
 template <int BITS>
-__device__ inline half8 field_operand(const uint4 (&w)[BITS / 2], int f) {
+__device__ inline half8 field_operand(const uint32_t (&w)[2 * BITS], int f) {
   u32x4 o;
-  const uint32_t* p = (const uint32_t*)&w[0];
   if (BITS == 2) {
-    const uint32_t x = (f & 1) ? (p[f >> 1] >> 8) : p[f >> 1];
+    const uint32_t x = (f & 1) ? (w[f >> 1] >> 8) : w[f >> 1];
     o[0] = x & 0x00030003u;
     o[1] = x & 0x000C000Cu;
     o[2] = x & 0x00300030u;
     o[3] = x & 0x00C000C0u;
   } else {
-    const uint32_t x = p[f], y = p[f] >> 8;
+    const uint32_t x = w[f], y = w[f] >> 8;
     o[0] = x & 0x000F000Fu;
     o[1] = x & 0x00F000F0u;
     o[2] = y & 0x000F000Fu;
@@ -102,25 +103,54 @@ __device__ inline half8 field_operand(const uint4 (&w)[BITS / 2], int f) {
   return __builtin_bit_cast(half8, o);
 }
 
+// Device-scope (all compute dies) relaxed accesses for data exchanged between workgroups.
+__device__ inline void coherent_store(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float coherent_load(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __device__ inline half8 lds_operand(const unsigned char* row, int byte) {
   return __builtin_bit_cast(half8, *(const u32x4*)(row + byte));
 }
 
+// Registers one wavefront loads for one mini-chunk (4 blocks), per lane.
+template <int BITS, int NV>
+struct McRegs {
+  uint32_t kc[4][2 * BITS];  // Key codes: this lane's 16 (32) bytes of each block
+  uint32_t vc[4][2 * BITS];  // Value codes
+  uint32_t ksp[4];         // Key steps of channels 2*lane, 2*lane+1 of each block's group
+  uint32_t ksz[4];         // Key zeros, same channels
+  uint32_t vsp[NV];        // Value steps of this lane's tokens (2*lane, 2*lane+1 of the 128), per value group
+  uint32_t vsz[NV];        // Value zeros, same tokens
+  uint32_t mkw;            // mask word of this lane's block (all ones for a block past the end)
+};
+
+// LDS of one wavefront.  The first group of arrays is used while scores are formed, the second
+// afterwards; they share storage.
 template <int GQ, int NV>
 struct WaveLds {
-  union {                                      // aop is dead once the scores are written
-    unsigned char aop[2 * GQ][kRowBytes];      // q-side operand rows: hi/lo per head, 128 channels
-    unsigned char pp[2 * GQ][kRowBytes];       // p rows (hi/lo per head), 128 tokens
+  union {
+    struct {
+      unsigned char q0[2 * GQ][kRowBytes];        // q rows (hi/lo per head), no step
+      unsigned char aop[4][2 * GQ][kRowBytes];    // q*step rows per block
+      unsigned char zk[4][kRowBytes];             // Key zeros per block, 128 channels
+    } k;
+    struct {
+      unsigned char pp[2 * GQ][kRowBytes];        // p rows (hi/lo per head), 128 tokens
+      unsigned char ps[NV][2 * GQ][kRowBytes];    // p*step rows per value group
+      unsigned char zv[NV + 1][kRowBytes];        // Value zeros per value group, 128 tokens; row NV = ones
+    } v;
   };
-  unsigned char ps[NV][2 * GQ][kRowBytes];     // p*step rows per value group (hi/lo per head), 128 tokens
-  float sc[GQ][128];                           // scores of the wave's 128 tokens
-  float qz[4][GQ];                             // sum_c q_c z_c per (block, head)
+  float sc[GQ][128];                              // scores of the 128 tokens
+  float qz[4][GQ];                                // sum_c q_c z_c per (block, head)
 };
 
 template <int GQ, int NV>
 struct MergeLds {
   float m[4][GQ], l[4][GQ];
-  float z[4][GQ][NV];                          // sum_t p_t z_t per value group
+  float z[4][GQ][NV];                             // sum_t p_t z_t per value group
   float o[4][GQ][kHeadDim];
 };
 
@@ -130,48 +160,228 @@ union DecodeLds {
   MergeLds<GQ, NV> mg;
 };
 
-// ---- merge the 4 wavefronts' results and write the chunk partial --------------------------------
-template <int GQ, int NV>
-__device__ inline void merge_and_store(MergeLds<GQ, NV>& mg, float* part, int tid) {
-  __syncthreads();
-  for (int i = tid; i < GQ * kHeadDim; i += 256) {
-    const int j = i / kHeadDim, c = i % kHeadDim;
-    const int jv = c / (kHeadDim / NV);
-    const float m = fmaxf(fmaxf(mg.m[0][j], mg.m[1][j]), fmaxf(mg.m[2][j], mg.m[3][j]));
-    float o = 0.f, l = 0.f;
+// Loads of one mini-chunk, in the four parts the compute phases consume.  A block past the end of
+// the quantized segment is replaced by the last block with every token masked, so that every
+// wave runs the same straight-line code.
+__device__ __forceinline__ int clamp_block(const DecodeArgs& a, int mc, int i) {
+  return min(mc * 4 + i, (a.n_quant >> 5) - 1);
+}
+template <int BITS, int NV>
+__device__ __forceinline__ void load_k_meta(McRegs<BITS, NV>& R, const DecodeArgs& a, int64_t u, int mc, int lane) {
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float f = __builtin_amdgcn_exp2f(mg.m[w][j] - m);
-      o += (mg.o[w][j][c] + mg.z[w][j][jv]) * f;
-      l += mg.l[w][j] * f;
-    }
-    part[j * (kHeadDim + 2) + 2 + c] = o;
-    if (c == 0) {
-      part[j * (kHeadDim + 2) + 0] = m;
-      part[j * (kHeadDim + 2) + 1] = l;
+  for (int i = 0; i < 4; ++i) {
+    const int blk = clamp_block(a, mc, i);
+    const uint32_t* km = a.k_meta + (u * a.d.groups_per_unit + (blk >> a.d.bpg_shift)) * kHeadDim;
+    R.ksp[i] = km[lane];
+    R.ksz[i] = km[64 + lane];
+  }
+}
+template <int BITS>
+__device__ __forceinline__ void load_codes(uint32_t (&w)[4][2 * BITS], const uint8_t* codes, const DecodeArgs& a,
+                                           int64_t u, int mc, int lane) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int64_t gb = u * a.d.blocks_per_unit + clamp_block(a, mc, i);
+    const uint4* p = (const uint4*)(codes + gb * a.d.block_bytes) + lane;
+#pragma unroll
+    for (int hf = 0; hf < BITS / 2; ++hf) {
+      const uint4 t = p[hf * 64];
+      w[i][4 * hf + 0] = t.x;
+      w[i][4 * hf + 1] = t.y;
+      w[i][4 * hf + 2] = t.z;
+      w[i][4 * hf + 3] = t.w;
     }
   }
 }
+template <int BITS, int NV>
+__device__ __forceinline__ void load_v_meta(McRegs<BITS, NV>& R, const DecodeArgs& a, int64_t u, int mc, int lane) {
+  const int nblocks = a.n_quant >> 5;
+  // this lane's tokens are 2*lane, 2*lane+1 of the 128: pair lane&15 of block lane>>4
+  const int myblk = mc * 4 + (lane >> 4);
+  const int64_t gb = u * a.d.blocks_per_unit + min(myblk, nblocks - 1);
+  const uint32_t mw = a.mask[gb];
+  R.mkw = (myblk < nblocks) ? mw : 0xFFFFFFFFu;
+  const uint32_t* p = (const uint32_t*)((const unsigned char*)a.v_meta + gb * (int64_t)(128 * NV) + (lane & 15) * 4 * NV);
+#pragma unroll
+  for (int jv = 0; jv < NV; ++jv) {
+    R.vsp[jv] = p[jv];
+    R.vsz[jv] = p[16 * NV + jv];
+  }
+}
 
-// grid (chunks_q + chunks_fp, kv_heads, batch), 256 threads
+// Running state of one wavefront over its mini-chunks.
+template <int GQ>
+struct WaveAcc {
+  float4v O[8];      // weighted values: 8 channel tiles; rows = heads (hi, lo)
+  float4v Dz;        // columns < NV: sum_t p_t z_t per value group; column NV: sum_t p_t
+  float m[GQ];       // running maximum per head (log2 domain)
+};
+
 template <int GQ, int BITS, int NV>
-__global__ void __launch_bounds__(256) decode_partial_kernel(DecodeArgs a) {
+__device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<GQ>& S, WaveLds<GQ, NV>& L,
+                                                  const float (&qa)[GQ][2], const float (&qaf)[GQ][2], int lane,
+                                                  const DecodeArgs& a, int64_t u, int mc_next, bool more) {
+  // Each group of registers is reloaded for the wave's next mini-chunk (mc_next, if `more`) right
+  // after its last use here, so those loads are in flight during the rest of this mini-chunk.
+  const int m16 = lane & 15, r = lane >> 4;
+  constexpr int R2 = 2 * GQ;
+  const int arow = m16 % R2;          // rows beyond 2*GQ repeat valid rows (their results are unused)
+
+  // ---- operand rows: q (hi/lo), q*step (hi/lo) per block, and the Key zeros ------------------------
+  wave_sync();                          // the previous mini-chunk is done with the shared storage
+#pragma unroll
+  for (int j = 0; j < GQ; ++j) {
+    uint32_t hi, lo;
+    split_pair(qa[j][0], qa[j][1], hi, lo);
+    ((uint32_t*)L.k.q0[2 * j])[lane] = hi;
+    ((uint32_t*)L.k.q0[2 * j + 1])[lane] = lo;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float s0 = h2f_bits(R.ksp[i] & 0xFFFFu), s1 = h2f_bits(R.ksp[i] >> 16);
+#pragma unroll
+    for (int j = 0; j < GQ; ++j) {
+      uint32_t hi, lo;
+      split_pair(qaf[j][0] * s0, qaf[j][1] * s1, hi, lo);
+      ((uint32_t*)L.k.aop[i][2 * j])[lane] = hi;
+      ((uint32_t*)L.k.aop[i][2 * j + 1])[lane] = lo;
+    }
+    ((uint32_t*)L.k.zk[i])[lane] = R.ksz[i];
+  }
+  if (more) load_k_meta<BITS, NV>(R, a, u, mc_next, lane);
+  wave_sync();
+
+  // ---- sum_c q_c z_c of the 4 blocks: column n of B = zeros of block n & 3 --------------------------
+  {
+    float4v Dq = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+      Dq = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.k.q0[arow], cb * 64 + r * 16),
+                                                  lds_operand(L.k.zk[m16 & 3], cb * 64 + r * 16), Dq, 0, 0, 0);
+    if (m16 < 4) {
+      if (2 * r < GQ) L.qz[m16][2 * r] = Dq[0] + Dq[1];
+      if (2 * r + 1 < GQ) L.qz[m16][(2 * r + 1) % GQ] = Dq[2] + Dq[3];
+    }
+  }
+  // ---- scores ------------------------------------------------------------------------------------
+  const float post_k = __builtin_amdgcn_exp2f((float)(24 - kShK));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    half8 aq[4];
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) aq[cb] = lds_operand(L.k.aop[i][arow], cb * 64 + r * 16);
+#pragma unroll
+    for (int th = 0; th < 2; ++th) {
+      float4v D = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb)
+        D = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq[cb], field_operand<BITS>(R.kc[i], 4 * th + cb), D, 0, 0, 0);
+      const int tl = i * 32 + th * 16 + m16;
+      if (2 * r < GQ) L.sc[2 * r][tl] = (D[0] + D[1]) * post_k;
+      if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][tl] = (D[2] + D[3]) * post_k;
+    }
+  }
+  if (more) load_codes<BITS>(R.kc, a.k_codes, a, u, mc_next, lane);
+  wave_sync();                          // scores visible; every read of the score-phase rows is done
+
+  // ---- softmax numerators of the 128 tokens against the running maximum; operand rows ---------------
+  {
+    const int bi = lane >> 4;                         // block of this lane's tokens (2*lane, 2*lane+1)
+    const uint32_t mword = R.mkw;
+    const int bit = (2 * lane) & 31;
+    const bool ok0 = !((mword >> bit) & 1u);
+    const bool ok1 = !((mword >> (bit + 1)) & 1u);
+    const float fv = __builtin_amdgcn_exp2f((float)(kShV - pair_pos<BITS>(lane & 3)));
+    float alpha[GQ];
+    bool rescale = false;
+#pragma unroll
+    for (int j = 0; j < GQ; ++j) {
+      const float2 s2 = *(const float2*)&L.sc[j][2 * lane];
+      const float qz = L.qz[bi][j];
+      const float x0 = ok0 ? s2.x + qz : kNegBig;
+      const float x1 = ok1 ? s2.y + qz : kNegBig;
+      const float mc = wave_max(fmaxf(x0, x1));
+      const float m = fmaxf(S.m[j], mc);
+      alpha[j] = __builtin_amdgcn_exp2f(S.m[j] - m);
+      rescale |= m > S.m[j];
+      S.m[j] = m;
+      const float p0 = ok0 ? __builtin_amdgcn_exp2f(x0 - m) : 0.f;
+      const float p1 = ok1 ? __builtin_amdgcn_exp2f(x1 - m) : 0.f;
+      uint32_t hi, lo;
+      split_pair(p0, p1, hi, lo);
+      ((uint32_t*)L.v.pp[2 * j])[lane] = hi;
+      ((uint32_t*)L.v.pp[2 * j + 1])[lane] = lo;
+      const float p0f = p0 * fv, p1f = p1 * fv;
+#pragma unroll
+      for (int jv = 0; jv < NV; ++jv) {
+        split_pair(p0f * h2f_bits(R.vsp[jv] & 0xFFFFu), p1f * h2f_bits(R.vsp[jv] >> 16), hi, lo);
+        ((uint32_t*)L.v.ps[jv][2 * j])[lane] = hi;
+        ((uint32_t*)L.v.ps[jv][2 * j + 1])[lane] = lo;
+      }
+    }
+#pragma unroll
+    for (int jv = 0; jv < NV; ++jv) ((uint32_t*)L.v.zv[jv])[lane] = R.vsz[jv];
+    ((uint32_t*)L.v.zv[NV])[lane] = 0x3C003C00u;      // fp16 ones
+    if (more) load_v_meta<BITS, NV>(R, a, u, mc_next, lane);
+    // the running maximum moved (wave-uniform, rare after the first mini-chunks): rescale
+    if (rescale) {
+      float a0 = 1.f, a1 = 1.f;
+#pragma unroll
+      for (int j = 0; j < GQ; ++j) {
+        a0 = (j == 2 * r) ? alpha[j] : a0;
+        a1 = (j == 2 * r + 1) ? alpha[j] : a1;
+      }
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) {
+        S.O[ct][0] *= a0;
+        S.O[ct][1] *= a0;
+        S.O[ct][2] *= a1;
+        S.O[ct][3] *= a1;
+      }
+      S.Dz[0] *= a0;
+      S.Dz[1] *= a0;
+      S.Dz[2] *= a1;
+      S.Dz[3] *= a1;
+    }
+  }
+  wave_sync();
+
+  // ---- weighted values; sum_t p_t z_t and sum_t p_t ride along as one more product -------------------
+  const int zrow = m16 < NV ? m16 : NV;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    S.Dz = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.v.pp[arow], i * 64 + r * 16),
+                                                  lds_operand(L.v.zv[zrow], i * 64 + r * 16), S.Dz, 0, 0, 0);
+    half8 ap[NV];
+#pragma unroll
+    for (int jv = 0; jv < NV; ++jv) ap[jv] = lds_operand(L.v.ps[jv][arow], i * 64 + r * 16);
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct)
+      S.O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ap[ct * NV / 8], field_operand<BITS>(R.vc[i], ct), S.O[ct], 0, 0, 0);
+  }
+  if (more) load_codes<BITS>(R.vc, a.v_codes, a, u, mc_next, lane);
+}
+
+// grid (splits_q + splits_fp, kv_heads, batch), 256 threads
+template <int GQ, int BITS, int NV>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) decode_kernel(DecodeArgs a) {
   __shared__ __align__(16) DecodeLds<GQ, NV> lds;
+  __shared__ int s_last;
   const Dims& d = a.d;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int m16 = lane & 15, r = lane >> 4;
-  const int chunk = blockIdx.x;
+  const int split = blockIdx.x;
   const int h = blockIdx.y, b = blockIdx.z;
   const int ul = b * d.kv_heads + h;
   const int64_t u = d.unit0 + ul;
   const float qscale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
-  constexpr int R2 = 2 * GQ;                  // operand rows in use
-  const int arow = m16 % R2;                  // rows beyond 2*GQ repeat valid rows (their results are unused)
+  constexpr int R2 = 2 * GQ;
+  const int arow = m16 % R2;
   WaveLds<GQ, NV>& L = lds.w[wave];
   const __half* qbase = a.q + ((int64_t)b * d.q_heads + (int64_t)h * GQ) * kHeadDim;
-  float* part = a.partials + ((int64_t)ul * (a.chunks_q + a.chunks_fp) + chunk) * GQ * (kHeadDim + 2);
+  const int n_splits = a.splits_q + a.splits_fp;
 
   // this lane's two channels (2*lane, 2*lane+1) of every query head, log2-domain scaled
   float qa[GQ][2];
@@ -182,195 +392,61 @@ __global__ void __launch_bounds__(256) decode_partial_kernel(DecodeArgs a) {
     qa[j][1] = h2f_bits(w2 >> 16) * qscale;
   }
 
-  if (chunk < a.chunks_q) {
-    // =================================== quantized chunk ===================================
-    const int nblocks = a.n_quant >> 5;
-    const int blk0 = chunk * (kChunkTokens / 32) + wave * 4;          // first block of this wave
-    // Blocks past the end are replaced by the last block with every token masked, so that all
-    // waves run the same straight-line code.
-    int blk[4];
-    uint32_t mk[4];
-    uint4 kc[4][BITS / 2], vc[4][BITS / 2];
-    uint32_t ksp[4];                                                  // this lane's two Key steps
-    const unsigned char* kmeta_g[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const bool ok = blk0 + i < nblocks;
-      blk[i] = min(blk0 + i, nblocks - 1);
-      const int64_t gb = u * d.blocks_per_unit + blk[i];
-      const uint4* kp = (const uint4*)(a.k_codes + gb * d.block_bytes) + lane;
-      const uint4* vp = (const uint4*)(a.v_codes + gb * d.block_bytes) + lane;
-#pragma unroll
-      for (int hf = 0; hf < BITS / 2; ++hf) {
-        kc[i][hf] = kp[hf * 64];
-        vc[i][hf] = vp[hf * 64];
-      }
-      kmeta_g[i] = (const unsigned char*)(a.k_meta + (u * d.groups_per_unit + (blk[i] >> d.bpg_shift)) * kHeadDim);
-      ksp[i] = ((const uint32_t*)kmeta_g[i])[lane];
-      const uint32_t mw_ = a.mask[gb];
-      mk[i] = ok ? mw_ : 0xFFFFFFFFu;
-    }
-    // Value steps of this lane's two tokens (pair lane&15 of block lane>>4): NV dwords (s_t0, s_t1)
-    uint32_t vsp[NV];
-    const unsigned char* vmeta_b[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      vmeta_b[i] = (const unsigned char*)a.v_meta + (u * d.blocks_per_unit + blk[i]) * (int64_t)(128 * NV);
-    {
-      const int bi = lane >> 4;
-      const unsigned char* vb = bi == 0 ? vmeta_b[0] : (bi == 1 ? vmeta_b[1] : (bi == 2 ? vmeta_b[2] : vmeta_b[3]));
-      const uint32_t* p = (const uint32_t*)(vb + (lane & 15) * 4 * NV);
-#pragma unroll
-      for (int jv = 0; jv < NV; ++jv) vsp[jv] = p[jv];
-    }
+  if (split < a.splits_q) {
+    // =================================== quantized workgroup ===================================
+    const int n_mc = (a.n_quant + kMiniChunk - 1) / kMiniChunk;
+    const int mc_end = min(n_mc, (split + 1) * a.mc_per_split);
+    int mc = split * a.mc_per_split + wave;
 
-    // ---- q rows (hi/lo, no step) -> sum_c q_c z_c of the 4 blocks in one pass: column n of the
-    //      B operand is the zero plane of block n's group -----------------------------------------
+    WaveAcc<GQ> S;
 #pragma unroll
-    for (int j = 0; j < GQ; ++j) {
-      uint32_t hi, lo;
-      split_pair(qa[j][0], qa[j][1], hi, lo);
-      ((uint32_t*)L.aop[2 * j])[lane] = hi;
-      ((uint32_t*)L.aop[2 * j + 1])[lane] = lo;
-    }
-    wave_sync();
-    {
-      float4v Dq = {0.f, 0.f, 0.f, 0.f};
-      const unsigned char* zg = m16 == 0 ? kmeta_g[0] : (m16 == 1 ? kmeta_g[1] : (m16 == 2 ? kmeta_g[2] : kmeta_g[3]));
+    for (int ct = 0; ct < 8; ++ct) S.O[ct] = float4v{0.f, 0.f, 0.f, 0.f};
+    S.Dz = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int cb = 0; cb < 4; ++cb) {
-        const uint4 zz = m16 < 4 ? *(const uint4*)(zg + 256 + cb * 64 + r * 16) : uint4{0, 0, 0, 0};
-        Dq = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.aop[arow], cb * 64 + r * 16),
-                                                    __builtin_bit_cast(half8, zz), Dq, 0, 0, 0);
-      }
-      if (m16 < 4) {
-        if (2 * r < GQ) L.qz[m16][2 * r] = Dq[0] + Dq[1];
-        if (2 * r + 1 < GQ) L.qz[m16][(2 * r + 1) % GQ] = Dq[2] + Dq[3];
-      }
-    }
+    for (int j = 0; j < GQ; ++j) S.m[j] = kNegBig;
 
-    // ---- scores of the wave's 4 blocks ------------------------------------------------------------
-    const float post_k = __builtin_amdgcn_exp2f((float)(24 - kShK));
-    {
-      const float fs = __builtin_amdgcn_exp2f((float)(kShK - pair_pos<BITS>(lane & 3)));
+    if (mc < mc_end) {
+      McRegs<BITS, NV> R;
+      load_k_meta<BITS, NV>(R, a, u, mc, lane);
+      load_codes<BITS>(R.kc, a.k_codes, a, u, mc, lane);
+      load_v_meta<BITS, NV>(R, a, u, mc, lane);
+      load_codes<BITS>(R.vc, a.v_codes, a, u, mc, lane);
       float qaf[GQ][2];
+      const float fs = __builtin_amdgcn_exp2f((float)(kShK - pair_pos<BITS>(lane & 3)));
 #pragma unroll
       for (int j = 0; j < GQ; ++j) {
         qaf[j][0] = qa[j][0] * fs;
         qaf[j][1] = qa[j][1] * fs;
       }
-      half8 aq[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        if ((i & ((1 << d.bpg_shift) - 1)) == 0) {      // first block of a Key group: new q*step rows
-          const float s0 = h2f_bits(ksp[i] & 0xFFFFu), s1 = h2f_bits(ksp[i] >> 16);
-          wave_sync();                                   // earlier reads of aop are done
-#pragma unroll
-          for (int j = 0; j < GQ; ++j) {
-            uint32_t hi, lo;
-            split_pair(qaf[j][0] * s0, qaf[j][1] * s1, hi, lo);
-            ((uint32_t*)L.aop[2 * j])[lane] = hi;
-            ((uint32_t*)L.aop[2 * j + 1])[lane] = lo;
-          }
-          wave_sync();
-#pragma unroll
-          for (int cb = 0; cb < 4; ++cb) aq[cb] = lds_operand(L.aop[arow], cb * 64 + r * 16);
-        }
-#pragma unroll
-        for (int th = 0; th < 2; ++th) {
-          float4v D = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int cb = 0; cb < 4; ++cb)
-            D = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq[cb], field_operand<BITS>(kc[i], 4 * th + cb), D, 0, 0, 0);
-          const int tl = i * 32 + th * 16 + m16;
-          if (2 * r < GQ) L.sc[2 * r][tl] = (D[0] + D[1]) * post_k;
-          if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][tl] = (D[2] + D[3]) * post_k;
-        }
-      }
-    }
-    wave_sync();
-
-    // ---- softmax numerators of the wave's 128 tokens; p and p*step operand rows ----------------
-    float mw[GQ];
-    {
-      const int bi = lane >> 4;                         // block of this lane's tokens (2*lane, 2*lane+1)
-      const uint32_t mword = bi == 0 ? mk[0] : (bi == 1 ? mk[1] : (bi == 2 ? mk[2] : mk[3]));
-      const int bit = (2 * lane) & 31;
-      const bool ok0 = !((mword >> bit) & 1u);
-      const bool ok1 = !((mword >> (bit + 1)) & 1u);
-      const float fv = __builtin_amdgcn_exp2f((float)(kShV - pair_pos<BITS>(lane & 3)));
-#pragma unroll
-      for (int j = 0; j < GQ; ++j) {
-        const float2 s2 = *(const float2*)&L.sc[j][2 * lane];
-        const float qz = L.qz[bi][j];
-        const float x0 = ok0 ? s2.x + qz : kNegBig;
-        const float x1 = ok1 ? s2.y + qz : kNegBig;
-        const float m = wave_max(fmaxf(x0, x1));
-        const float p0 = ok0 ? __builtin_amdgcn_exp2f(x0 - m) : 0.f;
-        const float p1 = ok1 ? __builtin_amdgcn_exp2f(x1 - m) : 0.f;
-        mw[j] = m;
-        uint32_t hi, lo;
-        split_pair(p0, p1, hi, lo);
-        ((uint32_t*)L.pp[2 * j])[lane] = hi;
-        ((uint32_t*)L.pp[2 * j + 1])[lane] = lo;
-        const float p0f = p0 * fv, p1f = p1 * fv;
-#pragma unroll
-        for (int jv = 0; jv < NV; ++jv) {
-          split_pair(p0f * h2f_bits(vsp[jv] & 0xFFFFu), p1f * h2f_bits(vsp[jv] >> 16), hi, lo);
-          ((uint32_t*)L.ps[jv][2 * j])[lane] = hi;
-          ((uint32_t*)L.ps[jv][2 * j + 1])[lane] = lo;
-        }
-      }
-    }
-    wave_sync();
-
-    // ---- weighted values; sum_t p_t z_t and sum_t p_t ride along as one more product ---------------
-    float4v O[8];
-#pragma unroll
-    for (int ct = 0; ct < 8; ++ct) O[ct] = float4v{0.f, 0.f, 0.f, 0.f};
-    float4v Dz = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      // B operand of the side product: column n < NV = zeros of value group n (8 tokens 8r..8r+7),
-      // column NV = ones, other columns 0
-      const uint4 zz = m16 < NV ? *(const uint4*)(vmeta_b[i] + 64 * NV + m16 * 64 + r * 16)
-                                : (m16 == NV ? uint4{0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u}
-                                             : uint4{0, 0, 0, 0});
-      Dz = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.pp[arow], i * 64 + r * 16),
-                                                  __builtin_bit_cast(half8, zz), Dz, 0, 0, 0);
-      half8 ap[NV];
-#pragma unroll
-      for (int jv = 0; jv < NV; ++jv) ap[jv] = lds_operand(L.ps[jv][arow], i * 64 + r * 16);
-#pragma unroll
-      for (int ct = 0; ct < 8; ++ct)
-        O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ap[ct * NV / 8], field_operand<BITS>(vc[i], ct), O[ct], 0, 0, 0);
+      for (; mc < mc_end; mc += 4)
+        compute_minichunk<GQ, BITS, NV>(R, S, L, qa, qaf, lane, a, u, mc + 4, mc + 4 < mc_end);
     }
     const float post_v = __builtin_amdgcn_exp2f((float)(24 - kShV));
 
-    // ---- hand the wave's result to the merge buffer --------------------------------------------------
+    // ---- hand the wave's result to the merge buffer ------------------------------------------------
     __syncthreads();                                     // every wave is done with its WaveLds
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj) {
       const int j = 2 * r + jj;
       if (j < GQ) {
 #pragma unroll
-        for (int ct = 0; ct < 8; ++ct) lds.mg.o[wave][j % GQ][16 * ct + m16] = (O[ct][2 * jj] + O[ct][2 * jj + 1]) * post_v;
-        const float zsum = Dz[2 * jj] + Dz[2 * jj + 1];
+        for (int ct = 0; ct < 8; ++ct)
+          lds.mg.o[wave][j % GQ][16 * ct + m16] = (S.O[ct][2 * jj] + S.O[ct][2 * jj + 1]) * post_v;
+        const float zsum = S.Dz[2 * jj] + S.Dz[2 * jj + 1];
         if (m16 < NV) lds.mg.z[wave][j % GQ][m16 % NV] = zsum;
         if (m16 == NV) lds.mg.l[wave][j % GQ] = zsum;
       }
     }
     if (lane == 0) {
 #pragma unroll
-      for (int j = 0; j < GQ; ++j) lds.mg.m[wave][j] = mw[j];
+      for (int j = 0; j < GQ; ++j) lds.mg.m[wave][j] = S.m[j];
     }
-    merge_and_store<GQ, NV>(lds.mg, part, tid);
   } else {
-    // ============================== full-precision chunk ===============================
+    // ============================== full-precision workgroup ===============================
     // 64 rows per workgroup, 16 per wavefront: residual ring rows, then pool slots, then
     // auxiliary slots.  q.k^T on the matrix cores (K rows are the B operand as they are);
     // the weighted values on the vector units (row-major V has the wrong operand shape).
-    const int row0 = (chunk - a.chunks_q) * kFpChunkRows + wave * 16;
+    const int row0 = (split - a.splits_q) * kFpChunkRows + wave * 16;
     const int n_pool = a.pool_count[u], n_aux = a.aux_count[u];
     // Row index -> element offset of the row inside (k_res | pool_k), or -1 for an empty slot.
     // Branch-free so that all 16 + 4 loads of the wave are issued before anything is waited on.
@@ -404,14 +480,14 @@ __global__ void __launch_bounds__(256) decode_partial_kernel(DecodeArgs a) {
     for (int j = 0; j < GQ; ++j) {
       uint32_t hi, lo;
       split_pair(qa[j][0], qa[j][1], hi, lo);
-      ((uint32_t*)L.aop[2 * j])[lane] = hi;
-      ((uint32_t*)L.aop[2 * j + 1])[lane] = lo;
+      ((uint32_t*)L.k.q0[2 * j])[lane] = hi;
+      ((uint32_t*)L.k.q0[2 * j + 1])[lane] = lo;
     }
     wave_sync();
     float4v D = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
-      D = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.aop[arow], cb * 64 + r * 16),
+      D = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.k.q0[arow], cb * 64 + r * 16),
                                                   __builtin_bit_cast(half8, kf[cb]), D, 0, 0, 0);
     if (2 * r < GQ) L.sc[2 * r][m16] = D[0] + D[1];
     if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][m16] = D[2] + D[3];
@@ -453,59 +529,89 @@ __global__ void __launch_bounds__(256) decode_partial_kernel(DecodeArgs a) {
         lds.mg.l[wave][j] = lw[j];
       }
     }
-    merge_and_store<GQ, NV>(lds.mg, part, tid);
   }
-}
 
-// grid (g, units_per_layer), 128 threads: merge chunk partials of one query head.
-__global__ void __launch_bounds__(128) decode_combine_kernel(DecodeArgs a) {
-  const Dims& d = a.d;
-  const int j = blockIdx.x, ul = blockIdx.y, c = threadIdx.x;
-  const int b = ul / d.kv_heads, h = ul - b * d.kv_heads;
-  const int n_chunks = a.chunks_q + a.chunks_fp;
-  const float* part = a.partials + (int64_t)ul * n_chunks * d.g * (kHeadDim + 2) + j * (kHeadDim + 2);
-  const int64_t stride = (int64_t)d.g * (kHeadDim + 2);
-  float m = kNegBig;
-  for (int i = 0; i < n_chunks; ++i) m = fmaxf(m, part[i * stride]);
-  float l = 0.f, o = 0.f;
-  for (int i = 0; i < n_chunks; ++i) {
-    const float w = exp2f(part[i * stride] - m);
-    l += part[i * stride + 1] * w;
-    o += part[i * stride + 2 + c] * w;
+  // ---- merge the 4 wavefronts and write this workgroup's partial ---------------------------------------
+  __syncthreads();
+  float* part = a.partials + ((int64_t)ul * n_splits + split) * GQ * (kHeadDim + 2);
+  for (int i = tid; i < GQ * kHeadDim; i += 256) {
+    const int j = i / kHeadDim, c = i % kHeadDim;
+    const int jv = c / (kHeadDim / NV);
+    const float m = fmaxf(fmaxf(lds.mg.m[0][j], lds.mg.m[1][j]), fmaxf(lds.mg.m[2][j], lds.mg.m[3][j]));
+    float o = 0.f, l = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float f = __builtin_amdgcn_exp2f(lds.mg.m[w][j] - m);
+      o += (lds.mg.o[w][j][c] + lds.mg.z[w][j][jv]) * f;
+      l += lds.mg.l[w][j] * f;
+    }
+    coherent_store(&part[j * (kHeadDim + 2) + 2 + c], o);
+    if (c == 0) {
+      coherent_store(&part[j * (kHeadDim + 2) + 0], m);
+      coherent_store(&part[j * (kHeadDim + 2) + 1], l);
+    }
   }
-  a.out[((int64_t)b * d.q_heads + h * d.g + j) * kHeadDim + c] = __float2half_rn(o / l);
+
+  // ---- the last workgroup of the unit to arrive merges the unit's partials ---------------------------
+  // Partials and the counter are accessed with device-scope atomic operations (they go to the
+  // point where the compute dies' L2 caches agree), so no cache write-back or invalidate is
+  // needed; the fences below only wait for this thread's own stores and keep the order.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+  if (tid == 0) {
+    const int old = __hip_atomic_fetch_add(&a.counters[ul], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (old == n_splits - 1);
+  }
+  __syncthreads();
+  if (s_last) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    const float* pu = a.partials + (int64_t)ul * n_splits * GQ * (kHeadDim + 2);
+    for (int i = tid; i < GQ * kHeadDim; i += 256) {
+      const int j = i / kHeadDim, c = i % kHeadDim;
+      const float* pj = pu + j * (kHeadDim + 2);
+      float m = kNegBig;
+      for (int s = 0; s < n_splits; ++s) m = fmaxf(m, coherent_load(&pj[(int64_t)s * GQ * (kHeadDim + 2)]));
+      float l = 0.f, o = 0.f;
+      for (int s = 0; s < n_splits; ++s) {
+        const float* ps = pj + (int64_t)s * GQ * (kHeadDim + 2);
+        const float w = __builtin_amdgcn_exp2f(coherent_load(&ps[0]) - m);
+        l += coherent_load(&ps[1]) * w;
+        o += coherent_load(&ps[2 + c]) * w;
+      }
+      a.out[((int64_t)b * d.q_heads + h * GQ + j) * kHeadDim + c] = __float2half_rn(o / l);
+    }
+    if (tid == 0)                                        // leave the counter as it was found
+      __hip_atomic_store(&a.counters[ul], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 
 template <int GQ, int BITS>
-void launch_partial_nv(const DecodeArgs& a, dim3 grid, hipStream_t s) {
+void launch_nv(const DecodeArgs& a, dim3 grid, hipStream_t s) {
   switch (a.d.vgroups) {
-    case 4: hipLaunchKernelGGL((decode_partial_kernel<GQ, BITS, 4>), grid, dim3(256), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((decode_partial_kernel<GQ, BITS, 2>), grid, dim3(256), 0, s, a); break;
-    default: hipLaunchKernelGGL((decode_partial_kernel<GQ, BITS, 1>), grid, dim3(256), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((decode_kernel<GQ, BITS, 4>), grid, dim3(256), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((decode_kernel<GQ, BITS, 2>), grid, dim3(256), 0, s, a); break;
+    default: hipLaunchKernelGGL((decode_kernel<GQ, BITS, 1>), grid, dim3(256), 0, s, a); break;
   }
 }
 
 template <int GQ>
-void launch_partial_bits(const DecodeArgs& a, dim3 grid, hipStream_t s) {
+void launch_bits(const DecodeArgs& a, dim3 grid, hipStream_t s) {
   if (a.d.bits == 2)
-    launch_partial_nv<GQ, 2>(a, grid, s);
+    launch_nv<GQ, 2>(a, grid, s);
   else
-    launch_partial_nv<GQ, 4>(a, grid, s);
+    launch_nv<GQ, 4>(a, grid, s);
 }
 
 }  // namespace
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s) {
-  const dim3 grid(a.chunks_q + a.chunks_fp, a.d.kv_heads, a.d.batch);
+  const dim3 grid(a.splits_q + a.splits_fp, a.d.kv_heads, a.d.batch);
   switch (a.d.g) {
-    case 1: launch_partial_bits<1>(a, grid, s); break;
-    case 2: launch_partial_bits<2>(a, grid, s); break;
-    case 4: launch_partial_bits<4>(a, grid, s); break;
-    default: launch_partial_bits<8>(a, grid, s); break;
+    case 1: launch_bits<1>(a, grid, s); break;
+    case 2: launch_bits<2>(a, grid, s); break;
+    case 4: launch_bits<4>(a, grid, s); break;
+    default: launch_bits<8>(a, grid, s); break;
   }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(decode_combine_kernel, dim3(a.d.g, a.d.units_per_layer), dim3(128), 0, s, a);
   return hipGetLastError();
 }
 

@@ -130,12 +130,12 @@ __global__ void __launch_bounds__(256) quantize_kernel(Dims d, int32_t group_ind
       const uint32_t m = (uint32_t)__half_as_ushort(st) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
       svm[i] = m;
       // global layout of a 32-token block's Value meta (NV = value groups per token):
-      // fp16 step[16 token pairs][NV][2], then fp16 zero[NV][32 tokens]
+      // fp16 step[16 token pairs][NV][2], then fp16 zero[16 token pairs][NV][2]
       const int64_t tok = (int64_t)group_index * G + t;
       const int tb = (int)(tok & 31);
       __half* gm = (__half*)(v_meta + (u * d.blocks_per_unit + (tok >> 5)) * 32 * d.vgroups);
       gm[((tb >> 1) * d.vgroups + j) * 2 + (tb & 1)] = st;
-      gm[32 * d.vgroups + j * 32 + tb] = __float2half_rn(mn);
+      gm[32 * d.vgroups + ((tb >> 1) * d.vgroups + j) * 2 + (tb & 1)] = __float2half_rn(mn);
     }
   }
   __syncthreads();

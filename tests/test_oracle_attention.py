@@ -165,7 +165,7 @@ def test_packer_against_hand_computed_positions_and_bijection():
     assert vm.shape == (2, 256)
     assert vm[0, 0] == 0 and vm[0, 1] == 4 and vm[0, 2] == 1 and vm[0, 3] == 5      # pair 0: (t0,j0),(t1,j0),(t0,j1),(t1,j1)
     assert vm[0, (3 * 4 + 2) * 2 + 1] == 4 * 7 + 2                                    # token 7 = pair 3, e = 1, group 2
-    assert vm[0, 128 + 2 * 32 + 7] == -(4 * 7 + 2)                                    # zero[j=2][t=7]
-    assert vm[1, 128 + 3 * 32 + 31] == -(4 * 63 + 3)
+    assert vm[0, 128 + (3 * 4 + 2) * 2 + 1] == -(4 * 7 + 2)                           # zero of token 7, group 2
+    assert vm[1, 128 + (15 * 4 + 3) * 2 + 1] == -(4 * 63 + 3)                         # token 63 = block 1, pair 15, e = 1
     mk = np.zeros(64, bool); mk[0] = mk[33] = mk[63] = True
     assert O.mask_words(mk).tolist() == [1, (1 << 1) | (1 << 31)]
