@@ -32,25 +32,28 @@ int64_t res_rows_of(const kvq_config* c) {
 
 // Split of one unit's decode work over workgroups.  Quantized tokens go in mini-chunks of 128
 // (one wavefront each at a time); a workgroup gets at least 4 of them when there are that many.
+// Full-precision rows go in groups of 16, dealt round-robin to all wavefronts of the unit, at
+// most two groups per wavefront.
 struct Split {
-  int32_t splits_q, mc_per_split, splits_fp;
+  int32_t splits, mc_per_split;
 };
 Split decode_split(int64_t units_per_layer, int32_t n_quant, int64_t fp_rows) {
   Split s;
   const int32_t mc = (n_quant + kvq::kMiniChunk - 1) / kvq::kMiniChunk;
-  if (mc == 0) {
-    s.splits_q = 0;
-    s.mc_per_split = 0;
-  } else {
+  int32_t splits_q = 0;
+  s.mc_per_split = 0;
+  if (mc > 0) {
     int64_t want = (kvq::kTargetWorkgroups + units_per_layer - 1) / units_per_layer;
     const int64_t cap = (mc + 3) / 4;
     if (want > cap) want = cap;
     if (want < 1) want = 1;
     s.mc_per_split = (int32_t)((mc + want - 1) / want);
-    s.splits_q = (mc + s.mc_per_split - 1) / s.mc_per_split;
+    splits_q = (mc + s.mc_per_split - 1) / s.mc_per_split;
   }
-  s.splits_fp = (int32_t)((fp_rows + kvq::kFpChunkRows - 1) / kvq::kFpChunkRows);
-  if (s.splits_fp < 1) s.splits_fp = 1;
+  const int64_t groups = (fp_rows + kvq::kFpGroupRows - 1) / kvq::kFpGroupRows;
+  const int32_t splits_fp = (int32_t)((groups + 7) / 8);
+  s.splits = splits_q > splits_fp ? splits_q : splits_fp;
+  if (s.splits < 1) s.splits = 1;
   return s;
 }
 constexpr int64_t kCounterBytes(int64_t upl) { return ((upl * 4 + 255) / 256) * 256; }
@@ -126,8 +129,9 @@ int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out) {
   const int64_t mc_max = (cfg->max_seq + kvq::kMiniChunk - 1) / kvq::kMiniChunk;
   if (sq_max > (mc_max + 3) / 4) sq_max = (mc_max + 3) / 4;
   if (sq_max < 1) sq_max = 1;
-  const int64_t sfp_max = (out->res_rows + slots + kvq::kFpChunkRows - 1) / kvq::kFpChunkRows;
-  out->workspace_bytes = kCounterBytes(upl) + upl * (sq_max + sfp_max) * g * (hd + 2) * 4;
+  const int64_t sfp_max = ((out->res_rows + slots + kvq::kFpGroupRows - 1) / kvq::kFpGroupRows + 7) / 8;
+  const int64_t s_max = sq_max > sfp_max ? sq_max : sfp_max;
+  out->workspace_bytes = kCounterBytes(upl) + upl * s_max * g * (hd + 2) * 4;
   return KVQ_OK;
 }
 
@@ -220,9 +224,8 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
   a.res_start = res_start;
   a.n_res = n_res;
   const Split sp = decode_split(a.d.units_per_layer, n_quant, (int64_t)n_res + a.d.pool_slots);
-  a.splits_q = sp.splits_q;
+  a.splits = sp.splits;
   a.mc_per_split = sp.mc_per_split;
-  a.splits_fp = sp.splits_fp;
   return from_hip(kvq::launch_decode(a, (hipStream_t)stream));
 }
 

@@ -13,7 +13,7 @@ constexpr int kHeadDim = 128;      // the only head size built
 constexpr int kBlockTokens = 32;   // tokens per packed block
 constexpr int kMiniChunk = 128;     // quantized tokens one wavefront handles at a time
 constexpr int kTargetWorkgroups = 768;  // decode workgroups wanted in flight (3 per compute unit)
-constexpr int kFpChunkRows = 64;   // full-precision rows per decode workgroup
+constexpr int kFpGroupRows = 16;   // full-precision rows one wavefront handles at a time
 constexpr float kNegBig = -1.0e30f;
 
 // Everything a kernel needs to find a unit's data, derived once on the host.
@@ -45,12 +45,11 @@ struct DecodeArgs {
   const int32_t* pool_count;
   const int32_t* aux_count;
   __half* out;
-  float* partials;      // [units_per_layer][splits_q + splits_fp][g][head_dim + 2]
+  float* partials;      // [units_per_layer][splits][g][head_dim + 2]
   int32_t* counters;    // [units_per_layer], zero on entry and on exit
   int32_t n_quant, res_start, n_res;
-  int32_t splits_q;     // workgroups per unit over the quantized segment
-  int32_t mc_per_split; // 128-token mini-chunks per such workgroup
-  int32_t splits_fp;    // workgroups per unit over the residual + pool rows
+  int32_t splits;       // workgroups per unit
+  int32_t mc_per_split; // 128-token mini-chunks of the quantized segment per workgroup
 };
 
 hipError_t launch_append(const Dims& d, const __half* k_new, const __half* v_new, __half* k_res, __half* v_res,

@@ -5,9 +5,10 @@
 // mini-chunks of 128 tokens (4 packed blocks).  A "quantized" workgroup owns a contiguous range
 // of mini-chunks; its 4 wavefronts take them round-robin, each keeping a running (max, sum,
 // weighted values) and loading its next mini-chunk into registers while it computes the current
-// one.  "Full-precision" workgroups take 64 rows of residual / pool / auxiliary pool each.  Every
-// workgroup merges its 4 wavefronts through LDS into one partial; the last workgroup of a unit to
-// arrive (per-unit counter) merges the partials and writes the fp16 output.
+// one.  The full-precision rows (residual ring, outlier pool, auxiliary pool) are dealt to the same
+// wavefronts in groups of 16 and are processed first, while the first quantized loads are in
+// flight.  Every workgroup merges its wavefronts' results through LDS into one partial; the last
+// workgroup of a unit to arrive (per-unit counter) merges the partials and writes the fp16 output.
 //
 // Arithmetic: every contraction runs on the matrix cores (v_mfma_f32_16x16x32_f16).
 //  * q.K^T:  A = q * step, split in fp16 hi + lo rows (two matrix rows per query head, so the
@@ -147,11 +148,13 @@ struct WaveLds {
   float qz[4][GQ];                                // sum_c q_c z_c per (block, head)
 };
 
+// Results handed to the workgroup merge: slots 0..3 = the wavefronts' quantized parts,
+// slots 4..7 = their full-precision parts.
 template <int GQ, int NV>
 struct MergeLds {
-  float m[4][GQ], l[4][GQ];
-  float z[4][GQ][NV];                             // sum_t p_t z_t per value group
-  float o[4][GQ][kHeadDim];
+  float m[8][GQ], l[8][GQ];
+  float z[4][GQ][NV];                             // sum_t p_t z_t per value group (quantized parts)
+  float o[8][GQ][kHeadDim];
 };
 
 template <int GQ, int NV>
@@ -160,32 +163,43 @@ union DecodeLds {
   MergeLds<GQ, NV> mg;
 };
 
+// Uniform (per wavefront) base pointers of the unit's quantized cache; loads add 32-bit offsets.
+struct UnitPtrs {
+  const unsigned char* kc;    // Key codes
+  const unsigned char* vc;    // Value codes
+  const unsigned char* km;    // Key meta
+  const unsigned char* vm;    // Value meta
+  const unsigned char* mask;
+  int nblocks;                // quantized blocks of the unit
+  int bpg_shift;
+  uint32_t block_bytes;
+};
+template <typename T>
+__device__ __forceinline__ T ld(const unsigned char* base, uint32_t off) {
+  return *(const T*)(base + off);
+}
+
 // Loads of one mini-chunk, in the four parts the compute phases consume.  A block past the end of
 // the quantized segment is replaced by the last block with every token masked, so that every
 // wave runs the same straight-line code.
-__device__ __forceinline__ int clamp_block(const DecodeArgs& a, int mc, int i) {
-  return min(mc * 4 + i, (a.n_quant >> 5) - 1);
-}
 template <int BITS, int NV>
-__device__ __forceinline__ void load_k_meta(McRegs<BITS, NV>& R, const DecodeArgs& a, int64_t u, int mc, int lane) {
+__device__ __forceinline__ void load_k_meta(McRegs<BITS, NV>& R, const UnitPtrs& P, int mc, int lane) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int blk = clamp_block(a, mc, i);
-    const uint32_t* km = a.k_meta + (u * a.d.groups_per_unit + (blk >> a.d.bpg_shift)) * kHeadDim;
-    R.ksp[i] = km[lane];
-    R.ksz[i] = km[64 + lane];
+    const uint32_t g = (uint32_t)min(mc * 4 + i, P.nblocks - 1) >> P.bpg_shift;
+    R.ksp[i] = ld<uint32_t>(P.km, g * 512u + lane * 4u);
+    R.ksz[i] = ld<uint32_t>(P.km, g * 512u + 256u + lane * 4u);
   }
 }
 template <int BITS>
-__device__ __forceinline__ void load_codes(uint32_t (&w)[4][2 * BITS], const uint8_t* codes, const DecodeArgs& a,
-                                           int64_t u, int mc, int lane) {
+__device__ __forceinline__ void load_codes(uint32_t (&w)[4][2 * BITS], const unsigned char* codes, const UnitPtrs& P,
+                                           int mc, int lane) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int64_t gb = u * a.d.blocks_per_unit + clamp_block(a, mc, i);
-    const uint4* p = (const uint4*)(codes + gb * a.d.block_bytes) + lane;
+    const uint32_t off = (uint32_t)min(mc * 4 + i, P.nblocks - 1) * P.block_bytes + lane * 16u;
 #pragma unroll
     for (int hf = 0; hf < BITS / 2; ++hf) {
-      const uint4 t = p[hf * 64];
+      const uint4 t = ld<uint4>(codes, off + hf * 1024u);
       w[i][4 * hf + 0] = t.x;
       w[i][4 * hf + 1] = t.y;
       w[i][4 * hf + 2] = t.z;
@@ -194,18 +208,17 @@ __device__ __forceinline__ void load_codes(uint32_t (&w)[4][2 * BITS], const uin
   }
 }
 template <int BITS, int NV>
-__device__ __forceinline__ void load_v_meta(McRegs<BITS, NV>& R, const DecodeArgs& a, int64_t u, int mc, int lane) {
-  const int nblocks = a.n_quant >> 5;
+__device__ __forceinline__ void load_v_meta(McRegs<BITS, NV>& R, const UnitPtrs& P, int mc, int lane) {
   // this lane's tokens are 2*lane, 2*lane+1 of the 128: pair lane&15 of block lane>>4
   const int myblk = mc * 4 + (lane >> 4);
-  const int64_t gb = u * a.d.blocks_per_unit + min(myblk, nblocks - 1);
-  const uint32_t mw = a.mask[gb];
-  R.mkw = (myblk < nblocks) ? mw : 0xFFFFFFFFu;
-  const uint32_t* p = (const uint32_t*)((const unsigned char*)a.v_meta + gb * (int64_t)(128 * NV) + (lane & 15) * 4 * NV);
+  const uint32_t blk = (uint32_t)min(myblk, P.nblocks - 1);
+  const uint32_t mw = ld<uint32_t>(P.mask, blk * 4u);
+  R.mkw = (myblk < P.nblocks) ? mw : 0xFFFFFFFFu;
+  const uint32_t off = blk * (128u * NV) + (lane & 15) * (4u * NV);
 #pragma unroll
   for (int jv = 0; jv < NV; ++jv) {
-    R.vsp[jv] = p[jv];
-    R.vsz[jv] = p[16 * NV + jv];
+    R.vsp[jv] = ld<uint32_t>(P.vm, off + 4u * jv);
+    R.vsz[jv] = ld<uint32_t>(P.vm, off + 64u * NV + 4u * jv);
   }
 }
 
@@ -217,12 +230,14 @@ struct WaveAcc {
   float m[GQ];       // running maximum per head (log2 domain)
 };
 
-template <int GQ, int BITS, int NV>
+template <int GQ, int BITS, int NV, bool more>
 __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<GQ>& S, WaveLds<GQ, NV>& L,
                                                   const float (&qa)[GQ][2], const float (&qaf)[GQ][2], int lane,
-                                                  const DecodeArgs& a, int64_t u, int mc_next, bool more) {
+                                                  const UnitPtrs& P, int mc_next) {
   // Each group of registers is reloaded for the wave's next mini-chunk (mc_next, if `more`) right
   // after its last use here, so those loads are in flight during the rest of this mini-chunk.
+  // `more` is a template parameter so that every path has a fixed number of loads in flight and
+  // the waits on them can be exact.
   const int m16 = lane & 15, r = lane >> 4;
   constexpr int R2 = 2 * GQ;
   const int arow = m16 % R2;          // rows beyond 2*GQ repeat valid rows (their results are unused)
@@ -248,7 +263,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
     }
     ((uint32_t*)L.k.zk[i])[lane] = R.ksz[i];
   }
-  if (more) load_k_meta<BITS, NV>(R, a, u, mc_next, lane);
+  if (more) load_k_meta<BITS, NV>(R, P, mc_next, lane);
   wave_sync();
 
   // ---- sum_c q_c z_c of the 4 blocks: column n of B = zeros of block n & 3 --------------------------
@@ -281,7 +296,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
       if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][tl] = (D[2] + D[3]) * post_k;
     }
   }
-  if (more) load_codes<BITS>(R.kc, a.k_codes, a, u, mc_next, lane);
+  if (more) load_codes<BITS>(R.kc, P.kc, P, mc_next, lane);
   wave_sync();                          // scores visible; every read of the score-phase rows is done
 
   // ---- softmax numerators of the 128 tokens against the running maximum; operand rows ---------------
@@ -322,7 +337,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
 #pragma unroll
     for (int jv = 0; jv < NV; ++jv) ((uint32_t*)L.v.zv[jv])[lane] = R.vsz[jv];
     ((uint32_t*)L.v.zv[NV])[lane] = 0x3C003C00u;      // fp16 ones
-    if (more) load_v_meta<BITS, NV>(R, a, u, mc_next, lane);
+    if (more) load_v_meta<BITS, NV>(R, P, mc_next, lane);
     // the running maximum moved (wave-uniform, rare after the first mini-chunks): rescale
     if (rescale) {
       float a0 = 1.f, a1 = 1.f;
@@ -359,10 +374,94 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
     for (int ct = 0; ct < 8; ++ct)
       S.O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ap[ct * NV / 8], field_operand<BITS>(R.vc[i], ct), S.O[ct], 0, 0, 0);
   }
-  if (more) load_codes<BITS>(R.vc, a.v_codes, a, u, mc_next, lane);
+  if (more) load_codes<BITS>(R.vc, P.vc, P, mc_next, lane);
 }
 
-// grid (splits_q + splits_fp, kv_heads, batch), 256 threads
+// Full-precision rows (residual ring, then outlier-pool slots, then auxiliary slots) in groups of
+// 16: q.k^T on the matrix cores (a K row is a B operand as it is), the weighted values on the
+// vector units (row-major V has the wrong operand shape).  Lane = channel pair for the values.
+template <int GQ>
+struct FpAcc {
+  float m[GQ], l[GQ];
+  float o[GQ][2];
+};
+
+template <int GQ, int NV>
+__device__ __forceinline__ void fp_row_group(FpAcc<GQ>& F, WaveLds<GQ, NV>& L, const DecodeArgs& a, int64_t u,
+                                             const __half* qbase, int row0, int n_pool, int n_aux, int lane) {
+  const Dims& d = a.d;
+  const int m16 = lane & 15, r = lane >> 4;
+  constexpr int R2 = 2 * GQ;
+  const int arow = m16 % R2;
+  // Row -> pointers.  An empty slot reads the query row instead (always valid memory) and is
+  // masked afterwards, so that no load sits behind a branch.
+  const __half* kres = a.k_res + u * d.res_rows * kHeadDim;
+  const __half* vres = a.v_res + u * d.res_rows * kHeadDim;
+  const __half* kpool = a.pool_k + u * d.pool_slots * kHeadDim;
+  const __half* vpool = a.pool_v + u * d.pool_slots * kHeadDim;
+  auto locate = [&](int row, const __half*& kp, const __half*& vp) -> bool {
+    const bool in_res = row < a.n_res;
+    int ring = a.res_start + row;
+    ring -= ring >= d.res_rows ? d.res_rows : 0;
+    const int slot = row - a.n_res;
+    const bool ok = in_res || (slot < d.N ? (slot < n_pool) : (slot < d.pool_slots && slot - d.N < n_aux));
+    kp = ok ? (in_res ? kres + ring * kHeadDim : kpool + slot * kHeadDim) : qbase;
+    vp = ok ? (in_res ? vres + ring * kHeadDim : vpool + slot * kHeadDim) : qbase;
+    return ok;
+  };
+  const __half *kp, *vp_unused;
+  const bool okk = locate(row0 + m16, kp, vp_unused);
+  uint4 kf[4];
+#pragma unroll
+  for (int cb = 0; cb < 4; ++cb) kf[cb] = *(const uint4*)(kp + cb * 32 + r * 8);
+  uint32_t vw[16];
+#pragma unroll
+  for (int t = 0; t < 16; ++t) {
+    const __half *kp_unused, *vp;
+    const bool okv = locate(row0 + t, kp_unused, vp);             // uniform over the wave
+    const uint32_t w = ((const uint32_t*)vp)[lane];
+    vw[t] = okv ? w : 0u;
+  }
+  float4v D = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int cb = 0; cb < 4; ++cb)
+    D = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.k.q0[arow], cb * 64 + r * 16),
+                                                __builtin_bit_cast(half8, kf[cb]), D, 0, 0, 0);
+  wave_sync();                                                     // earlier readers of sc are done
+  if (2 * r < GQ) L.sc[2 * r][m16] = okk ? D[0] + D[1] : kNegBig;
+  if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][m16] = okk ? D[2] + D[3] : kNegBig;
+  wave_sync();
+  float alpha[GQ];
+#pragma unroll
+  for (int j = 0; j < GQ; ++j) {
+    const float x = L.sc[j][lane & 15];                            // every lane: the 16 scores, 4 times over
+    const float mg = wave_max(x);
+    const float m = fmaxf(F.m[j], mg);
+    alpha[j] = __builtin_amdgcn_exp2f(F.m[j] - m);
+    F.m[j] = m;
+    const float p = x > 0.5f * kNegBig ? __builtin_amdgcn_exp2f(x - m) : 0.f;
+    F.l[j] = F.l[j] * alpha[j] + wave_sum(lane < 16 ? p : 0.f);
+    if (lane < 16) L.sc[j][16 + lane] = p;
+  }
+  wave_sync();
+#pragma unroll
+  for (int j = 0; j < GQ; ++j) {
+    F.o[j][0] *= alpha[j];
+    F.o[j][1] *= alpha[j];
+  }
+#pragma unroll
+  for (int t = 0; t < 16; ++t) {
+    const float v0 = h2f_bits(vw[t] & 0xFFFFu), v1 = h2f_bits(vw[t] >> 16);
+#pragma unroll
+    for (int j = 0; j < GQ; ++j) {
+      const float p = L.sc[j][16 + t];
+      F.o[j][0] += p * v0;
+      F.o[j][1] += p * v1;
+    }
+  }
+}
+
+// grid (splits, kv_heads, batch), 256 threads
 template <int GQ, int BITS, int NV>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) decode_kernel(DecodeArgs a) {
   __shared__ __align__(16) DecodeLds<GQ, NV> lds;
@@ -377,11 +476,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
   const int ul = b * d.kv_heads + h;
   const int64_t u = d.unit0 + ul;
   const float qscale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
-  constexpr int R2 = 2 * GQ;
-  const int arow = m16 % R2;
   WaveLds<GQ, NV>& L = lds.w[wave];
   const __half* qbase = a.q + ((int64_t)b * d.q_heads + (int64_t)h * GQ) * kHeadDim;
-  const int n_splits = a.splits_q + a.splits_fp;
+  const int n_splits = a.splits;
 
   // this lane's two channels (2*lane, 2*lane+1) of every query head, log2-domain scaled
   float qa[GQ][2];
@@ -392,157 +489,112 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
     qa[j][1] = h2f_bits(w2 >> 16) * qscale;
   }
 
-  if (split < a.splits_q) {
-    // =================================== quantized workgroup ===================================
-    const int n_mc = (a.n_quant + kMiniChunk - 1) / kMiniChunk;
-    const int mc_end = min(n_mc, (split + 1) * a.mc_per_split);
-    int mc = split * a.mc_per_split + wave;
+  // ---- quantized part: first loads go out before anything else -----------------------------------
+  UnitPtrs P;
+  P.nblocks = a.n_quant >> 5;
+  P.bpg_shift = d.bpg_shift;
+  P.block_bytes = (uint32_t)d.block_bytes;
+  P.kc = a.k_codes + u * d.blocks_per_unit * (int64_t)d.block_bytes;
+  P.vc = a.v_codes + u * d.blocks_per_unit * (int64_t)d.block_bytes;
+  P.km = (const unsigned char*)(a.k_meta + u * d.groups_per_unit * kHeadDim);
+  P.vm = (const unsigned char*)a.v_meta + u * d.blocks_per_unit * (int64_t)(128 * NV);
+  P.mask = (const unsigned char*)(a.mask + u * d.blocks_per_unit);
+  const int n_mc = (a.n_quant + kMiniChunk - 1) / kMiniChunk;
+  const int mc_end = min(n_mc, (split + 1) * a.mc_per_split);
+  int mc = split * a.mc_per_split + wave;
+  const bool has_q = mc < mc_end;                        // uniform over the wave
+  McRegs<BITS, NV> R;
+  if (has_q) {
+    load_k_meta<BITS, NV>(R, P, mc, lane);
+    load_codes<BITS>(R.kc, P.kc, P, mc, lane);
+    load_v_meta<BITS, NV>(R, P, mc, lane);
+    load_codes<BITS>(R.vc, P.vc, P, mc, lane);
+  }
 
-    WaveAcc<GQ> S;
+  // ---- full-precision part: this wave's row groups, while the first quantized loads are in flight --
+  FpAcc<GQ> F;
 #pragma unroll
-    for (int ct = 0; ct < 8; ++ct) S.O[ct] = float4v{0.f, 0.f, 0.f, 0.f};
-    S.Dz = float4v{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int j = 0; j < GQ; ++j) S.m[j] = kNegBig;
-
-    if (mc < mc_end) {
-      McRegs<BITS, NV> R;
-      load_k_meta<BITS, NV>(R, a, u, mc, lane);
-      load_codes<BITS>(R.kc, a.k_codes, a, u, mc, lane);
-      load_v_meta<BITS, NV>(R, a, u, mc, lane);
-      load_codes<BITS>(R.vc, a.v_codes, a, u, mc, lane);
-      float qaf[GQ][2];
-      const float fs = __builtin_amdgcn_exp2f((float)(kShK - pair_pos<BITS>(lane & 3)));
+  for (int j = 0; j < GQ; ++j) {
+    F.m[j] = kNegBig;
+    F.l[j] = 0.f;
+    F.o[j][0] = F.o[j][1] = 0.f;
+  }
+  {
+    const int fp_rows = a.n_res + d.pool_slots;
+    const int n_rg = (fp_rows + 15) >> 4;
+    int rg = split * 4 + wave;
+    if (rg < n_rg) {
+      const int n_pool = a.pool_count[u], n_aux = a.aux_count[u];
 #pragma unroll
       for (int j = 0; j < GQ; ++j) {
-        qaf[j][0] = qa[j][0] * fs;
-        qaf[j][1] = qa[j][1] * fs;
+        uint32_t hi, lo;
+        split_pair(qa[j][0], qa[j][1], hi, lo);
+        ((uint32_t*)L.k.q0[2 * j])[lane] = hi;
+        ((uint32_t*)L.k.q0[2 * j + 1])[lane] = lo;
       }
-      for (; mc < mc_end; mc += 4)
-        compute_minichunk<GQ, BITS, NV>(R, S, L, qa, qaf, lane, a, u, mc + 4, mc + 4 < mc_end);
-    }
-    const float post_v = __builtin_amdgcn_exp2f((float)(24 - kShV));
-
-    // ---- hand the wave's result to the merge buffer ------------------------------------------------
-    __syncthreads();                                     // every wave is done with its WaveLds
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj) {
-      const int j = 2 * r + jj;
-      if (j < GQ) {
-#pragma unroll
-        for (int ct = 0; ct < 8; ++ct)
-          lds.mg.o[wave][j % GQ][16 * ct + m16] = (S.O[ct][2 * jj] + S.O[ct][2 * jj + 1]) * post_v;
-        const float zsum = S.Dz[2 * jj] + S.Dz[2 * jj + 1];
-        if (m16 < NV) lds.mg.z[wave][j % GQ][m16 % NV] = zsum;
-        if (m16 == NV) lds.mg.l[wave][j % GQ] = zsum;
-      }
-    }
-    if (lane == 0) {
-#pragma unroll
-      for (int j = 0; j < GQ; ++j) lds.mg.m[wave][j] = S.m[j];
-    }
-  } else {
-    // ============================== full-precision workgroup ===============================
-    // 64 rows per workgroup, 16 per wavefront: residual ring rows, then pool slots, then
-    // auxiliary slots.  q.k^T on the matrix cores (K rows are the B operand as they are);
-    // the weighted values on the vector units (row-major V has the wrong operand shape).
-    const int row0 = (split - a.splits_q) * kFpChunkRows + wave * 16;
-    const int n_pool = a.pool_count[u], n_aux = a.aux_count[u];
-    // Row index -> element offset of the row inside (k_res | pool_k), or -1 for an empty slot.
-    // Branch-free so that all 16 + 4 loads of the wave are issued before anything is waited on.
-    const int64_t res_base = u * d.res_rows, pool_base = u * d.pool_slots;
-    auto row_off = [&](int row, bool& in_res) -> int64_t {
-      in_res = row < a.n_res;
-      int ring = a.res_start + row;
-      ring -= ring >= d.res_rows ? d.res_rows : 0;
-      const int slot = row - a.n_res;
-      const bool ok = in_res || (slot < d.N ? (slot < n_pool) : (slot < d.pool_slots && slot - d.N < n_aux));
-      const int64_t off = in_res ? (res_base + ring) * kHeadDim : (pool_base + slot) * kHeadDim;
-      return ok ? off : (int64_t)-1;
-    };
-    // K row of this lane's token (row0 + m16): 4 x 16 bytes, channels 32cb + 8r ..
-    bool kres;
-    const int64_t koff = row_off(row0 + m16, kres);
-    const __half* krow = (kres ? a.k_res : a.pool_k) + (koff < 0 ? 0 : koff);
-    uint4 kf[4];
-#pragma unroll
-    for (int cb = 0; cb < 4; ++cb) kf[cb] = koff >= 0 ? *(const uint4*)(krow + cb * 32 + r * 8) : uint4{0, 0, 0, 0};
-    // V rows of the wave's 16 tokens, this lane's channel pair (2*lane, 2*lane+1)
-    uint32_t vw[16];
-#pragma unroll
-    for (int t = 0; t < 16; ++t) {
-      bool vres;
-      const int64_t voff = row_off(row0 + t, vres);                 // uniform over the wave
-      const __half* vrow = (vres ? a.v_res : a.pool_v) + (voff < 0 ? 0 : voff);
-      vw[t] = voff >= 0 ? ((const uint32_t*)vrow)[lane] : 0u;
-    }
-#pragma unroll
-    for (int j = 0; j < GQ; ++j) {
-      uint32_t hi, lo;
-      split_pair(qa[j][0], qa[j][1], hi, lo);
-      ((uint32_t*)L.k.q0[2 * j])[lane] = hi;
-      ((uint32_t*)L.k.q0[2 * j + 1])[lane] = lo;
-    }
-    wave_sync();
-    float4v D = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int cb = 0; cb < 4; ++cb)
-      D = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.k.q0[arow], cb * 64 + r * 16),
-                                                  __builtin_bit_cast(half8, kf[cb]), D, 0, 0, 0);
-    if (2 * r < GQ) L.sc[2 * r][m16] = D[0] + D[1];
-    if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][m16] = D[2] + D[3];
-    wave_sync();
-    // softmax numerators of the 16 rows (lanes 0..15 hold one row each), kept in LDS as fp32
-    const bool okrow = (koff >= 0) && lane < 16;         // for lanes 0..15, m16 == lane
-    float mw[GQ], lw[GQ];
-#pragma unroll
-    for (int j = 0; j < GQ; ++j) {
-      const float x = okrow ? L.sc[j][lane & 15] : kNegBig;
-      const float m = wave_max(x);
-      const float p = okrow ? __builtin_amdgcn_exp2f(x - m) : 0.f;
-      mw[j] = m;
-      lw[j] = wave_sum(p);
-      if (lane < 16) L.sc[j][16 + lane] = p;
-    }
-    wave_sync();
-    // weighted values: lane = channel pair (2*lane, 2*lane+1); empty slots have p = 0 and v = 0
-    float ov[GQ][2];
-#pragma unroll
-    for (int j = 0; j < GQ; ++j) ov[j][0] = ov[j][1] = 0.f;
-#pragma unroll
-    for (int t = 0; t < 16; ++t) {
-      const float v0 = h2f_bits(vw[t] & 0xFFFFu), v1 = h2f_bits(vw[t] >> 16);
-#pragma unroll
-      for (int j = 0; j < GQ; ++j) {
-        const float p = L.sc[j][16 + t];
-        ov[j][0] += p * v0;
-        ov[j][1] += p * v1;
-      }
-    }
-    __syncthreads();                                     // every wave is done with its WaveLds
-#pragma unroll
-    for (int j = 0; j < GQ; ++j) {
-      *(float2*)&lds.mg.o[wave][j][2 * lane] = float2{ov[j][0], ov[j][1]};
-      if (lane < NV) lds.mg.z[wave][j][lane % NV] = 0.f;
-      if (lane == 0) {
-        lds.mg.m[wave][j] = mw[j];
-        lds.mg.l[wave][j] = lw[j];
-      }
+      wave_sync();
+      for (; rg < n_rg; rg += 4 * n_splits) fp_row_group<GQ, NV>(F, L, a, u, qbase, rg * 16, n_pool, n_aux, lane);
     }
   }
 
-  // ---- merge the 4 wavefronts and write this workgroup's partial ---------------------------------------
+  WaveAcc<GQ> S;
+#pragma unroll
+  for (int ct = 0; ct < 8; ++ct) S.O[ct] = float4v{0.f, 0.f, 0.f, 0.f};
+  S.Dz = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int j = 0; j < GQ; ++j) S.m[j] = kNegBig;
+  if (has_q) {
+    float qaf[GQ][2];
+    const float fs = __builtin_amdgcn_exp2f((float)(kShK - pair_pos<BITS>(lane & 3)));
+#pragma unroll
+    for (int j = 0; j < GQ; ++j) {
+      qaf[j][0] = qa[j][0] * fs;
+      qaf[j][1] = qa[j][1] * fs;
+    }
+    for (; mc + 4 < mc_end; mc += 4) compute_minichunk<GQ, BITS, NV, true>(R, S, L, qa, qaf, lane, P, mc + 4);
+    compute_minichunk<GQ, BITS, NV, false>(R, S, L, qa, qaf, lane, P, mc);
+  }
+  const float post_v = __builtin_amdgcn_exp2f((float)(24 - kShV));
+
+  // ---- hand both results of the wave to the merge buffer ---------------------------------------------
+  __syncthreads();                                       // every wave is done with its WaveLds
+#pragma unroll
+  for (int jj = 0; jj < 2; ++jj) {
+    const int j = 2 * r + jj;
+    if (j < GQ) {
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct)
+        lds.mg.o[wave][j % GQ][16 * ct + m16] = (S.O[ct][2 * jj] + S.O[ct][2 * jj + 1]) * post_v;
+      const float zsum = S.Dz[2 * jj] + S.Dz[2 * jj + 1];
+      if (m16 < NV) lds.mg.z[wave][j % GQ][m16 % NV] = zsum;
+      if (m16 == NV) lds.mg.l[wave][j % GQ] = zsum;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < GQ; ++j) {
+    *(float2*)&lds.mg.o[4 + wave][j][2 * lane] = float2{F.o[j][0], F.o[j][1]};
+    if (lane == 0) {
+      lds.mg.m[wave][j] = S.m[j];
+      lds.mg.m[4 + wave][j] = F.m[j];
+      lds.mg.l[4 + wave][j] = F.l[j];
+    }
+  }
+
+  // ---- merge the 8 results and write this workgroup's partial -------------------------------------------
   __syncthreads();
   float* part = a.partials + ((int64_t)ul * n_splits + split) * GQ * (kHeadDim + 2);
   for (int i = tid; i < GQ * kHeadDim; i += 256) {
     const int j = i / kHeadDim, c = i % kHeadDim;
     const int jv = c / (kHeadDim / NV);
-    const float m = fmaxf(fmaxf(lds.mg.m[0][j], lds.mg.m[1][j]), fmaxf(lds.mg.m[2][j], lds.mg.m[3][j]));
+    float m = kNegBig;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) m = fmaxf(m, lds.mg.m[w][j]);
     float o = 0.f, l = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < 8; ++w) {
       const float f = __builtin_amdgcn_exp2f(lds.mg.m[w][j] - m);
-      o += (lds.mg.o[w][j][c] + lds.mg.z[w][j][jv]) * f;
+      const float zt = w < 4 ? lds.mg.z[w & 3][j][jv] : 0.f;
+      o += (lds.mg.o[w][j][c] + zt) * f;
       l += lds.mg.l[w][j] * f;
     }
     coherent_store(&part[j * (kHeadDim + 2) + 2 + c], o);
@@ -605,7 +657,7 @@ void launch_bits(const DecodeArgs& a, dim3 grid, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s) {
-  const dim3 grid(a.splits_q + a.splits_fp, a.d.kv_heads, a.d.batch);
+  const dim3 grid(a.splits, a.d.kv_heads, a.d.batch);
   switch (a.d.g) {
     case 1: launch_bits<1>(a, grid, s); break;
     case 2: launch_bits<2>(a, grid, s); break;
