@@ -386,15 +386,18 @@ struct FpAcc {
   float o[GQ][2];
 };
 
-template <int GQ, int NV>
-__device__ __forceinline__ void fp_row_group(FpAcc<GQ>& F, WaveLds<GQ, NV>& L, const DecodeArgs& a, int64_t u,
-                                             const __half* qbase, int row0, int n_pool, int n_aux, int lane) {
+struct FpRegs {
+  uint4 kf[4];       // K row of token row0 + (lane & 15): channels 32cb + 8(lane >> 4) ..
+  uint32_t vw[16];   // V rows of the 16 tokens: this lane's channel pair
+  bool okk;          // this lane's K row exists
+};
+
+// Issue the loads of one group of 16 full-precision rows.  An empty slot reads the query row
+// instead (always valid memory) and is masked afterwards, so that no load sits behind a branch.
+__device__ __forceinline__ void fp_load(FpRegs& X, const DecodeArgs& a, int64_t u, const __half* qbase, int row0,
+                                        int n_pool, int n_aux, int lane) {
   const Dims& d = a.d;
   const int m16 = lane & 15, r = lane >> 4;
-  constexpr int R2 = 2 * GQ;
-  const int arow = m16 % R2;
-  // Row -> pointers.  An empty slot reads the query row instead (always valid memory) and is
-  // masked afterwards, so that no load sits behind a branch.
   const __half* kres = a.k_res + u * d.res_rows * kHeadDim;
   const __half* vres = a.v_res + u * d.res_rows * kHeadDim;
   const __half* kpool = a.pool_k + u * d.pool_slots * kHeadDim;
@@ -410,26 +413,31 @@ __device__ __forceinline__ void fp_row_group(FpAcc<GQ>& F, WaveLds<GQ, NV>& L, c
     return ok;
   };
   const __half *kp, *vp_unused;
-  const bool okk = locate(row0 + m16, kp, vp_unused);
-  uint4 kf[4];
+  X.okk = locate(row0 + m16, kp, vp_unused);
 #pragma unroll
-  for (int cb = 0; cb < 4; ++cb) kf[cb] = *(const uint4*)(kp + cb * 32 + r * 8);
-  uint32_t vw[16];
+  for (int cb = 0; cb < 4; ++cb) X.kf[cb] = *(const uint4*)(kp + cb * 32 + r * 8);
 #pragma unroll
   for (int t = 0; t < 16; ++t) {
     const __half *kp_unused, *vp;
     const bool okv = locate(row0 + t, kp_unused, vp);             // uniform over the wave
     const uint32_t w = ((const uint32_t*)vp)[lane];
-    vw[t] = okv ? w : 0u;
+    X.vw[t] = okv ? w : 0u;
   }
+}
+
+template <int GQ, int NV>
+__device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, NV>& L, int lane) {
+  const int m16 = lane & 15, r = lane >> 4;
+  constexpr int R2 = 2 * GQ;
+  const int arow = m16 % R2;
   float4v D = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int cb = 0; cb < 4; ++cb)
     D = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.k.q0[arow], cb * 64 + r * 16),
-                                                __builtin_bit_cast(half8, kf[cb]), D, 0, 0, 0);
+                                                __builtin_bit_cast(half8, X.kf[cb]), D, 0, 0, 0);
   wave_sync();                                                     // earlier readers of sc are done
-  if (2 * r < GQ) L.sc[2 * r][m16] = okk ? D[0] + D[1] : kNegBig;
-  if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][m16] = okk ? D[2] + D[3] : kNegBig;
+  if (2 * r < GQ) L.sc[2 * r][m16] = X.okk ? D[0] + D[1] : kNegBig;
+  if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][m16] = X.okk ? D[2] + D[3] : kNegBig;
   wave_sync();
   float alpha[GQ];
 #pragma unroll
@@ -451,7 +459,7 @@ __device__ __forceinline__ void fp_row_group(FpAcc<GQ>& F, WaveLds<GQ, NV>& L, c
   }
 #pragma unroll
   for (int t = 0; t < 16; ++t) {
-    const float v0 = h2f_bits(vw[t] & 0xFFFFu), v1 = h2f_bits(vw[t] >> 16);
+    const float v0 = h2f_bits(X.vw[t] & 0xFFFFu), v1 = h2f_bits(X.vw[t] >> 16);
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
       const float p = L.sc[j][16 + t];
@@ -480,16 +488,24 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
   const __half* qbase = a.q + ((int64_t)b * d.q_heads + (int64_t)h * GQ) * kHeadDim;
   const int n_splits = a.splits;
 
-  // this lane's two channels (2*lane, 2*lane+1) of every query head, log2-domain scaled
-  float qa[GQ][2];
+  // Loads go out in the order their data is needed, and all of them before anything is waited
+  // on: the query, the wave's first group of full-precision rows, its first quantized mini-chunk.
+  uint32_t qw[GQ];
 #pragma unroll
-  for (int j = 0; j < GQ; ++j) {
-    const uint32_t w2 = ((const uint32_t*)(qbase + j * kHeadDim))[lane];
-    qa[j][0] = h2f_bits(w2 & 0xFFFFu) * qscale;
-    qa[j][1] = h2f_bits(w2 >> 16) * qscale;
+  for (int j = 0; j < GQ; ++j) qw[j] = ((const uint32_t*)(qbase + j * kHeadDim))[lane];
+
+  const int fp_rows = a.n_res + d.pool_slots;
+  const int n_rg = (fp_rows + 15) >> 4;
+  int rg = split * 4 + wave;
+  const bool has_fp = rg < n_rg;                         // uniform over the wave
+  int n_pool = 0, n_aux = 0;
+  FpRegs X;
+  if (has_fp) {
+    n_pool = a.pool_count[u];
+    n_aux = a.aux_count[u];
+    fp_load(X, a, u, qbase, rg * 16, n_pool, n_aux, lane);
   }
 
-  // ---- quantized part: first loads go out before anything else -----------------------------------
   UnitPtrs P;
   P.nblocks = a.n_quant >> 5;
   P.bpg_shift = d.bpg_shift;
@@ -511,7 +527,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
     load_codes<BITS>(R.vc, P.vc, P, mc, lane);
   }
 
-  // ---- full-precision part: this wave's row groups, while the first quantized loads are in flight --
+  // this lane's two channels (2*lane, 2*lane+1) of every query head, log2-domain scaled
+  float qa[GQ][2];
+#pragma unroll
+  for (int j = 0; j < GQ; ++j) {
+    qa[j][0] = h2f_bits(qw[j] & 0xFFFFu) * qscale;
+    qa[j][1] = h2f_bits(qw[j] >> 16) * qscale;
+  }
+
+  // ---- full-precision part, while the first quantized loads are in flight --------------------------
   FpAcc<GQ> F;
 #pragma unroll
   for (int j = 0; j < GQ; ++j) {
@@ -519,21 +543,19 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
     F.l[j] = 0.f;
     F.o[j][0] = F.o[j][1] = 0.f;
   }
-  {
-    const int fp_rows = a.n_res + d.pool_slots;
-    const int n_rg = (fp_rows + 15) >> 4;
-    int rg = split * 4 + wave;
-    if (rg < n_rg) {
-      const int n_pool = a.pool_count[u], n_aux = a.aux_count[u];
+  if (has_fp) {
 #pragma unroll
-      for (int j = 0; j < GQ; ++j) {
-        uint32_t hi, lo;
-        split_pair(qa[j][0], qa[j][1], hi, lo);
-        ((uint32_t*)L.k.q0[2 * j])[lane] = hi;
-        ((uint32_t*)L.k.q0[2 * j + 1])[lane] = lo;
-      }
-      wave_sync();
-      for (; rg < n_rg; rg += 4 * n_splits) fp_row_group<GQ, NV>(F, L, a, u, qbase, rg * 16, n_pool, n_aux, lane);
+    for (int j = 0; j < GQ; ++j) {
+      uint32_t hi, lo;
+      split_pair(qa[j][0], qa[j][1], hi, lo);
+      ((uint32_t*)L.k.q0[2 * j])[lane] = hi;
+      ((uint32_t*)L.k.q0[2 * j + 1])[lane] = lo;
+    }
+    wave_sync();
+    fp_compute<GQ, NV>(X, F, L, lane);
+    for (rg += 4 * n_splits; rg < n_rg; rg += 4 * n_splits) {      // further groups (short quantized segment)
+      fp_load(X, a, u, qbase, rg * 16, n_pool, n_aux, lane);
+      fp_compute<GQ, NV>(X, F, L, lane);
     }
   }
 
@@ -580,7 +602,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
     }
   }
 
-  // ---- merge the 8 results and write this workgroup's partial -------------------------------------------
+  // ---- merge the 8 results: the output itself if this workgroup is the unit's only one, else its partial
   __syncthreads();
   float* part = a.partials + ((int64_t)ul * n_splits + split) * GQ * (kHeadDim + 2);
   for (int i = tid; i < GQ * kHeadDim; i += 256) {
@@ -597,12 +619,17 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
       o += (lds.mg.o[w][j][c] + zt) * f;
       l += lds.mg.l[w][j] * f;
     }
-    coherent_store(&part[j * (kHeadDim + 2) + 2 + c], o);
-    if (c == 0) {
-      coherent_store(&part[j * (kHeadDim + 2) + 0], m);
-      coherent_store(&part[j * (kHeadDim + 2) + 1], l);
+    if (n_splits == 1) {
+      a.out[((int64_t)b * d.q_heads + h * GQ + j) * kHeadDim + c] = __float2half_rn(o / l);
+    } else {
+      coherent_store(&part[j * (kHeadDim + 2) + 2 + c], o);
+      if (c == 0) {
+        coherent_store(&part[j * (kHeadDim + 2) + 0], m);
+        coherent_store(&part[j * (kHeadDim + 2) + 1], l);
+      }
     }
   }
+  if (n_splits == 1) return;
 
   // ---- the last workgroup of the unit to arrive merges the unit's partials ---------------------------
   // Partials and the counter are accessed with device-scope atomic operations (they go to the
@@ -618,17 +645,34 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
   if (s_last) {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     const float* pu = a.partials + (int64_t)ul * n_splits * GQ * (kHeadDim + 2);
+    constexpr int kBatch = 8;                            // partials fetched per round trip
     for (int i = tid; i < GQ * kHeadDim; i += 256) {
       const int j = i / kHeadDim, c = i % kHeadDim;
       const float* pj = pu + j * (kHeadDim + 2);
-      float m = kNegBig;
-      for (int s = 0; s < n_splits; ++s) m = fmaxf(m, coherent_load(&pj[(int64_t)s * GQ * (kHeadDim + 2)]));
-      float l = 0.f, o = 0.f;
-      for (int s = 0; s < n_splits; ++s) {
-        const float* ps = pj + (int64_t)s * GQ * (kHeadDim + 2);
-        const float w = __builtin_amdgcn_exp2f(coherent_load(&ps[0]) - m);
-        l += coherent_load(&ps[1]) * w;
-        o += coherent_load(&ps[2 + c]) * w;
+      float m = kNegBig, l = 0.f, o = 0.f;
+      for (int s0 = 0; s0 < n_splits; s0 += kBatch) {
+        float pm[kBatch], pl[kBatch], po[kBatch];
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+          const int sidx = min(s0 + k, n_splits - 1);
+          const float* ps = pj + (int64_t)sidx * GQ * (kHeadDim + 2);
+          pm[k] = coherent_load(&ps[0]);
+          pl[k] = coherent_load(&ps[1]);
+          po[k] = coherent_load(&ps[2 + c]);
+        }
+        float mb = m;
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) mb = fmaxf(mb, pm[k]);
+        const float fo = __builtin_amdgcn_exp2f(m - mb);
+        l *= fo;
+        o *= fo;
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+          const float w = (s0 + k < n_splits) ? __builtin_amdgcn_exp2f(pm[k] - mb) : 0.f;
+          l += pl[k] * w;
+          o += po[k] * w;
+        }
+        m = mb;
       }
       a.out[((int64_t)b * d.q_heads + h * GQ + j) * kHeadDim + c] = __float2half_rn(o / l);
     }
