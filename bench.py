@@ -21,6 +21,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, vendor figure
+# HBM bytes per decode launch from the FETCH_SIZE / WRITE_SIZE counters, scaled by what the same
+# counters read for a plain device copy of known size (profiles/decode_kernel_<workload>.md).
+MEASURED_TRAFFIC = {"llama2_7b_4k": 121_250_000}
 
 
 def algorithmic_bytes(w, n_quant, n_res, pool_rows):
@@ -40,10 +43,12 @@ def main():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="llama2_7b_4k")
-    ap.add_argument("--cpu-units", type=int, default=16, help="units of the workload the oracle is timed on")
+    ap.add_argument("--cpu-units", type=int, default=32, help="units of the workload the oracle is timed on")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--decode-only", type=int, default=0, metavar="N",
                     help="profiling aid: after set-up run N decode-attention launches over the cache copies and exit")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="profiling aid: run 8 plain device copies of MIB MiB and exit (scales the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -56,6 +61,16 @@ def main():
     from paper_2505_10938_amd import cache as KC
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(8):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "copies": 8}))
+        return
     w = S.WORKLOADS[args.workload]
     assert w.layers == 1, "bench.py times one layer; multi-layer workloads are run layer by layer elsewhere"
     G = w.group_k
@@ -151,7 +166,7 @@ def main():
         "frac_of_hbm_peak": round((dec_bytes + quant_bytes) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "roofline": {"bound": "hbm", "kernel": "decode attention (one launch of kvq_decode_attention)",
                      "achieved": round(dec_bytes / (dec_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(dec_bytes / (dec_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(dec_bytes / (dec_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(w.name),
                      "algorithmic_bytes": int(dec_bytes), "us_per_launch": round(dec_us, 3),
                      "us_per_launch_cache_resident": round(hot_us, 3)},
         "setup_s": round(t_setup, 1),
@@ -177,7 +192,7 @@ def main():
         import copy
         ctx = threadpool_limits(limits=1) if threadpool_limits else None
         t_cpu, reps_cpu, ref = 0.0, 0, None
-        while t_cpu < 10.0 and reps_cpu < 50:
+        while t_cpu < 12.0 and reps_cpu < 400:
             sts = copy.deepcopy(states)
             t1 = time.perf_counter()
             ref = []
