@@ -30,30 +30,29 @@ int64_t res_rows_of(const kvq_config* c) {
   return G * ((c->residual + G + G - 1) / G);
 }
 
-// Split of one unit's decode work over workgroups.  Quantized tokens go in mini-chunks of 128
-// (one wavefront each at a time); a workgroup gets at least 4 of them when there are that many.
-// Full-precision rows go in groups of 16, dealt round-robin to all wavefronts of the unit, at
-// most two groups per wavefront.
+// Split of one unit's decode work over wavefronts and workgroups.  Quantized tokens go in
+// mini-chunks of 128 (one wavefront each at a time), full-precision rows in groups of 16 that cost
+// about half a mini-chunk.  About kTargetWaves wavefronts are wanted over the whole launch, no more
+// per unit than it has items; they form as few workgroups as the LDS budget and the workgroup
+// size limit allow (one workgroup per unit needs no exchange through memory).
 struct Split {
-  int32_t splits, mc_per_split;
+  int32_t splits, nw, mc_per_split;
 };
-Split decode_split(int64_t units_per_layer, int32_t n_quant, int64_t fp_rows) {
+Split decode_split(int64_t units_per_layer, int g, int vgroups, int64_t n_quant, int64_t fp_rows) {
   Split s;
-  const int32_t mc = (n_quant + kvq::kMiniChunk - 1) / kvq::kMiniChunk;
-  int32_t splits_q = 0;
-  s.mc_per_split = 0;
-  if (mc > 0) {
-    int64_t want = (kvq::kTargetWorkgroups + units_per_layer - 1) / units_per_layer;
-    const int64_t cap = (mc + 3) / 4;
-    if (want > cap) want = cap;
-    if (want < 1) want = 1;
-    s.mc_per_split = (int32_t)((mc + want - 1) / want);
-    splits_q = (mc + s.mc_per_split - 1) / s.mc_per_split;
-  }
-  const int64_t groups = (fp_rows + kvq::kFpGroupRows - 1) / kvq::kFpGroupRows;
-  const int32_t splits_fp = (int32_t)((groups + 7) / 8);
-  s.splits = splits_q > splits_fp ? splits_q : splits_fp;
-  if (s.splits < 1) s.splits = 1;
+  const int64_t mc = (n_quant + kvq::kMiniChunk - 1) / kvq::kMiniChunk;
+  const int64_t rg = (fp_rows + kvq::kFpGroupRows - 1) / kvq::kFpGroupRows;
+  int64_t items = mc + (rg + 1) / 2;
+  if (items < 1) items = 1;
+  int64_t wpu = kvq::kTargetWaves / units_per_layer;
+  if (wpu > items) wpu = items;
+  if (wpu < 1) wpu = 1;
+  int64_t nw_max = kvq::kDecodeLdsBudget / kvq::decode_wave_lds_bytes(g, vgroups);
+  if (nw_max > kvq::kMaxWavesPerGroup) nw_max = kvq::kMaxWavesPerGroup;
+  if (nw_max < 1) nw_max = 1;
+  s.splits = (int32_t)((wpu + nw_max - 1) / nw_max);
+  s.nw = (int32_t)((wpu + s.splits - 1) / s.splits);
+  s.mc_per_split = (int32_t)((mc + s.splits - 1) / s.splits);
   return s;
 }
 constexpr int64_t kCounterBytes(int64_t upl) { return ((upl * 4 + 255) / 256) * 256; }
@@ -124,13 +123,8 @@ int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out) {
   out->pool_score_bytes = units * slots * 8;
   out->counter_bytes = units * 4;
   out->selected_bytes = upl * cfg->group_k;
-  // worst case over n_quant <= max_seq: the split count never exceeds this one
-  int64_t sq_max = (kvq::kTargetWorkgroups + upl - 1) / upl;
-  const int64_t mc_max = (cfg->max_seq + kvq::kMiniChunk - 1) / kvq::kMiniChunk;
-  if (sq_max > (mc_max + 3) / 4) sq_max = (mc_max + 3) / 4;
-  if (sq_max < 1) sq_max = 1;
-  const int64_t sfp_max = ((out->res_rows + slots + kvq::kFpGroupRows - 1) / kvq::kFpGroupRows + 7) / 8;
-  const int64_t s_max = sq_max > sfp_max ? sq_max : sfp_max;
+  // the split count grows with the amount of work: the largest is the one of a full cache
+  const int64_t s_max = decode_split(upl, (int)g, (int)(hd / cfg->group_v), cfg->max_seq, out->res_rows + slots).splits;
   out->workspace_bytes = kCounterBytes(upl) + upl * s_max * g * (hd + 2) * 4;
   return KVQ_OK;
 }
@@ -223,8 +217,9 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
   a.n_quant = n_quant;
   a.res_start = res_start;
   a.n_res = n_res;
-  const Split sp = decode_split(a.d.units_per_layer, n_quant, (int64_t)n_res + a.d.pool_slots);
+  const Split sp = decode_split(a.d.units_per_layer, a.d.g, a.d.vgroups, n_quant, (int64_t)n_res + a.d.pool_slots);
   a.splits = sp.splits;
+  a.nw = sp.nw;
   a.mc_per_split = sp.mc_per_split;
   return from_hip(kvq::launch_decode(a, (hipStream_t)stream));
 }

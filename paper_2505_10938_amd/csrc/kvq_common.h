@@ -12,7 +12,9 @@ namespace kvq {
 constexpr int kHeadDim = 128;      // the only head size built
 constexpr int kBlockTokens = 32;   // tokens per packed block
 constexpr int kMiniChunk = 128;     // quantized tokens one wavefront handles at a time
-constexpr int kTargetWorkgroups = 768;  // decode workgroups wanted in flight (3 per compute unit)
+constexpr int kTargetWaves = 3072;      // decode wavefronts wanted in flight (3 per SIMD)
+constexpr int kMaxWavesPerGroup = 12;   // wavefronts of one decode workgroup at most
+constexpr int kDecodeLdsBudget = 144 * 1024;   // LDS one decode workgroup may take
 constexpr int kFpGroupRows = 16;   // full-precision rows one wavefront handles at a time
 constexpr float kNegBig = -1.0e30f;
 
@@ -49,6 +51,7 @@ struct DecodeArgs {
   int32_t* counters;    // [units_per_layer], zero on entry and on exit
   int32_t n_quant, res_start, n_res;
   int32_t splits;       // workgroups per unit
+  int32_t nw;           // wavefronts per workgroup
   int32_t mc_per_split; // 128-token mini-chunks of the quantized segment per workgroup
 };
 
@@ -59,6 +62,7 @@ hipError_t launch_trace(const Dims& d, int32_t group_index, const __half* k_grou
 hipError_t launch_quantize(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
                            int64_t unit_stride, const uint8_t* selected, const kvq_qcache& qc, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
+int decode_wave_lds_bytes(int g, int vgroups);   // LDS one decode wavefront needs
 
 // ---- packed layout ---------------------------------------------------------------------------
 // Byte offset (inside a block) of the u32 word that holds field f of lane l, and the bit

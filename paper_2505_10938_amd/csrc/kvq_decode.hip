@@ -1,14 +1,16 @@
 // Decode-step attention (Eq. 1) over the quantized cache, the residual ring and the outlier
 // pools, for gfx950.  One kernel launch per call.
 //
-// Work split: grid = (splits, kv heads, batch).  The quantized tokens of a unit are cut into
-// mini-chunks of 128 tokens (4 packed blocks).  A "quantized" workgroup owns a contiguous range
-// of mini-chunks; its 4 wavefronts take them round-robin, each keeping a running (max, sum,
-// weighted values) and loading its next mini-chunk into registers while it computes the current
-// one.  The full-precision rows (residual ring, outlier pool, auxiliary pool) are dealt to the same
-// wavefronts in groups of 16 and are processed first, while the first quantized loads are in
-// flight.  Every workgroup merges its wavefronts' results through LDS into one partial; the last
-// workgroup of a unit to arrive (per-unit counter) merges the partials and writes the fp16 output.
+// Work split: grid = (splits, kv heads, batch), 1 to 12 wavefronts per workgroup.  The quantized
+// tokens of a unit are cut into mini-chunks of 128 tokens (4 packed blocks).  A workgroup owns a
+// contiguous range of mini-chunks; its wavefronts take them round-robin, each keeping a running
+// (max, sum, weighted values) and loading its next mini-chunk into registers while it computes
+// the current one.  The full-precision rows (residual ring, outlier pool, auxiliary pool) are
+// dealt to the same wavefronts in groups of 16, starting from the wavefronts with the fewest
+// mini-chunks, and are processed first, while the first quantized loads are in flight.  Every
+// workgroup merges its wavefronts' results through LDS.  With one workgroup per unit (the usual
+// case when there are many units) that is the output; otherwise it is a partial, and the last
+// workgroup of a unit to arrive (per-unit counter) merges the partials and writes the output.
 //
 // Arithmetic: every contraction runs on the matrix cores (v_mfma_f32_16x16x32_f16).
 //  * q.K^T:  A = q * step, split in fp16 hi + lo rows (two matrix rows per query head, so the
@@ -22,6 +24,8 @@
 // subnormal inputs exactly), and the factor 2^(-2v) is folded into the other operand.
 // Scores live in the log2 domain: s = (q . k) * log2(e) / sqrt(d).
 #include "kvq_common.h"
+
+#include <type_traits>
 
 namespace kvq {
 
@@ -148,20 +152,24 @@ struct WaveLds {
   float qz[4][GQ];                                // sum_c q_c z_c per (block, head)
 };
 
-// Results handed to the workgroup merge: slots 0..3 = the wavefronts' quantized parts,
-// slots 4..7 = their full-precision parts.
+// Results handed to the workgroup merge, laid over the wavefronts' storage once they are done
+// with it: slots 0..nw-1 = the wavefronts' quantized parts, slots nw..2nw-1 = their
+// full-precision parts.
 template <int GQ, int NV>
-struct MergeLds {
-  float m[8][GQ], l[8][GQ];
-  float z[4][GQ][NV];                             // sum_t p_t z_t per value group (quantized parts)
-  float o[8][GQ][kHeadDim];
+struct MergeView {
+  float* o;   // [2 nw][GQ][kHeadDim]
+  float* m;   // [2 nw][GQ]
+  float* l;   // [2 nw][GQ]
+  float* z;   // [nw][GQ][NV]: sum_t p_t z_t per value group (quantized parts)
+  __device__ MergeView(unsigned char* base, int nw) {
+    o = (float*)base;
+    m = o + 2 * nw * GQ * kHeadDim;
+    l = m + 2 * nw * GQ;
+    z = l + 2 * nw * GQ;
+  }
 };
-
 template <int GQ, int NV>
-union DecodeLds {
-  WaveLds<GQ, NV> w[4];
-  MergeLds<GQ, NV> mg;
-};
+constexpr int merge_bytes_per_wave() { return (2 * GQ * kHeadDim + 4 * GQ + GQ * NV) * 4; }
 
 // Uniform (per wavefront) base pointers of the unit's quantized cache; loads add 32-bit offsets.
 struct UnitPtrs {
@@ -389,45 +397,53 @@ struct FpAcc {
 struct FpRegs {
   uint4 kf[4];       // K row of token row0 + (lane & 15): channels 32cb + 8(lane >> 4) ..
   uint32_t vw[16];   // V rows of the 16 tokens: this lane's channel pair
-  bool okk;          // this lane's K row exists
+  int row0;
 };
 
-// Issue the loads of one group of 16 full-precision rows.  An empty slot reads the query row
-// instead (always valid memory) and is masked afterwards, so that no load sits behind a branch.
+// Issue the loads of one group of 16 full-precision rows.  Every pool slot is read, filled or
+// not (the slot counts are looked at only when the data is used, so that these loads do not wait
+// for them); a row past the last slot reads the query row instead (always valid memory).
 __device__ __forceinline__ void fp_load(FpRegs& X, const DecodeArgs& a, int64_t u, const __half* qbase, int row0,
-                                        int n_pool, int n_aux, int lane) {
+                                        int lane) {
   const Dims& d = a.d;
   const int m16 = lane & 15, r = lane >> 4;
   const __half* kres = a.k_res + u * d.res_rows * kHeadDim;
   const __half* vres = a.v_res + u * d.res_rows * kHeadDim;
   const __half* kpool = a.pool_k + u * d.pool_slots * kHeadDim;
   const __half* vpool = a.pool_v + u * d.pool_slots * kHeadDim;
-  auto locate = [&](int row, const __half*& kp, const __half*& vp) -> bool {
+  auto locate = [&](int row, const __half*& kp, const __half*& vp) {
     const bool in_res = row < a.n_res;
     int ring = a.res_start + row;
     ring -= ring >= d.res_rows ? d.res_rows : 0;
     const int slot = row - a.n_res;
-    const bool ok = in_res || (slot < d.N ? (slot < n_pool) : (slot < d.pool_slots && slot - d.N < n_aux));
-    kp = ok ? (in_res ? kres + ring * kHeadDim : kpool + slot * kHeadDim) : qbase;
-    vp = ok ? (in_res ? vres + ring * kHeadDim : vpool + slot * kHeadDim) : qbase;
-    return ok;
+    const bool in_pool = slot < d.pool_slots;
+    kp = in_res ? kres + ring * kHeadDim : (in_pool ? kpool + slot * kHeadDim : qbase);
+    vp = in_res ? vres + ring * kHeadDim : (in_pool ? vpool + slot * kHeadDim : qbase);
   };
+  X.row0 = row0;
   const __half *kp, *vp_unused;
-  X.okk = locate(row0 + m16, kp, vp_unused);
+  locate(row0 + m16, kp, vp_unused);
 #pragma unroll
   for (int cb = 0; cb < 4; ++cb) X.kf[cb] = *(const uint4*)(kp + cb * 32 + r * 8);
 #pragma unroll
   for (int t = 0; t < 16; ++t) {
     const __half *kp_unused, *vp;
-    const bool okv = locate(row0 + t, kp_unused, vp);             // uniform over the wave
-    const uint32_t w = ((const uint32_t*)vp)[lane];
-    X.vw[t] = okv ? w : 0u;
+    locate(row0 + t, kp_unused, vp);                               // uniform over the wave
+    X.vw[t] = ((const uint32_t*)vp)[lane];
   }
 }
 
+// Does full-precision row `row` of the unit hold a token?
+__device__ __forceinline__ bool fp_row_ok(const DecodeArgs& a, int row, int n_pool, int n_aux) {
+  const int slot = row - a.n_res;
+  return row < a.n_res || (slot < a.d.N ? (slot < n_pool) : (slot < a.d.pool_slots && slot - a.d.N < n_aux));
+}
+
 template <int GQ, int NV>
-__device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, NV>& L, int lane) {
+__device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, NV>& L, const DecodeArgs& a,
+                                           int n_pool, int n_aux, int lane) {
   const int m16 = lane & 15, r = lane >> 4;
+  const bool okk = fp_row_ok(a, X.row0 + m16, n_pool, n_aux);
   constexpr int R2 = 2 * GQ;
   const int arow = m16 % R2;
   float4v D = {0.f, 0.f, 0.f, 0.f};
@@ -436,8 +452,8 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
     D = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.k.q0[arow], cb * 64 + r * 16),
                                                 __builtin_bit_cast(half8, X.kf[cb]), D, 0, 0, 0);
   wave_sync();                                                     // earlier readers of sc are done
-  if (2 * r < GQ) L.sc[2 * r][m16] = X.okk ? D[0] + D[1] : kNegBig;
-  if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][m16] = X.okk ? D[2] + D[3] : kNegBig;
+  if (2 * r < GQ) L.sc[2 * r][m16] = okk ? D[0] + D[1] : kNegBig;
+  if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][m16] = okk ? D[2] + D[3] : kNegBig;
   wave_sync();
   float alpha[GQ];
 #pragma unroll
@@ -459,7 +475,8 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
   }
 #pragma unroll
   for (int t = 0; t < 16; ++t) {
-    const float v0 = h2f_bits(X.vw[t] & 0xFFFFu), v1 = h2f_bits(X.vw[t] >> 16);
+    const uint32_t vw = fp_row_ok(a, X.row0 + t, n_pool, n_aux) ? X.vw[t] : 0u;   // uniform; an empty slot may hold anything
+    const float v0 = h2f_bits(vw & 0xFFFFu), v1 = h2f_bits(vw >> 16);
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
       const float p = L.sc[j][16 + t];
@@ -469,22 +486,26 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
   }
 }
 
-// grid (splits, kv_heads, batch), 256 threads
+// grid (splits, kv_heads, batch), 64 * a.nw threads, a.nw * sizeof(WaveLds) bytes of dynamic LDS
+constexpr int kMaxThreads = 64 * kMaxWavesPerGroup;
+
 template <int GQ, int BITS, int NV>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) decode_kernel(DecodeArgs a) {
-  __shared__ __align__(16) DecodeLds<GQ, NV> lds;
+__global__ void __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(3))) decode_kernel(DecodeArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_last;
   const Dims& d = a.d;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nw = a.nw;
+  const int nthreads = nw * 64;
   const int m16 = lane & 15, r = lane >> 4;
   const int split = blockIdx.x;
   const int h = blockIdx.y, b = blockIdx.z;
   const int ul = b * d.kv_heads + h;
   const int64_t u = d.unit0 + ul;
   const float qscale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
-  WaveLds<GQ, NV>& L = lds.w[wave];
+  WaveLds<GQ, NV>& L = ((WaveLds<GQ, NV>*)smem)[wave];
   const __half* qbase = a.q + ((int64_t)b * d.q_heads + (int64_t)h * GQ) * kHeadDim;
   const int n_splits = a.splits;
 
@@ -494,16 +515,19 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
 #pragma unroll
   for (int j = 0; j < GQ; ++j) qw[j] = ((const uint32_t*)(qbase + j * kHeadDim))[lane];
 
+  // full-precision row groups go to the unit's wavefronts from the last one backwards (the
+  // first wavefronts of a workgroup are the ones that may hold one more mini-chunk)
   const int fp_rows = a.n_res + d.pool_slots;
   const int n_rg = (fp_rows + 15) >> 4;
-  int rg = split * 4 + wave;
+  const int unit_waves = n_splits * nw;
+  int rg = unit_waves - 1 - (split * nw + wave);
   const bool has_fp = rg < n_rg;                         // uniform over the wave
   int n_pool = 0, n_aux = 0;
   FpRegs X;
   if (has_fp) {
     n_pool = a.pool_count[u];
     n_aux = a.aux_count[u];
-    fp_load(X, a, u, qbase, rg * 16, n_pool, n_aux, lane);
+    fp_load(X, a, u, qbase, rg * 16, lane);
   }
 
   UnitPtrs P;
@@ -552,10 +576,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
       ((uint32_t*)L.k.q0[2 * j + 1])[lane] = lo;
     }
     wave_sync();
-    fp_compute<GQ, NV>(X, F, L, lane);
-    for (rg += 4 * n_splits; rg < n_rg; rg += 4 * n_splits) {      // further groups (short quantized segment)
-      fp_load(X, a, u, qbase, rg * 16, n_pool, n_aux, lane);
-      fp_compute<GQ, NV>(X, F, L, lane);
+    fp_compute<GQ, NV>(X, F, L, a, n_pool, n_aux, lane);
+    for (rg += unit_waves; rg < n_rg; rg += unit_waves) {          // further groups (short quantized segment)
+      fp_load(X, a, u, qbase, rg * 16, lane);
+      fp_compute<GQ, NV>(X, F, L, a, n_pool, n_aux, lane);
     }
   }
 
@@ -573,51 +597,54 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
       qaf[j][0] = qa[j][0] * fs;
       qaf[j][1] = qa[j][1] * fs;
     }
-    for (; mc + 4 < mc_end; mc += 4) compute_minichunk<GQ, BITS, NV, true>(R, S, L, qa, qaf, lane, P, mc + 4);
+    for (; mc + nw < mc_end; mc += nw) compute_minichunk<GQ, BITS, NV, true>(R, S, L, qa, qaf, lane, P, mc + nw);
     compute_minichunk<GQ, BITS, NV, false>(R, S, L, qa, qaf, lane, P, mc);
   }
   const float post_v = __builtin_amdgcn_exp2f((float)(24 - kShV));
 
   // ---- hand both results of the wave to the merge buffer ---------------------------------------------
   __syncthreads();                                       // every wave is done with its WaveLds
+  const MergeView<GQ, NV> mg(smem, nw);
 #pragma unroll
   for (int jj = 0; jj < 2; ++jj) {
     const int j = 2 * r + jj;
     if (j < GQ) {
 #pragma unroll
       for (int ct = 0; ct < 8; ++ct)
-        lds.mg.o[wave][j % GQ][16 * ct + m16] = (S.O[ct][2 * jj] + S.O[ct][2 * jj + 1]) * post_v;
+        mg.o[(wave * GQ + j % GQ) * kHeadDim + 16 * ct + m16] = (S.O[ct][2 * jj] + S.O[ct][2 * jj + 1]) * post_v;
       const float zsum = S.Dz[2 * jj] + S.Dz[2 * jj + 1];
-      if (m16 < NV) lds.mg.z[wave][j % GQ][m16 % NV] = zsum;
-      if (m16 == NV) lds.mg.l[wave][j % GQ] = zsum;
+      if (m16 < NV) mg.z[(wave * GQ + j % GQ) * NV + m16 % NV] = zsum;
+      if (m16 == NV) mg.l[wave * GQ + j % GQ] = zsum;
     }
   }
 #pragma unroll
   for (int j = 0; j < GQ; ++j) {
-    *(float2*)&lds.mg.o[4 + wave][j][2 * lane] = float2{F.o[j][0], F.o[j][1]};
+    *(float2*)&mg.o[((nw + wave) * GQ + j) * kHeadDim + 2 * lane] = float2{F.o[j][0], F.o[j][1]};
     if (lane == 0) {
-      lds.mg.m[wave][j] = S.m[j];
-      lds.mg.m[4 + wave][j] = F.m[j];
-      lds.mg.l[4 + wave][j] = F.l[j];
+      mg.m[wave * GQ + j] = S.m[j];
+      mg.m[(nw + wave) * GQ + j] = F.m[j];
+      mg.l[(nw + wave) * GQ + j] = F.l[j];
     }
   }
 
-  // ---- merge the 8 results: the output itself if this workgroup is the unit's only one, else its partial
+  // ---- merge the 2 nw results: the output itself if this workgroup is the unit's only one, else its partial
   __syncthreads();
   float* part = a.partials + ((int64_t)ul * n_splits + split) * GQ * (kHeadDim + 2);
-  for (int i = tid; i < GQ * kHeadDim; i += 256) {
+  for (int i = tid; i < GQ * kHeadDim; i += nthreads) {
     const int j = i / kHeadDim, c = i % kHeadDim;
     const int jv = c / (kHeadDim / NV);
     float m = kNegBig;
-#pragma unroll
-    for (int w = 0; w < 8; ++w) m = fmaxf(m, lds.mg.m[w][j]);
+    for (int w = 0; w < 2 * nw; ++w) m = fmaxf(m, mg.m[w * GQ + j]);
     float o = 0.f, l = 0.f;
-#pragma unroll
-    for (int w = 0; w < 8; ++w) {
-      const float f = __builtin_amdgcn_exp2f(lds.mg.m[w][j] - m);
-      const float zt = w < 4 ? lds.mg.z[w & 3][j][jv] : 0.f;
-      o += (lds.mg.o[w][j][c] + zt) * f;
-      l += lds.mg.l[w][j] * f;
+    for (int w = 0; w < nw; ++w) {                       // quantized parts carry their zero-point sums
+      const float f = __builtin_amdgcn_exp2f(mg.m[w * GQ + j] - m);
+      o += (mg.o[(w * GQ + j) * kHeadDim + c] + mg.z[(w * GQ + j) * NV + jv]) * f;
+      l += mg.l[w * GQ + j] * f;
+    }
+    for (int w = nw; w < 2 * nw; ++w) {
+      const float f = __builtin_amdgcn_exp2f(mg.m[w * GQ + j] - m);
+      o += mg.o[(w * GQ + j) * kHeadDim + c] * f;
+      l += mg.l[w * GQ + j] * f;
     }
     if (n_splits == 1) {
       a.out[((int64_t)b * d.q_heads + h * GQ + j) * kHeadDim + c] = __float2half_rn(o / l);
@@ -646,7 +673,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     const float* pu = a.partials + (int64_t)ul * n_splits * GQ * (kHeadDim + 2);
     constexpr int kBatch = 8;                            // partials fetched per round trip
-    for (int i = tid; i < GQ * kHeadDim; i += 256) {
+    for (int i = tid; i < GQ * kHeadDim; i += nthreads) {
       const int j = i / kHeadDim, c = i % kHeadDim;
       const float* pj = pu + j * (kHeadDim + 2);
       float m = kNegBig, l = 0.f, o = 0.f;
@@ -681,12 +708,22 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) d
   }
 }
 
+template <int GQ, int BITS, int NV>
+void launch_one(const DecodeArgs& a, dim3 grid, hipStream_t s) {
+  const size_t lds = (size_t)a.nw * sizeof(WaveLds<GQ, NV>);
+  static_assert(merge_bytes_per_wave<GQ, NV>() <= (int)sizeof(WaveLds<GQ, NV>), "merge view must fit");
+  if (lds > 48 * 1024)     // more than the default limit of dynamic LDS: raise it (cheap, idempotent)
+    (void)hipFuncSetAttribute((const void*)decode_kernel<GQ, BITS, NV>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds);
+  hipLaunchKernelGGL((decode_kernel<GQ, BITS, NV>), grid, dim3(64 * a.nw), lds, s, a);
+}
+
 template <int GQ, int BITS>
 void launch_nv(const DecodeArgs& a, dim3 grid, hipStream_t s) {
   switch (a.d.vgroups) {
-    case 4: hipLaunchKernelGGL((decode_kernel<GQ, BITS, 4>), grid, dim3(256), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((decode_kernel<GQ, BITS, 2>), grid, dim3(256), 0, s, a); break;
-    default: hipLaunchKernelGGL((decode_kernel<GQ, BITS, 1>), grid, dim3(256), 0, s, a); break;
+    case 4: launch_one<GQ, BITS, 4>(a, grid, s); break;
+    case 2: launch_one<GQ, BITS, 2>(a, grid, s); break;
+    default: launch_one<GQ, BITS, 1>(a, grid, s); break;
   }
 }
 
@@ -699,6 +736,19 @@ void launch_bits(const DecodeArgs& a, dim3 grid, hipStream_t s) {
 }
 
 }  // namespace
+
+int decode_wave_lds_bytes(int g, int nv) {
+  auto of_g = [&](auto gq) -> int {
+    constexpr int GQ = decltype(gq)::value;
+    return nv == 4 ? (int)sizeof(WaveLds<GQ, 4>) : nv == 2 ? (int)sizeof(WaveLds<GQ, 2>) : (int)sizeof(WaveLds<GQ, 1>);
+  };
+  switch (g) {
+    case 1: return of_g(std::integral_constant<int, 1>{});
+    case 2: return of_g(std::integral_constant<int, 2>{});
+    case 4: return of_g(std::integral_constant<int, 4>{});
+    default: return of_g(std::integral_constant<int, 8>{});
+  }
+}
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s) {
   const dim3 grid(a.splits, a.d.kv_heads, a.d.batch);
