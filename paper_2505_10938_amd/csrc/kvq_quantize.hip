@@ -46,108 +46,148 @@ __device__ inline __half step_of(float mn, float mx, int bits) {
   return __float2half_rn(s32);
 }
 
-// One workgroup per unit: the whole group (G x 128, K and V) lives in LDS.
-// LDS: 2 * G * 128 * 2 bytes (<= 64 KB) + meta.
-template <int BITS>
-__global__ void __launch_bounds__(256) quantize_kernel(Dims d, int32_t group_index, const __half* __restrict__ k_group,
-                                                       const __half* __restrict__ v_group, int64_t unit_stride,
-                                                       const uint8_t* __restrict__ selected, uint8_t* __restrict__ k_codes,
-                                                       uint32_t* __restrict__ k_meta, uint8_t* __restrict__ v_codes,
-                                                       uint32_t* __restrict__ v_meta, uint32_t* __restrict__ mask) {
+constexpr int kRowB = 272;   // LDS row: 128 fp16 + 16 bytes of padding (spreads rows over the banks)
+
+__device__ inline float half_at(const unsigned char* p) { return __half2float(*(const __half*)p); }
+__device__ inline float lo_half(uint32_t w) { return __half2float(__ushort_as_half((unsigned short)(w & 0xFFFFu))); }
+__device__ inline float hi_half(uint32_t w) { return __half2float(__ushort_as_half((unsigned short)(w >> 16))); }
+
+constexpr int kQuantThreads = 1024;
+
+// Minimum and maximum over groups of `n` adjacent lanes (n = 4, 8 or 16).
+__device__ inline void team_minmax(float& mn, float& mx, int n) {
+  for (int off = 1; off < n; off <<= 1) {
+    mn = fminf(mn, __shfl_xor(mn, off, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  }
+}
+
+// One workgroup of 16 wavefronts per unit: the whole group (G x 128, K and V) lives in LDS.  Every
+// global load of the kernel is issued before the first wait, so a launch costs one trip to
+// memory; the work after it is spread over all 1024 threads because nothing else hides latency.
+// LDS: 2 * G * 272 bytes (<= 68 KB) + meta.
+template <int BITS, int G>
+__global__ void __launch_bounds__(kQuantThreads) quantize_kernel(
+    Dims d, int32_t group_index, const __half* __restrict__ k_group, const __half* __restrict__ v_group,
+    int64_t unit_stride, const uint8_t* __restrict__ selected, uint8_t* __restrict__ k_codes,
+    uint32_t* __restrict__ k_meta, uint8_t* __restrict__ v_codes, uint32_t* __restrict__ v_meta,
+    uint32_t* __restrict__ mask) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const int G = d.G;
-  __half* sk = (__half*)smem;                        // [G][128]
-  __half* sv = sk + G * kHeadDim;                    // [G][128]
-  uint32_t* skm = (uint32_t*)(sv + G * kHeadDim);    // [128] K meta
-  uint32_t* svm = skm + kHeadDim;                    // [G][vgroups] V meta
+  unsigned char* sk = smem;                          // [G] rows of kRowB bytes
+  unsigned char* sv = sk + G * kRowB;                // [G] rows
+  uint32_t* skm = (uint32_t*)(sv + G * kRowB);       // [128] K meta: step | zero << 16
+  uint32_t* svm = skm + kHeadDim;                    // [vgroups][G] V meta
   uint8_t* ssel = (uint8_t*)(svm + G * d.vgroups);   // [G]
-  __shared__ int s_any;
 
   const int tid = threadIdx.x;
   const int ul = blockIdx.x;
   const int64_t u = d.unit0 + ul;
   const __half* gk = k_group + (int64_t)ul * unit_stride;
   const __half* gv = v_group + (int64_t)ul * unit_stride;
+  const int gv_shift = 31 - __clz(d.Gv);             // Gv is a power of two
 
-  if (tid == 0) s_any = 0;
-  __syncthreads();
-  // load rows (16 bytes per thread per step), selected flags
-  const int n16 = G * kHeadDim / 8;
-  for (int i = tid; i < n16; i += 256) {
-    ((uint4*)sk)[i] = ((const uint4*)gk)[i];
-    ((uint4*)sv)[i] = ((const uint4*)gv)[i];
+  // rows: 16 bytes per thread; K rows first, then V rows
+  constexpr int kLoads = 2 * G * 16 / kQuantThreads;  // 1, 2 or 4
+  uint4 rw[kLoads];
+#pragma unroll
+  for (int q = 0; q < kLoads; ++q) {
+    const int e = q * kQuantThreads + tid;
+    const int kv = e / (G * 16), rem = e % (G * 16);
+    rw[q] = *(const uint4*)((kv ? gv : gk) + (rem >> 4) * kHeadDim + (rem & 15) * 8);
   }
-  if (tid < G) {
-    const uint8_t f = selected ? selected[(int64_t)ul * G + tid] : (uint8_t)0;
-    ssel[tid] = f;
-    if (f) s_any = 1;
+  uint8_t flag = 0;
+  if (tid < G && selected) flag = selected[(int64_t)ul * G + tid];
+#pragma unroll
+  for (int q = 0; q < kLoads; ++q) {
+    const int e = q * kQuantThreads + tid;
+    const int kv = e / (G * 16), rem = e % (G * 16);
+    *(uint4*)((kv ? sv : sk) + (rem >> 4) * kRowB + (rem & 15) * 16) = rw[q];
   }
-  __syncthreads();
+  if (tid < G) ssel[tid] = flag;
+  const int any = __syncthreads_or(flag);
 
   // mean replacement: per-channel mean of the original rows of all G tokens, exact fp64 sum,
   // scaled by the power of two 1/G, rounded to fp32 then fp16.
-  if (s_any) {
-    const int c = tid & 127;
-    __half* rows = (tid < 128) ? sk : sv;
-    double sum = 0.0;
-    for (int t = 0; t < G; ++t) sum += (double)__half2float(rows[t * kHeadDim + c]);
-    const float m32 = (float)(sum / (double)G);
-    const __half m16 = __float2half_rn(m32);
-    for (int t = 0; t < G; ++t)
-      if (ssel[t]) rows[t * kHeadDim + c] = m16;
+  if (any) {
+    if (tid < 256) {
+      const int c = tid & 127;
+      unsigned char* rows = (tid < 128) ? sk : sv;
+      double sum = 0.0;
+#pragma unroll 8
+      for (int t = 0; t < G; ++t) sum += (double)half_at(rows + t * kRowB + 2 * c);
+      const float m32 = (float)(sum / (double)G);
+      const __half m16 = __float2half_rn(m32);
+      for (int t = 0; t < G; ++t)
+        if (ssel[t]) *(__half*)(rows + t * kRowB + 2 * c) = m16;
+    }
+    __syncthreads();
   }
-  __syncthreads();
 
-  // K meta: one channel per thread (threads 0..127); V meta: one (token, channel group) per
-  // thread step (threads 128..255).
-  if (tid < 128) {
-    const int c = tid;
-    float mn = __half2float(sk[c]), mx = mn;
-    for (int t = 1; t < G; ++t) {
-      const float x = __half2float(sk[t * kHeadDim + c]);
+  // K meta: 8 adjacent lanes share a channel, each taking every 8th token.
+  {
+    const int c = tid >> 3, part = tid & 7;
+    float mn = half_at(sk + part * kRowB + 2 * c), mx = mn;
+#pragma unroll
+    for (int t = part + 8; t < G; t += 8) {
+      const float x = half_at(sk + t * kRowB + 2 * c);
       mn = fminf(mn, x);
       mx = fmaxf(mx, x);
     }
-    const __half st = step_of(mn, mx, BITS);
-    const uint32_t m = (uint32_t)__half_as_ushort(st) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
-    skm[c] = m;
-    // global layout of a group's Key meta: fp16 step[128], then fp16 zero[128]
-    __half* gm = (__half*)(k_meta + (u * d.groups_per_unit + group_index) * kHeadDim);
-    gm[c] = st;
-    gm[kHeadDim + c] = __float2half_rn(mn);
-  } else {
-    const int nvg = G * d.vgroups;
-    for (int i = tid - 128; i < nvg; i += 128) {
-      const int t = i / d.vgroups, j = i - t * d.vgroups;
-      const __half* p = sv + t * kHeadDim + j * d.Gv;
-      float mn = __half2float(p[0]), mx = mn;
-      for (int c = 1; c < d.Gv; ++c) {
-        const float x = __half2float(p[c]);
-        mn = fminf(mn, x);
-        mx = fmaxf(mx, x);
-      }
+    team_minmax(mn, mx, 8);
+    if (part == 0) {
       const __half st = step_of(mn, mx, BITS);
-      const uint32_t m = (uint32_t)__half_as_ushort(st) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
-      svm[i] = m;
-      // global layout of a 32-token block's Value meta (NV = value groups per token):
-      // fp16 step[16 token pairs][NV][2], then fp16 zero[16 token pairs][NV][2]
-      const int64_t tok = (int64_t)group_index * G + t;
-      const int tb = (int)(tok & 31);
-      __half* gm = (__half*)(v_meta + (u * d.blocks_per_unit + (tok >> 5)) * 32 * d.vgroups);
-      gm[((tb >> 1) * d.vgroups + j) * 2 + (tb & 1)] = st;
-      gm[32 * d.vgroups + ((tb >> 1) * d.vgroups + j) * 2 + (tb & 1)] = __float2half_rn(mn);
+      skm[c] = (uint32_t)__half_as_ushort(st) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
+      // global layout of a group's Key meta: fp16 step[128], then fp16 zero[128]
+      __half* gm = (__half*)(k_meta + (u * d.groups_per_unit + group_index) * kHeadDim);
+      gm[c] = st;
+      gm[kHeadDim + c] = __float2half_rn(mn);
+    }
+  }
+  // V meta: Gv / 8 adjacent lanes share a (token, channel group), 8 channels each.
+  {
+    const int lanes = d.Gv >> 3;                       // 4, 8 or 16
+#pragma unroll 1
+    for (int e = tid; e < G * 16; e += kQuantThreads) {
+      const int t = e >> 4, c8 = e & 15;               // 8 channels from 8 * c8 on
+      const uint4 w = *(const uint4*)(sv + t * kRowB + c8 * 16);
+      const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+      float mn = lo_half(ww[0]), mx = mn;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float x0 = lo_half(ww[k]), x1 = hi_half(ww[k]);
+        mn = fminf(mn, fminf(x0, x1));
+        mx = fmaxf(mx, fmaxf(x0, x1));
+      }
+      team_minmax(mn, mx, lanes);
+      if ((c8 & (lanes - 1)) == 0) {
+        const int j = (c8 * 8) >> gv_shift;
+        const __half st = step_of(mn, mx, BITS);
+        svm[j * G + t] = (uint32_t)__half_as_ushort(st) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
+        // global layout of a 32-token block's Value meta (NV = value groups per token):
+        // fp16 step[16 token pairs][NV][2], then fp16 zero[16 token pairs][NV][2]
+        const int64_t tok = (int64_t)group_index * G + t;
+        const int tb = (int)(tok & 31);
+        __half* gm = (__half*)(v_meta + (u * d.blocks_per_unit + (tok >> 5)) * 32 * d.vgroups);
+        gm[((tb >> 1) * d.vgroups + j) * 2 + (tb & 1)] = st;
+        gm[32 * d.vgroups + ((tb >> 1) * d.vgroups + j) * 2 + (tb & 1)] = __float2half_rn(mn);
+      }
     }
   }
   __syncthreads();
 
-  // codes: one packed u32 word per thread step.  Word w of lane l of block blk holds
-  // 32/BITS codes of 32/BITS/8 fields.
+  // codes: one field (8 codes) of one packed u32 word of K or V per thread step.  Word w of lane l
+  // of block blk holds 4/BITS fields; with two fields per word, adjacent lanes hold them.
   constexpr int kLevels = (1 << BITS) - 1;
   constexpr int kWordsPerBlock = 128 * BITS;          // 512*BITS bytes / 4
   constexpr int kFieldsPerWord = 4 / BITS;            // 2 (2-bit) or 1 (4-bit)
-  const int nblk = G / kBlockTokens;
+  constexpr int nblk = G / kBlockTokens;
+  constexpr int kItems = 2 * nblk * kWordsPerBlock * kFieldsPerWord;   // a multiple of 1024
   const int first_block = group_index * nblk;
-  for (int i = tid; i < nblk * kWordsPerBlock; i += 256) {
+#pragma unroll 1
+  for (int e = tid; e < kItems; e += kQuantThreads) {
+    const int kv = e / (kItems / 2);
+    const int wf = e % (kItems / 2);
+    const int i = wf / kFieldsPerWord, ff = wf % kFieldsPerWord;
     const int blk = i / kWordsPerBlock;
     const int wi = i - blk * kWordsPerBlock;
     // invert word_byte(): byte = 4*wi
@@ -161,35 +201,38 @@ __global__ void __launch_bounds__(256) quantize_kernel(Dims d, int32_t group_ind
       f0 = half * 4 + (wi & 3);
     }
     const int r = lane >> 4, mn_ = lane & 15;
-    uint32_t kw = 0, vw = 0;
-    for (int ff = 0; ff < kFieldsPerWord; ++ff) {
-      const int f = f0 + ff;
+    const int f = f0 + ff;
+    uint32_t word = 0;
+    if (kv == 0) {  // Key: lane = 16 r + m, field = 4 th + cb: 8 consecutive channels of one token
+      const int t = 16 * (f >> 2) + mn_;
+      const int c0 = 32 * (f & 3) + 8 * r;
+      const uint4 xv = *(const uint4*)(sk + (blk * kBlockTokens + t) * kRowB + 2 * c0);
+      const uint4 m0 = *(const uint4*)(skm + c0), m1 = *(const uint4*)(skm + c0 + 4);
+      const uint32_t xs[4] = {xv.x, xv.y, xv.z, xv.w};
+      const uint32_t ms[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+#pragma unroll
       for (int x = 0; x < 8; ++x) {
-        const int bit = code_bit(BITS, f, x);
-        {  // Key: lane = 16 r + m, field = 4 th + cb
-          const int t = 16 * (f >> 2) + mn_;
-          const int c = 32 * (f & 3) + 8 * r + x;
-          const uint32_t meta = skm[c];
-          const float st = __half2float(__ushort_as_half((unsigned short)(meta & 0xFFFFu)));
-          const float zr = __half2float(__ushort_as_half((unsigned short)(meta >> 16)));
-          const float xv = __half2float(sk[(blk * kBlockTokens + t) * kHeadDim + c]);
-          kw |= quant_code(xv, zr, st, kLevels) << bit;
-        }
-        {  // Value: lane = 16 r + n, field = ct
-          const int t = 8 * r + x;
-          const int c = 16 * f + mn_;
-          const int tg = blk * kBlockTokens + t;
-          const uint32_t meta = svm[tg * d.vgroups + c / d.Gv];
-          const float st = __half2float(__ushort_as_half((unsigned short)(meta & 0xFFFFu)));
-          const float zr = __half2float(__ushort_as_half((unsigned short)(meta >> 16)));
-          const float xv = __half2float(sv[tg * kHeadDim + c]);
-          vw |= quant_code(xv, zr, st, kLevels) << bit;
-        }
+        const float val = (x & 1) ? hi_half(xs[x >> 1]) : lo_half(xs[x >> 1]);
+        word |= quant_code(val, hi_half(ms[x]), lo_half(ms[x]), kLevels) << code_bit(BITS, ff, x);
       }
+    } else {        // Value: lane = 16 r + n, field = ct: one channel of 8 consecutive tokens
+      const int c = 16 * f + mn_;
+      const int t0 = blk * kBlockTokens + 8 * r;
+      const uint32_t* pm = svm + (c >> gv_shift) * G + t0;
+      const uint4 m0 = *(const uint4*)pm, m1 = *(const uint4*)(pm + 4);
+      const uint32_t ms[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+      float val[8];
+#pragma unroll
+      for (int x = 0; x < 8; ++x) val[x] = half_at(sv + (t0 + x) * kRowB + 2 * c);
+#pragma unroll
+      for (int x = 0; x < 8; ++x)
+        word |= quant_code(val[x], hi_half(ms[x]), lo_half(ms[x]), kLevels) << code_bit(BITS, ff, x);
     }
-    const int64_t boff = (u * d.blocks_per_unit + first_block + blk) * (int64_t)d.block_bytes;
-    ((uint32_t*)(k_codes + boff))[wi] = kw;
-    ((uint32_t*)(v_codes + boff))[wi] = vw;
+    if (kFieldsPerWord == 2) word |= __shfl_xor(word, 1, 64);      // the word's other field
+    if (ff == 0) {
+      const int64_t boff = (u * d.blocks_per_unit + first_block + blk) * (int64_t)d.block_bytes;
+      ((uint32_t*)((kv ? v_codes : k_codes) + boff))[wi] = word;
+    }
   }
 
   // mask words
@@ -197,6 +240,31 @@ __global__ void __launch_bounds__(256) quantize_kernel(Dims d, int32_t group_ind
     uint32_t w = 0;
     for (int t = 0; t < 32; ++t) w |= (ssel[tid * 32 + t] ? 1u : 0u) << t;
     mask[u * d.blocks_per_unit + first_block + tid] = w;
+  }
+}
+
+template <int BITS, int G>
+hipError_t launch_quantize_one(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
+                               int64_t unit_stride, const uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
+  const size_t smem = (size_t)2 * G * kRowB + kHeadDim * 4 + (size_t)G * d.vgroups * 4 + G;
+  if (smem > 48 * 1024) {  // more than the default limit of dynamic LDS per workgroup
+    hipError_t e = hipFuncSetAttribute((const void*)quantize_kernel<BITS, G>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((quantize_kernel<BITS, G>), dim3(d.units_per_layer), dim3(kQuantThreads), smem, s, d, group_index, k_group,
+                     v_group, unit_stride, selected, (uint8_t*)qc.k_codes, (uint32_t*)qc.k_meta, (uint8_t*)qc.v_codes,
+                     (uint32_t*)qc.v_meta, (uint32_t*)qc.mask);
+  return hipGetLastError();
+}
+
+template <int BITS>
+hipError_t launch_quantize_bits(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
+                                int64_t unit_stride, const uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
+  switch (d.G) {
+    case 32: return launch_quantize_one<BITS, 32>(d, group_index, k_group, v_group, unit_stride, selected, qc, s);
+    case 64: return launch_quantize_one<BITS, 64>(d, group_index, k_group, v_group, unit_stride, selected, qc, s);
+    default: return launch_quantize_one<BITS, 128>(d, group_index, k_group, v_group, unit_stride, selected, qc, s);
   }
 }
 
@@ -210,22 +278,8 @@ hipError_t launch_append(const Dims& d, const __half* k_new, const __half* v_new
 
 hipError_t launch_quantize(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
                            int64_t unit_stride, const uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
-  const size_t smem = (size_t)2 * d.G * kHeadDim * 2 + kHeadDim * 4 + (size_t)d.G * d.vgroups * 4 + d.G;
-  if (smem > 64 * 1024) {  // G = 128 needs a little more than the default per-workgroup limit
-    hipError_t e = hipFuncSetAttribute(d.bits == 2 ? (const void*)quantize_kernel<2> : (const void*)quantize_kernel<4>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-  }
-  if (d.bits == 2) {
-    hipLaunchKernelGGL(quantize_kernel<2>, dim3(d.units_per_layer), dim3(256), smem, s, d, group_index, k_group, v_group,
-                       unit_stride, selected, (uint8_t*)qc.k_codes, (uint32_t*)qc.k_meta, (uint8_t*)qc.v_codes,
-                       (uint32_t*)qc.v_meta, (uint32_t*)qc.mask);
-  } else {
-    hipLaunchKernelGGL(quantize_kernel<4>, dim3(d.units_per_layer), dim3(256), smem, s, d, group_index, k_group, v_group,
-                       unit_stride, selected, (uint8_t*)qc.k_codes, (uint32_t*)qc.k_meta, (uint8_t*)qc.v_codes,
-                       (uint32_t*)qc.v_meta, (uint32_t*)qc.mask);
-  }
-  return hipGetLastError();
+  return d.bits == 2 ? launch_quantize_bits<2>(d, group_index, k_group, v_group, unit_stride, selected, qc, s)
+                     : launch_quantize_bits<4>(d, group_index, k_group, v_group, unit_stride, selected, qc, s);
 }
 
 }  // namespace kvq
