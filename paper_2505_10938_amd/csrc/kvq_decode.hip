@@ -129,7 +129,8 @@ struct McRegs {
   uint32_t ksz[4];         // Key zeros, same channels
   uint32_t vsp[NV];        // Value steps of this lane's tokens (2*lane, 2*lane+1 of the 128), per value group
   uint32_t vsz[NV];        // Value zeros, same tokens
-  uint32_t mkw;            // mask word of this lane's block (all ones for a block past the end)
+  uint32_t mkw;            // mask word of this lane's block
+  bool mk_valid;           // false for a block past the end (every token of it is masked)
 };
 
 // LDS of one wavefront.  The first group of arrays is used while scores are formed, the second
@@ -220,8 +221,9 @@ __device__ __forceinline__ void load_v_meta(McRegs<BITS, NV>& R, const UnitPtrs&
   // this lane's tokens are 2*lane, 2*lane+1 of the 128: pair lane&15 of block lane>>4
   const int myblk = mc * 4 + (lane >> 4);
   const uint32_t blk = (uint32_t)min(myblk, P.nblocks - 1);
-  const uint32_t mw = ld<uint32_t>(P.mask, blk * 4u);
-  R.mkw = (myblk < P.nblocks) ? mw : 0xFFFFFFFFu;
+  // the loaded word is not touched here: any use would make this point wait for the load
+  R.mkw = ld<uint32_t>(P.mask, blk * 4u);
+  R.mk_valid = myblk < P.nblocks;
   const uint32_t off = blk * (128u * NV) + (lane & 15) * (4u * NV);
 #pragma unroll
   for (int jv = 0; jv < NV; ++jv) {
@@ -310,7 +312,9 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
   // ---- softmax numerators of the 128 tokens against the running maximum; operand rows ---------------
   {
     const int bi = lane >> 4;                         // block of this lane's tokens (2*lane, 2*lane+1)
-    const uint32_t mword = R.mkw;
+    uint32_t mword = R.mkw;
+    asm volatile("" : "+v"(mword) :: "memory");       // first use of the loaded word stays here
+    mword = R.mk_valid ? mword : 0xFFFFFFFFu;
     const int bit = (2 * lane) & 31;
     const bool ok0 = !((mword >> bit) & 1u);
     const bool ok1 = !((mword >> (bit + 1)) & 1u);
