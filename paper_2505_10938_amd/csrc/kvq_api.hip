@@ -32,9 +32,10 @@ int64_t res_rows_of(const kvq_config* c) {
 
 // Split of one unit's decode work over wavefronts and workgroups.  Quantized tokens go in
 // mini-chunks of 128 (one wavefront each at a time), full-precision rows in groups of 16 that cost
-// about half a mini-chunk.  About kTargetWaves wavefronts are wanted over the whole launch, no more
-// per unit than it has items; they form as few workgroups as the LDS budget and the workgroup
-// size limit allow (one workgroup per unit needs no exchange through memory).
+// about half a mini-chunk.  As many wavefronts are wanted over the whole launch as fit on the chip
+// at once (3 per SIMD by registers, fewer when a wavefront's LDS is large), no more per unit than
+// it has items; they form as few workgroups as fit (one workgroup per unit needs no exchange
+// through memory).
 struct Split {
   int32_t splits, nw, mc_per_split;
 };
@@ -44,13 +45,13 @@ Split decode_split(int64_t units_per_layer, int g, int vgroups, int64_t n_quant,
   const int64_t rg = (fp_rows + kvq::kFpGroupRows - 1) / kvq::kFpGroupRows;
   int64_t items = mc + (rg + 1) / 2;
   if (items < 1) items = 1;
-  int64_t wpu = kvq::kTargetWaves / units_per_layer;
+  int64_t waves_per_cu = kvq::kLdsPerComputeUnit / kvq::decode_wave_lds_bytes(g, vgroups);
+  if (waves_per_cu > kvq::kMaxWavesPerGroup) waves_per_cu = kvq::kMaxWavesPerGroup;
+  if (waves_per_cu < 1) waves_per_cu = 1;
+  int64_t wpu = kvq::kComputeUnits * waves_per_cu / units_per_layer;
   if (wpu > items) wpu = items;
   if (wpu < 1) wpu = 1;
-  int64_t nw_max = kvq::kDecodeLdsBudget / kvq::decode_wave_lds_bytes(g, vgroups);
-  if (nw_max > kvq::kMaxWavesPerGroup) nw_max = kvq::kMaxWavesPerGroup;
-  if (nw_max < 1) nw_max = 1;
-  s.splits = (int32_t)((wpu + nw_max - 1) / nw_max);
+  s.splits = (int32_t)((wpu + waves_per_cu - 1) / waves_per_cu);
   s.nw = (int32_t)((wpu + s.splits - 1) / s.splits);
   s.mc_per_split = (int32_t)((mc + s.splits - 1) / s.splits);
   return s;

@@ -12,9 +12,9 @@ namespace kvq {
 constexpr int kHeadDim = 128;      // the only head size built
 constexpr int kBlockTokens = 32;   // tokens per packed block
 constexpr int kMiniChunk = 128;     // quantized tokens one wavefront handles at a time
-constexpr int kTargetWaves = 3072;      // decode wavefronts wanted in flight (3 per SIMD)
+constexpr int kComputeUnits = 256;      // of the device this build targets
+constexpr int kLdsPerComputeUnit = 160 * 1024;
 constexpr int kMaxWavesPerGroup = 12;   // wavefronts of one decode workgroup at most
-constexpr int kDecodeLdsBudget = 144 * 1024;   // LDS one decode workgroup may take
 constexpr int kFpGroupRows = 16;   // full-precision rows one wavefront handles at a time
 constexpr float kNegBig = -1.0e30f;
 
