@@ -8,17 +8,18 @@ import kvq_synth as S
 from oracle import kvq_oracle as O
 
 
-def oracle_states(w: S.Workload, K: np.ndarray, V: np.ndarray, n_quant: int):
+def oracle_states(w: S.Workload, K: np.ndarray, V: np.ndarray, n_quant: int, units=None):
     """K, V: fp16 [batch, kv_heads, n, hd] of one layer.  Streams the first n_quant tokens of
-    every unit through the oracle group by group.  Returns a flat list of UnitState."""
+    every unit (or of the units listed, as indices b * kv_heads + h) through the oracle group
+    by group.  Returns a flat list of UnitState, in the order of `units`."""
     states = []
     G = w.group_k
-    for b in range(w.batch):
-        for h in range(w.kv_heads):
-            st = O.UnitState(w.head_dim, w.bits, G, w.group_v, w.outlier_budget, w.aux_capacity)
-            for i in range(n_quant // G):
-                st.append_group(K[b, h, i * G:(i + 1) * G], V[b, h, i * G:(i + 1) * G])
-            states.append(st)
+    for ui in (range(w.batch * w.kv_heads) if units is None else units):
+        b, h = divmod(ui, w.kv_heads)
+        st = O.UnitState(w.head_dim, w.bits, G, w.group_v, w.outlier_budget, w.aux_capacity)
+        for i in range(n_quant // G):
+            st.append_group(K[b, h, i * G:(i + 1) * G], V[b, h, i * G:(i + 1) * G])
+        states.append(st)
     return states
 
 
@@ -45,9 +46,10 @@ def gpu_cache(w: S.Workload, K: np.ndarray, V: np.ndarray, n_quant: int, n_res: 
     return cache
 
 
-def compare_state(cache, states, w: S.Workload, n_quant: int, layer: int = 0):
+def compare_state(cache, states, w: S.Workload, n_quant: int, layer: int = 0, units=None):
     """Bit-exact comparison of packed codes, steps/zeros, mask words, pool / auxiliary sets
-    (token index, score, K and V rows) and the frozen flag, unit by unit."""
+    (token index, score, K and V rows) and the frozen flag, unit by unit (`units`: the unit
+    indices the states belong to; default all, in order).  Returns the unit list."""
     cfg, sz = cache.cfg, cache.sizes
     upl = w.batch * w.kv_heads
     u0 = layer * upl
@@ -69,7 +71,8 @@ def compare_state(cache, states, w: S.Workload, n_quant: int, layer: int = 0):
     acnt = cache.aux_count.cpu().numpy().view(np.int32)[:sz.units]
     frz = cache.frozen.cpu().numpy().view(np.int32)[:sz.units]
     N = w.outlier_budget
-    for i, st in enumerate(states):
+    unit_list = list(range(len(states))) if units is None else list(units)
+    for i, st in zip(unit_list, states):
         u = u0 + i
         ref = O.packed_unit(st)
         assert np.array_equal(km[u, :ng], ref["k_meta"].view(np.uint16)), f"k_meta unit {i}"
@@ -89,14 +92,16 @@ def compare_state(cache, states, w: S.Workload, n_quant: int, layer: int = 0):
                 assert np.array_equal(pv[u, s], m["v"].view(np.uint16)), f"{name} V row unit {i}"
 
 
-def oracle_attention(w: S.Workload, states, Q: np.ndarray, K: np.ndarray, V: np.ndarray, n_quant: int, n_res: int):
-    """fp64 [batch, q_heads, hd] reference outputs of one decode step."""
+def oracle_attention(w: S.Workload, states, Q: np.ndarray, K: np.ndarray, V: np.ndarray, n_quant: int, n_res: int,
+                     units=None):
+    """fp64 [batch, q_heads, hd] reference outputs of one decode step (rows of units that are
+    not listed stay NaN)."""
     g = w.q_heads // w.kv_heads
-    out = np.zeros((w.batch, w.q_heads, w.head_dim))
-    for b in range(w.batch):
-        for h in range(w.kv_heads):
-            st = states[b * w.kv_heads + h]
-            o, _ = O.decode_attention(Q[b, h * g:(h + 1) * g], st, K[b, h, n_quant:n_quant + n_res],
-                                      V[b, h, n_quant:n_quant + n_res])
-            out[b, h * g:(h + 1) * g] = o
+    out = np.full((w.batch, w.q_heads, w.head_dim), np.nan)
+    unit_list = list(range(w.batch * w.kv_heads)) if units is None else list(units)
+    for ui, st in zip(unit_list, states):
+        b, h = divmod(ui, w.kv_heads)
+        o, _ = O.decode_attention(Q[b, h * g:(h + 1) * g], st, K[b, h, n_quant:n_quant + n_res],
+                                  V[b, h, n_quant:n_quant + n_res])
+        out[b, h * g:(h + 1) * g] = o
     return out

@@ -77,3 +77,78 @@ def test_warmup_and_freeze_budget_equals_group():
     states = H.oracle_states(w, K, V, w.n_quant)
     assert any(st.frozen for st in states)
     run_case(w)
+
+
+# ---- full-size configurations: every unit runs on the GPU, the oracle checks sampled units -----------
+
+def run_sampled(w: S.Workload, units, regimes=("peaky", "diffuse")):
+    import torch
+    K, V = S.layer_kv(w, 0)
+    nq, nr = w.n_quant, w.n_res
+    states = H.oracle_states(w, K, V, nq, units)
+    cache = H.gpu_cache(w, K, V, nq, nr)
+    H.compare_state(cache, states, w, nq, units=units)
+    g = w.q_heads // w.kv_heads
+    for regime in regimes:
+        Q = S.layer_queries(w, 0, 0, regime)
+        ref = H.oracle_attention(w, states, Q, K, V, nq, nr, units)
+        out = cache.decode(0, torch.from_numpy(Q).cuda())
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all()
+        for ui in units:
+            b, h = divmod(ui, w.kv_heads)
+            err = float(np.abs(got[b, h * g:(h + 1) * g] - ref[b, h * g:(h + 1) * g]).max())
+            assert err <= ATT_TOL, (w.name, regime, ui, err)
+    return cache
+
+
+def test_full_size_llama2_7b_4k_sampled_units():
+    # the benchmark workload in the benchmark's launch shape (one workgroup of 12 wavefronts per unit)
+    w = S.WORKLOADS["llama2_7b_4k"]
+    run_sampled(w, [0, 37, 130, 255])
+
+
+def test_full_size_long_32k_sampled_units():
+    # long context, grouped queries, N = G: several workgroups per unit and the last-arrival merge
+    w = S.WORKLOADS["long_32k"]
+    run_sampled(w, [0, 31], regimes=("peaky",))
+
+
+def test_four_bit_full_batch_sampled_units():
+    w = S.WORKLOADS["llama2_7b_4k"].with_(name="llama2_7b_4k_4bit", bits=4, batch=4, context=2048 + 40)
+    run_sampled(w, [3, 100])
+
+
+def test_streaming_decode_matches_oracle_every_step():
+    # tokens arrive one by one (grouped queries, 2-bit): the ring fills, a group is traced and
+    # quantized every G steps, attention runs after every append
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    w = small("stream", batch=2, q_heads=8, kv_heads=2, context=600)
+    steps = 70
+    K, V = S.layer_kv(w, 0, w.context + steps)
+    nq0, nr0 = w.n_quant, w.n_res
+    G = w.group_k
+    ms = ((w.context + steps + G - 1) // G) * G
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ms, w.bits, G, w.group_v, w.residual,
+                         w.outlier_budget, w.aux_capacity, w.head_dim)
+    cache = H.gpu_cache(w, K, V, nq0, nr0, cache=KC.KVCache(cfg))
+    states = H.oracle_states(w, K, V, nq0)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    n, nq = w.context, nq0
+    for s in range(steps):
+        cache.append(0, Kd[:, :, n].contiguous(), Vd[:, :, n].contiguous())
+        n += 1
+        if n - nq == w.residual + G:                       # the oracle's schedule: same rule, written again
+            for ui, st in enumerate(states):
+                b, h = divmod(ui, w.kv_heads)
+                st.append_group(K[b, h, nq:nq + G], V[b, h, nq:nq + G])
+            nq += G
+        assert cache.n_quant[0] == nq and cache.n_res[0] == n - nq
+        if s % 9 == 0 or n - nq == w.residual:             # includes the steps right after a quantization
+            Q = S.layer_queries(w, 0, s, "peaky")
+            ref = H.oracle_attention(w, states, Q, K, V, nq, n - nq)
+            got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+            assert float(np.abs(got - ref).max()) <= ATT_TOL, (s, n, nq)
+    H.compare_state(cache, states, w, nq)
