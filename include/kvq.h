@@ -188,6 +188,16 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
                              kvq_pool pool, void* out, void* workspace, size_t workspace_bytes,
                              void* stream);
 
+/*
+ * Measurement aid, not part of the method: read `bytes` bytes (a multiple of 16) of device memory
+ * at `buf` (16-byte aligned) once with 16-byte loads, in one launch that fills the chip, and fold
+ * them into the 4 bytes at `sink` (device).  The benchmark times it over a buffer larger than the
+ * last-level cache to measure the read bandwidth a trivial kernel reaches on the device at hand.
+ * Returns KVQ_ERR_INVALID_ARG for a null pointer, a misaligned buffer or a size that is zero or not
+ * a multiple of 16.
+ */
+int32_t kvq_stream_read(const void* buf, size_t bytes, void* sink, void* stream);
+
 /* Static string for a kvq_status value. */
 const char* kvq_status_string(int32_t status);
 

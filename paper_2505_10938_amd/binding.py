@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libkvq.so")
 KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
-           "kvq_decode_attention", "kvq_status_string", "kvq_version"]
+           "kvq_decode_attention", "kvq_stream_read", "kvq_status_string", "kvq_version"]
 
 
 class kvq_config(C.Structure):
@@ -70,6 +70,8 @@ def load_library() -> C.CDLL:
     lib.kvq_status_string.argtypes = [i32]
     lib.kvq_query_sizes.restype = i32
     lib.kvq_query_sizes.argtypes = [cfgp, C.POINTER(kvq_sizes)]
+    lib.kvq_stream_read.restype = i32
+    lib.kvq_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
     lib.kvq_append_residual.restype = i32
     lib.kvq_append_residual.argtypes = [cfgp, i32, vp, vp, kvq_residual, i32, i32, vp]
     lib.kvq_trace_outliers.restype = i32
@@ -138,6 +140,12 @@ def kvq_quantize_group(cfg, layer, group_index, k_group, v_group, unit_stride, s
                                            unit_stride, _ptr(selected), qcache, _stream(stream))
     if st != KVQ_OK:
         raise KvqError(st, "kvq_quantize_group")
+
+
+def kvq_stream_read(buf, nbytes, sink, stream=None):
+    st = load_library().kvq_stream_read(_ptr(buf), nbytes, _ptr(sink), _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_stream_read")
 
 
 def kvq_decode_attention(cfg, layer, q, qcache: kvq_qcache, n_quant, res: kvq_residual, res_start, n_res,

@@ -84,11 +84,40 @@ Dims make_dims(const kvq_config* c, int32_t layer) {
 
 int32_t from_hip(hipError_t e) { return e == hipSuccess ? KVQ_OK : KVQ_ERR_LAUNCH; }
 
+// Plain streaming read: a workgroup reads contiguous runs of 32 KB (8 loads of 16 bytes per thread in
+// flight), the runs dealt round-robin to the workgroups.
+constexpr int kReadUnroll = 8;
+__global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restrict__ p, size_t n16, uint32_t* sink) {
+  const size_t run = 256 * kReadUnroll;               // 16-byte words per workgroup step
+  uint32_t acc = 0;
+  size_t base = (size_t)blockIdx.x * run;
+  for (; base + run <= n16; base += (size_t)gridDim.x * run) {
+    uint4 v[kReadUnroll];
+#pragma unroll
+    for (int k = 0; k < kReadUnroll; ++k) v[k] = p[base + k * 256 + threadIdx.x];
+#pragma unroll
+    for (int k = 0; k < kReadUnroll; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+  }
+  for (size_t i = base + threadIdx.x; i < n16 && base < n16; i += 256) {   // the last, partial run
+    if (i >= base + run) break;
+    const uint4 a = p[i];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
+  if (acc == 0x9E3779B9u) sink[0] = acc;      // keeps the loads alive; practically never taken
+}
+
 }  // namespace
 
 extern "C" {
 
 int32_t kvq_version(void) { return 1; }
+
+int32_t kvq_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (!buf || !sink || bytes == 0 || bytes % 16 != 0 || ((uintptr_t)buf & 15) != 0) return KVQ_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(stream_read_kernel, dim3(kvq::kComputeUnits * 8), dim3(256), 0, (hipStream_t)stream,
+                     (const uint4*)buf, bytes / 16, (uint32_t*)sink);
+  return from_hip(hipGetLastError());
+}
 
 const char* kvq_status_string(int32_t status) {
   switch (status) {
