@@ -185,7 +185,6 @@ def main():
     torch.cuda.synchronize()
     fp_us = e0.elapsed_time(e1) * 1e3 / 12
     fp_bytes = w.units * (w.context * 4 * w.head_dim + 2 * (w.q_heads // w.kv_heads) * w.head_dim * 2)
-    fp_out = outs[0].cpu().numpy().astype(np.float64)
     del fp_inst
 
     result = {
@@ -213,8 +212,7 @@ def main():
         "fp16_attention_same_entry_point": {
             "us_per_launch": round(fp_us, 3), "algorithmic_bytes": int(fp_bytes),
             "GBps": round(fp_bytes / (fp_us * 1e-6) / 1e9, 1),
-            "speedup_of_quantized_decode": round(fp_us / dec_us, 3),
-            "max_abs_diff_to_quantized_output": float(np.abs(fp_out - outs[-1].cpu().numpy().astype(np.float64)).max())},
+            "speedup_of_quantized_decode": round(fp_us / dec_us, 3)},
         "setup_s": round(t_setup, 1),
     }
 

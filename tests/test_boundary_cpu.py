@@ -95,3 +95,9 @@ def test_bad_call_arguments_rejected_before_launch():
     ap = lambda **k: lib.kvq_append_residual(C.byref(c), 0, 256, 256, res, k.get("start", 0), k.get("n", 0), None)
     assert ap(start=160) == B.KVQ_ERR_INVALID_ARG
     assert ap(n=160) == B.KVQ_ERR_INVALID_ARG
+    rd = lambda **k: lib.kvq_stream_read(k.get("buf", 256), k.get("n", 1024), k.get("sink", 256), None)
+    assert rd(buf=None) == B.KVQ_ERR_INVALID_ARG
+    assert rd(sink=None) == B.KVQ_ERR_INVALID_ARG
+    assert rd(buf=260) == B.KVQ_ERR_INVALID_ARG
+    assert rd(n=0) == B.KVQ_ERR_INVALID_ARG
+    assert rd(n=1000) == B.KVQ_ERR_INVALID_ARG

@@ -152,3 +152,23 @@ def test_streaming_decode_matches_oracle_every_step():
             got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
             assert float(np.abs(got - ref).max()) <= ATT_TOL, (s, n, nq)
     H.compare_state(cache, states, w, nq)
+
+
+def test_whole_context_in_full_precision():
+    # residual ring as long as the context: nothing is quantized, every row takes the full-precision
+    # path (the fp16 attention the benchmark sets beside the quantized one), several rows per wavefront
+    w = small("allfp", residual=2048, outlier_budget=0, aux_capacity=0, context=1900, q_heads=4)
+    assert w.n_quant == 0
+    run_case(w)
+
+
+def test_stream_read_reads_without_touching_the_buffer():
+    import torch
+    from paper_2505_10938_amd import binding as B
+    buf = torch.arange(1 << 20, dtype=torch.int32, device="cuda").view(torch.uint8)
+    keep = buf.clone()
+    sink = torch.zeros(4, dtype=torch.uint8, device="cuda")
+    for n in (16, 4096, 32768 + 48, buf.numel()):
+        B.kvq_stream_read(buf, n, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, keep)
