@@ -189,6 +189,24 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
                              void* stream);
 
 /*
+ * The whole group step in one launch, for the decode steps on which the ring fills: append the
+ * new token's Key and Value as kvq_append_residual does, then, on the oldest G rows of the ring,
+ * the outlier competition of kvq_trace_outliers and the quantization of kvq_quantize_group
+ * (Method, "Quantization": every G steps the oldest group is traced and quantized).  Results are
+ * those of the three calls in sequence.
+ *   res_start, n_res : as in kvq_append_residual (state before the append); the ring must be
+ *                      full after the append: n_res + 1 == residual + group_k, and res_start must
+ *                      be a multiple of group_k (the oldest group is one contiguous block)
+ *   n_quant          : tokens already quantized, a multiple of group_k, n_quant + group_k <= max_seq;
+ *                      the group is stored as group n_quant / group_k
+ *   selected         : device uint8 [batch*kv_heads][G], out, or NULL if the flags are not wanted
+ * Errors: as the three calls; KVQ_ERR_INVALID_ARG if the ring is not full after the append.
+ */
+int32_t kvq_append_trace_quantize(const kvq_config* cfg, int32_t layer, const void* k_new, const void* v_new,
+                                  kvq_residual res, int32_t res_start, int32_t n_res, int32_t n_quant,
+                                  kvq_pool pool, uint8_t* selected, kvq_qcache qcache, void* stream);
+
+/*
  * Measurement aid, not part of the method: read `bytes` bytes (a multiple of 16) of device memory
  * at `buf` (16-byte aligned) once with 16-byte loads, in one launch that fills the chip, and fold
  * them into the 4 bytes at `sink` (device).  The benchmark times it over a buffer larger than the

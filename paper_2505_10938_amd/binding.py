@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libkvq.so")
 KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
-           "kvq_decode_attention", "kvq_stream_read", "kvq_status_string", "kvq_version"]
+           "kvq_append_trace_quantize", "kvq_decode_attention", "kvq_stream_read", "kvq_status_string", "kvq_version"]
 
 
 class kvq_config(C.Structure):
@@ -78,6 +78,8 @@ def load_library() -> C.CDLL:
     lib.kvq_trace_outliers.argtypes = [cfgp, i32, i32, vp, vp, i64, kvq_pool, vp, vp]
     lib.kvq_quantize_group.restype = i32
     lib.kvq_quantize_group.argtypes = [cfgp, i32, i32, vp, vp, i64, vp, kvq_qcache, vp]
+    lib.kvq_append_trace_quantize.restype = i32
+    lib.kvq_append_trace_quantize.argtypes = [cfgp, i32, vp, vp, kvq_residual, i32, i32, i32, kvq_pool, vp, kvq_qcache, vp]
     lib.kvq_decode_attention.restype = i32
     lib.kvq_decode_attention.argtypes = [cfgp, i32, vp, kvq_qcache, i32, kvq_residual, i32, i32, kvq_pool,
                                          vp, vp, C.c_size_t, vp]
@@ -140,6 +142,14 @@ def kvq_quantize_group(cfg, layer, group_index, k_group, v_group, unit_stride, s
                                            unit_stride, _ptr(selected), qcache, _stream(stream))
     if st != KVQ_OK:
         raise KvqError(st, "kvq_quantize_group")
+
+
+def kvq_append_trace_quantize(cfg, layer, k_new, v_new, res: kvq_residual, res_start, n_res, n_quant, pool: kvq_pool,
+                              selected, qcache: kvq_qcache, stream=None):
+    st = load_library().kvq_append_trace_quantize(C.byref(cfg), layer, _ptr(k_new), _ptr(v_new), res, res_start,
+                                                  n_res, n_quant, pool, _ptr(selected), qcache, _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_append_trace_quantize")
 
 
 def kvq_stream_read(buf, nbytes, sink, stream=None):

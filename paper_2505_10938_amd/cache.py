@@ -64,13 +64,23 @@ class KVCache:
         return self.k_res.data_ptr() + off, self.v_res.data_ptr() + off, self.sizes.res_rows * hd
 
     # ---- the schedule --------------------------------------------------------------------------------
-    def append(self, layer, k_new, v_new, stream=None, trace=True):
-        """Append one token (fp16 [batch, kv_heads, head_dim] each); when the ring holds R + G
-        tokens, trace and quantize the oldest G.  Returns True if a group was quantized."""
+    def append(self, layer, k_new, v_new, stream=None, trace=True, fused=True):
+        """Append one token (fp16 [batch, kv_heads, head_dim] each); when the ring then holds R + G
+        tokens, trace and quantize the oldest G (in the same launch if `fused`, else with the three
+        separate calls).  Returns True if a group was quantized."""
         cfg = self.cfg
+        G = cfg.group_k
+        fills = self.n_res[layer] + 1 == cfg.residual + G
+        if fills and fused and trace:
+            B.kvq_append_trace_quantize(cfg, layer, k_new, v_new, self.res, self.res_start[layer], self.n_res[layer],
+                                        self.n_quant[layer], self.pool, self.selected, self.qcache, stream)
+            self.n_quant[layer] += G
+            self.n_res[layer] += 1 - G
+            self.res_start[layer] = (self.res_start[layer] + G) % self.sizes.res_rows
+            return True
         B.kvq_append_residual(cfg, layer, k_new, v_new, self.res, self.res_start[layer], self.n_res[layer], stream)
         self.n_res[layer] += 1
-        if self.n_res[layer] == cfg.residual + cfg.group_k:
+        if fills:
             self.quantize_oldest(layer, stream, trace)
             return True
         return False

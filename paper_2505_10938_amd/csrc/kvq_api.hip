@@ -206,6 +206,29 @@ int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_i
                                        unit_stride, selected, qc, (hipStream_t)stream));
 }
 
+int32_t kvq_append_trace_quantize(const kvq_config* cfg, int32_t layer, const void* k_new, const void* v_new,
+                                  kvq_residual res, int32_t res_start, int32_t n_res, int32_t n_quant,
+                                  kvq_pool pool, uint8_t* selected, kvq_qcache qc, void* stream) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
+  if (!k_new || !v_new || !res.k_res || !res.v_res) return KVQ_ERR_INVALID_ARG;
+  const int32_t rows = (int32_t)res_rows_of(cfg);
+  const int32_t G = cfg->group_k;
+  if (res_start < 0 || res_start >= rows || res_start % G != 0) return KVQ_ERR_INVALID_ARG;
+  if (n_res + 1 != cfg->residual + G) return KVQ_ERR_INVALID_ARG;
+  if (n_quant < 0 || n_quant % G != 0 || n_quant + G > cfg->max_seq) return KVQ_ERR_INVALID_ARG;
+  if (!pool.pool_count || !pool.aux_count || !pool.frozen) return KVQ_ERR_INVALID_ARG;
+  if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v || !pool.pool_idx || !pool.pool_score))
+    return KVQ_ERR_INVALID_ARG;
+  if (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask) return KVQ_ERR_INVALID_ARG;
+  if ((((uintptr_t)res.k_res) | ((uintptr_t)res.v_res)) & 15) return KVQ_ERR_INVALID_ARG;
+  const Dims d = make_dims(cfg, layer);
+  return from_hip(kvq::launch_group_step(d, n_quant / G, (const __half*)k_new, (const __half*)v_new,
+                                         (__half*)res.k_res, (__half*)res.v_res, (res_start + n_res) % rows,
+                                         res_start, pool, selected, qc, (hipStream_t)stream));
+}
+
 int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc, int32_t n_quant,
                              kvq_residual res, int32_t res_start, int32_t n_res, kvq_pool pool, void* out,
                              void* workspace, size_t workspace_bytes, void* stream) {

@@ -61,6 +61,9 @@ hipError_t launch_trace(const Dims& d, int32_t group_index, const __half* k_grou
                         int64_t unit_stride, const kvq_pool& pool, uint8_t* selected, hipStream_t s);
 hipError_t launch_quantize(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
                            int64_t unit_stride, const uint8_t* selected, const kvq_qcache& qc, hipStream_t s);
+hipError_t launch_group_step(const Dims& d, int32_t group_index, const __half* k_new, const __half* v_new, __half* k_res,
+                             __half* v_res, int32_t append_row, int32_t group_row0, const kvq_pool& pool,
+                             uint8_t* selected, const kvq_qcache& qc, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
 int decode_wave_lds_bytes(int g, int vgroups);   // LDS one decode wavefront needs
 

@@ -1,5 +1,7 @@
-// Residual append and group quantization (mean replacement, Eq. 2 per group, packing).
+// Residual append and group quantization (mean replacement, Eq. 2 per group, packing), and the
+// fused group step (append + outlier competition + quantization in one launch).
 #include "kvq_common.h"
+#include "kvq_trace_core.h"
 
 // The integer code decisions must not depend on how the compiler fuses multiplies and adds.
 #pragma clang fp contract(off)
@@ -62,47 +64,64 @@ __device__ inline void team_minmax(float& mn, float& mx, int n) {
   }
 }
 
-// One workgroup of 16 wavefronts per unit: the whole group (G x 128, K and V) lives in LDS.  Every
-// global load of the kernel is issued before the first wait, so a launch costs one trip to
-// memory; the work after it is spread over all 1024 threads because nothing else hides latency.
-// LDS: 2 * G * 272 bytes (<= 68 KB) + meta.
-template <int BITS, int G>
-__global__ void __launch_bounds__(kQuantThreads) quantize_kernel(
-    Dims d, int32_t group_index, const __half* __restrict__ k_group, const __half* __restrict__ v_group,
-    int64_t unit_stride, const uint8_t* __restrict__ selected, uint8_t* __restrict__ k_codes,
-    uint32_t* __restrict__ k_meta, uint8_t* __restrict__ v_codes, uint32_t* __restrict__ v_meta,
-    uint32_t* __restrict__ mask) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char* sk = smem;                          // [G] rows of kRowB bytes
-  unsigned char* sv = sk + G * kRowB;                // [G] rows
-  uint32_t* skm = (uint32_t*)(sv + G * kRowB);       // [128] K meta: step | zero << 16
-  uint32_t* svm = skm + kHeadDim;                    // [vgroups][G] V meta
-  uint8_t* ssel = (uint8_t*)(svm + G * d.vgroups);   // [G]
+// LDS of the quantization: the whole group (G x 128, K and V) and its meta.
+template <int G>
+struct QuantLds {
+  unsigned char* sk;     // [G] rows of kRowB bytes
+  unsigned char* sv;     // [G] rows
+  uint32_t* skm;         // [128] K meta: step | zero << 16
+  uint32_t* svm;         // [vgroups][G] V meta
+  uint8_t* ssel;         // [G] selected flags
+  __device__ QuantLds(unsigned char* smem, int vgroups) {
+    sk = smem;
+    sv = sk + G * kRowB;
+    skm = (uint32_t*)(sv + G * kRowB);
+    svm = skm + kHeadDim;
+    ssel = (uint8_t*)(svm + G * vgroups);
+  }
+};
+template <int G>
+size_t quant_lds_bytes(int vgroups) { return (size_t)2 * G * kRowB + kHeadDim * 4 + (size_t)G * vgroups * 4 + G; }
 
-  const int tid = threadIdx.x;
-  const int ul = blockIdx.x;
-  const int64_t u = d.unit0 + ul;
-  const __half* gk = k_group + (int64_t)ul * unit_stride;
-  const __half* gv = v_group + (int64_t)ul * unit_stride;
-  const int gv_shift = 31 - __clz(d.Gv);             // Gv is a power of two
-
-  // rows: 16 bytes per thread; K rows first, then V rows
-  constexpr int kLoads = 2 * G * 16 / kQuantThreads;  // 1, 2 or 4
+// The group's rows, 16 bytes per thread: K rows first, then V rows.
+template <int G>
+struct GroupRows {
+  static constexpr int kLoads = 2 * G * 16 / kQuantThreads;   // 1, 2 or 4
   uint4 rw[kLoads];
+};
+template <int G>
+__device__ __forceinline__ void rows_issue(GroupRows<G>& r, const __half* gk, const __half* gv, int tid) {
 #pragma unroll
-  for (int q = 0; q < kLoads; ++q) {
+  for (int q = 0; q < GroupRows<G>::kLoads; ++q) {
     const int e = q * kQuantThreads + tid;
     const int kv = e / (G * 16), rem = e % (G * 16);
-    rw[q] = *(const uint4*)((kv ? gv : gk) + (rem >> 4) * kHeadDim + (rem & 15) * 8);
+    r.rw[q] = *(const uint4*)((kv ? gv : gk) + (rem >> 4) * kHeadDim + (rem & 15) * 8);
   }
-  uint8_t flag = 0;
-  if (tid < G && selected) flag = selected[(int64_t)ul * G + tid];
+}
+template <int G>
+__device__ __forceinline__ void rows_to_lds(const GroupRows<G>& r, const QuantLds<G>& L, int tid) {
 #pragma unroll
-  for (int q = 0; q < kLoads; ++q) {
+  for (int q = 0; q < GroupRows<G>::kLoads; ++q) {
     const int e = q * kQuantThreads + tid;
     const int kv = e / (G * 16), rem = e % (G * 16);
-    *(uint4*)((kv ? sv : sk) + (rem >> 4) * kRowB + (rem & 15) * 16) = rw[q];
+    *(uint4*)((kv ? L.sv : L.sk) + (rem >> 4) * kRowB + (rem & 15) * 16) = r.rw[q];
   }
+}
+
+// Quantization of the group held in LDS (rows stored, not yet synchronized): mean replacement of
+// the rows flagged (`flag` = this thread's token, threads below G), meta, codes, mask words.
+// Every thread of the 1024-thread workgroup calls it.
+template <int BITS, int G>
+__device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t group_index, const QuantLds<G>& L,
+                                              uint8_t flag, uint8_t* __restrict__ k_codes,
+                                              uint32_t* __restrict__ k_meta, uint8_t* __restrict__ v_codes,
+                                              uint32_t* __restrict__ v_meta, uint32_t* __restrict__ mask, int tid) {
+  unsigned char* sk = L.sk;
+  unsigned char* sv = L.sv;
+  uint32_t* skm = L.skm;
+  uint32_t* svm = L.svm;
+  uint8_t* ssel = L.ssel;
+  const int gv_shift = 31 - __clz(d.Gv);             // Gv is a power of two
   if (tid < G) ssel[tid] = flag;
   const int any = __syncthreads_or(flag);
 
@@ -243,10 +262,82 @@ __global__ void __launch_bounds__(kQuantThreads) quantize_kernel(
   }
 }
 
+// One workgroup of 16 wavefronts per unit.  Every global load of the kernel is issued before the
+// first wait, so a launch costs one trip to memory; the work after it is spread over all 1024
+// threads because nothing else hides latency.  LDS: 2 * G * 272 bytes (<= 68 KB) + meta.
+template <int BITS, int G>
+__global__ void __launch_bounds__(kQuantThreads) quantize_kernel(
+    Dims d, int32_t group_index, const __half* __restrict__ k_group, const __half* __restrict__ v_group,
+    int64_t unit_stride, const uint8_t* __restrict__ selected, uint8_t* __restrict__ k_codes,
+    uint32_t* __restrict__ k_meta, uint8_t* __restrict__ v_codes, uint32_t* __restrict__ v_meta,
+    uint32_t* __restrict__ mask) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const QuantLds<G> L(smem, d.vgroups);
+  const int tid = threadIdx.x;
+  const int ul = blockIdx.x;
+  const int64_t u = d.unit0 + ul;
+  GroupRows<G> rows;
+  rows_issue<G>(rows, k_group + (int64_t)ul * unit_stride, v_group + (int64_t)ul * unit_stride, tid);
+  uint8_t flag = 0;
+  if (tid < G && selected) flag = selected[(int64_t)ul * G + tid];
+  rows_to_lds<G>(rows, L, tid);
+  quantize_body<BITS, G>(d, u, group_index, L, flag, k_codes, k_meta, v_codes, v_meta, mask, tid);
+}
+
+// The whole group step of one unit in one launch: append the new token's row to the ring, run the
+// outlier competition on the oldest G rows, quantize them.  The ring must be full after the
+// append (R + G rows), its oldest G rows starting at ring row `group_row0`.
+template <int BITS, int G>
+__global__ void __launch_bounds__(kQuantThreads) group_step_kernel(
+    Dims d, int32_t group_index, const __half* __restrict__ k_new, const __half* __restrict__ v_new, __half* k_res,
+    __half* v_res, int32_t append_row, int32_t group_row0, __half* pool_k, __half* pool_v, int32_t* pool_idx,
+    double* pool_score, int32_t* pool_count, int32_t* aux_count, int32_t* frozen, uint8_t* selected,
+    uint8_t* __restrict__ k_codes, uint32_t* __restrict__ k_meta, uint8_t* __restrict__ v_codes,
+    uint32_t* __restrict__ v_meta, uint32_t* __restrict__ mask) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const QuantLds<G> L(smem, d.vgroups);
+  const int tid = threadIdx.x;
+  const int ul = blockIdx.x;
+  const int64_t u = d.unit0 + ul;
+  __half* kring = k_res + u * d.res_rows * kHeadDim;
+  __half* vring = v_res + u * d.res_rows * kHeadDim;
+  if (tid < 128) {                                   // the new row: 64 threads for K, 64 for V, 4 bytes each
+    const int which = tid >> 6, lane = tid & 63;
+    const uint32_t* src = (const uint32_t*)((which ? v_new : k_new) + (int64_t)ul * kHeadDim);
+    ((uint32_t*)((which ? vring : kring) + append_row * kHeadDim))[lane] = src[lane];
+  }
+  if (append_row >= group_row0 && append_row < group_row0 + G) {   // R = 0: the new token closes the group
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+  const __half* gk = kring + group_row0 * kHeadDim;
+  const __half* gv = vring + group_row0 * kHeadDim;
+  GroupRows<G> rows;
+  rows_issue<G>(rows, gk, gv, tid);
+  uint8_t* sel = selected ? selected + (int64_t)ul * G : nullptr;
+  if (d.N > 0) {
+    const trace_core::UnitPool p =
+        trace_core::unit_pool(d, u, pool_k, pool_v, pool_idx, pool_score, pool_count, aux_count, frozen);
+    trace_core::Loaded<G> in;
+    trace_core::load<G>(in, d, p, gk, tid);
+    rows_to_lds<G>(rows, L, tid);
+    trace_core::compete<G>(in, d, group_index, p, gk, gv, sel, L.ssel, tid);
+  } else {
+    rows_to_lds<G>(rows, L, tid);
+    if (tid < G) {
+      L.ssel[tid] = 0;
+      if (sel) sel[tid] = 0;
+    }
+  }
+  __syncthreads();                                   // the flags are in LDS
+  const uint8_t flag = tid < G ? L.ssel[tid] : (uint8_t)0;
+  quantize_body<BITS, G>(d, u, group_index, L, flag, k_codes, k_meta, v_codes, v_meta, mask, tid);
+}
+
 template <int BITS, int G>
 hipError_t launch_quantize_one(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
                                int64_t unit_stride, const uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
-  const size_t smem = (size_t)2 * G * kRowB + kHeadDim * 4 + (size_t)G * d.vgroups * 4 + G;
+  const size_t smem = quant_lds_bytes<G>(d.vgroups);
   if (smem > 48 * 1024) {  // more than the default limit of dynamic LDS per workgroup
     hipError_t e = hipFuncSetAttribute((const void*)quantize_kernel<BITS, G>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)smem);
@@ -274,6 +365,46 @@ hipError_t launch_append(const Dims& d, const __half* k_new, const __half* v_new
                          int32_t row, hipStream_t s) {
   hipLaunchKernelGGL(append_kernel, dim3(d.units_per_layer), dim3(128), 0, s, d, k_new, v_new, k_res, v_res, row);
   return hipGetLastError();
+}
+
+namespace {
+
+template <int BITS, int G>
+hipError_t launch_group_step_one(const Dims& d, int32_t group_index, const __half* k_new, const __half* v_new,
+                                 __half* k_res, __half* v_res, int32_t append_row, int32_t group_row0,
+                                 const kvq_pool& pool, uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
+  const size_t smem = quant_lds_bytes<G>(d.vgroups);
+  if (smem > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)group_step_kernel<BITS, G>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((group_step_kernel<BITS, G>), dim3(d.units_per_layer), dim3(kQuantThreads), smem, s, d,
+                     group_index, k_new, v_new, k_res, v_res, append_row, group_row0, (__half*)pool.pool_k,
+                     (__half*)pool.pool_v, pool.pool_idx, pool.pool_score, pool.pool_count, pool.aux_count,
+                     pool.frozen, selected, (uint8_t*)qc.k_codes, (uint32_t*)qc.k_meta, (uint8_t*)qc.v_codes,
+                     (uint32_t*)qc.v_meta, (uint32_t*)qc.mask);
+  return hipGetLastError();
+}
+
+template <int BITS>
+hipError_t launch_group_step_bits(const Dims& d, int32_t group_index, const __half* k_new, const __half* v_new,
+                                  __half* k_res, __half* v_res, int32_t append_row, int32_t group_row0,
+                                  const kvq_pool& pool, uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
+  switch (d.G) {
+    case 32: return launch_group_step_one<BITS, 32>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, pool, selected, qc, s);
+    case 64: return launch_group_step_one<BITS, 64>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, pool, selected, qc, s);
+    default: return launch_group_step_one<BITS, 128>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, pool, selected, qc, s);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_group_step(const Dims& d, int32_t group_index, const __half* k_new, const __half* v_new,
+                             __half* k_res, __half* v_res, int32_t append_row, int32_t group_row0,
+                             const kvq_pool& pool, uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
+  return d.bits == 2 ? launch_group_step_bits<2>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, pool, selected, qc, s)
+                     : launch_group_step_bits<4>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, pool, selected, qc, s);
 }
 
 hipError_t launch_quantize(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,

@@ -1,0 +1,236 @@
+// Outlier-token competition for one unit, as device code shared by the stand-alone trace kernel
+// and the fused group step: L1 scores, ranking of pool + group, pool / auxiliary-pool update
+// (Method, "Quantization"; Appendix, "Competition Mechanism").
+#pragma once
+
+#include "kvq_common.h"
+
+namespace kvq {
+namespace trace_core {
+
+constexpr int kMaxCand = 64 + 128;                 // pool (N <= 64) + group (G <= 128)
+constexpr int kWorkers = 256;                      // threads of the workgroup that do the work
+constexpr int kMaxMovesPerTeam = (64 + 64) / 16;   // at most N evicted + N new rows, dealt to 16 teams
+
+// Sum over the 16 lanes of a row team.  fp64 adds of multiples of 2^-24 below 2^23 are exact,
+// so the order does not matter.
+__device__ inline double team_sum_f64(double v) {
+  for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+__device__ inline double abs_sum8(uint4 w) {
+  const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+  double s = 0.0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    s += (double)fabsf(__half2float(__ushort_as_half((unsigned short)(ws[k] & 0xFFFFu))));
+    s += (double)fabsf(__half2float(__ushort_as_half((unsigned short)(ws[k] >> 16))));
+  }
+  return s;
+}
+
+// The unit's pool, already offset to the unit.
+struct UnitPool {
+  __half* pk;
+  __half* pv;
+  int32_t* pidx;
+  double* psc;
+  int32_t* pool_count;
+  int32_t* aux_count;
+  int32_t* frozen;
+};
+
+__device__ inline UnitPool unit_pool(const Dims& d, int64_t u, __half* pool_k, __half* pool_v, int32_t* pool_idx,
+                                     double* pool_score, int32_t* pool_count, int32_t* aux_count, int32_t* frozen) {
+  UnitPool p;
+  p.pk = pool_k + u * d.pool_slots * kHeadDim;
+  p.pv = pool_v + u * d.pool_slots * kHeadDim;
+  p.pidx = pool_idx + u * d.pool_slots;
+  p.psc = pool_score + u * d.pool_slots;
+  p.pool_count = pool_count + u;
+  p.aux_count = aux_count + u;
+  p.frozen = frozen + u;
+  return p;
+}
+
+// What the first phase loads.
+template <int G>
+struct Loaded {
+  int is_frozen, n_old, n_aux;
+  double old_score;
+  int32_t old_idx;
+  uint4 kr[G / 16];      // Key rows 16p + team, this lane's 8 channels (threads below kWorkers)
+};
+
+// Issue every load of the first phase (state, stored scores, the group's Key rows); nothing is
+// waited for here.  Rows are handled by teams of 16 lanes (16 bytes per lane).  Requires N > 0.
+template <int G>
+__device__ __forceinline__ void load(Loaded<G>& in, const Dims& d, const UnitPool& p, const __half* gk, int tid) {
+  in.is_frozen = *p.frozen;
+  in.n_old = *p.pool_count;
+  in.n_aux = *p.aux_count;
+  in.old_score = 0.0;
+  in.old_idx = 0;
+  if (tid < d.N) {                                     // every pool slot is valid memory, filled or not
+    in.old_score = p.psc[tid];
+    in.old_idx = p.pidx[tid];
+  }
+  const int team = (tid & (kWorkers - 1)) >> 4, sub = tid & 15;
+  if (tid < kWorkers) {
+#pragma unroll
+    for (int q = 0; q < G / 16; ++q) in.kr[q] = *(const uint4*)(gk + (q * 16 + team) * kHeadDim + sub * 8);
+  }
+}
+
+// The competition and the pool update.  Every thread of the workgroup must call it (it holds
+// barriers); the work is done by threads 0 .. kWorkers-1.  Writes the group's selected flags to
+// `sel` (global, may be null) and `sel_lds` (LDS, may be null).  Requires N > 0.
+template <int G>
+__device__ __forceinline__ void compete(const Loaded<G>& in, const Dims& d, int group_index, const UnitPool& p,
+                                        const __half* gk, const __half* gv, uint8_t* sel, uint8_t* sel_lds, int tid) {
+  __shared__ double c_score[kMaxCand];
+  __shared__ int32_t c_idx[kMaxCand];
+  __shared__ int32_t ev_slots[64];       // old pool slots that fall out, ascending
+  __shared__ int32_t mv_src[128];        // rows that move: source (>= 0: pool slot, < 0: -(group row) - 1)
+  __shared__ int32_t mv_dst[128];        //                 destination slot
+  __shared__ int32_t s_nev, s_wnew[4];
+
+  const bool worker = tid < kWorkers;
+  const int team = (tid & (kWorkers - 1)) >> 4, sub = tid & 15;
+  const int N = d.N, A = d.A;
+  auto none_selected = [&]() {
+    if (tid < G) {
+      if (sel) sel[tid] = 0;
+      if (sel_lds) sel_lds[tid] = 0;
+    }
+  };
+  if (in.is_frozen) {                                  // uniform over the workgroup
+    none_selected();
+    return;
+  }
+  const int n_old = in.n_old, n_aux = in.n_aux;
+  const int n_cand = n_old + G;
+
+  // candidates: old pool members first (stored score), then the group's tokens (L1 norm of the key)
+  if (tid < n_old) {
+    c_score[tid] = in.old_score;
+    c_idx[tid] = in.old_idx;
+  }
+  if (worker) {
+#pragma unroll
+    for (int q = 0; q < G / 16; ++q) {
+      const double sc = team_sum_f64(abs_sum8(in.kr[q]));
+      if (sub == 0) {
+        const int t = q * 16 + team;
+        c_score[n_old + t] = sc;
+        c_idx[n_old + t] = group_index * G + t;
+      }
+    }
+  }
+  __syncthreads();
+
+  // rank by counting: (score, token index) ascending; indices are unique, so ranks are too.
+  // Scores are non-negative, so their bit patterns order like the values.  Each wavefront holds
+  // 64 candidates at a time in registers and broadcasts them one by one (no memory in the loop).
+  const int lane = tid & 63, wave = tid >> 6;
+  const int keep = min(N, n_cand);
+  bool is_ev = false, is_new = false;
+  if (wave * 64 < n_cand) {                            // uniform over the wavefront
+    const int me = min(tid, n_cand - 1);
+    const unsigned long long sme = (unsigned long long)__double_as_longlong(c_score[me]);
+    const int32_t ix = c_idx[me];
+    int rank = 0;
+    for (int base = 0; base < n_cand; base += 64) {
+      const int jn = min(64, n_cand - base);
+      const int jl = min(base + lane, n_cand - 1);
+      const unsigned long long sl = (unsigned long long)__double_as_longlong(c_score[jl]);
+      const int32_t il = c_idx[jl];
+      for (int j = 0; j < jn; ++j) {
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)sl, j);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(sl >> 32), j);
+        const int32_t ij = __builtin_amdgcn_readlane(il, j);
+        const unsigned long long sj = ((unsigned long long)hi << 32) | lo;
+        rank += (sj < sme || (sj == sme && ij < ix)) ? 1 : 0;
+      }
+    }
+    is_ev = (tid < n_old) && (rank >= keep);
+    is_new = (tid >= n_old) && (tid < n_cand) && (rank < keep);
+  }
+  // order of evicted members (by old slot: all of them sit in wavefront 0) and of new members
+  // (by token index = candidate order, over up to 4 wavefronts)
+  const unsigned long long bal_ev = __ballot(is_ev), bal_new = __ballot(is_new);
+  const unsigned long long below = (1ull << lane) - 1ull;
+  int my_order = __popcll((is_ev ? bal_ev : bal_new) & below);
+  if (is_ev) ev_slots[my_order] = tid;
+  if (lane == 0 && wave < 4) {
+    s_wnew[wave] = __popcll(bal_new);
+    if (wave == 0) s_nev = __popcll(bal_ev);
+  }
+  __syncthreads();
+  const int n_ev = s_nev;
+  const int n_new = s_wnew[0] + s_wnew[1] + s_wnew[2] + s_wnew[3];
+  if (is_new)
+    for (int w = 0; w < wave; ++w) my_order += s_wnew[w];
+
+  // stop rule: evicted members must all fit in the auxiliary pool, else freeze and change nothing
+  if (n_aux + n_ev > A) {
+    if (tid == 0) *p.frozen = 1;
+    none_selected();
+    return;
+  }
+
+  // list of moves: evicted rows first (-> auxiliary slots), then new members (-> freed, then free slots)
+  if (is_ev) {
+    mv_src[my_order] = tid;
+    mv_dst[my_order] = N + n_aux + my_order;
+  }
+  if (is_new) {
+    mv_src[n_ev + my_order] = -(tid - n_old) - 1;
+    mv_dst[n_ev + my_order] = (my_order < n_ev) ? ev_slots[my_order] : (n_old - n_ev + my_order);
+  }
+  if (tid >= n_old && tid < n_cand) {
+    if (sel) sel[tid - n_old] = is_new ? 1 : 0;
+    if (sel_lds) sel_lds[tid - n_old] = is_new ? 1 : 0;
+  }
+  __syncthreads();
+
+  // ---- load every moving row, then (all loads complete) store them ---------------------------------
+  const int n_moves = n_ev + n_new;
+  uint4 mk[kMaxMovesPerTeam], mvv[kMaxMovesPerTeam];
+#pragma unroll
+  for (int q = 0; q < kMaxMovesPerTeam; ++q) {
+    const int m = q * 16 + team;
+    if (worker && m < n_moves) {
+      const int src = mv_src[m];
+      const __half* rk = src >= 0 ? p.pk + (int64_t)src * kHeadDim : gk + (int64_t)(-src - 1) * kHeadDim;
+      const __half* rv = src >= 0 ? p.pv + (int64_t)src * kHeadDim : gv + (int64_t)(-src - 1) * kHeadDim;
+      mk[q] = *(const uint4*)(rk + sub * 8);
+      mvv[q] = *(const uint4*)(rv + sub * 8);
+    }
+  }
+  // a destination may be another move's source: every load must have returned before any store
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < kMaxMovesPerTeam; ++q) {
+    const int m = q * 16 + team;
+    if (worker && m < n_moves) {
+      const int src = mv_src[m], to = mv_dst[m];
+      *(uint4*)(p.pk + (int64_t)to * kHeadDim + sub * 8) = mk[q];
+      *(uint4*)(p.pv + (int64_t)to * kHeadDim + sub * 8) = mvv[q];
+      if (sub == 0) {
+        const int ci = src >= 0 ? src : n_old + (-src - 1);
+        p.pidx[to] = c_idx[ci];
+        p.psc[to] = c_score[ci];
+      }
+    }
+  }
+  if (tid == 0) {
+    *p.pool_count = n_old - n_ev + n_new;
+    *p.aux_count = n_aux + n_ev;
+  }
+}
+
+}  // namespace trace_core
+}  // namespace kvq

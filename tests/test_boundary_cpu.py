@@ -101,3 +101,11 @@ def test_bad_call_arguments_rejected_before_launch():
     assert rd(buf=260) == B.KVQ_ERR_INVALID_ARG
     assert rd(n=0) == B.KVQ_ERR_INVALID_ARG
     assert rd(n=1000) == B.KVQ_ERR_INVALID_ARG
+    fz = lambda **k: lib.kvq_append_trace_quantize(C.byref(c), 0, 256, 256, res, k.get("start", 0), k.get("n", 159),
+                                                   k.get("nq", 64), k.get("pool", pool), None, k.get("qc", qc), None)
+    assert fz(n=100) == B.KVQ_ERR_INVALID_ARG                # ring not full after the append
+    assert fz(start=16) == B.KVQ_ERR_INVALID_ARG             # oldest group not one contiguous block
+    assert fz(nq=48) == B.KVQ_ERR_INVALID_ARG
+    assert fz(nq=1024) == B.KVQ_ERR_INVALID_ARG              # no room for another group
+    assert fz(qc=B.kvq_qcache(256, 256, 256, 256, 0)) == B.KVQ_ERR_INVALID_ARG
+    assert fz(pool=B.kvq_pool(256, 256, 256, 256, 0, 256, 256)) == B.KVQ_ERR_INVALID_ARG

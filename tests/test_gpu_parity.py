@@ -120,13 +120,11 @@ def test_four_bit_full_batch_sampled_units():
     run_sampled(w, [3, 100])
 
 
-def test_streaming_decode_matches_oracle_every_step():
-    # tokens arrive one by one (grouped queries, 2-bit): the ring fills, a group is traced and
-    # quantized every G steps, attention runs after every append
+def run_streaming(w: S.Workload, steps: int, fused: bool, check_every: int = 9):
+    """Tokens arrive one by one: the ring fills, a group is traced and quantized every G steps (in
+    one launch if `fused`, else by the three separate calls), attention runs after appends."""
     import torch
     from paper_2505_10938_amd import cache as KC
-    w = small("stream", batch=2, q_heads=8, kv_heads=2, context=600)
-    steps = 70
     K, V = S.layer_kv(w, 0, w.context + steps)
     nq0, nr0 = w.n_quant, w.n_res
     G = w.group_k
@@ -137,21 +135,42 @@ def test_streaming_decode_matches_oracle_every_step():
     states = H.oracle_states(w, K, V, nq0)
     Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
     n, nq = w.context, nq0
+    quantized = 0
     for s in range(steps):
-        cache.append(0, Kd[:, :, n].contiguous(), Vd[:, :, n].contiguous())
+        did = cache.append(0, Kd[:, :, n].contiguous(), Vd[:, :, n].contiguous(), fused=fused)
         n += 1
         if n - nq == w.residual + G:                       # the oracle's schedule: same rule, written again
             for ui, st in enumerate(states):
                 b, h = divmod(ui, w.kv_heads)
                 st.append_group(K[b, h, nq:nq + G], V[b, h, nq:nq + G])
             nq += G
+            quantized += 1
+            assert did
         assert cache.n_quant[0] == nq and cache.n_res[0] == n - nq
-        if s % 9 == 0 or n - nq == w.residual:             # includes the steps right after a quantization
+        if s % check_every == 0 or n - nq == w.residual:   # includes the steps right after a quantization
             Q = S.layer_queries(w, 0, s, "peaky")
             ref = H.oracle_attention(w, states, Q, K, V, nq, n - nq)
             got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
             assert float(np.abs(got - ref).max()) <= ATT_TOL, (s, n, nq)
+    assert quantized >= 2
     H.compare_state(cache, states, w, nq)
+
+
+@pytest.mark.parametrize("fused", [True, False])
+def test_streaming_decode_matches_oracle_every_step(fused):
+    run_streaming(small("stream", batch=2, q_heads=8, kv_heads=2, context=600), 70, fused)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(bits=4, group_k=64, group_v=64, residual=32, outlier_budget=3),
+    dict(bits=2, group_k=128, group_v=128, residual=32, outlier_budget=3),
+    dict(bits=2, group_k=32, group_v=32, residual=0, outlier_budget=4),       # the new token closes the group
+    dict(bits=4, group_k=32, group_v=128, residual=128, outlier_budget=0),    # no pool
+    dict(bits=2, group_k=32, group_v=32, residual=64, outlier_budget=32, aux_capacity=32, rho=0.05),   # freezes
+])
+def test_fused_group_step_configurations(kw):
+    w = small("fusedcfg", batch=2, q_heads=4, kv_heads=2, context=700, **kw)
+    run_streaming(w, 2 * w.group_k + 5, True, check_every=17)
 
 
 def test_whole_context_in_full_precision():
