@@ -3,9 +3,10 @@
 
 A "step" is one pass of the whole hot path of one layer over one batch: append the new
 token's K/V to the residual ring, which fills it; trace outliers of the oldest group and
-quantize it; decode attention over the quantized cache + residual + pools.  Every step runs
-on its own copy of the cache, so each one starts from the same state and reads from HBM
-rather than from the 256 MB last-level cache.
+quantize it (these three in one launch, kvq_append_trace_quantize); decode attention over the
+quantized cache + residual + pools (kvq_decode_attention).  Every step runs on its own copy of
+the cache, so each one starts from the same state and reads from HBM rather than from the
+256 MB last-level cache.
 
 Prints ONE JSON line (metric = KV GB/s of algorithmic bytes; tokens/s alongside).
 """
@@ -198,7 +199,7 @@ def main():
         "config": {"workload": f"{w.name}: 1 layer, batch {w.batch}, {w.q_heads} q / {w.kv_heads} kv heads, "
                                f"head_dim {w.head_dim}, context {w.context}, {w.bits}-bit, G={G}, Gv={w.group_v}, "
                                f"R={w.residual}, N={w.outlier_budget}, A={w.aux_capacity}; step = append + trace + "
-                               f"quantize one group + decode attention",
+                               f"quantize one group (one launch) + decode attention (one launch)",
                    "cache_copies": n_inst},
         "tokens_per_s": round(w.batch / (ms_per_step * 1e-3), 1),
         "frac_of_hbm_peak": round((dec_bytes + quant_bytes) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),

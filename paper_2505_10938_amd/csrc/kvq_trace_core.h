@@ -91,6 +91,7 @@ __device__ __forceinline__ void compete(const Loaded<G>& in, const Dims& d, int 
                                         const __half* gk, const __half* gv, uint8_t* sel, uint8_t* sel_lds, int tid) {
   __shared__ double c_score[kMaxCand];
   __shared__ int32_t c_idx[kMaxCand];
+  __shared__ int32_t c_rank[kMaxCand];
   __shared__ int32_t ev_slots[64];       // old pool slots that fall out, ascending
   __shared__ int32_t mv_src[128];        // rows that move: source (>= 0: pool slot, < 0: -(group row) - 1)
   __shared__ int32_t mv_dst[128];        //                 destination slot
@@ -117,6 +118,7 @@ __device__ __forceinline__ void compete(const Loaded<G>& in, const Dims& d, int 
     c_score[tid] = in.old_score;
     c_idx[tid] = in.old_idx;
   }
+  if (tid < n_cand) c_rank[tid] = 0;
   if (worker) {
 #pragma unroll
     for (int q = 0; q < G / 16; ++q) {
@@ -131,31 +133,30 @@ __device__ __forceinline__ void compete(const Loaded<G>& in, const Dims& d, int 
   __syncthreads();
 
   // rank by counting: (score, token index) ascending; indices are unique, so ranks are too.
-  // Scores are non-negative, so their bit patterns order like the values.  Each wavefront holds
-  // 64 candidates at a time in registers and broadcasts them one by one (no memory in the loop).
+  // Scores are non-negative, so their bit patterns order like the values.  Lane = candidate
+  // (64 at a time), the wavefronts share the candidates to compare against; partial counts are
+  // added up in LDS (integer adds: any order).
   const int lane = tid & 63, wave = tid >> 6;
+  const int n_waves = (int)(blockDim.x >> 6);
   const int keep = min(N, n_cand);
-  bool is_ev = false, is_new = false;
-  if (wave * 64 < n_cand) {                            // uniform over the wavefront
-    const int me = min(tid, n_cand - 1);
+  for (int base = 0; base < n_cand; base += 64) {
+    const int me = min(base + lane, n_cand - 1);
     const unsigned long long sme = (unsigned long long)__double_as_longlong(c_score[me]);
     const int32_t ix = c_idx[me];
-    int rank = 0;
-    for (int base = 0; base < n_cand; base += 64) {
-      const int jn = min(64, n_cand - base);
-      const int jl = min(base + lane, n_cand - 1);
-      const unsigned long long sl = (unsigned long long)__double_as_longlong(c_score[jl]);
-      const int32_t il = c_idx[jl];
-      for (int j = 0; j < jn; ++j) {
-        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)sl, j);
-        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(sl >> 32), j);
-        const int32_t ij = __builtin_amdgcn_readlane(il, j);
-        const unsigned long long sj = ((unsigned long long)hi << 32) | lo;
-        rank += (sj < sme || (sj == sme && ij < ix)) ? 1 : 0;
-      }
+    int cnt = 0;
+#pragma unroll 4
+    for (int j = wave; j < n_cand; j += n_waves) {
+      const unsigned long long sj = (unsigned long long)__double_as_longlong(c_score[j]);
+      cnt += (sj < sme || (sj == sme && c_idx[j] < ix)) ? 1 : 0;
     }
+    if (base + lane < n_cand && cnt) atomicAdd(&c_rank[base + lane], cnt);
+  }
+  __syncthreads();
+  bool is_ev = false, is_new = false;
+  if (tid < n_cand) {
+    const int rank = c_rank[tid];
     is_ev = (tid < n_old) && (rank >= keep);
-    is_new = (tid >= n_old) && (tid < n_cand) && (rank < keep);
+    is_new = (tid >= n_old) && (rank < keep);
   }
   // order of evicted members (by old slot: all of them sit in wavefront 0) and of new members
   // (by token index = candidate order, over up to 4 wavefronts)
