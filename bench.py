@@ -75,12 +75,15 @@ def main():
     w = S.WORKLOADS[args.workload]
     assert w.layers == 1, "bench.py times one layer; multi-layer workloads are run layer by layer elsewhere"
     G = w.group_k
-    nq_final, nres_final = w.n_quant, w.n_res                 # state the decode sees (context = w.context)
+    # the decode sees the context right after a group was quantized: the longest one of that kind
+    # within the workload's context (for the default workload it is the workload's context itself)
+    ctx = w.residual + G * ((w.context - w.residual) // G)
+    nq_final, nres_final = ctx - w.residual, w.residual
     nq0 = nq_final - G                                        # state before the step: ring one short of full
     t_setup = time.time()
     K, V = S.layer_kv(w, 0)                                   # fp16 [B, Hkv, context, hd]
     Q = S.layer_queries(w, 0)
-    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ((w.context + G - 1) // G) * G, w.bits, G, w.group_v,
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ((ctx + G - 1) // G) * G, w.bits, G, w.group_v,
                          w.residual, w.outlier_budget, w.aux_capacity, w.head_dim)
     base = KC.KVCache(cfg)
     Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
@@ -169,11 +172,11 @@ def main():
 
     # the same entry point with the whole context held in full precision (residual ring as long as
     # the context, nothing quantized, no pool): the fp16 attention this cache replaces
-    fp_cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, G, w.bits, G, w.group_v, w.context, 0, 0, w.head_dim)
+    fp_cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, G, w.bits, G, w.group_v, ctx, 0, 0, w.head_dim)
     fp_inst = []
     for _ in range(3):
         c = KC.KVCache(fp_cfg)
-        c.load_residual(0, Kd[:, :, :w.context], Vd[:, :, :w.context])
+        c.load_residual(0, Kd[:, :, :ctx], Vd[:, :, :ctx])
         fp_inst.append(c)
     for c in fp_inst:
         c.decode(0, qd, outs[0])
@@ -185,7 +188,7 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     fp_us = e0.elapsed_time(e1) * 1e3 / 12
-    fp_bytes = w.units * (w.context * 4 * w.head_dim + 2 * (w.q_heads // w.kv_heads) * w.head_dim * 2)
+    fp_bytes = w.units * (ctx * 4 * w.head_dim + 2 * (w.q_heads // w.kv_heads) * w.head_dim * 2)
     del fp_inst
 
     result = {
@@ -197,7 +200,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{w.name}: 1 layer, batch {w.batch}, {w.q_heads} q / {w.kv_heads} kv heads, "
-                               f"head_dim {w.head_dim}, context {w.context}, {w.bits}-bit, G={G}, Gv={w.group_v}, "
+                               f"head_dim {w.head_dim}, context {ctx}, {w.bits}-bit, G={G}, Gv={w.group_v}, "
                                f"R={w.residual}, N={w.outlier_budget}, A={w.aux_capacity}; step = append + trace + "
                                f"quantize one group (one launch) + decode attention (one launch)",
                    "cache_copies": n_inst},
@@ -243,8 +246,8 @@ def main():
             ref = []
             for (b, h), st in zip(units, sts):
                 st.append_group(K[b, h, nq0:nq0 + G], V[b, h, nq0:nq0 + G])          # trace + quantize
-                o, _ = O.decode_attention(Q[b, h * g:(h + 1) * g], st, K[b, h, nq_final:w.context],
-                                          V[b, h, nq_final:w.context])
+                o, _ = O.decode_attention(Q[b, h * g:(h + 1) * g], st, K[b, h, nq_final:ctx],
+                                          V[b, h, nq_final:ctx])
                 ref.append(o)
             t_cpu += time.perf_counter() - t1
             reps_cpu += 1

@@ -63,6 +63,12 @@ WORKLOADS = {
     "mistral_7b_b128_4k": Workload("mistral_7b_b128_4k", 32, 128, 32, 8, 4096),
     "long_32k": Workload("long_32k", 1, 4, 32, 8, 32768, outlier_budget=32, rho=0.05),
 }
+# Variants of the second configuration: the paper's main setting (group 128, residual 32, 3 outlier
+# tokens) and its 4-bit and grouped-query relatives; same shapes otherwise.
+WORKLOADS["llama2_7b_4k_g128"] = WORKLOADS["llama2_7b_4k"].with_(name="llama2_7b_4k_g128", group_k=128, group_v=128,
+                                                                 residual=32, outlier_budget=3)
+WORKLOADS["llama2_7b_4k_4bit"] = WORKLOADS["llama2_7b_4k"].with_(name="llama2_7b_4k_4bit", bits=4)
+WORKLOADS["llama3_8b_4k_gqa"] = WORKLOADS["llama2_7b_4k"].with_(name="llama3_8b_4k_gqa", batch=32, kv_heads=8)
 
 
 def _unit_generator(seed: int, tag: int, layer: int, batch: int, head: int) -> np.random.Generator:
