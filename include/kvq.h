@@ -70,6 +70,7 @@ typedef struct kvq_sizes {
   int64_t counter_bytes;    /* each of pool_count, aux_count, frozen: [units] int32           */
   int64_t selected_bytes;   /* [batch*kv_heads][G] uint8, one layer                           */
   int64_t workspace_bytes;  /* decode-attention workspace for one layer                       */
+  int64_t prefill_selected_bytes; /* [batch*kv_heads][max_seq/G][G] uint8: flags of a whole prompt */
 } kvq_sizes;
 
 /*
@@ -187,6 +188,28 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
                              int32_t n_quant, kvq_residual res, int32_t res_start, int32_t n_res,
                              kvq_pool pool, void* out, void* workspace, size_t workspace_bytes,
                              void* stream);
+
+/*
+ * Quantize a whole prompt of one layer in one call (Method, "Quantization", prefill phase: the
+ * prompt's Keys and Values are quantized group by group, the last tokens stay in full precision).
+ * The result is the state that appending the n_tokens tokens one by one would leave: groups
+ * 0 .. n_q/G - 1 of the quantized cache with n_q = G * floor((n_tokens - R) / G) (0 if n_tokens <
+ * R + G), pool and auxiliary pool after the n_q/G competitions in order, and the last
+ * n_tokens - n_q rows in ring rows 0 .. (the caller continues with res_start = 0, n_res =
+ * n_tokens - n_q).  The layer's cache must be empty before the call (counts and frozen zero).
+ *   k_rows, v_rows : device fp16, unit (b, h)'s n_tokens rows of head_dim contiguous at element
+ *                    offset (b*kv_heads + h) * unit_stride; 16-byte aligned
+ *   unit_stride    : in fp16 elements, >= n_tokens * head_dim, multiple of 8
+ *   n_tokens       : 1 .. max_seq + R + G - 1, with n_q <= max_seq
+ *   selected       : device uint8 scratch of kvq_sizes.prefill_selected_bytes; on return
+ *                    selected[(unit * (n_q/G) + group) * G + t] = 1 if token t of that group entered
+ *                    the pool at its competition
+ * The competitions of a unit run one after the other inside one workgroup; the groups are then
+ * quantized in parallel over units and groups.
+ */
+int32_t kvq_prefill_quantize(const kvq_config* cfg, int32_t layer, const void* k_rows, const void* v_rows,
+                             int64_t unit_stride, int32_t n_tokens, kvq_pool pool, uint8_t* selected,
+                             kvq_qcache qcache, kvq_residual res, void* stream);
 
 /*
  * The whole group step in one launch, for the decode steps on which the ring fills: append the

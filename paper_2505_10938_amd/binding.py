@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libkvq.so")
 KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
-           "kvq_append_trace_quantize", "kvq_decode_attention", "kvq_stream_read", "kvq_status_string", "kvq_version"]
+           "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_decode_attention", "kvq_stream_read", "kvq_status_string", "kvq_version"]
 
 
 class kvq_config(C.Structure):
@@ -30,7 +30,8 @@ class kvq_sizes(C.Structure):
     _fields_ = [(n, C.c_int64) for n in
                 ("units", "res_rows", "pool_slots", "k_codes_bytes", "k_meta_bytes", "v_codes_bytes",
                  "v_meta_bytes", "mask_bytes", "res_bytes", "pool_rows_bytes", "pool_idx_bytes",
-                 "pool_score_bytes", "counter_bytes", "selected_bytes", "workspace_bytes")]
+                 "pool_score_bytes", "counter_bytes", "selected_bytes", "workspace_bytes",
+                 "prefill_selected_bytes")]
 
 
 class kvq_qcache(C.Structure):
@@ -78,6 +79,8 @@ def load_library() -> C.CDLL:
     lib.kvq_trace_outliers.argtypes = [cfgp, i32, i32, vp, vp, i64, kvq_pool, vp, vp]
     lib.kvq_quantize_group.restype = i32
     lib.kvq_quantize_group.argtypes = [cfgp, i32, i32, vp, vp, i64, vp, kvq_qcache, vp]
+    lib.kvq_prefill_quantize.restype = i32
+    lib.kvq_prefill_quantize.argtypes = [cfgp, i32, vp, vp, i64, i32, kvq_pool, vp, kvq_qcache, kvq_residual, vp]
     lib.kvq_append_trace_quantize.restype = i32
     lib.kvq_append_trace_quantize.argtypes = [cfgp, i32, vp, vp, kvq_residual, i32, i32, i32, kvq_pool, vp, kvq_qcache, vp]
     lib.kvq_decode_attention.restype = i32
@@ -150,6 +153,14 @@ def kvq_append_trace_quantize(cfg, layer, k_new, v_new, res: kvq_residual, res_s
                                                   n_res, n_quant, pool, _ptr(selected), qcache, _stream(stream))
     if st != KVQ_OK:
         raise KvqError(st, "kvq_append_trace_quantize")
+
+
+def kvq_prefill_quantize(cfg, layer, k_rows, v_rows, unit_stride, n_tokens, pool: kvq_pool, selected,
+                         qcache: kvq_qcache, res: kvq_residual, stream=None):
+    st = load_library().kvq_prefill_quantize(C.byref(cfg), layer, _ptr(k_rows), _ptr(v_rows), unit_stride, n_tokens,
+                                             pool, _ptr(selected), qcache, res, _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_prefill_quantize")
 
 
 def kvq_stream_read(buf, nbytes, sink, stream=None):

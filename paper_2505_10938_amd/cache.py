@@ -116,6 +116,21 @@ class KVCache:
                 view[u0:u1, 0:n - first] = src[:, first:]
         self.n_res[layer] = n
 
+    def prefill(self, layer, k_rows, v_rows, stream=None):
+        """Quantize a whole prompt (fp16 [batch, kv_heads, n, head_dim], contiguous) into the empty cache
+        of `layer`: the state that n appends would leave."""
+        cfg = self.cfg
+        n = k_rows.shape[2]
+        assert self.n_quant[layer] == 0 and self.n_res[layer] == 0 and k_rows.is_contiguous() and v_rows.is_contiguous()
+        if getattr(self, "prefill_selected", None) is None:
+            self.prefill_selected = torch.zeros(max(int(self.sizes.prefill_selected_bytes), 16), dtype=torch.uint8,
+                                                device=self.device)
+        B.kvq_prefill_quantize(cfg, layer, k_rows, v_rows, n * cfg.head_dim, n, self.pool, self.prefill_selected,
+                               self.qcache, self.res, stream)
+        G, R = cfg.group_k, cfg.residual
+        nq = G * ((n - R) // G) if n >= R + G else 0
+        self.n_quant[layer], self.n_res[layer], self.res_start[layer] = nq, n - nq, 0
+
     def decode(self, layer, q, out=None, stream=None):
         """Attention output (fp16 [batch, q_heads, head_dim]) of one decode step."""
         if out is None:
@@ -137,4 +152,5 @@ class KVCache:
         other.pool = B.kvq_pool(*(getattr(other, n).data_ptr() for n in names[7:14]))
         other.res = B.kvq_residual(other.k_res.data_ptr(), other.v_res.data_ptr())
         other.n_quant, other.res_start, other.n_res = list(self.n_quant), list(self.res_start), list(self.n_res)
+        other.prefill_selected = None
         return other

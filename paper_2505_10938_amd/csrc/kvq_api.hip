@@ -156,6 +156,7 @@ int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out) {
   // the split count grows with the amount of work: the largest is the one of a full cache
   const int64_t s_max = decode_split(upl, (int)g, (int)(hd / cfg->group_v), cfg->max_seq, out->res_rows + slots).splits;
   out->workspace_bytes = kCounterBytes(upl) + upl * s_max * g * (hd + 2) * 4;
+  out->prefill_selected_bytes = upl * cfg->max_seq;
   return KVQ_OK;
 }
 
@@ -202,8 +203,42 @@ int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_i
   if ((((uintptr_t)k_group) | ((uintptr_t)v_group)) & 15) return KVQ_ERR_INVALID_ARG;
   if (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask) return KVQ_ERR_INVALID_ARG;
   const Dims d = make_dims(cfg, layer);
-  return from_hip(kvq::launch_quantize(d, group_index, (const __half*)k_group, (const __half*)v_group,
-                                       unit_stride, selected, qc, (hipStream_t)stream));
+  return from_hip(kvq::launch_quantize(d, group_index, 1, (const __half*)k_group, (const __half*)v_group,
+                                       unit_stride, selected, cfg->group_k, qc, (hipStream_t)stream));
+}
+
+int32_t kvq_prefill_quantize(const kvq_config* cfg, int32_t layer, const void* k_rows, const void* v_rows,
+                             int64_t unit_stride, int32_t n_tokens, kvq_pool pool, uint8_t* selected, kvq_qcache qc,
+                             kvq_residual res, void* stream) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
+  if (!k_rows || !v_rows || !res.k_res || !res.v_res) return KVQ_ERR_INVALID_ARG;
+  if ((((uintptr_t)k_rows) | ((uintptr_t)v_rows) | ((uintptr_t)res.k_res) | ((uintptr_t)res.v_res)) & 15)
+    return KVQ_ERR_INVALID_ARG;
+  const int32_t G = cfg->group_k, R = cfg->residual;
+  if (n_tokens < 1 || (int64_t)n_tokens > (int64_t)cfg->max_seq + R + G - 1) return KVQ_ERR_INVALID_ARG;
+  if (unit_stride < (int64_t)n_tokens * cfg->head_dim || unit_stride % 8 != 0) return KVQ_ERR_INVALID_ARG;
+  const int32_t n_groups = n_tokens >= R + G ? (n_tokens - R) / G : 0;
+  if ((int64_t)n_groups * G > cfg->max_seq) return KVQ_ERR_INVALID_ARG;
+  if (!pool.pool_count || !pool.aux_count || !pool.frozen) return KVQ_ERR_INVALID_ARG;
+  if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v || !pool.pool_idx || !pool.pool_score))
+    return KVQ_ERR_INVALID_ARG;
+  if (n_groups > 0 && (!selected || !qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask))
+    return KVQ_ERR_INVALID_ARG;
+  const Dims d = make_dims(cfg, layer);
+  hipStream_t s = (hipStream_t)stream;
+  if (n_groups > 0) {
+    if (n_groups > 65535) return KVQ_ERR_UNSUPPORTED;                  // grid limit of the quantization launch
+    hipError_t e = kvq::launch_prefill_trace(d, n_groups, (const __half*)k_rows, (const __half*)v_rows, unit_stride,
+                                             pool, selected, s);
+    if (e != hipSuccess) return KVQ_ERR_LAUNCH;
+    e = kvq::launch_quantize(d, 0, n_groups, (const __half*)k_rows, (const __half*)v_rows, unit_stride, selected,
+                             (int64_t)n_groups * G, qc, s);
+    if (e != hipSuccess) return KVQ_ERR_LAUNCH;
+  }
+  return from_hip(kvq::launch_tail_copy(d, (const __half*)k_rows, (const __half*)v_rows, unit_stride, n_groups * G,
+                                        n_tokens - n_groups * G, (__half*)res.k_res, (__half*)res.v_res, s));
 }
 
 int32_t kvq_append_trace_quantize(const kvq_config* cfg, int32_t layer, const void* k_new, const void* v_new,

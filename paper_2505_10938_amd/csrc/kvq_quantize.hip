@@ -268,20 +268,40 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
 template <int BITS, int G>
 __global__ void __launch_bounds__(kQuantThreads) quantize_kernel(
     Dims d, int32_t group_index, const __half* __restrict__ k_group, const __half* __restrict__ v_group,
-    int64_t unit_stride, const uint8_t* __restrict__ selected, uint8_t* __restrict__ k_codes,
-    uint32_t* __restrict__ k_meta, uint8_t* __restrict__ v_codes, uint32_t* __restrict__ v_meta,
-    uint32_t* __restrict__ mask) {
+    int64_t unit_stride, const uint8_t* __restrict__ selected, int64_t selected_unit_stride,
+    uint8_t* __restrict__ k_codes, uint32_t* __restrict__ k_meta, uint8_t* __restrict__ v_codes,
+    uint32_t* __restrict__ v_meta, uint32_t* __restrict__ mask) {
+  // grid (units, groups): workgroup (ul, gy) quantizes the G rows from row gy * G of the unit's
+  // rows as group group_index + gy; its flags are selected[ul * selected_unit_stride + gy * G ..]
   extern __shared__ __align__(16) unsigned char smem[];
   const QuantLds<G> L(smem, d.vgroups);
   const int tid = threadIdx.x;
-  const int ul = blockIdx.x;
+  const int ul = blockIdx.x, gy = blockIdx.y;
   const int64_t u = d.unit0 + ul;
   GroupRows<G> rows;
-  rows_issue<G>(rows, k_group + (int64_t)ul * unit_stride, v_group + (int64_t)ul * unit_stride, tid);
+  const int64_t row0 = (int64_t)ul * unit_stride + (int64_t)gy * G * kHeadDim;
+  rows_issue<G>(rows, k_group + row0, v_group + row0, tid);
   uint8_t flag = 0;
-  if (tid < G && selected) flag = selected[(int64_t)ul * G + tid];
+  if (tid < G && selected) flag = selected[(int64_t)ul * selected_unit_stride + gy * G + tid];
   rows_to_lds<G>(rows, L, tid);
-  quantize_body<BITS, G>(d, u, group_index, L, flag, k_codes, k_meta, v_codes, v_meta, mask, tid);
+  quantize_body<BITS, G>(d, u, group_index + gy, L, flag, k_codes, k_meta, v_codes, v_meta, mask, tid);
+}
+
+// Rows n0 .. n0 + n - 1 of every unit's rows into ring rows 0 .. n - 1 (16 bytes per thread).
+__global__ void __launch_bounds__(256) tail_copy_kernel(Dims d, const __half* __restrict__ k_rows,
+                                                        const __half* __restrict__ v_rows, int64_t unit_stride,
+                                                        int32_t n0, int32_t n, __half* __restrict__ k_res,
+                                                        __half* __restrict__ v_res) {
+  const int ul = blockIdx.x;
+  const int64_t u = d.unit0 + ul;
+  const uint4* sk = (const uint4*)(k_rows + (int64_t)ul * unit_stride + (int64_t)n0 * kHeadDim);
+  const uint4* sv = (const uint4*)(v_rows + (int64_t)ul * unit_stride + (int64_t)n0 * kHeadDim);
+  uint4* dk = (uint4*)(k_res + u * d.res_rows * kHeadDim);
+  uint4* dv = (uint4*)(v_res + u * d.res_rows * kHeadDim);
+  for (int i = blockIdx.y * 256 + threadIdx.x; i < n * 16; i += gridDim.y * 256) {
+    dk[i] = sk[i];
+    dv[i] = sv[i];
+  }
 }
 
 // The whole group step of one unit in one launch: append the new token's row to the ring, run the
@@ -335,27 +355,29 @@ __global__ void __launch_bounds__(kQuantThreads) group_step_kernel(
 }
 
 template <int BITS, int G>
-hipError_t launch_quantize_one(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
-                               int64_t unit_stride, const uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
+hipError_t launch_quantize_one(const Dims& d, int32_t group_index, int32_t n_groups, const __half* k_group,
+                               const __half* v_group, int64_t unit_stride, const uint8_t* selected,
+                               int64_t selected_unit_stride, const kvq_qcache& qc, hipStream_t s) {
   const size_t smem = quant_lds_bytes<G>(d.vgroups);
   if (smem > 48 * 1024) {  // more than the default limit of dynamic LDS per workgroup
     hipError_t e = hipFuncSetAttribute((const void*)quantize_kernel<BITS, G>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)smem);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((quantize_kernel<BITS, G>), dim3(d.units_per_layer), dim3(kQuantThreads), smem, s, d, group_index, k_group,
-                     v_group, unit_stride, selected, (uint8_t*)qc.k_codes, (uint32_t*)qc.k_meta, (uint8_t*)qc.v_codes,
+  hipLaunchKernelGGL((quantize_kernel<BITS, G>), dim3(d.units_per_layer, n_groups), dim3(kQuantThreads), smem, s, d,
+                     group_index, k_group, v_group, unit_stride, selected, selected_unit_stride, (uint8_t*)qc.k_codes, (uint32_t*)qc.k_meta, (uint8_t*)qc.v_codes,
                      (uint32_t*)qc.v_meta, (uint32_t*)qc.mask);
   return hipGetLastError();
 }
 
 template <int BITS>
-hipError_t launch_quantize_bits(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
-                                int64_t unit_stride, const uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
+hipError_t launch_quantize_bits(const Dims& d, int32_t group_index, int32_t n_groups, const __half* k_group,
+                                const __half* v_group, int64_t unit_stride, const uint8_t* selected,
+                                int64_t selected_unit_stride, const kvq_qcache& qc, hipStream_t s) {
   switch (d.G) {
-    case 32: return launch_quantize_one<BITS, 32>(d, group_index, k_group, v_group, unit_stride, selected, qc, s);
-    case 64: return launch_quantize_one<BITS, 64>(d, group_index, k_group, v_group, unit_stride, selected, qc, s);
-    default: return launch_quantize_one<BITS, 128>(d, group_index, k_group, v_group, unit_stride, selected, qc, s);
+    case 32: return launch_quantize_one<BITS, 32>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, s);
+    case 64: return launch_quantize_one<BITS, 64>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, s);
+    default: return launch_quantize_one<BITS, 128>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, s);
   }
 }
 
@@ -407,10 +429,20 @@ hipError_t launch_group_step(const Dims& d, int32_t group_index, const __half* k
                      : launch_group_step_bits<4>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, pool, selected, qc, s);
 }
 
-hipError_t launch_quantize(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
-                           int64_t unit_stride, const uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
-  return d.bits == 2 ? launch_quantize_bits<2>(d, group_index, k_group, v_group, unit_stride, selected, qc, s)
-                     : launch_quantize_bits<4>(d, group_index, k_group, v_group, unit_stride, selected, qc, s);
+hipError_t launch_quantize(const Dims& d, int32_t group_index, int32_t n_groups, const __half* k_group,
+                           const __half* v_group, int64_t unit_stride, const uint8_t* selected,
+                           int64_t selected_unit_stride, const kvq_qcache& qc, hipStream_t s) {
+  return d.bits == 2 ? launch_quantize_bits<2>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, s)
+                     : launch_quantize_bits<4>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, s);
+}
+
+hipError_t launch_tail_copy(const Dims& d, const __half* k_rows, const __half* v_rows, int64_t unit_stride, int32_t n0,
+                            int32_t n, __half* k_res, __half* v_res, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const int by = (n * 16 + 255) / 256;
+  hipLaunchKernelGGL(tail_copy_kernel, dim3(d.units_per_layer, by > 16 ? 16 : by), dim3(256), 0, s, d, k_rows, v_rows,
+                     unit_stride, n0, n, k_res, v_res);
+  return hipGetLastError();
 }
 
 }  // namespace kvq

@@ -85,9 +85,10 @@ __device__ __forceinline__ void load(Loaded<G>& in, const Dims& d, const UnitPoo
 
 // The competition and the pool update.  Every thread of the workgroup must call it (it holds
 // barriers); the work is done by threads 0 .. kWorkers-1.  Writes the group's selected flags to
-// `sel` (global, may be null) and `sel_lds` (LDS, may be null).  Requires N > 0.
+// `sel` (global, may be null) and `sel_lds` (LDS, may be null), and leaves the unit's new state
+// (frozen flag, member counts) in `in`.  Requires N > 0.
 template <int G>
-__device__ __forceinline__ void compete(const Loaded<G>& in, const Dims& d, int group_index, const UnitPool& p,
+__device__ __forceinline__ void compete(Loaded<G>& in, const Dims& d, int group_index, const UnitPool& p,
                                         const __half* gk, const __half* gv, uint8_t* sel, uint8_t* sel_lds, int tid) {
   __shared__ double c_score[kMaxCand];
   __shared__ int32_t c_idx[kMaxCand];
@@ -177,6 +178,7 @@ __device__ __forceinline__ void compete(const Loaded<G>& in, const Dims& d, int 
   // stop rule: evicted members must all fit in the auxiliary pool, else freeze and change nothing
   if (n_aux + n_ev > A) {
     if (tid == 0) *p.frozen = 1;
+    in.is_frozen = 1;
     none_selected();
     return;
   }
@@ -230,6 +232,26 @@ __device__ __forceinline__ void compete(const Loaded<G>& in, const Dims& d, int 
   if (tid == 0) {
     *p.pool_count = n_old - n_ev + n_new;
     *p.aux_count = n_aux + n_ev;
+  }
+  in.n_old = n_old - n_ev + n_new;
+  in.n_aux = n_aux + n_ev;
+}
+
+// Loads for the next group of the same unit inside one kernel: the stored scores and indices as
+// they stand after the previous competition (whose stores were completed and ordered by the
+// caller) and the next group's Key rows; the counts and the frozen flag are carried in `in`.
+template <int G>
+__device__ __forceinline__ void load_next(Loaded<G>& in, const Dims& d, const UnitPool& p, const __half* gk, int tid) {
+  in.old_score = 0.0;
+  in.old_idx = 0;
+  if (tid < d.N) {
+    in.old_score = __hip_atomic_load(&p.psc[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    in.old_idx = __hip_atomic_load(&p.pidx[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+  const int team = (tid & (kWorkers - 1)) >> 4, sub = tid & 15;
+  if (tid < kWorkers) {
+#pragma unroll
+    for (int q = 0; q < G / 16; ++q) in.kr[q] = *(const uint4*)(gk + (q * 16 + team) * kHeadDim + sub * 8);
   }
 }
 

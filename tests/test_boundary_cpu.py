@@ -109,3 +109,11 @@ def test_bad_call_arguments_rejected_before_launch():
     assert fz(nq=1024) == B.KVQ_ERR_INVALID_ARG              # no room for another group
     assert fz(qc=B.kvq_qcache(256, 256, 256, 256, 0)) == B.KVQ_ERR_INVALID_ARG
     assert fz(pool=B.kvq_pool(256, 256, 256, 256, 0, 256, 256)) == B.KVQ_ERR_INVALID_ARG
+    pf = lambda **k: lib.kvq_prefill_quantize(C.byref(c), 0, k.get("kr", 256), 256, k.get("stride", 4096 * 128),
+                                              k.get("n", 1000), k.get("pool", pool), k.get("sel", 256), qc, res, None)
+    assert pf(n=0) == B.KVQ_ERR_INVALID_ARG
+    assert pf(n=1024 + 128 + 32) == B.KVQ_ERR_INVALID_ARG     # more than max_seq + R + G - 1 tokens
+    assert pf(stride=100) == B.KVQ_ERR_INVALID_ARG
+    assert pf(kr=258) == B.KVQ_ERR_INVALID_ARG
+    assert pf(sel=None) == B.KVQ_ERR_INVALID_ARG
+    assert pf(pool=B.kvq_pool(256, 256, 256, 256, 256, 256, 0)) == B.KVQ_ERR_INVALID_ARG

@@ -191,3 +191,70 @@ def test_stream_read_reads_without_touching_the_buffer():
         B.kvq_stream_read(buf, n, sink)
     torch.cuda.synchronize()
     assert torch.equal(buf, keep)
+
+
+# ---- whole-prompt quantization: the state that token-by-token appends would leave -----------------------
+
+def run_prefill(w: S.Workload, regimes=("peaky",)):
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    K, V = S.layer_kv(w, 0)
+    nq, nr = w.n_quant, w.n_res
+    states = H.oracle_states(w, K, V, nq)
+    G = w.group_k
+    cfg = KC.make_config(w.layers, w.batch, w.q_heads, w.kv_heads, max(G, ((nq + G - 1) // G) * G), w.bits, G,
+                         w.group_v, w.residual, w.outlier_budget, w.aux_capacity, w.head_dim)
+    cache = KC.KVCache(cfg)
+    cache.prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
+    torch.cuda.synchronize()
+    assert (cache.n_quant[0], cache.n_res[0], cache.res_start[0]) == (nq, nr, 0)
+    H.compare_state(cache, states, w, nq)
+    ring = cache.res_view("k").cpu().numpy()[:, :nr]
+    assert np.array_equal(ring.view(np.uint16), K.reshape(-1, w.context, w.head_dim)[:, nq:].view(np.uint16))
+    for regime in regimes:
+        Q = S.layer_queries(w, 0, 0, regime)
+        ref = H.oracle_attention(w, states, Q, K, V, nq, nr)
+        got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+        assert float(np.abs(got - ref).max()) <= ATT_TOL, regime
+    return cache
+
+
+@pytest.mark.parametrize("kw", [
+    dict(),
+    dict(bits=4, group_k=64, group_v=64, residual=32, outlier_budget=3),
+    dict(bits=2, group_k=128, group_v=128, residual=32, outlier_budget=3),
+    dict(residual=0, outlier_budget=4),
+    dict(outlier_budget=0, group_v=128),
+    dict(outlier_budget=32, aux_capacity=32, rho=0.05, context=2048 + 100),       # freezes on the way
+    dict(context=100),                                                            # nothing to quantize
+])
+def test_prefill_equals_streaming(kw):
+    base = dict(batch=2, q_heads=4, kv_heads=2, context=1024 + 77)
+    base.update(kw)
+    run_prefill(S.Workload("prefill", 1, **base))
+
+
+def test_prefill_then_stream():
+    # a prompt quantized in one call, then tokens appended one by one (fused group steps)
+    import torch
+    w = small("prefill_stream", batch=2, q_heads=4, kv_heads=2, context=500)
+    steps = 80
+    K, V = S.layer_kv(w, 0, w.context + steps)
+    from paper_2505_10938_amd import cache as KC
+    G = w.group_k
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ((w.context + steps + G - 1) // G) * G, w.bits, G,
+                         w.group_v, w.residual, w.outlier_budget, w.aux_capacity, w.head_dim)
+    cache = KC.KVCache(cfg)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    cache.prefill(0, Kd[:, :, :w.context].contiguous(), Vd[:, :, :w.context].contiguous())
+    for s in range(steps):
+        cache.append(0, Kd[:, :, w.context + s].contiguous(), Vd[:, :, w.context + s].contiguous())
+    n = w.context + steps
+    wf = w.with_(context=n)
+    states = H.oracle_states(wf, K, V, wf.n_quant)
+    assert cache.n_quant[0] == wf.n_quant and cache.n_res[0] == wf.n_res
+    H.compare_state(cache, states, wf, wf.n_quant)
+    Q = S.layer_queries(wf, 0, 0, "peaky")
+    ref = H.oracle_attention(wf, states, Q, K, V, wf.n_quant, wf.n_res)
+    got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+    assert float(np.abs(got - ref).max()) <= ATT_TOL
