@@ -1,4 +1,5 @@
-// Outlier-token competition as a kernel of its own (one workgroup of 4 wavefronts per unit).
+// Outlier-token competition as kernels of its own: one group per launch, or the groups of a whole
+// prompt one after the other (one workgroup of 4 wavefronts per unit in both).
 #include "kvq_common.h"
 #include "kvq_trace_core.h"
 

@@ -160,7 +160,7 @@ __device__ __forceinline__ void compete(Loaded<G>& in, const Dims& d, int group_
     is_new = (tid >= n_old) && (rank < keep);
   }
   // order of evicted members (by old slot: all of them sit in wavefront 0) and of new members
-  // (by token index = candidate order, over up to 4 wavefronts)
+  // (by token index = candidate order; they sit in the first 4 wavefronts)
   const unsigned long long bal_ev = __ballot(is_ev), bal_new = __ballot(is_new);
   const unsigned long long below = (1ull << lane) - 1ull;
   int my_order = __popcll((is_ev ? bal_ev : bal_new) & below);
