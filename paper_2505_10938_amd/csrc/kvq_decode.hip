@@ -137,9 +137,9 @@ struct McRegs {
 // afterwards; they share storage.
 template <int GQ, int NV>
 struct WaveLds {
+  unsigned char q0[2 * GQ][kRowBytes];            // q rows (hi/lo per head), no step; written once
   union {
     struct {
-      unsigned char q0[2 * GQ][kRowBytes];        // q rows (hi/lo per head), no step
       unsigned char aop[4][2 * GQ][kRowBytes];    // q*step rows per block
       unsigned char zk[4][kRowBytes];             // Key zeros per block, 128 channels
     } k;
@@ -195,9 +195,10 @@ template <int BITS, int NV>
 __device__ __forceinline__ void load_k_meta(McRegs<BITS, NV>& R, const UnitPtrs& P, int mc, int lane) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const uint32_t g = (uint32_t)min(mc * 4 + i, P.nblocks - 1) >> P.bpg_shift;
-    R.ksp[i] = ld<uint32_t>(P.km, g * 512u + lane * 4u);
-    R.ksz[i] = ld<uint32_t>(P.km, g * 512u + 256u + lane * 4u);
+    // uniform base (scalar registers) + one lane offset shared by all loads
+    const unsigned char* gp = P.km + ((uint32_t)min(mc * 4 + i, P.nblocks - 1) >> P.bpg_shift) * 512u;
+    R.ksp[i] = ld<uint32_t>(gp, lane * 4u);
+    R.ksz[i] = ld<uint32_t>(gp + 256, lane * 4u);
   }
 }
 template <int BITS>
@@ -205,10 +206,10 @@ __device__ __forceinline__ void load_codes(uint32_t (&w)[4][2 * BITS], const uns
                                            int mc, int lane) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const uint32_t off = (uint32_t)min(mc * 4 + i, P.nblocks - 1) * P.block_bytes + lane * 16u;
+    const unsigned char* bp = codes + (uint32_t)min(mc * 4 + i, P.nblocks - 1) * P.block_bytes;   // uniform
 #pragma unroll
     for (int hf = 0; hf < BITS / 2; ++hf) {
-      const uint4 t = ld<uint4>(codes, off + hf * 1024u);
+      const uint4 t = ld<uint4>(bp + hf * 1024, lane * 16u);
       w[i][4 * hf + 0] = t.x;
       w[i][4 * hf + 1] = t.y;
       w[i][4 * hf + 2] = t.z;
@@ -242,7 +243,7 @@ struct WaveAcc {
 
 template <int GQ, int BITS, int NV, bool more>
 __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<GQ>& S, WaveLds<GQ, NV>& L,
-                                                  const float (&qa)[GQ][2], const float (&qaf)[GQ][2], int lane,
+                                                  const float (&qaf)[GQ][2], int lane,
                                                   const UnitPtrs& P, int mc_next) {
   // Each group of registers is reloaded for the wave's next mini-chunk (mc_next, if `more`) right
   // after its last use here, so those loads are in flight during the rest of this mini-chunk.
@@ -254,13 +255,6 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
 
   // ---- operand rows: q (hi/lo), q*step (hi/lo) per block, and the Key zeros ------------------------
   wave_sync();                          // the previous mini-chunk is done with the shared storage
-#pragma unroll
-  for (int j = 0; j < GQ; ++j) {
-    uint32_t hi, lo;
-    split_pair(qa[j][0], qa[j][1], hi, lo);
-    ((uint32_t*)L.k.q0[2 * j])[lane] = hi;
-    ((uint32_t*)L.k.q0[2 * j + 1])[lane] = lo;
-  }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const float s0 = h2f_bits(R.ksp[i] & 0xFFFFu), s1 = h2f_bits(R.ksp[i] >> 16);
@@ -281,7 +275,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
     float4v Dq = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
-      Dq = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.k.q0[arow], cb * 64 + r * 16),
+      Dq = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.q0[arow], cb * 64 + r * 16),
                                                   lds_operand(L.k.zk[m16 & 3], cb * 64 + r * 16), Dq, 0, 0, 0);
     if (m16 < 4) {
       if (2 * r < GQ) L.qz[m16][2 * r] = Dq[0] + Dq[1];
@@ -292,18 +286,22 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
   const float post_k = __builtin_amdgcn_exp2f((float)(24 - kShK));
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    half8 aq[4];
+    // both 16-token halves of the block share each operand row read
+    float4v D0 = {0.f, 0.f, 0.f, 0.f}, D1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb) aq[cb] = lds_operand(L.k.aop[i][arow], cb * 64 + r * 16);
-#pragma unroll
-    for (int th = 0; th < 2; ++th) {
-      float4v D = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int cb = 0; cb < 4; ++cb)
-        D = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq[cb], field_operand<BITS>(R.kc[i], 4 * th + cb), D, 0, 0, 0);
-      const int tl = i * 32 + th * 16 + m16;
-      if (2 * r < GQ) L.sc[2 * r][tl] = (D[0] + D[1]) * post_k;
-      if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][tl] = (D[2] + D[3]) * post_k;
+    for (int cb = 0; cb < 4; ++cb) {
+      const half8 aq = lds_operand(L.k.aop[i][arow], cb * 64 + r * 16);
+      D0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq, field_operand<BITS>(R.kc[i], cb), D0, 0, 0, 0);
+      D1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq, field_operand<BITS>(R.kc[i], 4 + cb), D1, 0, 0, 0);
+    }
+    const int tl = i * 32 + m16;
+    if (2 * r < GQ) {
+      L.sc[2 * r][tl] = (D0[0] + D0[1]) * post_k;
+      L.sc[2 * r][tl + 16] = (D1[0] + D1[1]) * post_k;
+    }
+    if (2 * r + 1 < GQ) {
+      L.sc[(2 * r + 1) % GQ][tl] = (D0[2] + D0[3]) * post_k;
+      L.sc[(2 * r + 1) % GQ][tl + 16] = (D1[2] + D1[3]) * post_k;
     }
   }
   if (more) load_codes<BITS>(R.kc, P.kc, P, mc_next, lane);
@@ -379,12 +377,13 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
   for (int i = 0; i < 4; ++i) {
     S.Dz = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.v.pp[arow], i * 64 + r * 16),
                                                   lds_operand(L.v.zv[zrow], i * 64 + r * 16), S.Dz, 0, 0, 0);
-    half8 ap[NV];
 #pragma unroll
-    for (int jv = 0; jv < NV; ++jv) ap[jv] = lds_operand(L.v.ps[jv][arow], i * 64 + r * 16);
+    for (int jv = 0; jv < NV; ++jv) {                 // the channel tiles of one value group share an operand row
+      const half8 ap = lds_operand(L.v.ps[jv][arow], i * 64 + r * 16);
 #pragma unroll
-    for (int ct = 0; ct < 8; ++ct)
-      S.O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ap[ct * NV / 8], field_operand<BITS>(R.vc[i], ct), S.O[ct], 0, 0, 0);
+      for (int ct = jv * (8 / NV); ct < (jv + 1) * (8 / NV); ++ct)
+        S.O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ap, field_operand<BITS>(R.vc[i], ct), S.O[ct], 0, 0, 0);
+    }
   }
   if (more) load_codes<BITS>(R.vc, P.vc, P, mc_next, lane);
 }
@@ -453,7 +452,7 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
   float4v D = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int cb = 0; cb < 4; ++cb)
-    D = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.k.q0[arow], cb * 64 + r * 16),
+    D = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.q0[arow], cb * 64 + r * 16),
                                                 __builtin_bit_cast(half8, X.kf[cb]), D, 0, 0, 0);
   wave_sync();                                                     // earlier readers of sc are done
   if (2 * r < GQ) L.sc[2 * r][m16] = okk ? D[0] + D[1] : kNegBig;
@@ -571,15 +570,15 @@ __global__ void __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_e
     F.l[j] = 0.f;
     F.o[j][0] = F.o[j][1] = 0.f;
   }
-  if (has_fp) {
 #pragma unroll
-    for (int j = 0; j < GQ; ++j) {
-      uint32_t hi, lo;
-      split_pair(qa[j][0], qa[j][1], hi, lo);
-      ((uint32_t*)L.k.q0[2 * j])[lane] = hi;
-      ((uint32_t*)L.k.q0[2 * j + 1])[lane] = lo;
-    }
-    wave_sync();
+  for (int j = 0; j < GQ; ++j) {                         // the query rows, for both parts
+    uint32_t hi, lo;
+    split_pair(qa[j][0], qa[j][1], hi, lo);
+    ((uint32_t*)L.q0[2 * j])[lane] = hi;
+    ((uint32_t*)L.q0[2 * j + 1])[lane] = lo;
+  }
+  wave_sync();
+  if (has_fp) {
     fp_compute<GQ, NV>(X, F, L, a, n_pool, n_aux, lane);
     for (rg += unit_waves; rg < n_rg; rg += unit_waves) {          // further groups (short quantized segment)
       fp_load(X, a, u, qbase, rg * 16, lane);
@@ -601,8 +600,8 @@ __global__ void __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_e
       qaf[j][0] = qa[j][0] * fs;
       qaf[j][1] = qa[j][1] * fs;
     }
-    for (; mc + nw < mc_end; mc += nw) compute_minichunk<GQ, BITS, NV, true>(R, S, L, qa, qaf, lane, P, mc + nw);
-    compute_minichunk<GQ, BITS, NV, false>(R, S, L, qa, qaf, lane, P, mc);
+    for (; mc + nw < mc_end; mc += nw) compute_minichunk<GQ, BITS, NV, true>(R, S, L, qaf, lane, P, mc + nw);
+    compute_minichunk<GQ, BITS, NV, false>(R, S, L, qaf, lane, P, mc);
   }
   const float post_v = __builtin_amdgcn_exp2f((float)(24 - kShV));
 
