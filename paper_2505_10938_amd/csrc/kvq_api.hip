@@ -17,7 +17,7 @@ int32_t check_config(const kvq_config* c) {
   if (c->max_seq < c->group_k || c->max_seq % c->group_k != 0) return KVQ_ERR_INVALID_ARG;
   if (c->residual < 0 || c->outlier_budget < 0 || c->aux_capacity < 0) return KVQ_ERR_INVALID_ARG;
   if (c->residual > (1 << 20) || c->max_seq > (1 << 24)) return KVQ_ERR_INVALID_ARG;
-  if (c->batch > 65535 || c->kv_heads > 65535) return KVQ_ERR_INVALID_ARG;   // grid y/z limits
+  if (c->batch > 65535 || c->kv_heads > 32767) return KVQ_ERR_INVALID_ARG;   // grid y/z limits
   if (c->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;
   const int g = c->q_heads / c->kv_heads;
   if (g != 1 && g != 2 && g != 4 && g != 8) return KVQ_ERR_UNSUPPORTED;
@@ -57,6 +57,9 @@ Split decode_split(int64_t units_per_layer, int g, int vgroups, int64_t n_quant,
   return s;
 }
 constexpr int64_t kCounterBytes(int64_t upl) { return ((upl * 4 + 255) / 256) * 256; }
+// Eight query heads per kv head run as two workgroup rows of four (the same kernel instance as
+// g = 4; both rows read the unit's cache): eight at once do not fit the registers.
+constexpr int head_parts_of(int g) { return g == 8 ? 2 : 1; }
 
 Dims make_dims(const kvq_config* c, int32_t layer) {
   Dims d;
@@ -154,8 +157,9 @@ int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out) {
   out->counter_bytes = units * 4;
   out->selected_bytes = upl * cfg->group_k;
   // the split count grows with the amount of work: the largest is the one of a full cache
-  const int64_t s_max = decode_split(upl, (int)g, (int)(hd / cfg->group_v), cfg->max_seq, out->res_rows + slots).splits;
-  out->workspace_bytes = kCounterBytes(upl) + upl * s_max * g * (hd + 2) * 4;
+  const int hp = head_parts_of((int)g);
+  const int64_t s_max = decode_split(upl * hp, (int)g / hp, (int)(hd / cfg->group_v), cfg->max_seq, out->res_rows + slots).splits;
+  out->workspace_bytes = kCounterBytes(upl * hp) + upl * s_max * g * (hd + 2) * 4;
   out->prefill_selected_bytes = upl * cfg->max_seq;
   return KVQ_OK;
 }
@@ -301,11 +305,13 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
   a.aux_count = pool.aux_count;
   a.out = (__half*)out;
   a.counters = (int32_t*)workspace;
-  a.partials = (float*)((unsigned char*)workspace + kCounterBytes(a.d.units_per_layer));
+  a.partials = (float*)((unsigned char*)workspace + kCounterBytes((int64_t)a.d.units_per_layer * head_parts_of(a.d.g)));
   a.n_quant = n_quant;
   a.res_start = res_start;
   a.n_res = n_res;
-  const Split sp = decode_split(a.d.units_per_layer, a.d.g, a.d.vgroups, n_quant, (int64_t)n_res + a.d.pool_slots);
+  a.head_parts = head_parts_of(a.d.g);
+  const Split sp = decode_split((int64_t)a.d.units_per_layer * a.head_parts, a.d.g / a.head_parts, a.d.vgroups, n_quant,
+                                (int64_t)n_res + a.d.pool_slots);
   a.splits = sp.splits;
   a.nw = sp.nw;
   a.mc_per_split = sp.mc_per_split;

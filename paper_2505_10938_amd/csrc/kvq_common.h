@@ -52,6 +52,7 @@ struct DecodeArgs {
   int32_t n_quant, res_start, n_res;
   int32_t splits;       // workgroups per unit
   int32_t nw;           // wavefronts per workgroup
+  int32_t head_parts;   // workgroup rows that share a kv head's query heads (1, or 2 when g = 8)
   int32_t mc_per_split; // 128-token mini-chunks of the quantized segment per workgroup
 };
 

@@ -504,12 +504,17 @@ __global__ void __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_e
   const int nthreads = nw * 64;
   const int m16 = lane & 15, r = lane >> 4;
   const int split = blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z;
-  const int ul = b * d.kv_heads + h;
+  // the query heads of a kv head may be dealt to `head_parts` workgroup rows (part-major in
+  // blockIdx.y, so that the parts of one kv head tend to land on the same compute die)
+  const int h = blockIdx.y % d.kv_heads, part = blockIdx.y / d.kv_heads;
+  const int b = blockIdx.z;
+  const int ul = b * d.kv_heads + h;                     // the unit whose cache is read
+  const int wl = ul * a.head_parts + part;               // its slice of the workspace
+  const int hq0 = (h * a.head_parts + part) * GQ;        // first query head handled here
   const int64_t u = d.unit0 + ul;
   const float qscale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
   WaveLds<GQ, NV>& L = ((WaveLds<GQ, NV>*)smem)[wave];
-  const __half* qbase = a.q + ((int64_t)b * d.q_heads + (int64_t)h * GQ) * kHeadDim;
+  const __half* qbase = a.q + ((int64_t)b * d.q_heads + hq0) * kHeadDim;
   const int n_splits = a.splits;
 
   // Loads go out in the order their data is needed, and all of them before anything is waited
@@ -632,7 +637,7 @@ __global__ void __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_e
 
   // ---- merge the 2 nw results: the output itself if this workgroup is the unit's only one, else its partial
   __syncthreads();
-  float* part = a.partials + ((int64_t)ul * n_splits + split) * GQ * (kHeadDim + 2);
+  float* part_out = a.partials + ((int64_t)wl * n_splits + split) * GQ * (kHeadDim + 2);
   for (int i = tid; i < GQ * kHeadDim; i += nthreads) {
     const int j = i / kHeadDim, c = i % kHeadDim;
     const int jv = c / (kHeadDim / NV);
@@ -650,12 +655,12 @@ __global__ void __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_e
       l += mg.l[w * GQ + j] * f;
     }
     if (n_splits == 1) {
-      a.out[((int64_t)b * d.q_heads + h * GQ + j) * kHeadDim + c] = __float2half_rn(o / l);
+      a.out[((int64_t)b * d.q_heads + hq0 + j) * kHeadDim + c] = __float2half_rn(o / l);
     } else {
-      coherent_store(&part[j * (kHeadDim + 2) + 2 + c], o);
+      coherent_store(&part_out[j * (kHeadDim + 2) + 2 + c], o);
       if (c == 0) {
-        coherent_store(&part[j * (kHeadDim + 2) + 0], m);
-        coherent_store(&part[j * (kHeadDim + 2) + 1], l);
+        coherent_store(&part_out[j * (kHeadDim + 2) + 0], m);
+        coherent_store(&part_out[j * (kHeadDim + 2) + 1], l);
       }
     }
   }
@@ -668,13 +673,13 @@ __global__ void __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_e
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (tid == 0) {
-    const int old = __hip_atomic_fetch_add(&a.counters[ul], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int old = __hip_atomic_fetch_add(&a.counters[wl], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (old == n_splits - 1);
   }
   __syncthreads();
   if (s_last) {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    const float* pu = a.partials + (int64_t)ul * n_splits * GQ * (kHeadDim + 2);
+    const float* pu = a.partials + (int64_t)wl * n_splits * GQ * (kHeadDim + 2);
     constexpr int kBatch = 8;                            // partials fetched per round trip
     for (int i = tid; i < GQ * kHeadDim; i += nthreads) {
       const int j = i / kHeadDim, c = i % kHeadDim;
@@ -704,10 +709,10 @@ __global__ void __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_e
         }
         m = mb;
       }
-      a.out[((int64_t)b * d.q_heads + h * GQ + j) * kHeadDim + c] = __float2half_rn(o / l);
+      a.out[((int64_t)b * d.q_heads + hq0 + j) * kHeadDim + c] = __float2half_rn(o / l);
     }
     if (tid == 0)                                        // leave the counter as it was found
-      __hip_atomic_store(&a.counters[ul], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&a.counters[wl], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
@@ -748,18 +753,16 @@ int decode_wave_lds_bytes(int g, int nv) {
   switch (g) {
     case 1: return of_g(std::integral_constant<int, 1>{});
     case 2: return of_g(std::integral_constant<int, 2>{});
-    case 4: return of_g(std::integral_constant<int, 4>{});
-    default: return of_g(std::integral_constant<int, 8>{});
+    default: return of_g(std::integral_constant<int, 4>{});
   }
 }
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s) {
-  const dim3 grid(a.splits, a.d.kv_heads, a.d.batch);
-  switch (a.d.g) {
+  const dim3 grid(a.splits, a.d.kv_heads * a.head_parts, a.d.batch);
+  switch (a.d.g / a.head_parts) {
     case 1: launch_bits<1>(a, grid, s); break;
     case 2: launch_bits<2>(a, grid, s); break;
-    case 4: launch_bits<4>(a, grid, s); break;
-    default: launch_bits<8>(a, grid, s); break;
+    default: launch_bits<4>(a, grid, s); break;
   }
   return hipGetLastError();
 }
