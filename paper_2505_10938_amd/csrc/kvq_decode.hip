@@ -83,6 +83,19 @@ __device__ inline void split_pair(float x0, float x1, uint32_t& hi, uint32_t& lo
   lo = __builtin_bit_cast(uint32_t, l);
 }
 
+// Product of an unevaluated sum ah + al (packed fp16 pairs) with packed fp16 b, again as an
+// unevaluated sum: hi = fp16(ah*b); the rounding error ah*b - hi is exact in fp16 (a product of
+// two 11-bit significands has 22 bits) and joins al*b in lo.  Three packed instructions.
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+__device__ inline void mul_split(half2v ah, half2v al, half2v b, uint32_t& hi, uint32_t& lo) {
+  const half2v h = ah * b;
+  const half2v e = __builtin_elementwise_fma(ah, b, -h);
+  const half2v l = __builtin_elementwise_fma(al, b, e);
+  hi = __builtin_bit_cast(uint32_t, h);
+  lo = __builtin_bit_cast(uint32_t, l);
+}
+__device__ inline half2v as_half2(uint32_t w) { return __builtin_bit_cast(half2v, w); }
+
 // Exponent of the power of two carried by pair v (v = lane & 3 on the producing side) of a
 // field: a masked code at pair v is worth code * 2^(pos(v) - 24).
 template <int BITS>
@@ -140,12 +153,12 @@ struct WaveLds {
   unsigned char q0[2 * GQ][kRowBytes];            // q rows (hi/lo per head), no step; written once
   union {
     struct {
-      unsigned char aop[4][2 * GQ][kRowBytes];    // q*step rows per block
+      unsigned char aop[2][2 * GQ][kRowBytes];    // q*step rows of one block; two buffers, taken in turn
       unsigned char zk[4][kRowBytes];             // Key zeros per block, 128 channels
     } k;
     struct {
       unsigned char pp[2 * GQ][kRowBytes];        // p rows (hi/lo per head), 128 tokens
-      unsigned char ps[NV][2 * GQ][kRowBytes];    // p*step rows per value group
+      unsigned char ps[2][2 * GQ][kRowBytes];     // p*step rows of one value group; two buffers, taken in turn
       unsigned char zv[NV + 1][kRowBytes];        // Value zeros per value group, 128 tokens; row NV = ones
     } v;
   };
@@ -243,31 +256,34 @@ struct WaveAcc {
 
 template <int GQ, int BITS, int NV, bool more>
 __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<GQ>& S, WaveLds<GQ, NV>& L,
-                                                  const float (&qaf)[GQ][2], int lane,
+                                                  const half2v (&qh)[GQ], const half2v (&ql)[GQ], int lane,
                                                   const UnitPtrs& P, int mc_next) {
   // Each group of registers is reloaded for the wave's next mini-chunk (mc_next, if `more`) right
   // after its last use here, so those loads are in flight during the rest of this mini-chunk.
   // `more` is a template parameter so that every path has a fixed number of loads in flight and
   // the waits on them can be exact.
+  // Operand rows that depend on a block (q*step) or on a value group (p*step) are formed right
+  // before the products that read them, in two buffers taken in turn: LDS operations of a
+  // wavefront execute in program order, so a buffer can be rewritten as soon as the reads of its
+  // previous contents have been issued, and the vector work of the next rows runs under the
+  // matrix instructions of the current ones.
   const int m16 = lane & 15, r = lane >> 4;
   constexpr int R2 = 2 * GQ;
   const int arow = m16 % R2;          // rows beyond 2*GQ repeat valid rows (their results are unused)
-
-  // ---- operand rows: q (hi/lo), q*step (hi/lo) per block, and the Key zeros ------------------------
-  wave_sync();                          // the previous mini-chunk is done with the shared storage
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float s0 = h2f_bits(R.ksp[i] & 0xFFFFu), s1 = h2f_bits(R.ksp[i] >> 16);
+  auto key_rows = [&](int i) {          // q*step (hi/lo per head) of block i
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
       uint32_t hi, lo;
-      split_pair(qaf[j][0] * s0, qaf[j][1] * s1, hi, lo);
-      ((uint32_t*)L.k.aop[i][2 * j])[lane] = hi;
-      ((uint32_t*)L.k.aop[i][2 * j + 1])[lane] = lo;
+      mul_split(qh[j], ql[j], as_half2(R.ksp[i]), hi, lo);
+      ((uint32_t*)L.k.aop[i & 1][2 * j])[lane] = hi;
+      ((uint32_t*)L.k.aop[i & 1][2 * j + 1])[lane] = lo;
     }
-    ((uint32_t*)L.k.zk[i])[lane] = R.ksz[i];
-  }
-  if (more) load_k_meta<BITS, NV>(R, P, mc_next, lane);
+  };
+
+  wave_sync();                          // the previous mini-chunk is done with the shared storage
+#pragma unroll
+  for (int i = 0; i < 4; ++i) ((uint32_t*)L.k.zk[i])[lane] = R.ksz[i];
+  key_rows(0);
   wave_sync();
 
   // ---- sum_c q_c z_c of the 4 blocks: column n of B = zeros of block n & 3 --------------------------
@@ -282,33 +298,46 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
       if (2 * r + 1 < GQ) L.qz[m16][(2 * r + 1) % GQ] = Dq[2] + Dq[3];
     }
   }
-  // ---- scores ------------------------------------------------------------------------------------
-  const float post_k = __builtin_amdgcn_exp2f((float)(24 - kShK));
+  // ---- scores (left in units of 2^-(24 - kShK); the softmax scales them) -----------------------------
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
+    if (i + 1 < 4) key_rows(i + 1);
+    if (i == 2 && more) load_k_meta<BITS, NV>(R, P, mc_next, lane);
     // both 16-token halves of the block share each operand row read
     float4v D0 = {0.f, 0.f, 0.f, 0.f}, D1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb) {
-      const half8 aq = lds_operand(L.k.aop[i][arow], cb * 64 + r * 16);
+      const half8 aq = lds_operand(L.k.aop[i & 1][arow], cb * 64 + r * 16);
       D0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq, field_operand<BITS>(R.kc[i], cb), D0, 0, 0, 0);
       D1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq, field_operand<BITS>(R.kc[i], 4 + cb), D1, 0, 0, 0);
     }
     const int tl = i * 32 + m16;
     if (2 * r < GQ) {
-      L.sc[2 * r][tl] = (D0[0] + D0[1]) * post_k;
-      L.sc[2 * r][tl + 16] = (D1[0] + D1[1]) * post_k;
+      L.sc[2 * r][tl] = D0[0] + D0[1];
+      L.sc[2 * r][tl + 16] = D1[0] + D1[1];
     }
     if (2 * r + 1 < GQ) {
-      L.sc[(2 * r + 1) % GQ][tl] = (D0[2] + D0[3]) * post_k;
-      L.sc[(2 * r + 1) % GQ][tl + 16] = (D1[2] + D1[3]) * post_k;
+      L.sc[(2 * r + 1) % GQ][tl] = D0[2] + D0[3];
+      L.sc[(2 * r + 1) % GQ][tl + 16] = D1[2] + D1[3];
     }
+    wave_sync();                        // the next block's rows, at last the scores, are visible
   }
   if (more) load_codes<BITS>(R.kc, P.kc, P, mc_next, lane);
-  wave_sync();                          // scores visible; every read of the score-phase rows is done
 
   // ---- softmax numerators of the 128 tokens against the running maximum; operand rows ---------------
+  half2v ph[GQ], pl[GQ];                // p of this lane's two tokens, hi + lo
+  half2v vs[NV];                        // their Value steps, scaled for the fp16 split
+  auto value_rows = [&](int jv) {       // p*step (hi/lo per head) of value group jv
+#pragma unroll
+    for (int j = 0; j < GQ; ++j) {
+      uint32_t hi, lo;
+      mul_split(ph[j], pl[j], vs[jv], hi, lo);
+      ((uint32_t*)L.v.ps[jv & 1][2 * j])[lane] = hi;
+      ((uint32_t*)L.v.ps[jv & 1][2 * j + 1])[lane] = lo;
+    }
+  };
   {
+    const float post_k = __builtin_amdgcn_exp2f((float)(24 - kShK));
     const int bi = lane >> 4;                         // block of this lane's tokens (2*lane, 2*lane+1)
     uint32_t mword = R.mkw;
     asm volatile("" : "+v"(mword) :: "memory");       // first use of the loaded word stays here
@@ -316,15 +345,17 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
     const int bit = (2 * lane) & 31;
     const bool ok0 = !((mword >> bit) & 1u);
     const bool ok1 = !((mword >> (bit + 1)) & 1u);
-    const float fv = __builtin_amdgcn_exp2f((float)(kShV - pair_pos<BITS>(lane & 3)));
+    const _Float16 fv = (_Float16)__builtin_amdgcn_exp2f((float)(kShV - pair_pos<BITS>(lane & 3)));
+#pragma unroll
+    for (int jv = 0; jv < NV; ++jv) vs[jv] = as_half2(R.vsp[jv]) * half2v{fv, fv};
     float alpha[GQ];
     bool rescale = false;
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
       const float2 s2 = *(const float2*)&L.sc[j][2 * lane];
       const float qz = L.qz[bi][j];
-      const float x0 = ok0 ? s2.x + qz : kNegBig;
-      const float x1 = ok1 ? s2.y + qz : kNegBig;
+      const float x0 = ok0 ? __builtin_fmaf(s2.x, post_k, qz) : kNegBig;
+      const float x1 = ok1 ? __builtin_fmaf(s2.y, post_k, qz) : kNegBig;
       const float mc = wave_max(fmaxf(x0, x1));
       const float m = fmaxf(S.m[j], mc);
       alpha[j] = __builtin_amdgcn_exp2f(S.m[j] - m);
@@ -336,17 +367,13 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
       split_pair(p0, p1, hi, lo);
       ((uint32_t*)L.v.pp[2 * j])[lane] = hi;
       ((uint32_t*)L.v.pp[2 * j + 1])[lane] = lo;
-      const float p0f = p0 * fv, p1f = p1 * fv;
-#pragma unroll
-      for (int jv = 0; jv < NV; ++jv) {
-        split_pair(p0f * h2f_bits(R.vsp[jv] & 0xFFFFu), p1f * h2f_bits(R.vsp[jv] >> 16), hi, lo);
-        ((uint32_t*)L.v.ps[jv][2 * j])[lane] = hi;
-        ((uint32_t*)L.v.ps[jv][2 * j + 1])[lane] = lo;
-      }
+      ph[j] = as_half2(hi);
+      pl[j] = as_half2(lo);
     }
 #pragma unroll
     for (int jv = 0; jv < NV; ++jv) ((uint32_t*)L.v.zv[jv])[lane] = R.vsz[jv];
     ((uint32_t*)L.v.zv[NV])[lane] = 0x3C003C00u;      // fp16 ones
+    value_rows(0);
     if (more) load_v_meta<BITS, NV>(R, P, mc_next, lane);
     // the running maximum moved (wave-uniform, rare after the first mini-chunks): rescale
     if (rescale) {
@@ -374,16 +401,20 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
   // ---- weighted values; sum_t p_t z_t and sum_t p_t ride along as one more product -------------------
   const int zrow = m16 < NV ? m16 : NV;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 4; ++i)
     S.Dz = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.v.pp[arow], i * 64 + r * 16),
                                                   lds_operand(L.v.zv[zrow], i * 64 + r * 16), S.Dz, 0, 0, 0);
 #pragma unroll
-    for (int jv = 0; jv < NV; ++jv) {                 // the channel tiles of one value group share an operand row
-      const half8 ap = lds_operand(L.v.ps[jv][arow], i * 64 + r * 16);
+  for (int jv = 0; jv < NV; ++jv) {
+    if (jv + 1 < NV) value_rows(jv + 1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {                     // the channel tiles of one value group share an operand row
+      const half8 ap = lds_operand(L.v.ps[jv & 1][arow], i * 64 + r * 16);
 #pragma unroll
       for (int ct = jv * (8 / NV); ct < (jv + 1) * (8 / NV); ++ct)
         S.O[ct] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ap, field_operand<BITS>(R.vc[i], ct), S.O[ct], 0, 0, 0);
     }
+    if (jv + 1 < NV) wave_sync();                     // the next value group's rows are visible
   }
   if (more) load_codes<BITS>(R.vc, P.vc, P, mc_next, lane);
 }
@@ -598,15 +629,18 @@ __global__ void __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_e
 #pragma unroll
   for (int j = 0; j < GQ; ++j) S.m[j] = kNegBig;
   if (has_q) {
-    float qaf[GQ][2];
+    // q of this lane's channel pair, scaled for the fp16 split of q*step, as hi + lo
+    half2v qh[GQ], ql[GQ];
     const float fs = __builtin_amdgcn_exp2f((float)(kShK - pair_pos<BITS>(lane & 3)));
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
-      qaf[j][0] = qa[j][0] * fs;
-      qaf[j][1] = qa[j][1] * fs;
+      uint32_t hi, lo;
+      split_pair(qa[j][0] * fs, qa[j][1] * fs, hi, lo);
+      qh[j] = as_half2(hi);
+      ql[j] = as_half2(lo);
     }
-    for (; mc + nw < mc_end; mc += nw) compute_minichunk<GQ, BITS, NV, true>(R, S, L, qaf, lane, P, mc + nw);
-    compute_minichunk<GQ, BITS, NV, false>(R, S, L, qaf, lane, P, mc);
+    for (; mc + nw < mc_end; mc += nw) compute_minichunk<GQ, BITS, NV, true>(R, S, L, qh, ql, lane, P, mc + nw);
+    compute_minichunk<GQ, BITS, NV, false>(R, S, L, qh, ql, lane, P, mc);
   }
   const float post_v = __builtin_amdgcn_exp2f((float)(24 - kShV));
 
