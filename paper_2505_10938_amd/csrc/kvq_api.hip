@@ -33,7 +33,7 @@ int64_t res_rows_of(const kvq_config* c) {
 // Split of one unit's decode work over wavefronts and workgroups.  Quantized tokens go in
 // mini-chunks of 128 (one wavefront each at a time), full-precision rows in groups of 16 that cost
 // about half a mini-chunk.  As many wavefronts are wanted over the whole launch as fit on the chip
-// at once (3 per SIMD by registers, fewer when a wavefront's LDS is large), no more per unit than
+// at once (2 per SIMD by registers, fewer if a wavefront's LDS were larger), no more per unit than
 // it has items; they form as few workgroups as fit (one workgroup per unit needs no exchange
 // through memory).
 struct Split {
@@ -46,7 +46,8 @@ Split decode_split(int64_t units_per_layer, int g, int vgroups, int64_t n_quant,
   int64_t items = mc + (rg + 1) / 2;
   if (items < 1) items = 1;
   int64_t waves_per_cu = kvq::kLdsPerComputeUnit / kvq::decode_wave_lds_bytes(g, vgroups);
-  if (waves_per_cu > kvq::kMaxWavesPerGroup) waves_per_cu = kvq::kMaxWavesPerGroup;
+  const int64_t by_registers = 4 * kvq::kDecodeWavesPerSimd;
+  if (waves_per_cu > by_registers) waves_per_cu = by_registers;
   if (waves_per_cu < 1) waves_per_cu = 1;
   int64_t wpu = kvq::kComputeUnits * waves_per_cu / units_per_layer;
   if (wpu > items) wpu = items;

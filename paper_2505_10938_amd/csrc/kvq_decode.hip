@@ -1,7 +1,7 @@
 // Decode-step attention (Eq. 1) over the quantized cache, the residual ring and the outlier
 // pools, for gfx950.  One kernel launch per call.
 //
-// Work split: grid = (splits, kv heads, batch), 1 to 12 wavefronts per workgroup.  The quantized
+// Work split: grid = (splits, kv heads, batch), 1 to 8 wavefronts per workgroup.  The quantized
 // tokens of a unit are cut into mini-chunks of 128 tokens (4 packed blocks).  A workgroup owns a
 // contiguous range of mini-chunks; its wavefronts take them round-robin, each keeping a running
 // (max, sum, weighted values) and loading its next mini-chunk into registers while it computes
@@ -520,11 +520,12 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
   }
 }
 
-// grid (splits, kv_heads, batch), 64 * a.nw threads, a.nw * sizeof(WaveLds) bytes of dynamic LDS
-constexpr int kMaxThreads = 64 * kMaxWavesPerGroup;
+// grid (splits, kv_heads * head_parts, batch), 64 * a.nw threads (a.nw at most what one compute unit
+// holds of this instance), a.nw * sizeof(WaveLds) bytes of dynamic LDS
 
 template <int GQ, int BITS, int NV>
-__global__ void __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(3))) decode_kernel(DecodeArgs a) {
+__global__ void __launch_bounds__(64 * 4 * kDecodeWavesPerSimd) __attribute__((amdgpu_waves_per_eu(kDecodeWavesPerSimd)))
+decode_kernel(DecodeArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_last;
   const Dims& d = a.d;
