@@ -49,31 +49,47 @@ __device__ inline void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Wave-wide reductions on the DPP path (no LDS traffic): 4 steps inside each row of 16 lanes,
-// then row 0->1, 2->3 and rows {0,1}->{2,3}; the total is in lane 63 and is broadcast from there.
-template <int CTRL, int ROW_MASK>
-__device__ inline float dpp_f(float old, float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, v),
-                                                               CTRL, ROW_MASK, 0xF, false));
-}
-__device__ inline float wave_max(float v) {
-  v = fmaxf(v, dpp_f<0xB1, 0xF>(v, v));    // quad_perm [1,0,3,2]
-  v = fmaxf(v, dpp_f<0x4E, 0xF>(v, v));    // quad_perm [2,3,0,1]
-  v = fmaxf(v, dpp_f<0x141, 0xF>(v, v));   // row_half_mirror
-  v = fmaxf(v, dpp_f<0x140, 0xF>(v, v));   // row_mirror
-  v = fmaxf(v, dpp_f<0x142, 0xA>(v, v));   // row_bcast:15 into rows 1 and 3
-  v = fmaxf(v, dpp_f<0x143, 0xC>(v, v));   // row_bcast:31 into rows 2 and 3
+// Wave-wide reductions on the DPP path (no LDS traffic), N values at once: 4 steps inside each row
+// of 16 lanes, then row 0->1, 2->3 and rows {0,1}->{2,3}; the totals are in lane 63 and are
+// broadcast from there.  Written as instructions, one per value and step, operating in place (the
+// compiler's own form takes four).  A DPP operand must not be read sooner than two issue slots
+// after it was written: with four values the other three chains fill the slots, with fewer an
+// s_nop does.  Lanes a step does not write (rows outside row_mask) keep their value.
+#define KVQ_DPP_CTRL0 "quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf"
+#define KVQ_DPP_CTRL1 "quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf"
+#define KVQ_DPP_CTRL2 "row_half_mirror row_mask:0xf bank_mask:0xf"
+#define KVQ_DPP_CTRL3 "row_mirror row_mask:0xf bank_mask:0xf"
+#define KVQ_DPP_CTRL4 "row_bcast:15 row_mask:0xa bank_mask:0xf"
+#define KVQ_DPP_CTRL5 "row_bcast:31 row_mask:0xc bank_mask:0xf"
+#define KVQ_DPP_STEP1(OP, C) "s_nop 1\n\t" OP " %0, %0, %0 " C "\n\t"
+#define KVQ_DPP_STEP2(OP, C) "s_nop 0\n\t" OP " %0, %0, %0 " C "\n\t" OP " %1, %1, %1 " C "\n\t"
+#define KVQ_DPP_STEP4(OP, C) \
+  OP " %0, %0, %0 " C "\n\t" OP " %1, %1, %1 " C "\n\t" OP " %2, %2, %2 " C "\n\t" OP " %3, %3, %3 " C "\n\t"
+#define KVQ_DPP_ALL(STEP, OP)                                                                               \
+  STEP(OP, KVQ_DPP_CTRL0) STEP(OP, KVQ_DPP_CTRL1) STEP(OP, KVQ_DPP_CTRL2) STEP(OP, KVQ_DPP_CTRL3) \
+  STEP(OP, KVQ_DPP_CTRL4) STEP(OP, KVQ_DPP_CTRL5)
+__device__ inline float from_lane63(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
-__device__ inline float wave_sum(float v) {
-  v += dpp_f<0xB1, 0xF>(0.f, v);
-  v += dpp_f<0x4E, 0xF>(0.f, v);
-  v += dpp_f<0x141, 0xF>(0.f, v);
-  v += dpp_f<0x140, 0xF>(0.f, v);
-  v += dpp_f<0x142, 0xA>(0.f, v);
-  v += dpp_f<0x143, 0xC>(0.f, v);
-  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-}
+#define KVQ_WAVE_REDUCE(NAME, OP)                                                                      \
+  __device__ inline void NAME(float (&v)[1]) {                                                         \
+    asm(KVQ_DPP_ALL(KVQ_DPP_STEP1, OP) : "+v"(v[0]));                                                  \
+    v[0] = from_lane63(v[0]);                                                                          \
+  }                                                                                                    \
+  __device__ inline void NAME(float (&v)[2]) {                                                         \
+    asm("s_nop 0\n\t" KVQ_DPP_ALL(KVQ_DPP_STEP2, OP) : "+v"(v[0]), "+v"(v[1]));                        \
+    v[0] = from_lane63(v[0]);                                                                          \
+    v[1] = from_lane63(v[1]);                                                                          \
+  }                                                                                                    \
+  __device__ inline void NAME(float (&v)[4]) {                                                         \
+    asm("s_nop 1\n\t" KVQ_DPP_ALL(KVQ_DPP_STEP4, OP) : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3])); \
+    v[0] = from_lane63(v[0]);                                                                          \
+    v[1] = from_lane63(v[1]);                                                                          \
+    v[2] = from_lane63(v[2]);                                                                          \
+    v[3] = from_lane63(v[3]);                                                                          \
+  }
+KVQ_WAVE_REDUCE(wave_max, "v_max_f32_dpp")
+KVQ_WAVE_REDUCE(wave_sum, "v_add_f32_dpp")
 
 // fp16 hi/lo split of two floats: hi = fp16(x) (toward zero), lo = fp16(x - hi); packed pairs.
 __device__ inline void split_pair(float x0, float x1, uint32_t& hi, uint32_t& lo) {
@@ -348,21 +364,25 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
     const _Float16 fv = (_Float16)__builtin_amdgcn_exp2f((float)(kShV - pair_pos<BITS>(lane & 3)));
 #pragma unroll
     for (int jv = 0; jv < NV; ++jv) vs[jv] = as_half2(R.vsp[jv]) * half2v{fv, fv};
-    float alpha[GQ];
+    float alpha[GQ], x0[GQ], x1[GQ], mx[GQ];
     bool rescale = false;
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
       const float2 s2 = *(const float2*)&L.sc[j][2 * lane];
       const float qz = L.qz[bi][j];
-      const float x0 = ok0 ? __builtin_fmaf(s2.x, post_k, qz) : kNegBig;
-      const float x1 = ok1 ? __builtin_fmaf(s2.y, post_k, qz) : kNegBig;
-      const float mc = wave_max(fmaxf(x0, x1));
-      const float m = fmaxf(S.m[j], mc);
+      x0[j] = ok0 ? __builtin_fmaf(s2.x, post_k, qz) : kNegBig;
+      x1[j] = ok1 ? __builtin_fmaf(s2.y, post_k, qz) : kNegBig;
+      mx[j] = fmaxf(x0[j], x1[j]);
+    }
+    wave_max(mx);
+#pragma unroll
+    for (int j = 0; j < GQ; ++j) {
+      const float m = fmaxf(S.m[j], mx[j]);
       alpha[j] = __builtin_amdgcn_exp2f(S.m[j] - m);
       rescale |= m > S.m[j];
       S.m[j] = m;
-      const float p0 = ok0 ? __builtin_amdgcn_exp2f(x0 - m) : 0.f;
-      const float p1 = ok1 ? __builtin_amdgcn_exp2f(x1 - m) : 0.f;
+      const float p0 = ok0 ? __builtin_amdgcn_exp2f(x0[j] - m) : 0.f;
+      const float p1 = ok1 ? __builtin_amdgcn_exp2f(x1[j] - m) : 0.f;
       uint32_t hi, lo;
       split_pair(p0, p1, hi, lo);
       ((uint32_t*)L.v.pp[2 * j])[lane] = hi;
@@ -489,18 +509,22 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
   if (2 * r < GQ) L.sc[2 * r][m16] = okk ? D[0] + D[1] : kNegBig;
   if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][m16] = okk ? D[2] + D[3] : kNegBig;
   wave_sync();
-  float alpha[GQ];
+  float alpha[GQ], x[GQ], red[GQ];
+#pragma unroll
+  for (int j = 0; j < GQ; ++j) red[j] = x[j] = L.sc[j][lane & 15];   // every lane: the 16 scores, 4 times over
+  wave_max(red);
 #pragma unroll
   for (int j = 0; j < GQ; ++j) {
-    const float x = L.sc[j][lane & 15];                            // every lane: the 16 scores, 4 times over
-    const float mg = wave_max(x);
-    const float m = fmaxf(F.m[j], mg);
+    const float m = fmaxf(F.m[j], red[j]);
     alpha[j] = __builtin_amdgcn_exp2f(F.m[j] - m);
     F.m[j] = m;
-    const float p = x > 0.5f * kNegBig ? __builtin_amdgcn_exp2f(x - m) : 0.f;
-    F.l[j] = F.l[j] * alpha[j] + wave_sum(lane < 16 ? p : 0.f);
-    if (lane < 16) L.sc[j][16 + lane] = p;
+    x[j] = x[j] > 0.5f * kNegBig ? __builtin_amdgcn_exp2f(x[j] - m) : 0.f;   // now p
+    red[j] = lane < 16 ? x[j] : 0.f;
+    if (lane < 16) L.sc[j][16 + lane] = x[j];
   }
+  wave_sum(red);
+#pragma unroll
+  for (int j = 0; j < GQ; ++j) F.l[j] = F.l[j] * alpha[j] + red[j];
   wave_sync();
 #pragma unroll
   for (int j = 0; j < GQ; ++j) {
