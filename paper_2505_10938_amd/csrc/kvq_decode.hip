@@ -209,6 +209,7 @@ struct UnitPtrs {
   const unsigned char* vm;    // Value meta
   const unsigned char* mask;
   int nblocks;                // quantized blocks of the unit
+  int last_block;             // the last of them (0 if there is none: the cache holds at least one block)
   int bpg_shift;
   uint32_t block_bytes;
 };
@@ -225,7 +226,7 @@ __device__ __forceinline__ void load_k_meta(McRegs<BITS, NV>& R, const UnitPtrs&
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     // uniform base (scalar registers) + one lane offset shared by all loads
-    const unsigned char* gp = P.km + ((uint32_t)min(mc * 4 + i, P.nblocks - 1) >> P.bpg_shift) * 512u;
+    const unsigned char* gp = P.km + ((uint32_t)min(mc * 4 + i, P.last_block) >> P.bpg_shift) * 512u;
     R.ksp[i] = ld<uint32_t>(gp, lane * 4u);
     R.ksz[i] = ld<uint32_t>(gp + 256, lane * 4u);
   }
@@ -235,7 +236,7 @@ __device__ __forceinline__ void load_codes(uint32_t (&w)[4][2 * BITS], const uns
                                            int mc, int lane) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const unsigned char* bp = codes + (uint32_t)min(mc * 4 + i, P.nblocks - 1) * P.block_bytes;   // uniform
+    const unsigned char* bp = codes + (uint32_t)min(mc * 4 + i, P.last_block) * P.block_bytes;   // uniform
 #pragma unroll
     for (int hf = 0; hf < BITS / 2; ++hf) {
       const uint4 t = ld<uint4>(bp + hf * 1024, lane * 16u);
@@ -250,7 +251,7 @@ template <int BITS, int NV>
 __device__ __forceinline__ void load_v_meta(McRegs<BITS, NV>& R, const UnitPtrs& P, int mc, int lane) {
   // this lane's tokens are 2*lane, 2*lane+1 of the 128: pair lane&15 of block lane>>4
   const int myblk = mc * 4 + (lane >> 4);
-  const uint32_t blk = (uint32_t)min(myblk, P.nblocks - 1);
+  const uint32_t blk = (uint32_t)min(myblk, P.last_block);
   // the loaded word is not touched here: any use would make this point wait for the load
   R.mkw = ld<uint32_t>(P.mask, blk * 4u);
   R.mk_valid = myblk < P.nblocks;
@@ -553,6 +554,14 @@ decode_kernel(DecodeArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_last;
   const Dims& d = a.d;
+  // Every argument the loads below depend on is fetched here, in one round trip (left to
+  // itself the compiler fetches an argument where it is first used, and each such place waits
+  // for everything that is in flight on the scalar side).
+  asm volatile("" ::"s"(a.nw), "s"(a.splits), "s"(a.head_parts), "s"(a.mc_per_split), "s"(a.n_quant), "s"(a.res_start),
+               "s"(a.n_res), "s"(d.kv_heads), "s"(d.q_heads), "s"(d.unit0), "s"(d.pool_slots), "s"(d.res_rows), "s"(d.N),
+               "s"(d.bpg_shift), "s"(d.block_bytes), "s"(d.blocks_per_unit), "s"(d.groups_per_unit), "s"(a.q),
+               "s"(a.k_codes), "s"(a.k_meta), "s"(a.v_codes), "s"(a.v_meta), "s"(a.mask), "s"(a.k_res), "s"(a.v_res),
+               "s"(a.pool_k), "s"(a.pool_v), "s"(a.pool_count), "s"(a.aux_count));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -586,16 +595,23 @@ decode_kernel(DecodeArgs a) {
   const int unit_waves = n_splits * nw;
   int rg = unit_waves - 1 - (split * nw + wave);
   const bool has_fp = rg < n_rg;                         // uniform over the wave
-  int n_pool = 0, n_aux = 0;
+  // The unit's slot counts come through the vector memory path, ahead of the rows they qualify:
+  // a scalar load in flight would hold up the next wait on the scalar side, which comes before
+  // the quantized loads below.
+  // Every wavefront issues the same loads, whether or not it has rows or a mini-chunk to work on
+  // (the loaders fall back on addresses that are always valid: the query row, the unit's last
+  // block): only then are the loads in flight the same on every path, and only then can the
+  // waits leave the younger ones in flight.
   FpRegs X;
-  if (has_fp) {
-    n_pool = a.pool_count[u];
-    n_aux = a.aux_count[u];
-    fp_load(X, a, u, qbase, rg * 16, lane);
-  }
+  int64_t uv = u;
+  asm("" : "+v"(uv));                                    // a vector address: a vector load
+  int n_pool = a.pool_count[uv];
+  int n_aux = a.aux_count[uv];
+  fp_load(X, a, u, qbase, rg * 16, lane);
 
   UnitPtrs P;
   P.nblocks = a.n_quant >> 5;
+  P.last_block = max(P.nblocks - 1, 0);
   P.bpg_shift = d.bpg_shift;
   P.block_bytes = (uint32_t)d.block_bytes;
   P.kc = a.k_codes + u * d.blocks_per_unit * (int64_t)d.block_bytes;
@@ -608,12 +624,10 @@ decode_kernel(DecodeArgs a) {
   int mc = split * a.mc_per_split + wave;
   const bool has_q = mc < mc_end;                        // uniform over the wave
   McRegs<BITS, NV> R;
-  if (has_q) {
-    load_k_meta<BITS, NV>(R, P, mc, lane);
-    load_codes<BITS>(R.kc, P.kc, P, mc, lane);
-    load_v_meta<BITS, NV>(R, P, mc, lane);
-    load_codes<BITS>(R.vc, P.vc, P, mc, lane);
-  }
+  load_k_meta<BITS, NV>(R, P, mc, lane);
+  load_codes<BITS>(R.kc, P.kc, P, mc, lane);
+  load_v_meta<BITS, NV>(R, P, mc, lane);
+  load_codes<BITS>(R.vc, P.vc, P, mc, lane);
 
   // this lane's two channels (2*lane, 2*lane+1) of every query head, log2-domain scaled
   float qa[GQ][2];
@@ -640,6 +654,8 @@ decode_kernel(DecodeArgs a) {
   }
   wave_sync();
   if (has_fp) {
+    n_pool = __builtin_amdgcn_readfirstlane(n_pool);
+    n_aux = __builtin_amdgcn_readfirstlane(n_aux);
     fp_compute<GQ, NV>(X, F, L, a, n_pool, n_aux, lane);
     for (rg += unit_waves; rg < n_rg; rg += unit_waves) {          // further groups (short quantized segment)
       fp_load(X, a, u, qbase, rg * 16, lane);
