@@ -24,7 +24,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, vendor figure
 # HBM bytes per decode launch from the FETCH_SIZE / WRITE_SIZE counters, scaled by what the same
 # counters read for a plain device copy of known size (profiles/decode_kernel_<workload>.md).
-MEASURED_TRAFFIC = {"llama2_7b_4k": 120_200_000}
+MEASURED_TRAFFIC = {"llama2_7b_4k": 120_320_000}
 
 
 def algorithmic_bytes(w, n_quant, n_res, pool_rows):
@@ -238,7 +238,7 @@ def main():
                 st.append_group(K[b, h, i * G:(i + 1) * G], V[b, h, i * G:(i + 1) * G])
             states.append(st)
         import copy
-        ctx = threadpool_limits(limits=1) if threadpool_limits else None
+        tp_limit = threadpool_limits(limits=1) if threadpool_limits else None
         t_cpu, reps_cpu, ref = 0.0, 0, None
         while t_cpu < 12.0 and reps_cpu < 400:
             sts = copy.deepcopy(states)
@@ -251,8 +251,8 @@ def main():
                 ref.append(o)
             t_cpu += time.perf_counter() - t1
             reps_cpu += 1
-        if ctx is not None:
-            ctx.__exit__(None, None, None)
+        if tp_limit is not None:
+            tp_limit.__exit__(None, None, None)
         cpu_step_s = t_cpu / reps_cpu
         got = outs[-1].cpu().numpy().astype(np.float64)
         err = max(float(np.abs(got[b, h * g:(h + 1) * g] - o).max()) for (b, h), o in zip(units, ref))
