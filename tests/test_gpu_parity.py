@@ -48,6 +48,13 @@ def test_gqa_ratios(g):
     run_case(small(f"g{g}", q_heads=2 * g, context=1500))
 
 
+@pytest.mark.parametrize("g", [4, 8])
+@pytest.mark.parametrize("Gv", [32, 64, 128])
+def test_gqa_ratios_four_bit(g, Gv):
+    # the kernel instances of four query heads per workgroup row with 4-bit codes (g = 8: two rows)
+    run_case(small(f"g{g}b4v{Gv}", q_heads=2 * g, bits=4, group_v=Gv, context=1500))
+
+
 @pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("G,Gv,R,N", [(32, 32, 128, 8), (64, 64, 32, 3), (128, 128, 32, 3), (32, 128, 0, 4)])
 def test_hyper_parameter_grid(bits, G, Gv, R, N):
@@ -104,7 +111,7 @@ def run_sampled(w: S.Workload, units, regimes=("peaky", "diffuse")):
 
 
 def test_full_size_llama2_7b_4k_sampled_units():
-    # the benchmark workload in the benchmark's launch shape (one workgroup of 12 wavefronts per unit)
+    # the benchmark workload in the benchmark's launch shape (one workgroup of 8 wavefronts per unit)
     w = S.WORKLOADS["llama2_7b_4k"]
     run_sampled(w, [0, 37, 130, 255])
 
@@ -113,6 +120,21 @@ def test_full_size_long_32k_sampled_units():
     # long context, grouped queries, N = G: several workgroups per unit and the last-arrival merge
     w = S.WORKLOADS["long_32k"]
     run_sampled(w, [0, 31], regimes=("peaky",))
+
+
+def test_full_size_llama3_8b_8k_sampled_units():
+    # grouped queries at batch 16, context 8192: two workgroups per unit, four query heads each
+    w = S.WORKLOADS["llama3_8b_8k_stream"]
+    run_sampled(w, [0, 77, 127], regimes=("peaky",))
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_batch_128_layer_shape_sampled_units(bits):
+    # the 32-layer configuration's layer shape (8 kv heads, 4 query heads each, 2 wavefronts per
+    # unit) at a quarter of its batch and a shorter context
+    w = S.WORKLOADS["mistral_7b_b128_4k_layer"].with_(name=f"b32_layer_{bits}bit", batch=32, context=1024 + 128,
+                                                      bits=bits)
+    run_sampled(w, [0, 100, 255], regimes=("peaky",))
 
 
 def test_four_bit_full_batch_sampled_units():
