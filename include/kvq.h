@@ -230,6 +230,44 @@ int32_t kvq_append_trace_quantize(const kvq_config* cfg, int32_t layer, const vo
                                   kvq_pool pool, uint8_t* selected, kvq_qcache qcache, void* stream);
 
 /*
+ * Batches whose sequences differ in length (the paper's runs use one length per batch; a serving
+ * loop does not).  The per-sequence state lives in device memory so that a step needs no host
+ * decision:
+ *   seq_state : device int32 [batch][4], 16-byte aligned: {n_quant, res_start, n_res, active} of
+ *               each sequence, with the meanings and invariants of the uniform calls (n_quant a
+ *               multiple of group_k; res_start a multiple of group_k below res_rows; n_res <
+ *               residual + group_k between steps).  A sequence with active == 0 is skipped by
+ *               kvq_append_trace_quantize_ragged and kvq_seq_advance.
+ * The kernels clamp what they read to the buffers' sizes, so a corrupt array gives wrong results
+ * for its sequence but no access outside the buffers.
+ *
+ * kvq_append_trace_quantize_ragged: one decode step's cache update of one layer, in one launch.
+ * Every active sequence's new row (k_new, v_new as in kvq_append_residual) is appended to its ring;
+ * the sequences whose ring is full with it (n_res + 1 == residual + group_k, and n_quant + group_k
+ * <= max_seq) have their oldest group traced and quantized as in kvq_append_trace_quantize.
+ * seq_state is read only: call it for every layer with the same array, then kvq_seq_advance once.
+ *   selected : device uint8 [batch*kv_heads][G] or NULL; written only for sequences that quantized
+ *
+ * kvq_seq_advance: applies the same rule to the array itself: n_res + 1, and where the ring filled,
+ * n_quant + group_k, res_start + group_k (mod res_rows), n_res - group_k.
+ *
+ * kvq_decode_attention_ragged: kvq_decode_attention with each sequence's own state.
+ *   max_n_quant : upper bound of the sequences' n_quant, a multiple of group_k, <= max_seq
+ *   max_n_res   : upper bound of the sequences' n_res, <= res_rows; max_n_quant + max_n_res >= 1
+ *                 (the two bounds size the launch; a longer sequence is truncated to them).  A
+ *                 sequence with no token at all gets an all-zero output row.
+ *   other arguments, workspace and errors as kvq_decode_attention.
+ */
+int32_t kvq_append_trace_quantize_ragged(const kvq_config* cfg, int32_t layer, const void* k_new,
+                                         const void* v_new, kvq_residual res, const int32_t* seq_state,
+                                         kvq_pool pool, uint8_t* selected, kvq_qcache qcache, void* stream);
+int32_t kvq_seq_advance(const kvq_config* cfg, int32_t* seq_state, void* stream);
+int32_t kvq_decode_attention_ragged(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qcache,
+                                    kvq_residual res, const int32_t* seq_state, int32_t max_n_quant,
+                                    int32_t max_n_res, kvq_pool pool, void* out, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid, not part of the method: read `bytes` bytes (a multiple of 16) of device memory
  * at `buf` (16-byte aligned) once with 16-byte loads, in one launch that fills the chip, and fold
  * them into the 4 bytes at `sink` (device).  The benchmark times it over a buffer larger than the

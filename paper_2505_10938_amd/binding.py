@@ -17,7 +17,9 @@ LIB_PATH = os.path.join(HERE, "libkvq.so")
 KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
-           "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_decode_attention", "kvq_stream_read", "kvq_status_string", "kvq_version"]
+           "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_decode_attention",
+           "kvq_append_trace_quantize_ragged", "kvq_seq_advance", "kvq_decode_attention_ragged", "kvq_stream_read",
+           "kvq_status_string", "kvq_version"]
 
 
 class kvq_config(C.Structure):
@@ -86,6 +88,13 @@ def load_library() -> C.CDLL:
     lib.kvq_decode_attention.restype = i32
     lib.kvq_decode_attention.argtypes = [cfgp, i32, vp, kvq_qcache, i32, kvq_residual, i32, i32, kvq_pool,
                                          vp, vp, C.c_size_t, vp]
+    lib.kvq_append_trace_quantize_ragged.restype = i32
+    lib.kvq_append_trace_quantize_ragged.argtypes = [cfgp, i32, vp, vp, kvq_residual, vp, kvq_pool, vp, kvq_qcache, vp]
+    lib.kvq_seq_advance.restype = i32
+    lib.kvq_seq_advance.argtypes = [cfgp, vp, vp]
+    lib.kvq_decode_attention_ragged.restype = i32
+    lib.kvq_decode_attention_ragged.argtypes = [cfgp, i32, vp, kvq_qcache, kvq_residual, vp, i32, i32, kvq_pool,
+                                                vp, vp, C.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -161,6 +170,30 @@ def kvq_prefill_quantize(cfg, layer, k_rows, v_rows, unit_stride, n_tokens, pool
                                              pool, _ptr(selected), qcache, res, _stream(stream))
     if st != KVQ_OK:
         raise KvqError(st, "kvq_prefill_quantize")
+
+
+def kvq_append_trace_quantize_ragged(cfg, layer, k_new, v_new, res: kvq_residual, seq_state, pool: kvq_pool, selected,
+                                     qcache: kvq_qcache, stream=None):
+    st = load_library().kvq_append_trace_quantize_ragged(C.byref(cfg), layer, _ptr(k_new), _ptr(v_new), res,
+                                                         _ptr(seq_state), pool, _ptr(selected), qcache,
+                                                         _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_append_trace_quantize_ragged")
+
+
+def kvq_seq_advance(cfg, seq_state, stream=None):
+    st = load_library().kvq_seq_advance(C.byref(cfg), _ptr(seq_state), _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_seq_advance")
+
+
+def kvq_decode_attention_ragged(cfg, layer, q, qcache: kvq_qcache, res: kvq_residual, seq_state, max_n_quant,
+                                max_n_res, pool: kvq_pool, out, workspace, workspace_bytes, stream=None):
+    st = load_library().kvq_decode_attention_ragged(C.byref(cfg), layer, _ptr(q), qcache, res, _ptr(seq_state),
+                                                    max_n_quant, max_n_res, pool, _ptr(out), _ptr(workspace),
+                                                    workspace_bytes, _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_decode_attention_ragged")
 
 
 def kvq_stream_read(buf, nbytes, sink, stream=None):

@@ -154,3 +154,45 @@ class KVCache:
         other.n_quant, other.res_start, other.n_res = list(self.n_quant), list(self.res_start), list(self.n_res)
         other.prefill_selected = None
         return other
+
+
+class RaggedKVCache(KVCache):
+    """A cache whose sequences differ in length.  The per-sequence state {n_quant, res_start,
+    n_res, active} is a device array that the library reads and advances; the host keeps only
+    an upper bound of the longest sequence, which sizes the decode launch."""
+
+    def __init__(self, cfg: B.kvq_config, device="cuda:0"):
+        super().__init__(cfg, device)
+        self.seq_state = torch.zeros(cfg.batch, 4, dtype=torch.int32, device=self.device)
+        self.longest = 0                                  # tokens of the longest sequence, at most
+
+    def set_active(self, active):
+        """active: bool / int tensor or list [batch]: the sequences that take part in the next steps."""
+        self.seq_state[:, 3] = torch.as_tensor(active, device=self.device).to(torch.int32)
+
+    def append(self, layer, k_new, v_new, stream=None):
+        """One token per active sequence (fp16 [batch, kv_heads, head_dim] each; rows of inactive
+        sequences are ignored) into `layer`; sequences whose ring fills have their oldest group
+        traced and quantized in the same launch.  Call for every layer, then advance()."""
+        B.kvq_append_trace_quantize_ragged(self.cfg, layer, k_new, v_new, self.res, self.seq_state, self.pool, None,
+                                           self.qcache, stream)
+
+    def advance(self, stream=None):
+        """The sequences' states after the token just appended to every layer."""
+        B.kvq_seq_advance(self.cfg, self.seq_state, stream)
+        self.longest += 1
+
+    def bounds(self):
+        """(max_n_quant, max_n_res) over all sequences, from the host's bound of the longest one."""
+        G, R = self.cfg.group_k, self.cfg.residual
+        n = self.longest
+        nq = G * ((n - R) // G) if n >= R + G else 0
+        return min(nq, self.cfg.max_seq), min(n, R + G - 1)
+
+    def decode(self, layer, q, out=None, stream=None):
+        if out is None:
+            out = torch.empty_like(q)
+        nq, nr = self.bounds()
+        B.kvq_decode_attention_ragged(self.cfg, layer, q, self.qcache, self.res, self.seq_state, nq, nr, self.pool, out,
+                                      self.workspace, self.workspace.numel(), stream)
+        return out

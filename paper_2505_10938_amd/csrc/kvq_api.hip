@@ -75,6 +75,7 @@ Dims make_dims(const kvq_config* c, int32_t layer) {
   d.A = c->aux_capacity;
   d.max_seq = c->max_seq;
   d.res_rows = (int32_t)res_rows_of(c);
+  d.R = c->residual;
   d.pool_slots = c->outlier_budget + c->aux_capacity;
   d.units_per_layer = c->batch * c->kv_heads;
   d.unit0 = (int64_t)layer * d.units_per_layer;
@@ -266,12 +267,42 @@ int32_t kvq_append_trace_quantize(const kvq_config* cfg, int32_t layer, const vo
   const Dims d = make_dims(cfg, layer);
   return from_hip(kvq::launch_group_step(d, n_quant / G, (const __half*)k_new, (const __half*)v_new,
                                          (__half*)res.k_res, (__half*)res.v_res, (res_start + n_res) % rows,
-                                         res_start, pool, selected, qc, (hipStream_t)stream));
+                                         res_start, nullptr, pool, selected, qc, (hipStream_t)stream));
 }
 
-int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc, int32_t n_quant,
-                             kvq_residual res, int32_t res_start, int32_t n_res, kvq_pool pool, void* out,
-                             void* workspace, size_t workspace_bytes, void* stream) {
+int32_t kvq_append_trace_quantize_ragged(const kvq_config* cfg, int32_t layer, const void* k_new, const void* v_new,
+                                         kvq_residual res, const int32_t* seq_state, kvq_pool pool,
+                                         uint8_t* selected, kvq_qcache qc, void* stream) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
+  if (!k_new || !v_new || !res.k_res || !res.v_res || !seq_state) return KVQ_ERR_INVALID_ARG;
+  if (((uintptr_t)seq_state) & 15) return KVQ_ERR_INVALID_ARG;
+  if (!pool.pool_count || !pool.aux_count || !pool.frozen) return KVQ_ERR_INVALID_ARG;
+  if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v || !pool.pool_idx || !pool.pool_score))
+    return KVQ_ERR_INVALID_ARG;
+  if (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask) return KVQ_ERR_INVALID_ARG;
+  if ((((uintptr_t)res.k_res) | ((uintptr_t)res.v_res)) & 15) return KVQ_ERR_INVALID_ARG;
+  const Dims d = make_dims(cfg, layer);
+  return from_hip(kvq::launch_group_step(d, 0, (const __half*)k_new, (const __half*)v_new, (__half*)res.k_res,
+                                         (__half*)res.v_res, 0, 0, seq_state, pool, selected, qc,
+                                         (hipStream_t)stream));
+}
+
+int32_t kvq_seq_advance(const kvq_config* cfg, int32_t* seq_state, void* stream) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  if (!seq_state || (((uintptr_t)seq_state) & 15)) return KVQ_ERR_INVALID_ARG;
+  return from_hip(kvq::launch_seq_advance(make_dims(cfg, 0), seq_state, (hipStream_t)stream));
+}
+
+namespace {
+
+// The decode launch, shared by the two entry points: `seq_state` null = every sequence has the
+// state given; otherwise n_quant and n_res are upper bounds and each sequence brings its own.
+int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc, int32_t n_quant,
+                      kvq_residual res, int32_t res_start, int32_t n_res, const int32_t* seq_state, kvq_pool pool,
+                      void* out, void* workspace, size_t workspace_bytes, void* stream) {
   const int32_t st = check_config(cfg);
   if (st != KVQ_OK) return st;
   if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
@@ -310,6 +341,7 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
   a.n_quant = n_quant;
   a.res_start = res_start;
   a.n_res = n_res;
+  a.seq = seq_state;
   a.head_parts = head_parts_of(a.d.g);
   const Split sp = decode_split((int64_t)a.d.units_per_layer * a.head_parts, a.d.g / a.head_parts, a.d.vgroups, n_quant,
                                 (int64_t)n_res + a.d.pool_slots);
@@ -317,6 +349,26 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
   a.nw = sp.nw;
   a.mc_per_split = sp.mc_per_split;
   return from_hip(kvq::launch_decode(a, (hipStream_t)stream));
+}
+
+}  // namespace
+
+int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc, int32_t n_quant,
+                             kvq_residual res, int32_t res_start, int32_t n_res, kvq_pool pool, void* out,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_common(cfg, layer, q, qc, n_quant, res, res_start, n_res, nullptr, pool, out, workspace,
+                       workspace_bytes, stream);
+}
+
+int32_t kvq_decode_attention_ragged(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc,
+                                    kvq_residual res, const int32_t* seq_state, int32_t max_n_quant,
+                                    int32_t max_n_res, kvq_pool pool, void* out, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  if (!seq_state || (((uintptr_t)seq_state) & 15)) return KVQ_ERR_INVALID_ARG;
+  if (max_n_quant > 0 && (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask))
+    return KVQ_ERR_INVALID_ARG;
+  return decode_common(cfg, layer, q, qc, max_n_quant, res, 0, max_n_res, seq_state, pool, out, workspace,
+                       workspace_bytes, stream);
 }
 
 }  // extern "C"

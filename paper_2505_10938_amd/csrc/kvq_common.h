@@ -26,6 +26,7 @@ struct Dims {
   int32_t batch, q_heads, kv_heads, g;       // g = q_heads / kv_heads
   int32_t bits, G, Gv, N, A;
   int32_t max_seq, res_rows, pool_slots;
+  int32_t R;                                  // residual length (the ring is full at R + G rows)
   int32_t units_per_layer;                    // batch * kv_heads
   int64_t unit0;                              // first unit of the layer being processed
   int32_t block_bytes;                        // 512 * bits
@@ -52,7 +53,8 @@ struct DecodeArgs {
   __half* out;
   float* partials;      // [units_per_layer][splits][g][head_dim + 2]
   int32_t* counters;    // [units_per_layer], zero on entry and on exit
-  int32_t n_quant, res_start, n_res;
+  int32_t n_quant, res_start, n_res;   // the batch's state; with `seq`, upper bounds of n_quant and n_res
+  const int32_t* seq;   // per-sequence state [batch][4] = {n_quant, res_start, n_res, active}, or null
   int32_t splits;       // workgroups per unit
   int32_t nw;           // wavefronts per workgroup
   int32_t head_parts;   // workgroup rows that share a kv head's query heads (1, or 2 when g = 8)
@@ -71,8 +73,9 @@ hipError_t launch_prefill_trace(const Dims& d, int32_t n_groups, const __half* k
 hipError_t launch_tail_copy(const Dims& d, const __half* k_rows, const __half* v_rows, int64_t unit_stride, int32_t n0,
                             int32_t n, __half* k_res, __half* v_res, hipStream_t s);
 hipError_t launch_group_step(const Dims& d, int32_t group_index, const __half* k_new, const __half* v_new, __half* k_res,
-                             __half* v_res, int32_t append_row, int32_t group_row0, const kvq_pool& pool,
-                             uint8_t* selected, const kvq_qcache& qc, hipStream_t s);
+                             __half* v_res, int32_t append_row, int32_t group_row0, const int32_t* seq,
+                             const kvq_pool& pool, uint8_t* selected, const kvq_qcache& qc, hipStream_t s);
+hipError_t launch_seq_advance(const Dims& d, int32_t* seq, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
 int decode_wave_lds_bytes(int g, int vgroups);   // LDS one decode wavefront needs
 

@@ -449,6 +449,11 @@ struct FpAcc {
   float o[GQ][2];
 };
 
+// The state of the sequence a workgroup works on: the batch's (kernel arguments), or its own.
+struct Seq {
+  int n_quant, res_start, n_res;
+};
+
 struct FpRegs {
   uint4 kf[4];       // K row of token row0 + (lane & 15): channels 32cb + 8(lane >> 4) ..
   uint32_t vw[16];   // V rows of the 16 tokens: this lane's channel pair
@@ -458,8 +463,8 @@ struct FpRegs {
 // Issue the loads of one group of 16 full-precision rows.  Every pool slot is read, filled or
 // not (the slot counts are looked at only when the data is used, so that these loads do not wait
 // for them); a row past the last slot reads the query row instead (always valid memory).
-__device__ __forceinline__ void fp_load(FpRegs& X, const DecodeArgs& a, int64_t u, const __half* qbase, int row0,
-                                        int lane) {
+__device__ __forceinline__ void fp_load(FpRegs& X, const DecodeArgs& a, const Seq& sq, int64_t u, const __half* qbase,
+                                        int row0, int lane) {
   const Dims& d = a.d;
   const int m16 = lane & 15, r = lane >> 4;
   const __half* kres = a.k_res + u * d.res_rows * kHeadDim;
@@ -467,10 +472,10 @@ __device__ __forceinline__ void fp_load(FpRegs& X, const DecodeArgs& a, int64_t 
   const __half* kpool = a.pool_k + u * d.pool_slots * kHeadDim;
   const __half* vpool = a.pool_v + u * d.pool_slots * kHeadDim;
   auto locate = [&](int row, const __half*& kp, const __half*& vp) {
-    const bool in_res = row < a.n_res;
-    int ring = a.res_start + row;
+    const bool in_res = row < sq.n_res;
+    int ring = sq.res_start + row;
     ring -= ring >= d.res_rows ? d.res_rows : 0;
-    const int slot = row - a.n_res;
+    const int slot = row - sq.n_res;
     const bool in_pool = slot < d.pool_slots;
     kp = in_res ? kres + ring * kHeadDim : (in_pool ? kpool + slot * kHeadDim : qbase);
     vp = in_res ? vres + ring * kHeadDim : (in_pool ? vpool + slot * kHeadDim : qbase);
@@ -489,16 +494,16 @@ __device__ __forceinline__ void fp_load(FpRegs& X, const DecodeArgs& a, int64_t 
 }
 
 // Does full-precision row `row` of the unit hold a token?
-__device__ __forceinline__ bool fp_row_ok(const DecodeArgs& a, int row, int n_pool, int n_aux) {
-  const int slot = row - a.n_res;
-  return row < a.n_res || (slot < a.d.N ? (slot < n_pool) : (slot < a.d.pool_slots && slot - a.d.N < n_aux));
+__device__ __forceinline__ bool fp_row_ok(const DecodeArgs& a, const Seq& sq, int row, int n_pool, int n_aux) {
+  const int slot = row - sq.n_res;
+  return row < sq.n_res || (slot < a.d.N ? (slot < n_pool) : (slot < a.d.pool_slots && slot - a.d.N < n_aux));
 }
 
 template <int GQ, int NV>
 __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, NV>& L, const DecodeArgs& a,
-                                           int n_pool, int n_aux, int lane) {
+                                           const Seq& sq, int n_pool, int n_aux, int lane) {
   const int m16 = lane & 15, r = lane >> 4;
-  const bool okk = fp_row_ok(a, X.row0 + m16, n_pool, n_aux);
+  const bool okk = fp_row_ok(a, sq, X.row0 + m16, n_pool, n_aux);
   constexpr int R2 = 2 * GQ;
   const int arow = m16 % R2;
   float4v D = {0.f, 0.f, 0.f, 0.f};
@@ -534,7 +539,7 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
   }
 #pragma unroll
   for (int t = 0; t < 16; ++t) {
-    const uint32_t vw = fp_row_ok(a, X.row0 + t, n_pool, n_aux) ? X.vw[t] : 0u;   // uniform; an empty slot may hold anything
+    const uint32_t vw = fp_row_ok(a, sq, X.row0 + t, n_pool, n_aux) ? X.vw[t] : 0u;   // uniform; an empty slot may hold anything
     const float v0 = h2f_bits(vw & 0xFFFFu), v1 = h2f_bits(vw >> 16);
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
@@ -561,7 +566,7 @@ decode_kernel(DecodeArgs a) {
                "s"(a.n_res), "s"(d.kv_heads), "s"(d.q_heads), "s"(d.unit0), "s"(d.pool_slots), "s"(d.res_rows), "s"(d.N),
                "s"(d.bpg_shift), "s"(d.block_bytes), "s"(d.blocks_per_unit), "s"(d.groups_per_unit), "s"(a.q),
                "s"(a.k_codes), "s"(a.k_meta), "s"(a.v_codes), "s"(a.v_meta), "s"(a.mask), "s"(a.k_res), "s"(a.v_res),
-               "s"(a.pool_k), "s"(a.pool_v), "s"(a.pool_count), "s"(a.aux_count));
+               "s"(a.pool_k), "s"(a.pool_v), "s"(a.pool_count), "s"(a.aux_count), "s"(a.seq));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -581,6 +586,16 @@ decode_kernel(DecodeArgs a) {
   WaveLds<GQ, NV>& L = ((WaveLds<GQ, NV>*)smem)[wave];
   const __half* qbase = a.q + ((int64_t)b * d.q_heads + hq0) * kHeadDim;
   const int n_splits = a.splits;
+  // A batch of sequences of different lengths: each sequence's own state, read from memory.  The
+  // arguments' values bound it (the host has checked them against the buffers), so that whatever
+  // the array holds every access below stays inside the buffers.
+  Seq sq = {a.n_quant, a.res_start, a.n_res};
+  if (a.seq) {
+    const int4 own = *(const int4*)(a.seq + 4 * b);        // uniform: one scalar load
+    sq.n_quant = min(max(own.x, 0), a.n_quant) & ~(kBlockTokens - 1);
+    sq.res_start = (own.y >= 0 && own.y < d.res_rows) ? own.y : 0;
+    sq.n_res = min(max(own.z, 0), a.n_res);
+  }
 
   // Loads go out in the order their data is needed, and all of them before anything is waited
   // on: the query, the wave's first group of full-precision rows, its first quantized mini-chunk.
@@ -590,7 +605,7 @@ decode_kernel(DecodeArgs a) {
 
   // full-precision row groups go to the unit's wavefronts from the last one backwards (the
   // first wavefronts of a workgroup are the ones that may hold one more mini-chunk)
-  const int fp_rows = a.n_res + d.pool_slots;
+  const int fp_rows = sq.n_res + d.pool_slots;
   const int n_rg = (fp_rows + 15) >> 4;
   const int unit_waves = n_splits * nw;
   int rg = unit_waves - 1 - (split * nw + wave);
@@ -607,10 +622,10 @@ decode_kernel(DecodeArgs a) {
   asm("" : "+v"(uv));                                    // a vector address: a vector load
   int n_pool = a.pool_count[uv];
   int n_aux = a.aux_count[uv];
-  fp_load(X, a, u, qbase, rg * 16, lane);
+  fp_load(X, a, sq, u, qbase, rg * 16, lane);
 
   UnitPtrs P;
-  P.nblocks = a.n_quant >> 5;
+  P.nblocks = sq.n_quant >> 5;
   P.last_block = max(P.nblocks - 1, 0);
   P.bpg_shift = d.bpg_shift;
   P.block_bytes = (uint32_t)d.block_bytes;
@@ -619,7 +634,7 @@ decode_kernel(DecodeArgs a) {
   P.km = (const unsigned char*)(a.k_meta + u * d.groups_per_unit * kHeadDim);
   P.vm = (const unsigned char*)a.v_meta + u * d.blocks_per_unit * (int64_t)(128 * NV);
   P.mask = (const unsigned char*)(a.mask + u * d.blocks_per_unit);
-  const int n_mc = (a.n_quant + kMiniChunk - 1) / kMiniChunk;
+  const int n_mc = (sq.n_quant + kMiniChunk - 1) / kMiniChunk;
   const int mc_end = min(n_mc, (split + 1) * a.mc_per_split);
   int mc = split * a.mc_per_split + wave;
   const bool has_q = mc < mc_end;                        // uniform over the wave
@@ -656,10 +671,10 @@ decode_kernel(DecodeArgs a) {
   if (has_fp) {
     n_pool = __builtin_amdgcn_readfirstlane(n_pool);
     n_aux = __builtin_amdgcn_readfirstlane(n_aux);
-    fp_compute<GQ, NV>(X, F, L, a, n_pool, n_aux, lane);
+    fp_compute<GQ, NV>(X, F, L, a, sq, n_pool, n_aux, lane);
     for (rg += unit_waves; rg < n_rg; rg += unit_waves) {          // further groups (short quantized segment)
-      fp_load(X, a, u, qbase, rg * 16, lane);
-      fp_compute<GQ, NV>(X, F, L, a, n_pool, n_aux, lane);
+      fp_load(X, a, sq, u, qbase, rg * 16, lane);
+      fp_compute<GQ, NV>(X, F, L, a, sq, n_pool, n_aux, lane);
     }
   }
 
@@ -730,7 +745,7 @@ decode_kernel(DecodeArgs a) {
       l += mg.l[w * GQ + j] * f;
     }
     if (n_splits == 1) {
-      a.out[((int64_t)b * d.q_heads + hq0 + j) * kHeadDim + c] = __float2half_rn(o / l);
+      a.out[((int64_t)b * d.q_heads + hq0 + j) * kHeadDim + c] = __float2half_rn(l > 0.f ? o / l : 0.f);
     } else {
       coherent_store(&part_out[j * (kHeadDim + 2) + 2 + c], o);
       if (c == 0) {
@@ -784,7 +799,7 @@ decode_kernel(DecodeArgs a) {
         }
         m = mb;
       }
-      a.out[((int64_t)b * d.q_heads + hq0 + j) * kHeadDim + c] = __float2half_rn(o / l);
+      a.out[((int64_t)b * d.q_heads + hq0 + j) * kHeadDim + c] = __float2half_rn(l > 0.f ? o / l : 0.f);
     }
     if (tid == 0)                                        // leave the counter as it was found
       __hip_atomic_store(&a.counters[wl], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -310,7 +310,8 @@ __global__ void __launch_bounds__(256) tail_copy_kernel(Dims d, const __half* __
 template <int BITS, int G>
 __global__ void __launch_bounds__(kQuantThreads) group_step_kernel(
     Dims d, int32_t group_index, const __half* __restrict__ k_new, const __half* __restrict__ v_new, __half* k_res,
-    __half* v_res, int32_t append_row, int32_t group_row0, __half* pool_k, __half* pool_v, int32_t* pool_idx,
+    __half* v_res, int32_t append_row, int32_t group_row0, const int32_t* __restrict__ seq, __half* pool_k,
+    __half* pool_v, int32_t* pool_idx,
     double* pool_score, int32_t* pool_count, int32_t* aux_count, int32_t* frozen, uint8_t* selected,
     uint8_t* __restrict__ k_codes, uint32_t* __restrict__ k_meta, uint8_t* __restrict__ v_codes,
     uint32_t* __restrict__ v_meta, uint32_t* __restrict__ mask) {
@@ -321,11 +322,26 @@ __global__ void __launch_bounds__(kQuantThreads) group_step_kernel(
   const int64_t u = d.unit0 + ul;
   __half* kring = k_res + u * d.res_rows * kHeadDim;
   __half* vring = v_res + u * d.res_rows * kHeadDim;
+  bool close_group = true;
+  if (seq) {
+    // A batch of sequences of different lengths: the unit's sequence says where its new row goes
+    // and whether its ring is full with it.  A sequence that is inactive, or whose state does not
+    // fit the buffers, is left alone; all of this is uniform over the workgroup.
+    const int4 own = *(const int4*)(seq + 4 * (ul / d.kv_heads));
+    const int nq = own.x, rs = own.y, nr = own.z;
+    if (!own.w || nq < 0 || rs < 0 || rs >= d.res_rows || nr < 0 || nr >= d.res_rows) return;
+    append_row = rs + nr;
+    append_row -= append_row >= d.res_rows ? d.res_rows : 0;
+    group_row0 = rs;
+    group_index = nq / G;
+    close_group = nr + 1 == d.R + G && rs % G == 0 && nq % G == 0 && nq + G <= d.max_seq;
+  }
   if (tid < 128) {                                   // the new row: 64 threads for K, 64 for V, 4 bytes each
     const int which = tid >> 6, lane = tid & 63;
     const uint32_t* src = (const uint32_t*)((which ? v_new : k_new) + (int64_t)ul * kHeadDim);
     ((uint32_t*)((which ? vring : kring) + append_row * kHeadDim))[lane] = src[lane];
   }
+  if (!close_group) return;
   if (append_row >= group_row0 && append_row < group_row0 + G) {   // R = 0: the new token closes the group
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -394,7 +410,8 @@ namespace {
 template <int BITS, int G>
 hipError_t launch_group_step_one(const Dims& d, int32_t group_index, const __half* k_new, const __half* v_new,
                                  __half* k_res, __half* v_res, int32_t append_row, int32_t group_row0,
-                                 const kvq_pool& pool, uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
+                                 const int32_t* seq, const kvq_pool& pool, uint8_t* selected, const kvq_qcache& qc,
+                                 hipStream_t s) {
   const size_t smem = quant_lds_bytes<G>(d.vgroups);
   if (smem > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)group_step_kernel<BITS, G>,
@@ -402,7 +419,7 @@ hipError_t launch_group_step_one(const Dims& d, int32_t group_index, const __hal
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL((group_step_kernel<BITS, G>), dim3(d.units_per_layer), dim3(kQuantThreads), smem, s, d,
-                     group_index, k_new, v_new, k_res, v_res, append_row, group_row0, (__half*)pool.pool_k,
+                     group_index, k_new, v_new, k_res, v_res, append_row, group_row0, seq, (__half*)pool.pool_k,
                      (__half*)pool.pool_v, pool.pool_idx, pool.pool_score, pool.pool_count, pool.aux_count,
                      pool.frozen, selected, (uint8_t*)qc.k_codes, (uint32_t*)qc.k_meta, (uint8_t*)qc.v_codes,
                      (uint32_t*)qc.v_meta, (uint32_t*)qc.mask);
@@ -412,21 +429,47 @@ hipError_t launch_group_step_one(const Dims& d, int32_t group_index, const __hal
 template <int BITS>
 hipError_t launch_group_step_bits(const Dims& d, int32_t group_index, const __half* k_new, const __half* v_new,
                                   __half* k_res, __half* v_res, int32_t append_row, int32_t group_row0,
-                                  const kvq_pool& pool, uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
+                                  const int32_t* seq, const kvq_pool& pool, uint8_t* selected, const kvq_qcache& qc,
+                                  hipStream_t s) {
   switch (d.G) {
-    case 32: return launch_group_step_one<BITS, 32>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, pool, selected, qc, s);
-    case 64: return launch_group_step_one<BITS, 64>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, pool, selected, qc, s);
-    default: return launch_group_step_one<BITS, 128>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, pool, selected, qc, s);
+    case 32: return launch_group_step_one<BITS, 32>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, seq, pool, selected, qc, s);
+    case 64: return launch_group_step_one<BITS, 64>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, seq, pool, selected, qc, s);
+    default: return launch_group_step_one<BITS, 128>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, seq, pool, selected, qc, s);
   }
 }
 
 }  // namespace
 
+// The state of every active sequence after one token has been appended to it (and its oldest group
+// quantized if that filled its ring): the rule group_step_kernel applies, applied to the array.
+__global__ void seq_advance_kernel(Dims d, int32_t* seq) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= d.batch) return;
+  int4 own = *(const int4*)(seq + 4 * b);
+  if (!own.w || own.x < 0 || own.y < 0 || own.y >= d.res_rows || own.z < 0 || own.z >= d.res_rows) return;
+  const bool close_group =
+      own.z + 1 == d.R + d.G && own.y % d.G == 0 && own.x % d.G == 0 && own.x + d.G <= d.max_seq;
+  own.z += 1;
+  if (close_group) {
+    own.x += d.G;
+    own.z -= d.G;
+    own.y += d.G;
+    own.y -= own.y >= d.res_rows ? d.res_rows : 0;
+  }
+  *(int4*)(seq + 4 * b) = own;
+}
+
+hipError_t launch_seq_advance(const Dims& d, int32_t* seq, hipStream_t s) {
+  hipLaunchKernelGGL(seq_advance_kernel, dim3((d.batch + 255) / 256), dim3(256), 0, s, d, seq);
+  return hipGetLastError();
+}
+
 hipError_t launch_group_step(const Dims& d, int32_t group_index, const __half* k_new, const __half* v_new,
                              __half* k_res, __half* v_res, int32_t append_row, int32_t group_row0,
-                             const kvq_pool& pool, uint8_t* selected, const kvq_qcache& qc, hipStream_t s) {
-  return d.bits == 2 ? launch_group_step_bits<2>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, pool, selected, qc, s)
-                     : launch_group_step_bits<4>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, pool, selected, qc, s);
+                             const int32_t* seq, const kvq_pool& pool, uint8_t* selected, const kvq_qcache& qc,
+                             hipStream_t s) {
+  return d.bits == 2 ? launch_group_step_bits<2>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, seq, pool, selected, qc, s)
+                     : launch_group_step_bits<4>(d, group_index, k_new, v_new, k_res, v_res, append_row, group_row0, seq, pool, selected, qc, s);
 }
 
 hipError_t launch_quantize(const Dims& d, int32_t group_index, int32_t n_groups, const __half* k_group,

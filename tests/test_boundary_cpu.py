@@ -117,3 +117,36 @@ def test_bad_call_arguments_rejected_before_launch():
     assert pf(kr=258) == B.KVQ_ERR_INVALID_ARG
     assert pf(sel=None) == B.KVQ_ERR_INVALID_ARG
     assert pf(pool=B.kvq_pool(256, 256, 256, 256, 256, 256, 0)) == B.KVQ_ERR_INVALID_ARG
+
+
+def test_bad_ragged_call_arguments_rejected_before_launch():
+    lib = P.load_library()
+    c = cfg()
+    qc = B.kvq_qcache(256, 256, 256, 256, 256)
+    pool = B.kvq_pool(256, 256, 256, 256, 256, 256, 256)
+    res = B.kvq_residual(256, 256)
+    ws = P.kvq_query_sizes(c).workspace_bytes
+    dec = lambda **k: lib.kvq_decode_attention_ragged(C.byref(c), k.get("layer", 0), 256, k.get("qc", qc), res,
+                                                      k.get("seq", 256), k.get("mq", 64), k.get("mr", 10), pool, 256,
+                                                      k.get("ws", 512), ws, None)
+    assert dec(seq=None) == B.KVQ_ERR_INVALID_ARG
+    assert dec(seq=260) == B.KVQ_ERR_INVALID_ARG             # the state array is read 16 bytes at a time
+    assert dec(mq=40) == B.KVQ_ERR_INVALID_ARG               # the bound is a multiple of the group size
+    assert dec(mq=2048) == B.KVQ_ERR_INVALID_ARG
+    assert dec(mr=161) == B.KVQ_ERR_INVALID_ARG
+    assert dec(mq=0, mr=0) == B.KVQ_ERR_INVALID_ARG
+    assert dec(layer=1) == B.KVQ_ERR_INVALID_ARG
+    assert dec(qc=B.kvq_qcache(256, 256, 0, 256, 256)) == B.KVQ_ERR_INVALID_ARG
+    assert dec(ws=None) == B.KVQ_ERR_WORKSPACE
+    st = lambda **k: lib.kvq_append_trace_quantize_ragged(C.byref(c), k.get("layer", 0), k.get("kn", 256), 256, res,
+                                                          k.get("seq", 256), k.get("pool", pool), None,
+                                                          k.get("qc", qc), None)
+    assert st(seq=None) == B.KVQ_ERR_INVALID_ARG
+    assert st(seq=264) == B.KVQ_ERR_INVALID_ARG
+    assert st(kn=None) == B.KVQ_ERR_INVALID_ARG
+    assert st(layer=-1) == B.KVQ_ERR_INVALID_ARG
+    assert st(qc=B.kvq_qcache(0, 256, 256, 256, 256)) == B.KVQ_ERR_INVALID_ARG
+    assert st(pool=B.kvq_pool(256, 256, 256, 256, 256, 256, 0)) == B.KVQ_ERR_INVALID_ARG
+    adv = lambda seq: lib.kvq_seq_advance(C.byref(c), seq, None)
+    assert adv(None) == B.KVQ_ERR_INVALID_ARG
+    assert adv(8) == B.KVQ_ERR_INVALID_ARG

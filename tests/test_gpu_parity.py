@@ -280,3 +280,83 @@ def test_prefill_then_stream():
     ref = H.oracle_attention(wf, states, Q, K, V, wf.n_quant, wf.n_res)
     got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
     assert float(np.abs(got - ref).max()) <= ATT_TOL
+
+
+def ragged_lengths_state(n, G, R):
+    nq = G * ((n - R) // G) if n >= R + G else 0
+    return nq, n - nq
+
+
+@pytest.mark.parametrize("kw,lengths", [
+    (dict(bits=2, group_k=32, group_v=32, residual=32, outlier_budget=4), [45, 300, 161, 96]),
+    (dict(bits=4, group_k=64, group_v=64, residual=32, outlier_budget=3, q_heads=8), [1, 400, 95, 96]),
+    (dict(bits=2, group_k=32, group_v=128, residual=0, outlier_budget=4), [32, 31, 257, 0]),
+])
+def test_ragged_batch_streaming(kw, lengths):
+    """Sequences of different lengths in one batch: tokens are appended step by step to the
+    sequences that are still growing (one launch per step and layer, the state kept on the device),
+    then one decode launch serves all of them.  Every unit is compared with the oracle run on its
+    own sequence alone."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    base = dict(layers=1, batch=len(lengths), q_heads=4, kv_heads=2, context=max(lengths))
+    base.update(kw)
+    w = S.Workload("ragged", **base)
+    G, R = w.group_k, w.residual
+    K, V = S.layer_kv(w, 0, max(lengths))
+    ms = ((max(lengths) + G - 1) // G) * G
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ms, w.bits, G, w.group_v, R, w.outlier_budget,
+                         w.aux_capacity, w.head_dim)
+    cache = KC.RaggedKVCache(cfg)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    for t in range(max(lengths)):
+        cache.set_active([t < n for n in lengths])
+        cache.append(0, Kd[:, :, t].contiguous(), Vd[:, :, t].contiguous())
+        cache.advance()
+    torch.cuda.synchronize()
+    state = cache.seq_state.cpu().numpy()
+    Q = S.layer_queries(w, 0, 0, "peaky")
+    got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    g = w.q_heads // w.kv_heads
+    rows = cache.sizes.res_rows
+    for b, n in enumerate(lengths):
+        nq, nr = ragged_lengths_state(n, G, R)
+        assert (state[b, 0], state[b, 2]) == (nq, nr), (b, state[b])
+        assert state[b, 1] == nq % rows
+        units = [b * w.kv_heads + h for h in range(w.kv_heads)]
+        states = H.oracle_states(w, K, V, nq, units)
+        H.compare_state(cache, states, w, nq, units=units)
+        if n == 0:
+            assert not got[b].any()                         # a sequence without tokens: zeros
+            continue
+        ref = H.oracle_attention(w, states, Q, K, V, nq, nr, units)
+        err = float(np.abs(got[b] - ref[b]).max())
+        assert err <= ATT_TOL, (b, n, err)
+
+
+def test_ragged_equals_uniform_when_lengths_agree():
+    """The ragged entry points on a batch whose sequences all have the same state give the bytes and
+    the outputs of the uniform ones."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    w = small("ragged_uniform", q_heads=4, context=32 * 9 + 5, residual=64)
+    G, R = w.group_k, w.residual
+    K, V = S.layer_kv(w, 0)
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ((w.context + G - 1) // G) * G, w.bits, G, w.group_v, R,
+                         w.outlier_budget, w.aux_capacity, w.head_dim)
+    a, b = KC.KVCache(cfg), KC.RaggedKVCache(cfg)
+    b.set_active([1] * w.batch)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    for t in range(w.context):
+        k, v = Kd[:, :, t].contiguous(), Vd[:, :, t].contiguous()
+        a.append(0, k, v)
+        b.append(0, k, v)
+        b.advance()
+    q = torch.from_numpy(S.layer_queries(w, 0, 0, "peaky")).cuda()
+    oa, ob = a.decode(0, q), b.decode(0, q)
+    torch.cuda.synchronize()
+    nb = a.n_quant[0] // 32
+    for name in ("k_codes", "v_codes", "k_meta", "v_meta", "mask", "pool_idx", "pool_count", "aux_count"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    assert nb > 0 and torch.equal(oa, ob)
