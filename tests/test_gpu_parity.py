@@ -360,3 +360,35 @@ def test_ragged_equals_uniform_when_lengths_agree():
     for name in ("k_codes", "v_codes", "k_meta", "v_meta", "mask", "pool_idx", "pool_count", "aux_count"):
         assert torch.equal(getattr(a, name), getattr(b, name)), name
     assert nb > 0 and torch.equal(oa, ob)
+
+
+@pytest.mark.parametrize("g", [1, 4])
+def test_decode_replayed_from_a_captured_graph(g):
+    """The decode launch allocates nothing, synchronises nothing and leaves its workspace as it found
+    it, so it can be captured into a graph; every replay, with eager launches between the replays,
+    gives the eager result.  Few units: each is spread over several workgroups, so the replays
+    also depend on the arrival counters being zero again after every launch."""
+    import torch
+    w = small(f"graph_g{g}", batch=1, q_heads=2 * g, context=1500)
+    K, V = S.layer_kv(w, 0)
+    cache = H.gpu_cache(w, K, V, w.n_quant, w.n_res)
+    q = torch.from_numpy(S.layer_queries(w, 0, 0, "peaky")).cuda()
+    q_other = torch.from_numpy(S.layer_queries(w, 0, 1, "diffuse")).cuda()
+    eager = cache.decode(0, q).clone()
+    eager_other = cache.decode(0, q_other).clone()
+    out = torch.empty_like(q)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        cache.decode(0, q, out)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cache.decode(0, q, out)
+    for _ in range(4):
+        out.zero_()
+        assert torch.equal(cache.decode(0, q_other), eager_other)      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager)
