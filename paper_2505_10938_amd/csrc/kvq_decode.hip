@@ -222,30 +222,35 @@ __device__ __forceinline__ T ld(const unsigned char* base, uint32_t off) {
 // the quantized segment is replaced by the last block with every token masked, so that every
 // wave runs the same straight-line code.
 template <int BITS, int NV>
+__device__ __forceinline__ void load_k_meta_block(McRegs<BITS, NV>& R, const UnitPtrs& P, int mc, int i, int lane) {
+  // uniform base (scalar registers) + one lane offset shared by all loads
+  const unsigned char* gp = P.km + ((uint32_t)min(mc * 4 + i, P.last_block) >> P.bpg_shift) * 512u;
+  R.ksp[i] = ld<uint32_t>(gp, lane * 4u);
+  R.ksz[i] = ld<uint32_t>(gp + 256, lane * 4u);
+}
+template <int BITS, int NV>
 __device__ __forceinline__ void load_k_meta(McRegs<BITS, NV>& R, const UnitPtrs& P, int mc, int lane) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    // uniform base (scalar registers) + one lane offset shared by all loads
-    const unsigned char* gp = P.km + ((uint32_t)min(mc * 4 + i, P.last_block) >> P.bpg_shift) * 512u;
-    R.ksp[i] = ld<uint32_t>(gp, lane * 4u);
-    R.ksz[i] = ld<uint32_t>(gp + 256, lane * 4u);
+  for (int i = 0; i < 4; ++i) load_k_meta_block<BITS, NV>(R, P, mc, i, lane);
+}
+template <int BITS>
+__device__ __forceinline__ void load_codes_block(uint32_t (&w)[4][2 * BITS], const unsigned char* codes,
+                                                 const UnitPtrs& P, int mc, int i, int lane) {
+  const unsigned char* bp = codes + (uint32_t)min(mc * 4 + i, P.last_block) * P.block_bytes;   // uniform
+#pragma unroll
+  for (int hf = 0; hf < BITS / 2; ++hf) {
+    const uint4 t = ld<uint4>(bp + hf * 1024, lane * 16u);
+    w[i][4 * hf + 0] = t.x;
+    w[i][4 * hf + 1] = t.y;
+    w[i][4 * hf + 2] = t.z;
+    w[i][4 * hf + 3] = t.w;
   }
 }
 template <int BITS>
 __device__ __forceinline__ void load_codes(uint32_t (&w)[4][2 * BITS], const unsigned char* codes, const UnitPtrs& P,
                                            int mc, int lane) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const unsigned char* bp = codes + (uint32_t)min(mc * 4 + i, P.last_block) * P.block_bytes;   // uniform
-#pragma unroll
-    for (int hf = 0; hf < BITS / 2; ++hf) {
-      const uint4 t = ld<uint4>(bp + hf * 1024, lane * 16u);
-      w[i][4 * hf + 0] = t.x;
-      w[i][4 * hf + 1] = t.y;
-      w[i][4 * hf + 2] = t.z;
-      w[i][4 * hf + 3] = t.w;
-    }
-  }
+  for (int i = 0; i < 4; ++i) load_codes_block<BITS>(w, codes, P, mc, i, lane);
 }
 template <int BITS, int NV>
 __device__ __forceinline__ void load_v_meta(McRegs<BITS, NV>& R, const UnitPtrs& P, int mc, int lane) {
@@ -301,6 +306,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
 #pragma unroll
   for (int i = 0; i < 4; ++i) ((uint32_t*)L.k.zk[i])[lane] = R.ksz[i];
   key_rows(0);
+  if (more) load_k_meta_block<BITS, NV>(R, P, mc_next, 0, lane);
   wave_sync();
 
   // ---- sum_c q_c z_c of the 4 blocks: column n of B = zeros of block n & 3 --------------------------
@@ -318,8 +324,10 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
   // ---- scores (left in units of 2^-(24 - kShK); the softmax scales them) -----------------------------
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    if (i + 1 < 4) key_rows(i + 1);
-    if (i == 2 && more) load_k_meta<BITS, NV>(R, P, mc_next, lane);
+    if (i + 1 < 4) {
+      key_rows(i + 1);
+      if (more) load_k_meta_block<BITS, NV>(R, P, mc_next, i + 1, lane);
+    }
     // both 16-token halves of the block share each operand row read
     float4v D0 = {0.f, 0.f, 0.f, 0.f}, D1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -328,6 +336,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
       D0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq, field_operand<BITS>(R.kc[i], cb), D0, 0, 0, 0);
       D1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq, field_operand<BITS>(R.kc[i], 4 + cb), D1, 0, 0, 0);
     }
+    if (more) load_codes_block<BITS>(R.kc, P.kc, P, mc_next, i, lane);
     const int tl = i * 32 + m16;
     if (2 * r < GQ) {
       L.sc[2 * r][tl] = D0[0] + D0[1];
@@ -339,7 +348,6 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
     }
     wave_sync();                        // the next block's rows, at last the scores, are visible
   }
-  if (more) load_codes<BITS>(R.kc, P.kc, P, mc_next, lane);
 
   // ---- softmax numerators of the 128 tokens against the running maximum; operand rows ---------------
   half2v ph[GQ], pl[GQ];                // p of this lane's two tokens, hi + lo
@@ -395,7 +403,6 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
     for (int jv = 0; jv < NV; ++jv) ((uint32_t*)L.v.zv[jv])[lane] = R.vsz[jv];
     ((uint32_t*)L.v.zv[NV])[lane] = 0x3C003C00u;      // fp16 ones
     value_rows(0);
-    if (more) load_v_meta<BITS, NV>(R, P, mc_next, lane);
     // the running maximum moved (wave-uniform, rare after the first mini-chunks): rescale
     if (rescale) {
       float a0 = 1.f, a1 = 1.f;
@@ -437,6 +444,10 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
     }
     if (jv + 1 < NV) wave_sync();                     // the next value group's rows are visible
   }
+  // (the Value steps, zeros and mask word are reloaded here and not right after their last use:
+  // held in flight across the products above they were moved to other registers at the end of
+  // every pass, and such a move waits for the load)
+  if (more) load_v_meta<BITS, NV>(R, P, mc_next, lane);
   if (more) load_codes<BITS>(R.vc, P.vc, P, mc_next, lane);
 }
 
