@@ -515,6 +515,9 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
                                            const Seq& sq, int n_pool, int n_aux, int lane) {
   const int m16 = lane & 15, r = lane >> 4;
   const bool okk = fp_row_ok(a, sq, X.row0 + m16, n_pool, n_aux);
+  // which of the 16 rows hold a token, as a wave-uniform bit mask (lanes 0..15 are rows 0..15):
+  // asking row by row costs some 25 scalar instructions per row
+  const uint32_t ok_rows = (uint32_t)__ballot(okk) & 0xFFFFu;
   constexpr int R2 = 2 * GQ;
   const int arow = m16 % R2;
   float4v D = {0.f, 0.f, 0.f, 0.f};
@@ -550,7 +553,7 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
   }
 #pragma unroll
   for (int t = 0; t < 16; ++t) {
-    const uint32_t vw = fp_row_ok(a, sq, X.row0 + t, n_pool, n_aux) ? X.vw[t] : 0u;   // uniform; an empty slot may hold anything
+    const uint32_t vw = ((ok_rows >> t) & 1u) ? X.vw[t] : 0u;     // uniform; an empty slot may hold anything
     const float v0 = h2f_bits(vw & 0xFFFFu), v1 = h2f_bits(vw >> 16);
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
