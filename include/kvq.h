@@ -77,9 +77,12 @@ typedef struct kvq_sizes {
  * Quantized cache (device).  Packed format.  Codes are stored in blocks of 32 tokens x 128
  * channels = 512*bits bytes, block i of a unit holding tokens 32i .. 32i+31.  A block is
  * 64 "lanes" of 8 "fields" of 8 codes.  Code x = 2v + e (v in 0..3, e in 0..1) of field f
- * of lane l sits in a little-endian u32 word at
- *     bits = 2:  bit 16e + 2(4(f&1) + v)  of the word at byte  16 l + 4 (f>>1)
- *     bits = 4:  bit 16e + 4v             of the word at byte  1024 (f>>2) + 16 l + 4 (f&3)
+ * of lane l occupies `bits` bits of a little-endian u32 word, starting at
+ *     bits = 2:  bit (16e + 2(v+1) + 8(f&1)) mod 32        of the word at byte  16 l + 4 (f>>1)
+ *     bits = 4:  bit (16e + 2 + 4(v&1) + 8(v>>1)) mod 32   of the word at byte  1024 (f>>2) + 16 l + 4 (f&3)
+ * and continuing at bit 0 of the same word after bit 31 (the code is rotated into place; only
+ * the 4-bit code x = 7 wraps).  Read as two fp16 halves, the word - or the word rotated right by
+ * 8 - thus shows a field's codes at bits 2..9 of each half.
  * Key block:   token t = 16 th + m, channel c = 32 cb + 8 r + x  ->  lane 16 r + m, field 4 th + cb.
  * Value block: channel c = 16 ct + n, token t = 8 r + x          ->  lane 16 r + n, field ct.
  * (A lane's 16 bytes are what one wavefront lane loads with one dwordx4; a field is one
@@ -228,6 +231,23 @@ int32_t kvq_prefill_quantize(const kvq_config* cfg, int32_t layer, const void* k
 int32_t kvq_append_trace_quantize(const kvq_config* cfg, int32_t layer, const void* k_new, const void* v_new,
                                   kvq_residual res, int32_t res_start, int32_t n_res, int32_t n_quant,
                                   kvq_pool pool, uint8_t* selected, kvq_qcache qcache, void* stream);
+
+/*
+ * A decode step on which the ring does not fill, in one launch: the attention of
+ * kvq_decode_attention over the cache as it is plus the token being decoded (Background, decoding
+ * phase: K = K_<n || K_n), whose rows come with the call and are also stored in the ring, as
+ * kvq_append_residual would have stored them before.  Result and ring contents equal those of
+ * kvq_append_residual followed by kvq_decode_attention with n_res + 1.
+ *   k_new, v_new     : device fp16 [batch][kv_heads][head_dim], 4-byte aligned
+ *   res_start, n_res : the ring's state BEFORE the token; n_res + 1 < residual + group_k (on the
+ *                      step that fills the ring call kvq_append_trace_quantize, then
+ *                      kvq_decode_attention).  The caller counts the token: n_res + 1 afterwards
+ *   other arguments, workspace and errors as kvq_decode_attention.
+ */
+int32_t kvq_append_decode_attention(const kvq_config* cfg, int32_t layer, const void* q, const void* k_new,
+                                    const void* v_new, kvq_qcache qcache, int32_t n_quant, kvq_residual res,
+                                    int32_t res_start, int32_t n_res, kvq_pool pool, void* out,
+                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Batches whose sequences differ in length (the paper's runs use one length per batch; a serving

@@ -256,10 +256,11 @@ def decode_attention(q_heads: np.ndarray, state: UnitState, k_res: np.ndarray, v
 # --------------------------------------------------------------------------
 # A block is 32 tokens x 128 channels of b-bit codes = 512*b bytes, seen as 64
 # "lanes" of 8 "fields" of 8 codes.  Code x = 2*v + e (v in 0..3, e in 0..1) of a
-# field sits, inside a little-endian u32 word, at bit
-#     b=2:  16*e + 2*(4*(f & 1) + v)   of word (f >> 1) of the lane's 4 words
-#     b=4:  16*e + 4*v                 of word (f & 3) of half (f >> 2)
-# and the lane's words live at byte  half*1024 + lane*16 + 4*word.
+# field occupies, inside a little-endian u32 word, the b bits that start at bit
+#     b=2:  (16*e + 2*(v + 1) + 8*(f & 1)) mod 32           of word (f >> 1) of the lane's 4 words
+#     b=4:  (16*e + 2 + 4*(v & 1) + 8*(v >> 1)) mod 32      of word (f & 3) of half (f >> 2)
+# and continue, past bit 31, at bit 0 of the same word (the code is rotated into place);
+# the lane's words live at byte  half*1024 + lane*16 + 4*word.
 # K block: token t = 16*th + m, channel c = 32*cb + 8*r + x -> lane 16*r + m, field 4*th + cb.
 # V block: channel c = 16*ct + n, token t = 8*r + x        -> lane 16*r + n, field ct.
 # Meta (fp16): Key group = step[128] then zero[128]; Value block = step[16 pairs][NV][2] then
@@ -272,11 +273,13 @@ def _pack_fields(fields: np.ndarray, bits: int) -> np.ndarray:
         for f in range(8):
             for x in range(8):
                 v, e = x >> 1, x & 1
-                code = np.uint32(fields[lane, f, x])
+                code = int(fields[lane, f, x])
                 if bits == 2:
-                    words[0, lane, f >> 1] |= code << np.uint32(16 * e + 2 * (4 * (f & 1) + v))
+                    start, half, word = (16 * e + 2 * (v + 1) + 8 * (f & 1)) % 32, 0, f >> 1
                 else:
-                    words[f >> 2, lane, f & 3] |= code << np.uint32(16 * e + 4 * v)
+                    start, half, word = (16 * e + 2 + 4 * (v & 1) + 8 * (v >> 1)) % 32, f >> 2, f & 3
+                placed = code << start                      # bits pushed past bit 31 re-enter at bit 0
+                words[half, lane, word] |= np.uint32((placed & 0xFFFFFFFF) | (placed >> 32))
     return words.astype("<u4").view(np.uint8).reshape(-1)
 
 

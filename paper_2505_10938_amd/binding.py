@@ -18,7 +18,8 @@ KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAU
 
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
            "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_decode_attention",
-           "kvq_append_trace_quantize_ragged", "kvq_seq_advance", "kvq_decode_attention_ragged", "kvq_stream_read",
+           "kvq_append_decode_attention", "kvq_append_trace_quantize_ragged", "kvq_seq_advance",
+           "kvq_decode_attention_ragged", "kvq_stream_read",
            "kvq_status_string", "kvq_version"]
 
 
@@ -88,6 +89,9 @@ def load_library() -> C.CDLL:
     lib.kvq_decode_attention.restype = i32
     lib.kvq_decode_attention.argtypes = [cfgp, i32, vp, kvq_qcache, i32, kvq_residual, i32, i32, kvq_pool,
                                          vp, vp, C.c_size_t, vp]
+    lib.kvq_append_decode_attention.restype = i32
+    lib.kvq_append_decode_attention.argtypes = [cfgp, i32, vp, vp, vp, kvq_qcache, i32, kvq_residual, i32, i32, kvq_pool,
+                                                vp, vp, C.c_size_t, vp]
     lib.kvq_append_trace_quantize_ragged.restype = i32
     lib.kvq_append_trace_quantize_ragged.argtypes = [cfgp, i32, vp, vp, kvq_residual, vp, kvq_pool, vp, kvq_qcache, vp]
     lib.kvq_seq_advance.restype = i32
@@ -170,6 +174,15 @@ def kvq_prefill_quantize(cfg, layer, k_rows, v_rows, unit_stride, n_tokens, pool
                                              pool, _ptr(selected), qcache, res, _stream(stream))
     if st != KVQ_OK:
         raise KvqError(st, "kvq_prefill_quantize")
+
+
+def kvq_append_decode_attention(cfg, layer, q, k_new, v_new, qcache: kvq_qcache, n_quant, res: kvq_residual, res_start,
+                                n_res, pool: kvq_pool, out, workspace, workspace_bytes, stream=None):
+    st = load_library().kvq_append_decode_attention(C.byref(cfg), layer, _ptr(q), _ptr(k_new), _ptr(v_new), qcache,
+                                                    n_quant, res, res_start, n_res, pool, _ptr(out), _ptr(workspace),
+                                                    workspace_bytes, _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_append_decode_attention")
 
 
 def kvq_append_trace_quantize_ragged(cfg, layer, k_new, v_new, res: kvq_residual, seq_state, pool: kvq_pool, selected,

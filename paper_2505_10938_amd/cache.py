@@ -140,6 +140,21 @@ class KVCache:
                                self.workspace.numel(), stream)
         return out
 
+    def step(self, layer, k_new, v_new, q, out=None, stream=None):
+        """One decode step of `layer`: the new token joins the cache and the attention output (fp16
+        [batch, q_heads, head_dim]) over the cache including it is returned.  Two launches on the steps
+        on which the ring fills (group step, then attention), one on all others."""
+        if out is None:
+            out = torch.empty_like(q)
+        if self.n_res[layer] + 1 == self.cfg.residual + self.cfg.group_k:
+            self.append(layer, k_new, v_new, stream)
+            return self.decode(layer, q, out, stream)
+        B.kvq_append_decode_attention(self.cfg, layer, q, k_new, v_new, self.qcache, self.n_quant[layer], self.res,
+                                      self.res_start[layer], self.n_res[layer], self.pool, out, self.workspace,
+                                      self.workspace.numel(), stream)
+        self.n_res[layer] += 1
+        return out
+
     def clone(self):
         """A second cache with the same contents in its own device memory."""
         other = KVCache.__new__(KVCache)

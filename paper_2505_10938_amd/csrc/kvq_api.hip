@@ -301,8 +301,9 @@ namespace {
 // The decode launch, shared by the two entry points: `seq_state` null = every sequence has the
 // state given; otherwise n_quant and n_res are upper bounds and each sequence brings its own.
 int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc, int32_t n_quant,
-                      kvq_residual res, int32_t res_start, int32_t n_res, const int32_t* seq_state, kvq_pool pool,
-                      void* out, void* workspace, size_t workspace_bytes, void* stream) {
+                      kvq_residual res, int32_t res_start, int32_t n_res, const int32_t* seq_state,
+                      const void* k_new, const void* v_new, kvq_pool pool, void* out, void* workspace,
+                      size_t workspace_bytes, void* stream) {
   const int32_t st = check_config(cfg);
   if (st != KVQ_OK) return st;
   if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
@@ -310,7 +311,12 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, kvq_q
   if (n_quant < 0 || n_quant > cfg->max_seq || n_quant % cfg->group_k != 0) return KVQ_ERR_INVALID_ARG;
   const int32_t rows = (int32_t)res_rows_of(cfg);
   if (n_res < 0 || n_res > rows || res_start < 0 || res_start >= rows) return KVQ_ERR_INVALID_ARG;
-  if (n_quant + n_res < 1) return KVQ_ERR_INVALID_ARG;
+  if (n_quant + n_res + (k_new ? 1 : 0) < 1) return KVQ_ERR_INVALID_ARG;
+  if ((k_new != nullptr) != (v_new != nullptr)) return KVQ_ERR_INVALID_ARG;
+  if (k_new) {                                          // the new token must leave the ring short of full
+    if (n_res + 1 >= cfg->residual + cfg->group_k || !res.k_res || !res.v_res) return KVQ_ERR_INVALID_ARG;
+    if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 3) return KVQ_ERR_INVALID_ARG;
+  }
   if (n_quant > 0 && (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask))
     return KVQ_ERR_INVALID_ARG;
   if (n_res > 0 && (!res.k_res || !res.v_res)) return KVQ_ERR_INVALID_ARG;
@@ -342,9 +348,11 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, kvq_q
   a.res_start = res_start;
   a.n_res = n_res;
   a.seq = seq_state;
+  a.k_new = (const __half*)k_new;
+  a.v_new = (const __half*)v_new;
   a.head_parts = head_parts_of(a.d.g);
   const Split sp = decode_split((int64_t)a.d.units_per_layer * a.head_parts, a.d.g / a.head_parts, a.d.vgroups, n_quant,
-                                (int64_t)n_res + a.d.pool_slots);
+                                (int64_t)n_res + (k_new ? 1 : 0) + a.d.pool_slots);
   a.splits = sp.splits;
   a.nw = sp.nw;
   a.mc_per_split = sp.mc_per_split;
@@ -356,8 +364,17 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, kvq_q
 int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc, int32_t n_quant,
                              kvq_residual res, int32_t res_start, int32_t n_res, kvq_pool pool, void* out,
                              void* workspace, size_t workspace_bytes, void* stream) {
-  return decode_common(cfg, layer, q, qc, n_quant, res, res_start, n_res, nullptr, pool, out, workspace,
-                       workspace_bytes, stream);
+  return decode_common(cfg, layer, q, qc, n_quant, res, res_start, n_res, nullptr, nullptr, nullptr, pool, out,
+                       workspace, workspace_bytes, stream);
+}
+
+int32_t kvq_append_decode_attention(const kvq_config* cfg, int32_t layer, const void* q, const void* k_new,
+                                    const void* v_new, kvq_qcache qc, int32_t n_quant, kvq_residual res,
+                                    int32_t res_start, int32_t n_res, kvq_pool pool, void* out, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  if (!k_new || !v_new) return KVQ_ERR_INVALID_ARG;
+  return decode_common(cfg, layer, q, qc, n_quant, res, res_start, n_res, nullptr, k_new, v_new, pool, out,
+                       workspace, workspace_bytes, stream);
 }
 
 int32_t kvq_decode_attention_ragged(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc,
@@ -367,8 +384,8 @@ int32_t kvq_decode_attention_ragged(const kvq_config* cfg, int32_t layer, const 
   if (!seq_state || (((uintptr_t)seq_state) & 15)) return KVQ_ERR_INVALID_ARG;
   if (max_n_quant > 0 && (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask))
     return KVQ_ERR_INVALID_ARG;
-  return decode_common(cfg, layer, q, qc, max_n_quant, res, 0, max_n_res, seq_state, pool, out, workspace,
-                       workspace_bytes, stream);
+  return decode_common(cfg, layer, q, qc, max_n_quant, res, 0, max_n_res, seq_state, nullptr, nullptr, pool, out,
+                       workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

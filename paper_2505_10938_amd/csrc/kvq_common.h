@@ -55,6 +55,8 @@ struct DecodeArgs {
   int32_t* counters;    // [units_per_layer], zero on entry and on exit
   int32_t n_quant, res_start, n_res;   // the batch's state; with `seq`, upper bounds of n_quant and n_res
   const int32_t* seq;   // per-sequence state [batch][4] = {n_quant, res_start, n_res, active}, or null
+  const __half* k_new;  // [batch][kv_heads][head_dim] rows of the token being decoded, not yet in the ring (it is
+  const __half* v_new;  // attended as the newest residual row, and stored in the ring by the launch), or null
   int32_t splits;       // workgroups per unit
   int32_t nw;           // wavefronts per workgroup
   int32_t head_parts;   // workgroup rows that share a kv head's query heads (1, or 2 when g = 8)
@@ -81,14 +83,18 @@ int decode_wave_lds_bytes(int g, int vgroups);   // LDS one decode wavefront nee
 
 // ---- packed layout ---------------------------------------------------------------------------
 // Byte offset (inside a block) of the u32 word that holds field f of lane l, and the bit
-// offset of code x = 2v + e inside that word.
+// offset of code x = 2v + e inside that word.  A code occupies bits code_bit .. code_bit + bits - 1
+// taken modulo 32 (one 4-bit code wraps around the end of its word): it is put in place with a
+// rotation.  Positions are chosen so that the word (for half of the fields: the word rotated right
+// by 8) holds a field's codes at bits 2..9 of each 16-bit half, the top of an fp16 significand.
 __host__ __device__ inline int word_byte(int bits, int lane, int f) {
   return bits == 2 ? 16 * lane + 4 * (f >> 1) : 1024 * (f >> 2) + 16 * lane + 4 * (f & 3);
 }
 __host__ __device__ inline int code_bit(int bits, int f, int x) {
   const int v = x >> 1, e = x & 1;
-  return bits == 2 ? 16 * e + 2 * (4 * (f & 1) + v) : 16 * e + 4 * v;
+  return (bits == 2 ? 16 * e + 2 * (v + 1) + 8 * (f & 1) : 16 * e + 2 + 4 * (v & 1) + 8 * (v >> 1)) & 31;
 }
+__host__ __device__ inline uint32_t place_code(uint32_t code, int bit) { return (code << bit) | (code >> ((32 - bit) & 31)); }
 // Key block: (token t in 0..31, channel c) -> (lane, field, x)
 __host__ __device__ inline void k_pos(int t, int c, int& lane, int& f, int& x) {
   lane = 16 * ((c & 31) >> 3) + (t & 15);

@@ -20,8 +20,12 @@
 //            fp16 zeros of the group; sum_t p_t z_t (one scalar per head and value group) and
 //            sum_t p_t are A = p (hi/lo) times B = [zeros | ones].
 // A packed code becomes an fp16 operand with ONE `and`: masked in place, a 2-bit code at bits
-// [2v, 2v+2) of a half-word is the fp16 subnormal code * 2^(2v-24) (the matrix cores take
-// subnormal inputs exactly), and the factor 2^(-2v) is folded into the other operand.
+// [p, p+2) of a half-word is the fp16 subnormal code * 2^(p-24), and the factor 2^(-p) is folded
+// into the other operand.  The matrix cores take a subnormal input at its value, but they align
+// the products of one instruction as if its exponent were that of the smallest normal number and
+// drop what falls below their window: measured, the sum is off by up to 2^-15 of the largest
+// product with codes at bits 0..7 and by 2^-18 with codes at bits 2..9 (2^-23 with normal numbers),
+// so the packed format keeps every code as high in the significand as one rotation allows.
 // Scores live in the log2 domain: s = (q . k) * log2(e) / sqrt(d).
 #include "kvq_common.h"
 
@@ -36,8 +40,8 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRowBytes = 272;   // LDS row of 128 fp16 + 16 bytes of padding (bank spread)
-constexpr int kShK = 6;          // q*step operand is scaled by 2^(kShK - pos) before the fp16 split
-constexpr int kShV = 8;          // p*step operand likewise
+constexpr int kShK = 8;          // q*step operand is scaled by 2^(kShK - pos) before the fp16 split
+constexpr int kShV = 10;         // p*step operand likewise
 
 __device__ inline float h2f_bits(uint32_t bits16) { return __half2float(__ushort_as_half((unsigned short)bits16)); }
 
@@ -91,10 +95,14 @@ __device__ inline float from_lane63(float v) {
 KVQ_WAVE_REDUCE(wave_max, "v_max_f32_dpp")
 KVQ_WAVE_REDUCE(wave_sum, "v_add_f32_dpp")
 
-// fp16 hi/lo split of two floats: hi = fp16(x) (toward zero), lo = fp16(x - hi); packed pairs.
+// fp16 hi/lo split of two floats: hi = fp16(x), lo = fp16(x - hi), both rounded to nearest, so that
+// hi + lo = x (1 + e) with |e| <= 2^-22 and no bias (truncating hi instead leaves 2^-21, one-sided);
+// packed pairs.
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float float2v __attribute__((ext_vector_type(2)));
 __device__ inline void split_pair(float x0, float x1, uint32_t& hi, uint32_t& lo) {
-  const auto h = __builtin_amdgcn_cvt_pkrtz(x0, x1);
-  const auto l = __builtin_amdgcn_cvt_pkrtz(x0 - (float)h[0], x1 - (float)h[1]);
+  const half2v h = __builtin_convertvector(float2v{x0, x1}, half2v);
+  const half2v l = __builtin_convertvector(float2v{x0 - (float)h[0], x1 - (float)h[1]}, half2v);
   hi = __builtin_bit_cast(uint32_t, h);
   lo = __builtin_bit_cast(uint32_t, l);
 }
@@ -102,7 +110,6 @@ __device__ inline void split_pair(float x0, float x1, uint32_t& hi, uint32_t& lo
 // Product of an unevaluated sum ah + al (packed fp16 pairs) with packed fp16 b, again as an
 // unevaluated sum: hi = fp16(ah*b); the rounding error ah*b - hi is exact in fp16 (a product of
 // two 11-bit significands has 22 bits) and joins al*b in lo.  Three packed instructions.
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 __device__ inline void mul_split(half2v ah, half2v al, half2v b, uint32_t& hi, uint32_t& lo) {
   const half2v h = ah * b;
   const half2v e = __builtin_elementwise_fma(ah, b, -h);
@@ -115,24 +122,25 @@ __device__ inline half2v as_half2(uint32_t w) { return __builtin_bit_cast(half2v
 // Exponent of the power of two carried by pair v (v = lane & 3 on the producing side) of a
 // field: a masked code at pair v is worth code * 2^(pos(v) - 24).
 template <int BITS>
-__device__ inline int pair_pos(int v) { return BITS == 2 ? 2 * v : 4 * (v & 1); }
+__device__ inline int pair_pos(int v) { return BITS == 2 ? 2 + 2 * v : 2 + 4 * (v & 1); }
 
-// One matrix-core operand (8 fp16 = 4 dwords) from field f of a lane's packed words.
+// One matrix-core operand (8 fp16 = 4 dwords) from field f of a lane's packed words.  The codes of
+// a field sit at bits 2..9 of each half-word, of the word itself or of the word rotated by 8.
 template <int BITS>
 __device__ inline half8 field_operand(const uint32_t (&w)[2 * BITS], int f) {
   u32x4 o;
   if (BITS == 2) {
-    const uint32_t x = (f & 1) ? (w[f >> 1] >> 8) : w[f >> 1];
-    o[0] = x & 0x00030003u;
-    o[1] = x & 0x000C000Cu;
-    o[2] = x & 0x00300030u;
-    o[3] = x & 0x00C000C0u;
+    const uint32_t x = (f & 1) ? __builtin_amdgcn_alignbit(w[f >> 1], w[f >> 1], 8) : w[f >> 1];
+    o[0] = x & 0x000C000Cu;
+    o[1] = x & 0x00300030u;
+    o[2] = x & 0x00C000C0u;
+    o[3] = x & 0x03000300u;
   } else {
-    const uint32_t x = w[f], y = w[f] >> 8;
-    o[0] = x & 0x000F000Fu;
-    o[1] = x & 0x00F000F0u;
-    o[2] = y & 0x000F000Fu;
-    o[3] = y & 0x00F000F0u;
+    const uint32_t x = w[f], y = __builtin_amdgcn_alignbit(w[f], w[f], 8);
+    o[0] = x & 0x003C003Cu;
+    o[1] = x & 0x03C003C0u;
+    o[2] = y & 0x003C003Cu;
+    o[3] = y & 0x03C003C0u;
   }
   return __builtin_bit_cast(half8, o);
 }
@@ -463,6 +471,7 @@ struct FpAcc {
 // The state of the sequence a workgroup works on: the batch's (kernel arguments), or its own.
 struct Seq {
   int n_quant, res_start, n_res;
+  int n_ring;   // residual rows that are in the ring; n_res - n_ring (0 or 1) newest row comes with the call
 };
 
 struct FpRegs {
@@ -478,6 +487,7 @@ __device__ __forceinline__ void fp_load(FpRegs& X, const DecodeArgs& a, const Se
                                         int row0, int lane) {
   const Dims& d = a.d;
   const int m16 = lane & 15, r = lane >> 4;
+  const int64_t new_off = (u - d.unit0) * kHeadDim;                // the unit's row of k_new / v_new
   const __half* kres = a.k_res + u * d.res_rows * kHeadDim;
   const __half* vres = a.v_res + u * d.res_rows * kHeadDim;
   const __half* kpool = a.pool_k + u * d.pool_slots * kHeadDim;
@@ -488,8 +498,9 @@ __device__ __forceinline__ void fp_load(FpRegs& X, const DecodeArgs& a, const Se
     ring -= ring >= d.res_rows ? d.res_rows : 0;
     const int slot = row - sq.n_res;
     const bool in_pool = slot < d.pool_slots;
-    kp = in_res ? kres + ring * kHeadDim : (in_pool ? kpool + slot * kHeadDim : qbase);
-    vp = in_res ? vres + ring * kHeadDim : (in_pool ? vpool + slot * kHeadDim : qbase);
+    const bool in_ring = row < sq.n_ring;
+    kp = in_ring ? kres + ring * kHeadDim : in_res ? a.k_new + new_off : (in_pool ? kpool + slot * kHeadDim : qbase);
+    vp = in_ring ? vres + ring * kHeadDim : in_res ? a.v_new + new_off : (in_pool ? vpool + slot * kHeadDim : qbase);
   };
   X.row0 = row0;
   const __half *kp, *vp_unused;
@@ -581,6 +592,7 @@ decode_kernel(DecodeArgs a) {
                "s"(d.bpg_shift), "s"(d.block_bytes), "s"(d.blocks_per_unit), "s"(d.groups_per_unit), "s"(a.q),
                "s"(a.k_codes), "s"(a.k_meta), "s"(a.v_codes), "s"(a.v_meta), "s"(a.mask), "s"(a.k_res), "s"(a.v_res),
                "s"(a.pool_k), "s"(a.pool_v), "s"(a.pool_count), "s"(a.aux_count), "s"(a.seq));
+  asm volatile("" ::"s"(a.k_new), "s"(a.v_new));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -603,12 +615,14 @@ decode_kernel(DecodeArgs a) {
   // A batch of sequences of different lengths: each sequence's own state, read from memory.  The
   // arguments' values bound it (the host has checked them against the buffers), so that whatever
   // the array holds every access below stays inside the buffers.
-  Seq sq = {a.n_quant, a.res_start, a.n_res};
+  Seq sq = {a.n_quant, a.res_start, a.n_res, a.n_res};
+  if (a.k_new) sq.n_res += 1;                            // the token being decoded: the newest residual row
   if (a.seq) {
     const int4 own = *(const int4*)(a.seq + 4 * b);        // uniform: one scalar load
     sq.n_quant = min(max(own.x, 0), a.n_quant) & ~(kBlockTokens - 1);
     sq.res_start = (own.y >= 0 && own.y < d.res_rows) ? own.y : 0;
     sq.n_res = min(max(own.z, 0), a.n_res);
+    sq.n_ring = sq.n_res;
   }
 
   // Loads go out in the order their data is needed, and all of them before anything is waited
@@ -616,6 +630,13 @@ decode_kernel(DecodeArgs a) {
   uint32_t qw[GQ];
 #pragma unroll
   for (int j = 0; j < GQ; ++j) qw[j] = ((const uint32_t*)(qbase + j * kHeadDim))[lane];
+  // The rows of the token being decoded, if they come with the call: one wavefront of the unit
+  // stores them in the ring at the end (every wavefront loads them, so that all issue the same
+  // loads; without such rows the query row is read instead).
+  const __half* k_new_row = a.k_new ? a.k_new + (int64_t)ul * kHeadDim : qbase;
+  const __half* v_new_row = a.k_new ? a.v_new + (int64_t)ul * kHeadDim : qbase;
+  const uint32_t k_new_word = ((const uint32_t*)k_new_row)[lane];
+  const uint32_t v_new_word = ((const uint32_t*)v_new_row)[lane];
 
   // full-precision row groups go to the unit's wavefronts from the last one backwards (the
   // first wavefronts of a workgroup are the ones that may hold one more mini-chunk)
@@ -713,6 +734,12 @@ decode_kernel(DecodeArgs a) {
     compute_minichunk<GQ, BITS, NV, false>(R, S, L, qh, ql, lane, P, mc);
   }
   const float post_v = __builtin_amdgcn_exp2f((float)(24 - kShV));
+  if (a.k_new && split == 0 && part == 0 && wave == 0) {     // append: the ring row after the live ones
+    int row = sq.res_start + sq.n_ring;
+    row -= row >= d.res_rows ? d.res_rows : 0;
+    ((uint32_t*)(const_cast<__half*>(a.k_res) + (u * d.res_rows + row) * kHeadDim))[lane] = k_new_word;
+    ((uint32_t*)(const_cast<__half*>(a.v_res) + (u * d.res_rows + row) * kHeadDim))[lane] = v_new_word;
+  }
 
   // ---- hand both results of the wave to the merge buffer ---------------------------------------------
   __syncthreads();                                       // every wave is done with its WaveLds

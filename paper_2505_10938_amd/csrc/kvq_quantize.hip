@@ -232,7 +232,7 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
 #pragma unroll
       for (int x = 0; x < 8; ++x) {
         const float val = (x & 1) ? hi_half(xs[x >> 1]) : lo_half(xs[x >> 1]);
-        word |= quant_code(val, hi_half(ms[x]), lo_half(ms[x]), kLevels) << code_bit(BITS, ff, x);
+        word |= place_code(quant_code(val, hi_half(ms[x]), lo_half(ms[x]), kLevels), code_bit(BITS, ff, x));
       }
     } else {        // Value: lane = 16 r + n, field = ct: one channel of 8 consecutive tokens
       const int c = 16 * f + mn_;
@@ -245,7 +245,7 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
       for (int x = 0; x < 8; ++x) val[x] = half_at(sv + (t0 + x) * kRowB + 2 * c);
 #pragma unroll
       for (int x = 0; x < 8; ++x)
-        word |= quant_code(val[x], hi_half(ms[x]), lo_half(ms[x]), kLevels) << code_bit(BITS, ff, x);
+        word |= place_code(quant_code(val[x], hi_half(ms[x]), lo_half(ms[x]), kLevels), code_bit(BITS, ff, x));
     }
     if (kFieldsPerWord == 2) word |= __shfl_xor(word, 1, 64);      // the word's other field
     if (ff == 0) {

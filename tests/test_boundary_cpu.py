@@ -150,3 +150,22 @@ def test_bad_ragged_call_arguments_rejected_before_launch():
     adv = lambda seq: lib.kvq_seq_advance(C.byref(c), seq, None)
     assert adv(None) == B.KVQ_ERR_INVALID_ARG
     assert adv(8) == B.KVQ_ERR_INVALID_ARG
+
+
+def test_bad_append_decode_arguments_rejected_before_launch():
+    lib = P.load_library()
+    c = cfg()
+    qc = B.kvq_qcache(256, 256, 256, 256, 256)
+    pool = B.kvq_pool(256, 256, 256, 256, 256, 256, 256)
+    res = B.kvq_residual(256, 256)
+    ws = P.kvq_query_sizes(c).workspace_bytes
+    ad = lambda **k: lib.kvq_append_decode_attention(C.byref(c), 0, 256, k.get("kn", 256), k.get("vn", 256), qc,
+                                                     k.get("nq", 64), k.get("res", res), 0, k.get("n", 10), pool, 256,
+                                                     512, ws, None)
+    assert ad(kn=None) == B.KVQ_ERR_INVALID_ARG
+    assert ad(vn=None) == B.KVQ_ERR_INVALID_ARG
+    assert ad(kn=258) == B.KVQ_ERR_INVALID_ARG               # rows are read 4 bytes at a time
+    assert ad(n=159) == B.KVQ_ERR_INVALID_ARG                # the token would fill the ring: group step first
+    assert ad(n=160) == B.KVQ_ERR_INVALID_ARG
+    assert ad(nq=48) == B.KVQ_ERR_INVALID_ARG
+    assert ad(res=B.kvq_residual(0, 256)) == B.KVQ_ERR_INVALID_ARG

@@ -392,3 +392,50 @@ def test_decode_replayed_from_a_captured_graph(g):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out, eager)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(bits=2, group_k=32, group_v=32, residual=128, outlier_budget=8),
+    dict(bits=4, group_k=64, group_v=64, residual=32, outlier_budget=3, q_heads=8),
+    dict(bits=2, group_k=32, group_v=128, residual=0, outlier_budget=4),      # every 32nd step fills the ring
+])
+def test_streaming_steps_with_the_append_inside_the_decode_launch(kw):
+    """Token by token with KVCache.step: on the steps that do not fill the ring the new token's rows
+    come with the decode launch, which attends to them and stores them; on the others the group step
+    runs first.  The output of every step is compared with the oracle, so a row that the launch
+    failed to store shows up in the following steps."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    base = dict(layers=1, batch=2, q_heads=2, kv_heads=2, context=300)
+    base.update(kw)
+    w = S.Workload("step", **base)
+    steps = 2 * w.group_k + 9
+    K, V = S.layer_kv(w, 0, w.context + steps)
+    G = w.group_k
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ((w.context + steps + G - 1) // G) * G, w.bits, G,
+                         w.group_v, w.residual, w.outlier_budget, w.aux_capacity, w.head_dim)
+    nq, nr = w.n_quant, w.n_res
+    cache = H.gpu_cache(w, K, V, nq, nr, cache=KC.KVCache(cfg))
+    states = H.oracle_states(w, K, V, nq)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    n = w.context
+    fused = 0
+    for s in range(steps):
+        Q = S.layer_queries(w, 0, s, "peaky")
+        before = cache.n_quant[0]
+        out = cache.step(0, Kd[:, :, n].contiguous(), Vd[:, :, n].contiguous(), torch.from_numpy(Q).cuda())
+        n += 1
+        if n - nq == w.residual + G:
+            for ui, st in enumerate(states):
+                b, h = divmod(ui, w.kv_heads)
+                st.append_group(K[b, h, nq:nq + G], V[b, h, nq:nq + G])
+            nq += G
+            assert cache.n_quant[0] == before + G
+        else:
+            fused += 1
+        assert cache.n_quant[0] == nq and cache.n_res[0] == n - nq
+        ref = H.oracle_attention(w, states, Q, K, V, nq, n - nq)
+        got = out.cpu().numpy().astype(np.float64)
+        assert float(np.abs(got - ref).max()) <= ATT_TOL, (s, n, nq)
+    assert fused >= steps - 3
+    H.compare_state(cache, states, w, nq)

@@ -133,16 +133,18 @@ def test_packer_against_hand_computed_positions_and_bijection():
     with open(os.path.join(HERE, "golden", "packed_layout_positions.txt")) as f:
         for line in f:
             if line.strip() and not line.startswith("#"):
-                kind, bits, t, c, byte, bit = line.split()
-                rows.append((kind, int(bits), int(t), int(c), int(byte), int(bit)))
+                kind, bits, t, c, byte, start = line.split()
+                rows.append((kind, int(bits), int(t), int(c), int(byte), int(start)))
     assert len(rows) >= 20
-    for kind, bits, t, c, byte, bit in rows:
-        codes = np.zeros((32, 128), np.uint8)
-        codes[t, c] = (1 << bits) - 1
-        packed = (O.pack_k_block if kind == "K" else O.pack_v_block)(codes, bits)
-        want = np.zeros(512 * bits, np.uint8)
-        want[byte] = ((1 << bits) - 1) << bit
-        assert np.array_equal(packed, want), (kind, bits, t, c)
+    for kind, bits, t, c, byte, start in rows:
+        for code in ((1 << bits) - 1, 1):               # all bits of the code, then its lowest bit alone
+            codes = np.zeros((32, 128), np.uint8)
+            codes[t, c] = code
+            packed = (O.pack_k_block if kind == "K" else O.pack_v_block)(codes, bits)
+            want = np.zeros(128 * bits, np.uint32)
+            for i in range(bits):
+                want[byte // 4] |= np.uint32(((code >> i) & 1) << ((start + i) % 32))
+            assert np.array_equal(packed.view("<u4"), want), (kind, bits, t, c)
     # bijection: each (t, c) owns its own bits; all-ones fills every bit
     for bits in (2, 4):
         for fn in (O.pack_k_block, O.pack_v_block):
