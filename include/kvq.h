@@ -95,6 +95,20 @@ typedef struct kvq_sizes {
  * mask[u][block] bit t%32 is set when token
  * 32*block + t was selected as an outlier (it then lives in the outlier or auxiliary pool and
  * its codes are placeholders).
+ *
+ * Paged cache (page_table != NULL; what a serving stack needs, the paper uses fixed lengths): the
+ * five arrays are a pool of pages shared by the sequences.  A page holds one Key group (group_k
+ * tokens) of one sequence, for every layer and kv head: the arrays are laid out as above with the
+ * "unit" replaced by the plane p = layer * kv_heads + h and max_seq by n_pages * group_k, i.e. they
+ * have the sizes kvq_query_sizes gives for the same configuration with batch = 1 and
+ * max_seq = n_pages * group_k.  Key group j (tokens j*group_k ...) of sequence b is stored as group
+ * page_table[b * table_stride + j] of its planes.  The table is device memory, int32, read by the
+ * kernels when they run; table_stride >= max_seq / group_k, 0 < n_pages <= 2^20.  An entry outside
+ * [0, n_pages) is clamped to that range by the kernels (results are then wrong, accesses stay inside
+ * the arrays); entries of groups that no call touches are not read, with one exception: entry 0 of
+ * a sequence is read even while the sequence has no quantized token.  Two sequences must not name
+ * the same page.  Every entry point that takes a kvq_qcache accepts both forms; page_table == NULL
+ * (n_pages and table_stride ignored) is the dense form.
  */
 typedef struct kvq_qcache {
   void* k_codes;
@@ -102,6 +116,9 @@ typedef struct kvq_qcache {
   void* v_codes;
   void* v_meta;
   void* mask;
+  const int32_t* page_table;
+  int32_t table_stride;
+  int32_t n_pages;
 } kvq_qcache;
 
 /* Outlier pool and auxiliary pool (device).  Occupied slots are [0, pool_count[u]) and

@@ -38,7 +38,8 @@ class kvq_sizes(C.Structure):
 
 
 class kvq_qcache(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_meta", "v_codes", "v_meta", "mask")]
+    _fields_ = [(n, C.c_void_p) for n in ("k_codes", "k_meta", "v_codes", "v_meta", "mask", "page_table")] + \
+               [("table_stride", C.c_int32), ("n_pages", C.c_int32)]
 
 
 class kvq_pool(C.Structure):

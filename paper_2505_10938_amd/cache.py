@@ -18,37 +18,72 @@ def make_config(layers, batch, q_heads, kv_heads, max_seq, bits=2, group_k=32, g
 
 
 class KVCache:
-    """All caller-owned buffers of kvq for one configuration, on one device."""
+    """All caller-owned buffers of kvq for one configuration, on one device.
 
-    def __init__(self, cfg: B.kvq_config, device="cuda:0"):
+    With `n_pages` the quantized arrays are a pool of that many pages (one Key group of one
+    sequence each, for all layers and kv heads) and `page_table` (int32 [batch, max_seq / G], device)
+    says which page holds which group of which sequence; the caller fills it before the group is
+    quantized."""
+
+    def __init__(self, cfg: B.kvq_config, device="cuda:0", n_pages=None):
         self.cfg = cfg
         self.sizes = sz = B.kvq_query_sizes(cfg)
         dev = torch.device(device)
         self.device = dev
+        self.n_pages = n_pages
+        self.page_table = None
 
         def raw(nbytes):
             return torch.zeros(max(int(nbytes), 16), dtype=torch.uint8, device=dev)
 
-        self.k_codes, self.k_meta = raw(sz.k_codes_bytes), raw(sz.k_meta_bytes)
-        self.v_codes, self.v_meta = raw(sz.v_codes_bytes), raw(sz.v_meta_bytes)
-        self.mask = raw(sz.mask_bytes)
+        qsz = sz
+        if n_pages is not None:      # the pool is laid out as the dense cache of one sequence of n_pages groups
+            qsz = B.kvq_query_sizes(make_config(cfg.layers, 1, cfg.kv_heads, cfg.kv_heads, n_pages * cfg.group_k,
+                                                cfg.bits, cfg.group_k, cfg.group_v, cfg.residual, cfg.outlier_budget,
+                                                cfg.aux_capacity, cfg.head_dim))
+            self.page_table = torch.zeros(cfg.batch, cfg.max_seq // cfg.group_k, dtype=torch.int32, device=dev)
+        self.k_codes, self.k_meta = raw(qsz.k_codes_bytes), raw(qsz.k_meta_bytes)
+        self.v_codes, self.v_meta = raw(qsz.v_codes_bytes), raw(qsz.v_meta_bytes)
+        self.mask = raw(qsz.mask_bytes)
         self.k_res, self.v_res = raw(sz.res_bytes), raw(sz.res_bytes)
         self.pool_k, self.pool_v = raw(sz.pool_rows_bytes), raw(sz.pool_rows_bytes)
         self.pool_idx, self.pool_score = raw(sz.pool_idx_bytes), raw(sz.pool_score_bytes)
         self.pool_count, self.aux_count, self.frozen = (raw(sz.counter_bytes) for _ in range(3))
         self.selected = raw(sz.selected_bytes)
         self.workspace = raw(sz.workspace_bytes)
-        self.qcache = B.kvq_qcache(*(t.data_ptr() for t in (self.k_codes, self.k_meta, self.v_codes, self.v_meta,
-                                                            self.mask)))
-        self.pool = B.kvq_pool(*(t.data_ptr() for t in (self.pool_k, self.pool_v, self.pool_idx, self.pool_score,
-                                                        self.pool_count, self.aux_count, self.frozen)))
-        self.res = B.kvq_residual(self.k_res.data_ptr(), self.v_res.data_ptr())
+        self._bind()
         # per-layer schedule state (uniform over the batch)
         self.n_quant = [0] * cfg.layers
         self.res_start = [0] * cfg.layers
         self.n_res = [0] * cfg.layers
 
+    def _bind(self):
+        """The structures the library takes, from the tensors."""
+        ptrs = [t.data_ptr() for t in (self.k_codes, self.k_meta, self.v_codes, self.v_meta, self.mask)]
+        if self.page_table is None:
+            self.qcache = B.kvq_qcache(*ptrs)
+        else:
+            self.qcache = B.kvq_qcache(*ptrs, self.page_table.data_ptr(), self.page_table.shape[1], self.n_pages)
+        self.pool = B.kvq_pool(*(t.data_ptr() for t in (self.pool_k, self.pool_v, self.pool_idx, self.pool_score,
+                                                        self.pool_count, self.aux_count, self.frozen)))
+        self.res = B.kvq_residual(self.k_res.data_ptr(), self.v_res.data_ptr())
+
     # ---- views for tests / loaders -------------------------------------------------------------
+    def dense_quantized(self):
+        """The five quantized arrays in the dense layout [units, ...] (uint8 tensors): the arrays
+        themselves, or, for a paged cache, its pages gathered through the table."""
+        arrays = (self.k_codes, self.k_meta, self.v_codes, self.v_meta, self.mask)
+        if self.page_table is None:
+            return arrays
+        c = self.cfg
+        table = self.page_table.long().clamp(0, self.n_pages - 1)
+        out = []
+        for t in arrays:
+            per_page = t.numel() // (c.layers * c.kv_heads * self.n_pages)
+            pages = t[:c.layers * c.kv_heads * self.n_pages * per_page].view(c.layers, c.kv_heads, self.n_pages, per_page)
+            out.append(pages[:, :, table].permute(0, 2, 1, 3, 4).reshape(-1))   # [layers, batch, kv_heads, groups, bytes]
+        return tuple(out)
+
     @property
     def units_per_layer(self):
         return self.cfg.batch * self.cfg.kv_heads
@@ -158,14 +193,13 @@ class KVCache:
     def clone(self):
         """A second cache with the same contents in its own device memory."""
         other = KVCache.__new__(KVCache)
-        other.cfg, other.sizes, other.device = self.cfg, self.sizes, self.device
+        other.cfg, other.sizes, other.device, other.n_pages = self.cfg, self.sizes, self.device, self.n_pages
         names = ("k_codes", "k_meta", "v_codes", "v_meta", "mask", "k_res", "v_res", "pool_k", "pool_v",
                  "pool_idx", "pool_score", "pool_count", "aux_count", "frozen", "selected", "workspace")
         for n in names:
             setattr(other, n, getattr(self, n).clone())
-        other.qcache = B.kvq_qcache(*(getattr(other, n).data_ptr() for n in names[:5]))
-        other.pool = B.kvq_pool(*(getattr(other, n).data_ptr() for n in names[7:14]))
-        other.res = B.kvq_residual(other.k_res.data_ptr(), other.v_res.data_ptr())
+        other.page_table = None if self.page_table is None else self.page_table.clone()
+        other._bind()
         other.n_quant, other.res_start, other.n_res = list(self.n_quant), list(self.res_start), list(self.n_res)
         other.prefill_selected = None
         return other
@@ -176,8 +210,8 @@ class RaggedKVCache(KVCache):
     n_res, active} is a device array that the library reads and advances; the host keeps only
     an upper bound of the longest sequence, which sizes the decode launch."""
 
-    def __init__(self, cfg: B.kvq_config, device="cuda:0"):
-        super().__init__(cfg, device)
+    def __init__(self, cfg: B.kvq_config, device="cuda:0", n_pages=None):
+        super().__init__(cfg, device, n_pages)
         self.seq_state = torch.zeros(cfg.batch, 4, dtype=torch.int32, device=self.device)
         self.longest = 0                                  # tokens of the longest sequence, at most
 

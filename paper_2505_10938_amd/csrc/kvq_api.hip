@@ -84,6 +84,30 @@ Dims make_dims(const kvq_config* c, int32_t layer) {
   d.groups_per_unit = c->max_seq / c->group_k;
   d.vgroups = c->head_dim / c->group_v;
   d.bpg_shift = c->group_k == 32 ? 0 : (c->group_k == 64 ? 1 : 2);
+  d.page_table = nullptr;
+  d.table_stride = 0;
+  d.n_pages = 0;
+  d.plane0 = (int64_t)layer * c->kv_heads;
+  return d;
+}
+
+// The five arrays and, for a paged cache, its table's shape.
+bool qcache_ok(const kvq_config* c, const kvq_qcache& qc) {
+  if (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask) return false;
+  if (!qc.page_table) return true;
+  return qc.n_pages > 0 && qc.n_pages <= (1 << 20) && qc.table_stride >= c->max_seq / c->group_k &&
+         (((uintptr_t)qc.page_table) & 3) == 0;
+}
+// Dims of a launch that reads or writes the quantized cache `qc`.
+Dims make_dims(const kvq_config* c, int32_t layer, const kvq_qcache& qc) {
+  Dims d = make_dims(c, layer);
+  if (qc.page_table) {
+    d.page_table = qc.page_table;
+    d.table_stride = qc.table_stride;
+    d.n_pages = qc.n_pages;
+    d.groups_per_unit = qc.n_pages;
+    d.blocks_per_unit = qc.n_pages << d.bpg_shift;
+  }
   return d;
 }
 
@@ -207,8 +231,8 @@ int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_i
   if (!k_group || !v_group) return KVQ_ERR_INVALID_ARG;
   if (unit_stride < (int64_t)cfg->group_k * cfg->head_dim || unit_stride % 8 != 0) return KVQ_ERR_INVALID_ARG;
   if ((((uintptr_t)k_group) | ((uintptr_t)v_group)) & 15) return KVQ_ERR_INVALID_ARG;
-  if (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask) return KVQ_ERR_INVALID_ARG;
-  const Dims d = make_dims(cfg, layer);
+  if (!qcache_ok(cfg, qc)) return KVQ_ERR_INVALID_ARG;
+  const Dims d = make_dims(cfg, layer, qc);
   return from_hip(kvq::launch_quantize(d, group_index, 1, (const __half*)k_group, (const __half*)v_group,
                                        unit_stride, selected, cfg->group_k, qc, (hipStream_t)stream));
 }
@@ -230,9 +254,8 @@ int32_t kvq_prefill_quantize(const kvq_config* cfg, int32_t layer, const void* k
   if (!pool.pool_count || !pool.aux_count || !pool.frozen) return KVQ_ERR_INVALID_ARG;
   if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v || !pool.pool_idx || !pool.pool_score))
     return KVQ_ERR_INVALID_ARG;
-  if (n_groups > 0 && (!selected || !qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask))
-    return KVQ_ERR_INVALID_ARG;
-  const Dims d = make_dims(cfg, layer);
+  if (n_groups > 0 && (!selected || !qcache_ok(cfg, qc))) return KVQ_ERR_INVALID_ARG;
+  const Dims d = n_groups > 0 ? make_dims(cfg, layer, qc) : make_dims(cfg, layer);
   hipStream_t s = (hipStream_t)stream;
   if (n_groups > 0) {
     if (n_groups > 65535) return KVQ_ERR_UNSUPPORTED;                  // grid limit of the quantization launch
@@ -262,9 +285,9 @@ int32_t kvq_append_trace_quantize(const kvq_config* cfg, int32_t layer, const vo
   if (!pool.pool_count || !pool.aux_count || !pool.frozen) return KVQ_ERR_INVALID_ARG;
   if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v || !pool.pool_idx || !pool.pool_score))
     return KVQ_ERR_INVALID_ARG;
-  if (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask) return KVQ_ERR_INVALID_ARG;
+  if (!qcache_ok(cfg, qc)) return KVQ_ERR_INVALID_ARG;
   if ((((uintptr_t)res.k_res) | ((uintptr_t)res.v_res)) & 15) return KVQ_ERR_INVALID_ARG;
-  const Dims d = make_dims(cfg, layer);
+  const Dims d = make_dims(cfg, layer, qc);
   return from_hip(kvq::launch_group_step(d, n_quant / G, (const __half*)k_new, (const __half*)v_new,
                                          (__half*)res.k_res, (__half*)res.v_res, (res_start + n_res) % rows,
                                          res_start, nullptr, pool, selected, qc, (hipStream_t)stream));
@@ -281,9 +304,9 @@ int32_t kvq_append_trace_quantize_ragged(const kvq_config* cfg, int32_t layer, c
   if (!pool.pool_count || !pool.aux_count || !pool.frozen) return KVQ_ERR_INVALID_ARG;
   if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v || !pool.pool_idx || !pool.pool_score))
     return KVQ_ERR_INVALID_ARG;
-  if (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask) return KVQ_ERR_INVALID_ARG;
+  if (!qcache_ok(cfg, qc)) return KVQ_ERR_INVALID_ARG;
   if ((((uintptr_t)res.k_res) | ((uintptr_t)res.v_res)) & 15) return KVQ_ERR_INVALID_ARG;
-  const Dims d = make_dims(cfg, layer);
+  const Dims d = make_dims(cfg, layer, qc);
   return from_hip(kvq::launch_group_step(d, 0, (const __half*)k_new, (const __half*)v_new, (__half*)res.k_res,
                                          (__half*)res.v_res, 0, 0, seq_state, pool, selected, qc,
                                          (hipStream_t)stream));
@@ -317,18 +340,20 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, kvq_q
     if (n_res + 1 >= cfg->residual + cfg->group_k || !res.k_res || !res.v_res) return KVQ_ERR_INVALID_ARG;
     if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 3) return KVQ_ERR_INVALID_ARG;
   }
-  if (n_quant > 0 && (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask))
-    return KVQ_ERR_INVALID_ARG;
+  // the arrays are needed even when nothing is quantized yet: every workgroup issues the loads of a
+  // first block (the last one, or block 0) whether or not it has quantized tokens to work on
+  if (!qcache_ok(cfg, qc)) return KVQ_ERR_INVALID_ARG;
   if (n_res > 0 && (!res.k_res || !res.v_res)) return KVQ_ERR_INVALID_ARG;
   if (!pool.pool_count || !pool.aux_count) return KVQ_ERR_INVALID_ARG;
-  if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v)) return KVQ_ERR_INVALID_ARG;
+  // every pool slot is read, filled or not, so the rows must exist whenever there are slots
+  if (cfg->outlier_budget + cfg->aux_capacity > 0 && (!pool.pool_k || !pool.pool_v)) return KVQ_ERR_INVALID_ARG;
   kvq_sizes sz;
   kvq_query_sizes(cfg, &sz);
   if (!workspace || ((uintptr_t)workspace & 255) != 0) return KVQ_ERR_WORKSPACE;
   if ((int64_t)workspace_bytes < sz.workspace_bytes) return KVQ_ERR_WORKSPACE;
 
   kvq::DecodeArgs a;
-  a.d = make_dims(cfg, layer);
+  a.d = make_dims(cfg, layer, qc);
   a.q = (const __half*)q;
   a.k_codes = (const uint8_t*)qc.k_codes;
   a.k_meta = (const uint32_t*)qc.k_meta;
@@ -382,8 +407,6 @@ int32_t kvq_decode_attention_ragged(const kvq_config* cfg, int32_t layer, const 
                                     int32_t max_n_res, kvq_pool pool, void* out, void* workspace,
                                     size_t workspace_bytes, void* stream) {
   if (!seq_state || (((uintptr_t)seq_state) & 15)) return KVQ_ERR_INVALID_ARG;
-  if (max_n_quant > 0 && (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask))
-    return KVQ_ERR_INVALID_ARG;
   return decode_common(cfg, layer, q, qc, max_n_quant, res, 0, max_n_res, seq_state, nullptr, nullptr, pool, out,
                        workspace, workspace_bytes, stream);
 }

@@ -30,11 +30,31 @@ struct Dims {
   int32_t units_per_layer;                    // batch * kv_heads
   int64_t unit0;                              // first unit of the layer being processed
   int32_t block_bytes;                        // 512 * bits
-  int32_t blocks_per_unit;                    // max_seq / 32
-  int32_t groups_per_unit;                    // max_seq / G
+  int32_t blocks_per_unit;                    // max_seq / 32; paged: blocks per plane = n_pages * G / 32
+  int32_t groups_per_unit;                    // max_seq / G;  paged: n_pages
   int32_t vgroups;                            // head_dim / Gv
   int32_t bpg_shift;                          // log2(G / 32): blocks per Key group
+  // Paged quantized cache (page_table != null): the quantized arrays hold, per plane (layer, kv head),
+  // n_pages pages of one Key group each; group j of sequence b is page page_table[b * table_stride + j].
+  const int32_t* page_table;
+  int32_t table_stride;
+  int32_t n_pages;
+  int64_t plane0;                             // layer * kv_heads
 };
+
+// Where group `group` of local unit ul = b * kv_heads + h is stored: `row` indexes runs of
+// groups_per_unit groups (blocks_per_unit blocks), `slot` the group inside the run.  A page number
+// outside [0, n_pages) is clamped, so that whatever the table holds the access stays inside the pool.
+struct GroupPlace {
+  int64_t row;
+  int32_t slot;
+};
+__device__ inline GroupPlace place_of_group(const Dims& d, int ul, int group) {
+  if (!d.page_table) return {d.unit0 + ul, group};
+  const int b = ul / d.kv_heads, h = ul - b * d.kv_heads;
+  const int page = d.page_table[(int64_t)b * d.table_stride + group];
+  return {d.plane0 + h, min(max(page, 0), d.n_pages - 1)};
+}
 
 struct DecodeArgs {
   Dims d;

@@ -210,6 +210,10 @@ template <int GQ, int NV>
 constexpr int merge_bytes_per_wave() { return (2 * GQ * kHeadDim + 4 * GQ + GQ * NV) * 4; }
 
 // Uniform (per wavefront) base pointers of the unit's quantized cache; loads add 32-bit offsets.
+// Block i of a dense cache is the unit's i-th block.  In a paged cache the blocks of Key group j
+// are those of page table[j] of the plane (layer, kv head) the pointers address; the physical
+// block numbers of the mini-chunk about to be loaded are kept in `pb`.
+template <bool PAGED>
 struct UnitPtrs {
   const unsigned char* kc;    // Key codes
   const unsigned char* vc;    // Value codes
@@ -220,6 +224,44 @@ struct UnitPtrs {
   int last_block;             // the last of them (0 if there is none: the cache holds at least one block)
   int bpg_shift;
   uint32_t block_bytes;
+  const int32_t* table;       // paged: the sequence's row of the page table
+  int n_pages;                // paged: pages per plane
+  uint32_t pb0, pb1, pb2, pb3;  // paged: where the four blocks of the mini-chunk being loaded are stored
+  uint32_t pbl;               // paged: the same for block lane >> 4 (per lane)
+
+  // block i of mini-chunk mc, as stored (a block past the end is replaced by the last one)
+  __device__ __forceinline__ uint32_t block(int mc, int i) const {
+    if constexpr (PAGED) return i == 0 ? pb0 : i == 1 ? pb1 : i == 2 ? pb2 : pb3;
+    else return (uint32_t)min(mc * 4 + i, last_block);
+  }
+  // the block of this lane's token pair: block lane >> 4 of the mini-chunk
+  __device__ __forceinline__ uint32_t lane_block(int mc, int lane) const {
+    if constexpr (PAGED) return pbl;
+    else return (uint32_t)min(mc * 4 + (lane >> 4), last_block);
+  }
+  // Page-table entries of mini-chunk mc: that of block lane & 3 (lanes 0..3 are read out to scalar
+  // registers) and that of the lane's own block lane >> 4.  Vector loads: they take their turn among
+  // the other loads in flight.  `resolve` turns them into block numbers.  An entry outside
+  // [0, n_pages) is clamped: whatever the table holds, accesses stay inside the pool.
+  struct Pages {
+    uint32_t of_block, of_lane;
+  };
+  __device__ __forceinline__ Pages fetch_pages(int mc, int lane) const {
+    const uint32_t b0 = (uint32_t)min(mc * 4 + (lane & 3), last_block);
+    const uint32_t b1 = (uint32_t)min(mc * 4 + (lane >> 4), last_block);
+    return {(uint32_t)table[b0 >> bpg_shift], (uint32_t)table[b1 >> bpg_shift]};
+  }
+  __device__ __forceinline__ uint32_t stored_block(uint32_t logical, uint32_t entry) const {
+    const int page = min(max((int)entry, 0), n_pages - 1);
+    return ((uint32_t)page << bpg_shift) | (logical & ((1u << bpg_shift) - 1u));
+  }
+  __device__ __forceinline__ void resolve(int mc, Pages e, int lane) {
+    pb0 = stored_block((uint32_t)min(mc * 4 + 0, last_block), __builtin_amdgcn_readlane(e.of_block, 0));
+    pb1 = stored_block((uint32_t)min(mc * 4 + 1, last_block), __builtin_amdgcn_readlane(e.of_block, 1));
+    pb2 = stored_block((uint32_t)min(mc * 4 + 2, last_block), __builtin_amdgcn_readlane(e.of_block, 2));
+    pb3 = stored_block((uint32_t)min(mc * 4 + 3, last_block), __builtin_amdgcn_readlane(e.of_block, 3));
+    pbl = stored_block((uint32_t)min(mc * 4 + (lane >> 4), last_block), e.of_lane);
+  }
 };
 template <typename T>
 __device__ __forceinline__ T ld(const unsigned char* base, uint32_t off) {
@@ -229,22 +271,22 @@ __device__ __forceinline__ T ld(const unsigned char* base, uint32_t off) {
 // Loads of one mini-chunk, in the four parts the compute phases consume.  A block past the end of
 // the quantized segment is replaced by the last block with every token masked, so that every
 // wave runs the same straight-line code.
-template <int BITS, int NV>
-__device__ __forceinline__ void load_k_meta_block(McRegs<BITS, NV>& R, const UnitPtrs& P, int mc, int i, int lane) {
+template <int BITS, int NV, class PT>
+__device__ __forceinline__ void load_k_meta_block(McRegs<BITS, NV>& R, const PT& P, int mc, int i, int lane) {
   // uniform base (scalar registers) + one lane offset shared by all loads
-  const unsigned char* gp = P.km + ((uint32_t)min(mc * 4 + i, P.last_block) >> P.bpg_shift) * 512u;
+  const unsigned char* gp = P.km + (P.block(mc, i) >> P.bpg_shift) * 512u;
   R.ksp[i] = ld<uint32_t>(gp, lane * 4u);
   R.ksz[i] = ld<uint32_t>(gp + 256, lane * 4u);
 }
-template <int BITS, int NV>
-__device__ __forceinline__ void load_k_meta(McRegs<BITS, NV>& R, const UnitPtrs& P, int mc, int lane) {
+template <int BITS, int NV, class PT>
+__device__ __forceinline__ void load_k_meta(McRegs<BITS, NV>& R, const PT& P, int mc, int lane) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) load_k_meta_block<BITS, NV>(R, P, mc, i, lane);
+  for (int i = 0; i < 4; ++i) load_k_meta_block(R, P, mc, i, lane);
 }
-template <int BITS>
+template <int BITS, class PT>
 __device__ __forceinline__ void load_codes_block(uint32_t (&w)[4][2 * BITS], const unsigned char* codes,
-                                                 const UnitPtrs& P, int mc, int i, int lane) {
-  const unsigned char* bp = codes + (uint32_t)min(mc * 4 + i, P.last_block) * P.block_bytes;   // uniform
+                                                 const PT& P, int mc, int i, int lane) {
+  const unsigned char* bp = codes + P.block(mc, i) * P.block_bytes;   // uniform
 #pragma unroll
   for (int hf = 0; hf < BITS / 2; ++hf) {
     const uint4 t = ld<uint4>(bp + hf * 1024, lane * 16u);
@@ -254,17 +296,17 @@ __device__ __forceinline__ void load_codes_block(uint32_t (&w)[4][2 * BITS], con
     w[i][4 * hf + 3] = t.w;
   }
 }
-template <int BITS>
-__device__ __forceinline__ void load_codes(uint32_t (&w)[4][2 * BITS], const unsigned char* codes, const UnitPtrs& P,
+template <int BITS, class PT>
+__device__ __forceinline__ void load_codes(uint32_t (&w)[4][2 * BITS], const unsigned char* codes, const PT& P,
                                            int mc, int lane) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) load_codes_block<BITS>(w, codes, P, mc, i, lane);
 }
-template <int BITS, int NV>
-__device__ __forceinline__ void load_v_meta(McRegs<BITS, NV>& R, const UnitPtrs& P, int mc, int lane) {
+template <int BITS, int NV, class PT>
+__device__ __forceinline__ void load_v_meta(McRegs<BITS, NV>& R, const PT& P, int mc, int lane) {
   // this lane's tokens are 2*lane, 2*lane+1 of the 128: pair lane&15 of block lane>>4
   const int myblk = mc * 4 + (lane >> 4);
-  const uint32_t blk = (uint32_t)min(myblk, P.last_block);
+  const uint32_t blk = P.lane_block(mc, lane);
   // the loaded word is not touched here: any use would make this point wait for the load
   R.mkw = ld<uint32_t>(P.mask, blk * 4u);
   R.mk_valid = myblk < P.nblocks;
@@ -284,10 +326,10 @@ struct WaveAcc {
   float m[GQ];       // running maximum per head (log2 domain)
 };
 
-template <int GQ, int BITS, int NV, bool more>
+template <int GQ, int BITS, int NV, bool more, class PT>
 __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<GQ>& S, WaveLds<GQ, NV>& L,
                                                   const half2v (&qh)[GQ], const half2v (&ql)[GQ], int lane,
-                                                  const UnitPtrs& P, int mc_next) {
+                                                  const PT& P, int mc_next) {
   // Each group of registers is reloaded for the wave's next mini-chunk (mc_next, if `more`) right
   // after its last use here, so those loads are in flight during the rest of this mini-chunk.
   // `more` is a template parameter so that every path has a fixed number of loads in flight and
@@ -314,7 +356,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
 #pragma unroll
   for (int i = 0; i < 4; ++i) ((uint32_t*)L.k.zk[i])[lane] = R.ksz[i];
   key_rows(0);
-  if (more) load_k_meta_block<BITS, NV>(R, P, mc_next, 0, lane);
+  if (more) load_k_meta_block(R, P, mc_next, 0, lane);
   wave_sync();
 
   // ---- sum_c q_c z_c of the 4 blocks: column n of B = zeros of block n & 3 --------------------------
@@ -334,7 +376,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
   for (int i = 0; i < 4; ++i) {
     if (i + 1 < 4) {
       key_rows(i + 1);
-      if (more) load_k_meta_block<BITS, NV>(R, P, mc_next, i + 1, lane);
+      if (more) load_k_meta_block(R, P, mc_next, i + 1, lane);
     }
     // both 16-token halves of the block share each operand row read
     float4v D0 = {0.f, 0.f, 0.f, 0.f}, D1 = {0.f, 0.f, 0.f, 0.f};
@@ -455,7 +497,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
   // (the Value steps, zeros and mask word are reloaded here and not right after their last use:
   // held in flight across the products above they were moved to other registers at the end of
   // every pass, and such a move waits for the load)
-  if (more) load_v_meta<BITS, NV>(R, P, mc_next, lane);
+  if (more) load_v_meta(R, P, mc_next, lane);
   if (more) load_codes<BITS>(R.vc, P.vc, P, mc_next, lane);
 }
 
@@ -578,7 +620,7 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
 // grid (splits, kv_heads * head_parts, batch), 64 * a.nw threads (a.nw at most what one compute unit
 // holds of this instance), a.nw * sizeof(WaveLds) bytes of dynamic LDS
 
-template <int GQ, int BITS, int NV>
+template <int GQ, int BITS, int NV, bool PAGED>
 __global__ void __launch_bounds__(64 * 4 * kDecodeWavesPerSimd) __attribute__((amdgpu_waves_per_eu(kDecodeWavesPerSimd)))
 decode_kernel(DecodeArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -592,7 +634,7 @@ decode_kernel(DecodeArgs a) {
                "s"(d.bpg_shift), "s"(d.block_bytes), "s"(d.blocks_per_unit), "s"(d.groups_per_unit), "s"(a.q),
                "s"(a.k_codes), "s"(a.k_meta), "s"(a.v_codes), "s"(a.v_meta), "s"(a.mask), "s"(a.k_res), "s"(a.v_res),
                "s"(a.pool_k), "s"(a.pool_v), "s"(a.pool_count), "s"(a.aux_count), "s"(a.seq));
-  asm volatile("" ::"s"(a.k_new), "s"(a.v_new));
+  asm volatile("" ::"s"(a.k_new), "s"(a.v_new), "s"(d.page_table), "s"(d.table_stride), "s"(d.n_pages), "s"(d.plane0));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -623,6 +665,23 @@ decode_kernel(DecodeArgs a) {
     sq.res_start = (own.y >= 0 && own.y < d.res_rows) ? own.y : 0;
     sq.n_res = min(max(own.z, 0), a.n_res);
     sq.n_ring = sq.n_res;
+  }
+
+  UnitPtrs<PAGED> P;
+  P.nblocks = sq.n_quant >> 5;
+  P.last_block = max(P.nblocks - 1, 0);
+  P.bpg_shift = d.bpg_shift;
+  P.block_bytes = (uint32_t)d.block_bytes;
+  P.table = PAGED ? d.page_table + (int64_t)b * d.table_stride : nullptr;
+  P.n_pages = d.n_pages;
+  int mc = split * a.mc_per_split + wave;
+  // A paged cache: the page numbers of the wave's first two mini-chunks are asked for before
+  // everything else, so that the loads of the first mini-chunk can follow as soon as possible
+  // (from then on the entries of a mini-chunk are fetched one mini-chunk ahead of its loads).
+  typename UnitPtrs<PAGED>::Pages pages_now = {0, 0}, pages_next = {0, 0};
+  if constexpr (PAGED) {
+    pages_now = P.fetch_pages(mc, lane);
+    pages_next = P.fetch_pages(mc + nw, lane);
   }
 
   // Loads go out in the order their data is needed, and all of them before anything is waited
@@ -659,24 +718,22 @@ decode_kernel(DecodeArgs a) {
   int n_aux = a.aux_count[uv];
   fp_load(X, a, sq, u, qbase, rg * 16, lane);
 
-  UnitPtrs P;
-  P.nblocks = sq.n_quant >> 5;
-  P.last_block = max(P.nblocks - 1, 0);
-  P.bpg_shift = d.bpg_shift;
-  P.block_bytes = (uint32_t)d.block_bytes;
-  P.kc = a.k_codes + u * d.blocks_per_unit * (int64_t)d.block_bytes;
-  P.vc = a.v_codes + u * d.blocks_per_unit * (int64_t)d.block_bytes;
-  P.km = (const unsigned char*)(a.k_meta + u * d.groups_per_unit * kHeadDim);
-  P.vm = (const unsigned char*)a.v_meta + u * d.blocks_per_unit * (int64_t)(128 * NV);
-  P.mask = (const unsigned char*)(a.mask + u * d.blocks_per_unit);
+  // Quantized arrays: a dense cache keeps the blocks of unit u together, a paged one those of the
+  // plane (layer, kv head); there d.blocks_per_unit and d.groups_per_unit are the plane's.
+  const int64_t uq = PAGED ? d.plane0 + h : u;
+  P.kc = a.k_codes + uq * d.blocks_per_unit * (int64_t)d.block_bytes;
+  P.vc = a.v_codes + uq * d.blocks_per_unit * (int64_t)d.block_bytes;
+  P.km = (const unsigned char*)(a.k_meta + uq * d.groups_per_unit * kHeadDim);
+  P.vm = (const unsigned char*)a.v_meta + uq * d.blocks_per_unit * (int64_t)(128 * NV);
+  P.mask = (const unsigned char*)(a.mask + uq * d.blocks_per_unit);
   const int n_mc = (sq.n_quant + kMiniChunk - 1) / kMiniChunk;
   const int mc_end = min(n_mc, (split + 1) * a.mc_per_split);
-  int mc = split * a.mc_per_split + wave;
   const bool has_q = mc < mc_end;                        // uniform over the wave
   McRegs<BITS, NV> R;
-  load_k_meta<BITS, NV>(R, P, mc, lane);
+  if constexpr (PAGED) P.resolve(mc, pages_now, lane);
+  load_k_meta(R, P, mc, lane);
   load_codes<BITS>(R.kc, P.kc, P, mc, lane);
-  load_v_meta<BITS, NV>(R, P, mc, lane);
+  load_v_meta(R, P, mc, lane);
   load_codes<BITS>(R.vc, P.vc, P, mc, lane);
 
   // this lane's two channels (2*lane, 2*lane+1) of every query head, log2-domain scaled
@@ -730,7 +787,14 @@ decode_kernel(DecodeArgs a) {
       qh[j] = as_half2(hi);
       ql[j] = as_half2(lo);
     }
-    for (; mc + nw < mc_end; mc += nw) compute_minichunk<GQ, BITS, NV, true>(R, S, L, qh, ql, lane, P, mc + nw);
+    for (; mc + nw < mc_end; mc += nw) {
+      if constexpr (PAGED) {
+        const auto pages_after = P.fetch_pages(mc + 2 * nw, lane);
+        P.resolve(mc + nw, pages_next, lane);
+        pages_next = pages_after;
+      }
+      compute_minichunk<GQ, BITS, NV, true>(R, S, L, qh, ql, lane, P, mc + nw);
+    }
     compute_minichunk<GQ, BITS, NV, false>(R, S, L, qh, ql, lane, P, mc);
   }
   const float post_v = __builtin_amdgcn_exp2f((float)(24 - kShV));
@@ -847,14 +911,19 @@ decode_kernel(DecodeArgs a) {
   }
 }
 
-template <int GQ, int BITS, int NV>
-void launch_one(const DecodeArgs& a, dim3 grid, hipStream_t s) {
+template <int GQ, int BITS, int NV, bool PAGED>
+void launch_paged(const DecodeArgs& a, dim3 grid, hipStream_t s) {
   const size_t lds = (size_t)a.nw * sizeof(WaveLds<GQ, NV>);
   static_assert(merge_bytes_per_wave<GQ, NV>() <= (int)sizeof(WaveLds<GQ, NV>), "merge view must fit");
   if (lds > 48 * 1024)     // more than the default limit of dynamic LDS: raise it (cheap, idempotent)
-    (void)hipFuncSetAttribute((const void*)decode_kernel<GQ, BITS, NV>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds);
-  hipLaunchKernelGGL((decode_kernel<GQ, BITS, NV>), grid, dim3(64 * a.nw), lds, s, a);
+    (void)hipFuncSetAttribute((const void*)decode_kernel<GQ, BITS, NV, PAGED>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipLaunchKernelGGL((decode_kernel<GQ, BITS, NV, PAGED>), grid, dim3(64 * a.nw), lds, s, a);
+}
+template <int GQ, int BITS, int NV>
+void launch_one(const DecodeArgs& a, dim3 grid, hipStream_t s) {
+  if (a.d.page_table) launch_paged<GQ, BITS, NV, true>(a, grid, s);
+  else launch_paged<GQ, BITS, NV, false>(a, grid, s);
 }
 
 template <int GQ, int BITS>

@@ -110,7 +110,8 @@ __device__ __forceinline__ void rows_to_lds(const GroupRows<G>& r, const QuantLd
 
 // Quantization of the group held in LDS (rows stored, not yet synchronized): mean replacement of
 // the rows flagged (`flag` = this thread's token, threads below G), meta, codes, mask words.
-// Every thread of the 1024-thread workgroup calls it.
+// Every thread of the 1024-thread workgroup calls it.  (u, group_index) say where the group is stored
+// (place_of_group): the unit and the group's index, or, in a paged cache, the plane and the page.
 template <int BITS, int G>
 __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t group_index, const QuantLds<G>& L,
                                               uint8_t flag, uint8_t* __restrict__ k_codes,
@@ -283,8 +284,9 @@ __global__ void __launch_bounds__(kQuantThreads) quantize_kernel(
   rows_issue<G>(rows, k_group + row0, v_group + row0, tid);
   uint8_t flag = 0;
   if (tid < G && selected) flag = selected[(int64_t)ul * selected_unit_stride + gy * G + tid];
+  const GroupPlace at = place_of_group(d, ul, group_index + gy);
   rows_to_lds<G>(rows, L, tid);
-  quantize_body<BITS, G>(d, u, group_index + gy, L, flag, k_codes, k_meta, v_codes, v_meta, mask, tid);
+  quantize_body<BITS, G>(d, at.row, at.slot, L, flag, k_codes, k_meta, v_codes, v_meta, mask, tid);
 }
 
 // Rows n0 .. n0 + n - 1 of every unit's rows into ring rows 0 .. n - 1 (16 bytes per thread).
@@ -342,6 +344,7 @@ __global__ void __launch_bounds__(kQuantThreads) group_step_kernel(
     ((uint32_t*)((which ? vring : kring) + append_row * kHeadDim))[lane] = src[lane];
   }
   if (!close_group) return;
+  const GroupPlace at = place_of_group(d, ul, group_index);        // where the group's codes and meta go
   if (append_row >= group_row0 && append_row < group_row0 + G) {   // R = 0: the new token closes the group
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -367,7 +370,7 @@ __global__ void __launch_bounds__(kQuantThreads) group_step_kernel(
   }
   __syncthreads();                                   // the flags are in LDS
   const uint8_t flag = tid < G ? L.ssel[tid] : (uint8_t)0;
-  quantize_body<BITS, G>(d, u, group_index, L, flag, k_codes, k_meta, v_codes, v_meta, mask, tid);
+  quantize_body<BITS, G>(d, at.row, at.slot, L, flag, k_codes, k_meta, v_codes, v_meta, mask, tid);
 }
 
 template <int BITS, int G>

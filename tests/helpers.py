@@ -56,12 +56,14 @@ def compare_state(cache, states, w: S.Workload, n_quant: int, layer: int = 0, un
     nb = n_quant // 32
     ng = n_quant // w.group_k
     bb = 512 * w.bits
-    kc = cache.k_codes.cpu().numpy().reshape(sz.units, cfg.max_seq // 32, bb)
-    vc = cache.v_codes.cpu().numpy().reshape(sz.units, cfg.max_seq // 32, bb)
+    k_codes, k_meta, v_codes, v_meta, mask = (t.cpu().numpy() for t in cache.dense_quantized())
+    nblk, ngrp = cfg.max_seq // 32, cfg.max_seq // w.group_k
     nv = w.head_dim // w.group_v
-    km = cache.k_meta.cpu().numpy().view(np.uint16).reshape(sz.units, cfg.max_seq // w.group_k, 2, w.head_dim)
-    vm = cache.v_meta.cpu().numpy().view(np.uint16).reshape(sz.units, cfg.max_seq // 32, 64 * nv)
-    mk = cache.mask.cpu().numpy().view(np.uint32).reshape(sz.units, cfg.max_seq // 32)
+    kc = k_codes[:sz.units * nblk * bb].reshape(sz.units, nblk, bb)
+    vc = v_codes[:sz.units * nblk * bb].reshape(sz.units, nblk, bb)
+    km = k_meta.view(np.uint16)[:sz.units * ngrp * 2 * w.head_dim].reshape(sz.units, ngrp, 2, w.head_dim)
+    vm = v_meta.view(np.uint16)[:sz.units * nblk * 64 * nv].reshape(sz.units, nblk, 64 * nv)
+    mk = mask.view(np.uint32)[:sz.units * nblk].reshape(sz.units, nblk)
     slots = sz.pool_slots
     pk = cache.pool_k.cpu().numpy().view(np.uint16)[:sz.units * slots * w.head_dim].reshape(sz.units, slots, w.head_dim)
     pv = cache.pool_v.cpu().numpy().view(np.uint16)[:sz.units * slots * w.head_dim].reshape(sz.units, slots, w.head_dim)

@@ -169,3 +169,25 @@ def test_bad_append_decode_arguments_rejected_before_launch():
     assert ad(n=160) == B.KVQ_ERR_INVALID_ARG
     assert ad(nq=48) == B.KVQ_ERR_INVALID_ARG
     assert ad(res=B.kvq_residual(0, 256)) == B.KVQ_ERR_INVALID_ARG
+
+
+def test_bad_page_tables_rejected_before_launch():
+    lib = P.load_library()
+    c = cfg()
+    pool = B.kvq_pool(256, 256, 256, 256, 256, 256, 256)
+    res = B.kvq_residual(256, 256)
+    ws = P.kvq_query_sizes(c).workspace_bytes
+    groups = c.max_seq // c.group_k
+    paged = lambda table=256, stride=groups, pages=50: B.kvq_qcache(256, 256, 256, 256, 256, table, stride, pages)
+    dec = lambda qc: lib.kvq_decode_attention(C.byref(c), 0, 256, qc, 64, res, 0, 10, pool, 256, 512, ws, None)
+    step = lambda qc: lib.kvq_append_trace_quantize(C.byref(c), 0, 256, 256, res, 0, c.residual + c.group_k - 1, 64,
+                                                    pool, None, qc, None)
+    for call in (dec, step):
+        assert call(paged(pages=0)) == B.KVQ_ERR_INVALID_ARG            # an empty pool
+        assert call(paged(pages=-3)) == B.KVQ_ERR_INVALID_ARG
+        assert call(paged(pages=(1 << 20) + 1)) == B.KVQ_ERR_INVALID_ARG
+        assert call(paged(stride=groups - 1)) == B.KVQ_ERR_INVALID_ARG  # a table row shorter than a sequence can get
+        assert call(paged(table=258)) == B.KVQ_ERR_INVALID_ARG          # int32 entries
+    # the quantized arrays are needed even with nothing quantized: the first block is always loaded
+    assert lib.kvq_decode_attention(C.byref(c), 0, 256, B.kvq_qcache(0, 256, 256, 256, 256), 0, res, 0, 10, pool, 256,
+                                    512, ws, None) == B.KVQ_ERR_INVALID_ARG

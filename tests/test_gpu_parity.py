@@ -142,7 +142,7 @@ def test_four_bit_full_batch_sampled_units():
     run_sampled(w, [3, 100])
 
 
-def run_streaming(w: S.Workload, steps: int, fused: bool, check_every: int = 9):
+def run_streaming(w: S.Workload, steps: int, fused: bool, check_every: int = 9, make_cache=None):
     """Tokens arrive one by one: the ring fills, a group is traced and quantized every G steps (in
     one launch if `fused`, else by the three separate calls), attention runs after appends."""
     import torch
@@ -153,7 +153,7 @@ def run_streaming(w: S.Workload, steps: int, fused: bool, check_every: int = 9):
     ms = ((w.context + steps + G - 1) // G) * G
     cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ms, w.bits, G, w.group_v, w.residual,
                          w.outlier_budget, w.aux_capacity, w.head_dim)
-    cache = H.gpu_cache(w, K, V, nq0, nr0, cache=KC.KVCache(cfg))
+    cache = H.gpu_cache(w, K, V, nq0, nr0, cache=(make_cache or KC.KVCache)(cfg))
     states = H.oracle_states(w, K, V, nq0)
     Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
     n, nq = w.context, nq0
@@ -217,7 +217,7 @@ def test_stream_read_reads_without_touching_the_buffer():
 
 # ---- whole-prompt quantization: the state that token-by-token appends would leave -----------------------
 
-def run_prefill(w: S.Workload, regimes=("peaky",)):
+def run_prefill(w: S.Workload, regimes=("peaky",), make_cache=None):
     import torch
     from paper_2505_10938_amd import cache as KC
     K, V = S.layer_kv(w, 0)
@@ -226,7 +226,7 @@ def run_prefill(w: S.Workload, regimes=("peaky",)):
     G = w.group_k
     cfg = KC.make_config(w.layers, w.batch, w.q_heads, w.kv_heads, max(G, ((nq + G - 1) // G) * G), w.bits, G,
                          w.group_v, w.residual, w.outlier_budget, w.aux_capacity, w.head_dim)
-    cache = KC.KVCache(cfg)
+    cache = (make_cache or KC.KVCache)(cfg)
     cache.prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
     torch.cuda.synchronize()
     assert (cache.n_quant[0], cache.n_res[0], cache.res_start[0]) == (nq, nr, 0)
@@ -293,6 +293,10 @@ def ragged_lengths_state(n, G, R):
     (dict(bits=2, group_k=32, group_v=128, residual=0, outlier_budget=4), [32, 31, 257, 0]),
 ])
 def test_ragged_batch_streaming(kw, lengths):
+    run_ragged(kw, lengths)
+
+
+def run_ragged(kw, lengths, make_cache=None):
     """Sequences of different lengths in one batch: tokens are appended step by step to the
     sequences that are still growing (one launch per step and layer, the state kept on the device),
     then one decode launch serves all of them.  Every unit is compared with the oracle run on its
@@ -307,7 +311,7 @@ def test_ragged_batch_streaming(kw, lengths):
     ms = ((max(lengths) + G - 1) // G) * G
     cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ms, w.bits, G, w.group_v, R, w.outlier_budget,
                          w.aux_capacity, w.head_dim)
-    cache = KC.RaggedKVCache(cfg)
+    cache = (make_cache or KC.RaggedKVCache)(cfg)
     Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
     for t in range(max(lengths)):
         cache.set_active([t < n for n in lengths])
@@ -439,3 +443,115 @@ def test_streaming_steps_with_the_append_inside_the_decode_launch(kw):
         assert float(np.abs(got - ref).max()) <= ATT_TOL, (s, n, nq)
     assert fused >= steps - 3
     H.compare_state(cache, states, w, nq)
+
+
+# ---- paged quantized cache: pages of one Key group each, dealt to the sequences by a table ----------------
+
+def paged(cfg, seed=11, spare=7, kind=None):
+    """A paged cache whose pool has `spare` pages more than all sequences can fill, every group of
+    every sequence assigned a page of its own in a seeded random order."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    groups = cfg.max_seq // cfg.group_k
+    n_pages = cfg.batch * groups + spare
+    cache = (kind or KC.KVCache)(cfg, n_pages=n_pages)
+    deal = np.random.default_rng(seed).permutation(n_pages)[:cfg.batch * groups].reshape(cfg.batch, groups)
+    assert len(set(deal.reshape(-1).tolist())) == deal.size
+    cache.page_table.copy_(torch.from_numpy(deal.astype(np.int32)))
+    return cache
+
+
+@pytest.mark.parametrize("kw", [
+    dict(bits=2, group_k=32, group_v=32, residual=128, outlier_budget=8),                 # four pages per mini-chunk
+    dict(bits=4, group_k=64, group_v=64, residual=32, outlier_budget=3, q_heads=8),       # two
+    dict(bits=2, group_k=128, group_v=128, residual=32, outlier_budget=3, q_heads=16),    # one; two workgroup rows
+    dict(bits=2, group_k=32, group_v=128, residual=0, outlier_budget=4, batch=3),
+])
+def test_paged_streaming(kw):
+    """The streaming test on a paged cache: group steps write through the table, the decode launch
+    reads through it; pages gathered through the table must be the oracle's bytes."""
+    base = dict(batch=2, q_heads=4, kv_heads=2, context=1100)
+    base.update(kw)
+    w = small("paged", **base)
+    run_streaming(w, 2 * w.group_k + 5, True, check_every=13, make_cache=paged)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(),
+    dict(bits=4, group_k=64, group_v=64, residual=32, outlier_budget=3),
+    dict(bits=2, group_k=128, group_v=128, residual=32, outlier_budget=3, context=2048 + 300),
+    dict(context=100),                                                            # nothing to quantize
+])
+def test_paged_prefill(kw):
+    base = dict(batch=2, q_heads=4, kv_heads=2, context=1024 + 77)
+    base.update(kw)
+    run_prefill(S.Workload("paged_prefill", 1, **base), make_cache=paged)
+
+
+def test_paged_ragged_batch():
+    from paper_2505_10938_amd import cache as KC
+    run_ragged(dict(bits=2, group_k=32, group_v=32, residual=32, outlier_budget=4), [45, 300, 161, 96],
+               make_cache=lambda cfg: paged(cfg, kind=KC.RaggedKVCache))
+
+
+def test_paged_equals_dense_bit_for_bit_second_layer():
+    """Two layers, work on the second: a paged and a dense cache fed the same tokens hold the same
+    bytes (pages gathered through the table) and give the same outputs, bit for bit; the pages of the
+    first layer, and the pool's spare pages, stay untouched."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    w = small("paged_layers", layers=2, batch=2, q_heads=8, kv_heads=2, context=32 * 21 + 40, residual=32)
+    K, V = S.layer_kv(w, 1)
+    G = w.group_k
+    cfg = KC.make_config(w.layers, w.batch, w.q_heads, w.kv_heads, ((w.context + G - 1) // G) * G, w.bits, G,
+                         w.group_v, w.residual, w.outlier_budget, w.aux_capacity, w.head_dim)
+    a = H.gpu_cache(w, K, V, w.n_quant, w.n_res, layer=1, cache=KC.KVCache(cfg))
+    b = paged(cfg)
+    b.k_codes.fill_(0xA5)
+    b.v_codes.fill_(0xA5)
+    b = H.gpu_cache(w, K, V, w.n_quant, w.n_res, layer=1, cache=b)
+    for x, y, name in zip(a.dense_quantized(), b.dense_quantized(), ("k_codes", "k_meta", "v_codes", "v_meta", "mask")):
+        per_unit = x.numel() // a.sizes.units
+        n_used = {"k_codes": w.n_quant // 32 * 512 * w.bits, "v_codes": w.n_quant // 32 * 512 * w.bits}.get(name)
+        xs, ys = x.view(a.sizes.units, per_unit), y[:x.numel()].view(a.sizes.units, per_unit)
+        upl = w.batch * w.kv_heads
+        sl = slice(None) if n_used is None else slice(0, n_used)
+        assert torch.equal(xs[upl:, sl], ys[upl:, sl]), name
+    # pages never written: the first layer's planes and the spare pages keep the fill pattern
+    page_bytes = G // 32 * 512 * w.bits
+    planes = b.k_codes[:cfg.layers * cfg.kv_heads * b.n_pages * page_bytes].view(cfg.layers, cfg.kv_heads, b.n_pages, page_bytes)
+    assert bool((planes[0] == 0xA5).all())
+    used = set(b.page_table.cpu().numpy()[:, :w.n_quant // G].reshape(-1).tolist())
+    spare = [p for p in range(b.n_pages) if p not in used]
+    assert len(spare) >= 7 and bool((planes[1][:, spare] == 0xA5).all())
+    states = H.oracle_states(w, K, V, w.n_quant)
+    H.compare_state(b, states, w, w.n_quant, layer=1)
+    q = torch.from_numpy(S.layer_queries(w, 1, 0, "peaky")).cuda()
+    oa, ob = a.decode(1, q), b.decode(1, q)
+    torch.cuda.synchronize()
+    assert torch.equal(oa, ob)
+    ref = H.oracle_attention(w, states, S.layer_queries(w, 1, 0, "peaky"), K, V, w.n_quant, w.n_res)
+    assert float(np.abs(ob.cpu().numpy().astype(np.float64) - ref).max()) <= ATT_TOL
+
+
+def test_paged_table_entries_out_of_range_are_clamped():
+    """Entries of groups beyond a sequence's quantized part are never used, and an entry outside the
+    pool is clamped: a table poisoned there must change nothing, and a decode over a table with
+    wild entries for live groups must still finish without touching memory outside the pool."""
+    import torch
+    w = small("paged_poison", batch=2, q_heads=4, kv_heads=2, context=32 * 9 + 50, residual=32)
+    K, V = S.layer_kv(w, 0)
+    from paper_2505_10938_amd import cache as KC
+    G = w.group_k
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, 32 * 40, w.bits, G, w.group_v, w.residual,
+                         w.outlier_budget, w.aux_capacity, w.head_dim)
+    cache = H.gpu_cache(w, K, V, w.n_quant, w.n_res, cache=paged(cfg))
+    q = torch.from_numpy(S.layer_queries(w, 0, 0, "peaky")).cuda()
+    good = cache.decode(0, q).clone()
+    cache.page_table[:, w.n_quant // G:] = 2 ** 30          # groups not yet quantized
+    assert torch.equal(cache.decode(0, q), good)
+    cache.page_table[:, 1] = -7                             # live groups: results change, accesses stay inside
+    cache.page_table[:, 2] = 2 ** 30
+    out = cache.decode(0, q)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out.float()).all())
