@@ -198,6 +198,10 @@ int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_i
  *   n_quant  : multiple of G, <= max_seq
  *   res_start, n_res : live part of the residual ring, n_res <= res_rows;
  *              n_quant + n_res >= 1
+ *   qcache   : all five arrays must be valid device memory of the sizes kvq_query_sizes gives, also
+ *              when n_quant == 0: every workgroup loads a first block whether or not it has quantized
+ *              tokens to work on.  Likewise pool.pool_k / pool_v whenever outlier_budget +
+ *              aux_capacity > 0 (every slot is loaded, filled or not) and pool_count, aux_count
  *   out      : device fp16 [batch][q_heads][head_dim]
  *   workspace: device scratch of at least kvq_sizes.workspace_bytes, 256-byte aligned.  It must
  *              be zero-filled once before its first use; every call leaves the part it relies on
