@@ -191,6 +191,21 @@ def main():
     fp_bytes = w.units * (ctx * 4 * w.head_dim + 2 * (w.q_heads // w.kv_heads) * w.head_dim * 2)
     del fp_inst
 
+    # a step on which the ring does not fill (G - 1 of G decode steps): the append rides in the
+    # decode launch, one launch per layer.  Every copy takes one such step (its ring holds R rows).
+    steady_out = torch.empty_like(qd)
+    steady_us = None
+    if G > 2:
+        inst[0].step(0, k_new, v_new, qd, steady_out)
+        torch.cuda.synchronize()
+        e0.record()
+        for c in inst[1:]:
+            c.step(0, k_new, v_new, qd, steady_out)
+        e1.record()
+        torch.cuda.synchronize()
+        steady_us = e0.elapsed_time(e1) * 1e3 / (n_inst - 1)
+        assert all(c.n_res[0] == nres_final + 1 for c in inst)
+
     result = {
         "metric": "decode_attention_kv_GBps_2bit_1xMI355X" if w.bits == 2 else "decode_attention_kv_GBps",
         "value": round((dec_bytes + quant_bytes) / (ms_per_step * 1e-3) / 1e9, 2),
@@ -219,6 +234,12 @@ def main():
             "speedup_of_quantized_decode": round(fp_us / dec_us, 3)},
         "setup_s": round(t_setup, 1),
     }
+    if steady_us is not None:
+        mean_us = (ms_per_step * 1e3 + (G - 1) * steady_us) / G
+        result["step_without_group_quantize"] = {
+            "us_per_step": round(steady_us, 3), "launches": 1,
+            "mean_us_over_a_group_of_steps": round(mean_us, 3),
+            "tokens_per_s_mean": round(w.batch / (mean_us * 1e-6), 1)}
 
     # parity spot check + CPU baseline on a bounded sample of units
     if not args.no_cpu:
