@@ -202,6 +202,10 @@ int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_i
  *              when n_quant == 0: every workgroup loads a first block whether or not it has quantized
  *              tokens to work on.  Likewise pool.pool_k / pool_v whenever outlier_budget +
  *              aux_capacity > 0 (every slot is loaded, filled or not) and pool_count, aux_count
+ *   Range    : the products run on fp16 operands with fp32 accumulation.  Results are finite and within
+ *              the stated tolerance while |q_c| * step_c < 32 000 for every channel c and Key group
+ *              (step = the group's quantization step of that channel) and every Value step < 4000;
+ *              beyond that an operand overflows fp16 and outputs become infinite or NaN
  *   out      : device fp16 [batch][q_heads][head_dim]
  *   workspace: device scratch of at least kvq_sizes.workspace_bytes, 256-byte aligned.  It must
  *              be zero-filled once before its first use; every call leaves the part it relies on

@@ -40,8 +40,14 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRowBytes = 272;   // LDS row of 128 fp16 + 16 bytes of padding (bank spread)
-constexpr int kShK = 8;          // q*step operand is scaled by 2^(kShK - pos) before the fp16 split
-constexpr int kShV = 10;         // p*step operand likewise
+// The operands q*step and p*step are formed from q (p) scaled by 2^(kSh - pos) and split in fp16 hi + lo
+// (pos = bit position of the code they meet, 2..8).  The largest factor, 2^(kSh - 2), bounds what fits
+// fp16: |q| * step * log2(e)/sqrt(d) < 2^12 and Value steps < 2^12.  The smallest, 2^(kSh - 8), pushes
+// the lo parts of small elements into fp16 subnormals (spacing 2^-24): an absolute error of up to
+// 2^(pos - 25 - kSh) * step * code per element in score units, 1e-5 for a Key step of 40 at pos = 8,
+// and 2^(pos - 25 - kSh) * code per token in output units.
+constexpr int kShK = 6;
+constexpr int kShV = 6;
 
 __device__ inline float h2f_bits(uint32_t bits16) { return __half2float(__ushort_as_half((unsigned short)bits16)); }
 

@@ -195,6 +195,26 @@ def test_fused_group_step_configurations(kw):
     run_streaming(w, 2 * w.group_k + 5, True, check_every=17)
 
 
+def test_large_magnitudes_stay_in_the_fp16_range_of_the_operands():
+    """Keys 8 times and queries 4 times the usual size: Key steps of several hundred, |q| * step up
+    to about 10^4, a quarter of what the fp16 operand rows can hold; Values 16 times the usual size."""
+    import torch
+    w = small("large", batch=2, q_heads=4, kv_heads=2, context=32 * 12 + 60, residual=32)
+    K, V = S.layer_kv(w, 0)
+    K, V = (K * np.float16(8)).astype(np.float16), (V * np.float16(16)).astype(np.float16)
+    assert np.isfinite(K).all() and np.isfinite(V).all()
+    states = H.oracle_states(w, K, V, w.n_quant)
+    assert max(float(st.k_step.max()) for st in states) > 300
+    cache = H.gpu_cache(w, K, V, w.n_quant, w.n_res)
+    H.compare_state(cache, states, w, w.n_quant)
+    Q = (S.layer_queries(w, 0, 0, "diffuse") * np.float16(4)).astype(np.float16)
+    ref = H.oracle_attention(w, states, Q, K, V, w.n_quant, w.n_res)
+    got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    # outputs are 16 times larger than usual, and so is the rounding of the fp16 result
+    assert float(np.abs(got - ref).max()) <= 16 * ATT_TOL
+
+
 def test_whole_context_in_full_precision():
     # residual ring as long as the context: nothing is quantized, every row takes the full-precision
     # path (the fp16 attention the benchmark sets beside the quantized one), several rows per wavefront
