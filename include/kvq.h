@@ -146,7 +146,7 @@ int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out);
 /*
  * Append the new token's Key and Value (K = K_<n || K_n, V likewise: Background,
  * decoding phase) of one layer to the residual ring.
- *   k_new, v_new : device fp16 [batch][kv_heads][head_dim]
+ *   k_new, v_new : device fp16 [batch][kv_heads][head_dim], 4-byte aligned (as must be the ring)
  *   res_start    : ring row of the oldest live token, in [0, res_rows)
  *   n_res        : live rows before the append, in [0, res_rows)
  * Writes ring row (res_start + n_res) mod res_rows of every unit of `layer`.
@@ -194,7 +194,8 @@ int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_i
  * precision; then the n_res residual tokens in full precision.  One softmax over
  * all of them, scale 1/sqrt(head_dim).  Query head j reads kv head j / (q_heads /
  * kv_heads).
- *   q        : device fp16 [batch][q_heads][head_dim]
+ *   q        : device fp16 [batch][q_heads][head_dim], 16-byte aligned (as must be the code arrays,
+ *              the residual ring and the pool rows; steps/zeros and mask words 4-byte aligned)
  *   n_quant  : multiple of G, <= max_seq
  *   res_start, n_res : live part of the residual ring, n_res <= res_rows;
  *              n_quant + n_res >= 1

@@ -196,6 +196,8 @@ int32_t kvq_append_residual(const kvq_config* cfg, int32_t layer, const void* k_
   if (st != KVQ_OK) return st;
   if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
   if (!k_new || !v_new || !res.k_res || !res.v_res) return KVQ_ERR_INVALID_ARG;
+  if ((((uintptr_t)k_new) | ((uintptr_t)v_new) | ((uintptr_t)res.k_res) | ((uintptr_t)res.v_res)) & 3)
+    return KVQ_ERR_INVALID_ARG;                         // rows are copied 4 bytes at a time
   const int32_t rows = (int32_t)res_rows_of(cfg);
   if (res_start < 0 || res_start >= rows || n_res < 0 || n_res >= rows) return KVQ_ERR_INVALID_ARG;
   const Dims d = make_dims(cfg, layer);
@@ -277,6 +279,7 @@ int32_t kvq_append_trace_quantize(const kvq_config* cfg, int32_t layer, const vo
   if (st != KVQ_OK) return st;
   if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
   if (!k_new || !v_new || !res.k_res || !res.v_res) return KVQ_ERR_INVALID_ARG;
+  if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 3) return KVQ_ERR_INVALID_ARG;
   const int32_t rows = (int32_t)res_rows_of(cfg);
   const int32_t G = cfg->group_k;
   if (res_start < 0 || res_start >= rows || res_start % G != 0) return KVQ_ERR_INVALID_ARG;
@@ -300,6 +303,7 @@ int32_t kvq_append_trace_quantize_ragged(const kvq_config* cfg, int32_t layer, c
   if (st != KVQ_OK) return st;
   if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
   if (!k_new || !v_new || !res.k_res || !res.v_res || !seq_state) return KVQ_ERR_INVALID_ARG;
+  if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 3) return KVQ_ERR_INVALID_ARG;
   if (((uintptr_t)seq_state) & 15) return KVQ_ERR_INVALID_ARG;
   if (!pool.pool_count || !pool.aux_count || !pool.frozen) return KVQ_ERR_INVALID_ARG;
   if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v || !pool.pool_idx || !pool.pool_score))
@@ -331,6 +335,12 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, kvq_q
   if (st != KVQ_OK) return st;
   if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
   if (!q || !out) return KVQ_ERR_INVALID_ARG;
+  // rows are read 16 bytes at a time (the query rows too: they stand in for rows past the last pool slot)
+  if ((((uintptr_t)q) | ((uintptr_t)res.k_res) | ((uintptr_t)res.v_res) | ((uintptr_t)pool.pool_k) |
+       ((uintptr_t)pool.pool_v) | ((uintptr_t)qc.k_codes) | ((uintptr_t)qc.v_codes)) & 15)
+    return KVQ_ERR_INVALID_ARG;
+  if ((((uintptr_t)out) & 1) || ((((uintptr_t)qc.k_meta) | ((uintptr_t)qc.v_meta) | ((uintptr_t)qc.mask)) & 3))
+    return KVQ_ERR_INVALID_ARG;
   if (n_quant < 0 || n_quant > cfg->max_seq || n_quant % cfg->group_k != 0) return KVQ_ERR_INVALID_ARG;
   const int32_t rows = (int32_t)res_rows_of(cfg);
   if (n_res < 0 || n_res > rows || res_start < 0 || res_start >= rows) return KVQ_ERR_INVALID_ARG;

@@ -191,3 +191,21 @@ def test_bad_page_tables_rejected_before_launch():
     # the quantized arrays are needed even with nothing quantized: the first block is always loaded
     assert lib.kvq_decode_attention(C.byref(c), 0, 256, B.kvq_qcache(0, 256, 256, 256, 256), 0, res, 0, 10, pool, 256,
                                     512, ws, None) == B.KVQ_ERR_INVALID_ARG
+
+
+def test_misaligned_decode_buffers_rejected_before_launch():
+    lib = P.load_library()
+    c = cfg()
+    ws = P.kvq_query_sizes(c).workspace_bytes
+    def dec(q=256, qc=(256,) * 5, res=(256, 256), rows=(256, 256), out=256):
+        pool = B.kvq_pool(rows[0], rows[1], 256, 256, 256, 256, 256)
+        return lib.kvq_decode_attention(C.byref(c), 0, q, B.kvq_qcache(*qc), 64, B.kvq_residual(*res), 0, 10, pool, out,
+                                        512, ws, None)
+    bad = B.KVQ_ERR_INVALID_ARG
+    assert dec(q=264) == bad                                  # rows are read 16 bytes at a time
+    assert dec(res=(264, 256)) == bad and dec(res=(256, 260)) == bad
+    assert dec(rows=(258, 256)) == bad and dec(rows=(256, 264)) == bad
+    assert dec(qc=(264, 256, 256, 256, 256)) == bad and dec(qc=(256, 256, 260, 256, 256)) == bad
+    assert dec(qc=(256, 258, 256, 256, 256)) == bad and dec(qc=(256, 256, 256, 256, 257)) == bad
+    assert dec(out=257) == bad
+    assert dec(rows=(0, 256)) == bad                          # pool slots exist (N + A > 0): their rows are read
