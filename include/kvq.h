@@ -241,6 +241,21 @@ int32_t kvq_prefill_quantize(const kvq_config* cfg, int32_t layer, const void* k
                              kvq_qcache qcache, kvq_residual res, void* stream);
 
 /*
+ * The same for ONE sequence of the batch, for a serving loop in which sequences join a running batch
+ * (the paper's experiments use batches of equal length): the prompt of sequence `seq` (0 .. batch-1) is
+ * quantized into that sequence's units of `layer`, whatever they held before - its pools are emptied
+ * first, its ring rows and, for a paged cache, the pages its table row names are overwritten.  Other
+ * sequences are not touched.
+ *   k_rows, v_rows : device fp16, kv head h's n_tokens rows at element offset h * unit_stride
+ *   selected       : device uint8 scratch, at least kv_heads * n_q bytes
+ * Everything else as kvq_prefill_quantize.  With per-sequence state (kvq_decode_attention_ragged) the
+ * caller then writes {n_q, 0, n_tokens - n_q, active} into the sequence's entry of that array.
+ */
+int32_t kvq_prefill_quantize_seq(const kvq_config* cfg, int32_t layer, int32_t seq, const void* k_rows,
+                                 const void* v_rows, int64_t unit_stride, int32_t n_tokens, kvq_pool pool,
+                                 uint8_t* selected, kvq_qcache qcache, kvq_residual res, void* stream);
+
+/*
  * The whole group step in one launch, for the decode steps on which the ring fills: append the
  * new token's Key and Value as kvq_append_residual does, then, on the oldest G rows of the ring,
  * the outlier competition of kvq_trace_outliers and the quantization of kvq_quantize_group

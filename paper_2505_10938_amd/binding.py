@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libkvq.so")
 KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
-           "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_decode_attention",
+           "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_prefill_quantize_seq", "kvq_decode_attention",
            "kvq_append_decode_attention", "kvq_append_trace_quantize_ragged", "kvq_seq_advance",
            "kvq_decode_attention_ragged", "kvq_stream_read",
            "kvq_status_string", "kvq_version"]
@@ -85,6 +85,8 @@ def load_library() -> C.CDLL:
     lib.kvq_quantize_group.argtypes = [cfgp, i32, i32, vp, vp, i64, vp, kvq_qcache, vp]
     lib.kvq_prefill_quantize.restype = i32
     lib.kvq_prefill_quantize.argtypes = [cfgp, i32, vp, vp, i64, i32, kvq_pool, vp, kvq_qcache, kvq_residual, vp]
+    lib.kvq_prefill_quantize_seq.restype = i32
+    lib.kvq_prefill_quantize_seq.argtypes = [cfgp, i32, i32, vp, vp, i64, i32, kvq_pool, vp, kvq_qcache, kvq_residual, vp]
     lib.kvq_append_trace_quantize.restype = i32
     lib.kvq_append_trace_quantize.argtypes = [cfgp, i32, vp, vp, kvq_residual, i32, i32, i32, kvq_pool, vp, kvq_qcache, vp]
     lib.kvq_decode_attention.restype = i32
@@ -175,6 +177,14 @@ def kvq_prefill_quantize(cfg, layer, k_rows, v_rows, unit_stride, n_tokens, pool
                                              pool, _ptr(selected), qcache, res, _stream(stream))
     if st != KVQ_OK:
         raise KvqError(st, "kvq_prefill_quantize")
+
+
+def kvq_prefill_quantize_seq(cfg, layer, seq, k_rows, v_rows, unit_stride, n_tokens, pool: kvq_pool, selected,
+                             qcache: kvq_qcache, res: kvq_residual, stream=None):
+    st = load_library().kvq_prefill_quantize_seq(C.byref(cfg), layer, seq, _ptr(k_rows), _ptr(v_rows), unit_stride,
+                                                 n_tokens, pool, _ptr(selected), qcache, res, _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_prefill_quantize_seq")
 
 
 def kvq_append_decode_attention(cfg, layer, q, k_new, v_new, qcache: kvq_qcache, n_quant, res: kvq_residual, res_start,

@@ -226,6 +226,25 @@ class RaggedKVCache(KVCache):
         B.kvq_append_trace_quantize_ragged(self.cfg, layer, k_new, v_new, self.res, self.seq_state, self.pool, None,
                                            self.qcache, stream)
 
+    def prefill_sequence(self, b, k_rows, v_rows, active=True, stream=None):
+        """A new sequence in slot `b`: its prompt (per layer: fp16 [kv_heads, n, head_dim], contiguous;
+        `k_rows`, `v_rows` are lists over the layers) quantized in one call per layer, whatever the slot
+        held before; the other sequences are not touched."""
+        cfg = self.cfg
+        n = k_rows[0].shape[1]
+        G, R = cfg.group_k, cfg.residual
+        nq = G * ((n - R) // G) if n >= R + G else 0
+        if getattr(self, "prefill_selected", None) is None:
+            self.prefill_selected = torch.zeros(max(cfg.kv_heads * cfg.max_seq, 16), dtype=torch.uint8, device=self.device)
+        for layer in range(cfg.layers):
+            k, v = k_rows[layer], v_rows[layer]
+            assert k.shape == (cfg.kv_heads, n, cfg.head_dim) and k.is_contiguous() and v.is_contiguous()
+            B.kvq_prefill_quantize_seq(cfg, layer, b, k, v, n * cfg.head_dim, n, self.pool, self.prefill_selected,
+                                       self.qcache, self.res, stream)
+        state = torch.tensor([nq, 0, n - nq, 1 if active else 0], dtype=torch.int32)
+        self.seq_state[b].copy_(state.to(self.device), non_blocking=False)
+        self.longest = max(self.longest, n)
+
     def advance(self, stream=None):
         """The sequences' states after the token just appended to every layer."""
         B.kvq_seq_advance(self.cfg, self.seq_state, stream)

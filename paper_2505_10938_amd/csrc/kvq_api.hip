@@ -88,6 +88,7 @@ Dims make_dims(const kvq_config* c, int32_t layer) {
   d.table_stride = 0;
   d.n_pages = 0;
   d.plane0 = (int64_t)layer * c->kv_heads;
+  d.seq0 = 0;
   return d;
 }
 
@@ -239,9 +240,13 @@ int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_i
                                        unit_stride, selected, cfg->group_k, qc, (hipStream_t)stream));
 }
 
-int32_t kvq_prefill_quantize(const kvq_config* cfg, int32_t layer, const void* k_rows, const void* v_rows,
-                             int64_t unit_stride, int32_t n_tokens, kvq_pool pool, uint8_t* selected, kvq_qcache qc,
-                             kvq_residual res, void* stream) {
+namespace {
+
+// Whole-prompt quantization of every sequence of the batch (seq < 0) or of sequence `seq` alone,
+// whose pools are emptied first.
+int32_t prefill_common(const kvq_config* cfg, int32_t layer, int32_t seq, const void* k_rows, const void* v_rows,
+                       int64_t unit_stride, int32_t n_tokens, kvq_pool pool, uint8_t* selected, kvq_qcache qc,
+                       kvq_residual res, void* stream) {
   const int32_t st = check_config(cfg);
   if (st != KVQ_OK) return st;
   if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
@@ -257,10 +262,16 @@ int32_t kvq_prefill_quantize(const kvq_config* cfg, int32_t layer, const void* k
   if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v || !pool.pool_idx || !pool.pool_score))
     return KVQ_ERR_INVALID_ARG;
   if (n_groups > 0 && (!selected || !qcache_ok(cfg, qc))) return KVQ_ERR_INVALID_ARG;
-  const Dims d = n_groups > 0 ? make_dims(cfg, layer, qc) : make_dims(cfg, layer);
+  if (n_groups > 65535) return KVQ_ERR_UNSUPPORTED;                    // grid limit of the quantization launch
+  Dims d = n_groups > 0 ? make_dims(cfg, layer, qc) : make_dims(cfg, layer);
   hipStream_t s = (hipStream_t)stream;
+  if (seq >= 0) {                                        // the launches cover the units of this sequence only
+    d.unit0 += (int64_t)seq * cfg->kv_heads;
+    d.units_per_layer = cfg->kv_heads;
+    d.seq0 = seq;
+    if (kvq::launch_reset_pools(d, pool, s) != hipSuccess) return KVQ_ERR_LAUNCH;
+  }
   if (n_groups > 0) {
-    if (n_groups > 65535) return KVQ_ERR_UNSUPPORTED;                  // grid limit of the quantization launch
     hipError_t e = kvq::launch_prefill_trace(d, n_groups, (const __half*)k_rows, (const __half*)v_rows, unit_stride,
                                              pool, selected, s);
     if (e != hipSuccess) return KVQ_ERR_LAUNCH;
@@ -270,6 +281,21 @@ int32_t kvq_prefill_quantize(const kvq_config* cfg, int32_t layer, const void* k
   }
   return from_hip(kvq::launch_tail_copy(d, (const __half*)k_rows, (const __half*)v_rows, unit_stride, n_groups * G,
                                         n_tokens - n_groups * G, (__half*)res.k_res, (__half*)res.v_res, s));
+}
+
+}  // namespace
+
+int32_t kvq_prefill_quantize(const kvq_config* cfg, int32_t layer, const void* k_rows, const void* v_rows,
+                             int64_t unit_stride, int32_t n_tokens, kvq_pool pool, uint8_t* selected, kvq_qcache qc,
+                             kvq_residual res, void* stream) {
+  return prefill_common(cfg, layer, -1, k_rows, v_rows, unit_stride, n_tokens, pool, selected, qc, res, stream);
+}
+
+int32_t kvq_prefill_quantize_seq(const kvq_config* cfg, int32_t layer, int32_t seq, const void* k_rows,
+                                 const void* v_rows, int64_t unit_stride, int32_t n_tokens, kvq_pool pool,
+                                 uint8_t* selected, kvq_qcache qc, kvq_residual res, void* stream) {
+  if (!cfg || seq < 0 || seq >= cfg->batch) return KVQ_ERR_INVALID_ARG;
+  return prefill_common(cfg, layer, seq, k_rows, v_rows, unit_stride, n_tokens, pool, selected, qc, res, stream);
 }
 
 int32_t kvq_append_trace_quantize(const kvq_config* cfg, int32_t layer, const void* k_new, const void* v_new,

@@ -40,6 +40,8 @@ struct Dims {
   int32_t table_stride;
   int32_t n_pages;
   int64_t plane0;                             // layer * kv_heads
+  // A launch over the units of ONE sequence (units_per_layer = kv_heads, unit0 includes the sequence):
+  int32_t seq0;                               // that sequence (0 for launches over the whole batch)
 };
 
 // Where group `group` of local unit ul = b * kv_heads + h is stored: `row` indexes runs of
@@ -52,7 +54,7 @@ struct GroupPlace {
 __device__ inline GroupPlace place_of_group(const Dims& d, int ul, int group) {
   if (!d.page_table) return {d.unit0 + ul, group};
   const int b = ul / d.kv_heads, h = ul - b * d.kv_heads;
-  const int page = d.page_table[(int64_t)b * d.table_stride + group];
+  const int page = d.page_table[(int64_t)(d.seq0 + b) * d.table_stride + group];
   return {d.plane0 + h, min(max(page, 0), d.n_pages - 1)};
 }
 
@@ -85,6 +87,7 @@ struct DecodeArgs {
 
 hipError_t launch_append(const Dims& d, const __half* k_new, const __half* v_new, __half* k_res, __half* v_res,
                          int32_t row, hipStream_t s);
+hipError_t launch_reset_pools(const Dims& d, const kvq_pool& pool, hipStream_t s);
 hipError_t launch_trace(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
                         int64_t unit_stride, const kvq_pool& pool, uint8_t* selected, hipStream_t s);
 hipError_t launch_quantize(const Dims& d, int32_t group_index, int32_t n_groups, const __half* k_group,

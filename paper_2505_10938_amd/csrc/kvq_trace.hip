@@ -88,6 +88,20 @@ hipError_t launch_prefill_trace(const Dims& d, int32_t n_groups, const __half* k
   return hipGetLastError();
 }
 
+// Empty pools for the units of the launch (a new sequence in a slot that held another).
+__global__ void reset_pools_kernel(Dims d, int32_t* pool_count, int32_t* aux_count, int32_t* frozen) {
+  const int ul = blockIdx.x * blockDim.x + threadIdx.x;
+  if (ul >= d.units_per_layer) return;
+  pool_count[d.unit0 + ul] = 0;
+  aux_count[d.unit0 + ul] = 0;
+  frozen[d.unit0 + ul] = 0;
+}
+hipError_t launch_reset_pools(const Dims& d, const kvq_pool& pool, hipStream_t s) {
+  hipLaunchKernelGGL(reset_pools_kernel, dim3((d.units_per_layer + 63) / 64), dim3(64), 0, s, d, pool.pool_count,
+                     pool.aux_count, pool.frozen);
+  return hipGetLastError();
+}
+
 hipError_t launch_trace(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
                         int64_t unit_stride, const kvq_pool& pool, uint8_t* selected, hipStream_t s) {
   auto go = [&](auto kern) {

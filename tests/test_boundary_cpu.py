@@ -209,3 +209,19 @@ def test_misaligned_decode_buffers_rejected_before_launch():
     assert dec(qc=(256, 258, 256, 256, 256)) == bad and dec(qc=(256, 256, 256, 256, 257)) == bad
     assert dec(out=257) == bad
     assert dec(rows=(0, 256)) == bad                          # pool slots exist (N + A > 0): their rows are read
+
+
+def test_bad_sequence_prefill_arguments_rejected_before_launch():
+    lib = P.load_library()
+    c = cfg()
+    qc = B.kvq_qcache(256, 256, 256, 256, 256)
+    pool = B.kvq_pool(256, 256, 256, 256, 256, 256, 256)
+    res = B.kvq_residual(256, 256)
+    pf = lambda seq=0, n=300, stride=300 * 128, k=256: lib.kvq_prefill_quantize_seq(
+        C.byref(c), 0, seq, k, 256, stride, n, pool, 256, qc, res, None)
+    assert pf(seq=-1) == B.KVQ_ERR_INVALID_ARG
+    assert pf(seq=c.batch) == B.KVQ_ERR_INVALID_ARG
+    assert pf(n=0) == B.KVQ_ERR_INVALID_ARG
+    assert pf(stride=299 * 128) == B.KVQ_ERR_INVALID_ARG
+    assert pf(k=264) == B.KVQ_ERR_INVALID_ARG
+    assert lib.kvq_prefill_quantize_seq(None, 0, 0, 256, 256, 300 * 128, 300, pool, 256, qc, res, None) == B.KVQ_ERR_INVALID_ARG

@@ -575,3 +575,62 @@ def test_paged_table_entries_out_of_range_are_clamped():
     out = cache.decode(0, q)
     torch.cuda.synchronize()
     assert bool(torch.isfinite(out.float()).all())
+
+
+@pytest.mark.parametrize("use_pages", [False, True])
+def test_sequences_join_a_running_batch_by_their_own_prefill(use_pages):
+    """Each sequence's prompt is quantized by its own call (different lengths; one slot is then
+    taken over by a new sequence, which must not inherit the old one's pool or frozen flag), the
+    batch decodes, streams a few tokens and decodes again; every unit is compared with the oracle
+    run on its own sequence alone."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    lengths = [300, 45, 161, 0]                               # slot 3 stays empty
+    steps = 40
+    kw = dict(bits=2, group_k=32, group_v=32, residual=32, outlier_budget=4, aux_capacity=4, rho=0.05)
+    w = S.Workload("join", layers=1, batch=4, q_heads=4, kv_heads=2, context=max(lengths) + steps, **kw)
+    G, R = w.group_k, w.residual
+    K, V = S.layer_kv(w, 0)
+    K2, V2 = S.layer_kv(w.with_(seed=w.seed + 1), 0)         # the sequence that takes slot 0 over
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ((w.context + G - 1) // G) * G, w.bits, G, w.group_v, R,
+                         w.outlier_budget, w.aux_capacity, w.head_dim)
+    cache = paged(cfg, kind=KC.RaggedKVCache) if use_pages else KC.RaggedKVCache(cfg)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    for b, n in enumerate(lengths):
+        if n:
+            cache.prefill_sequence(b, [Kd[b, :, :n].contiguous()], [Vd[b, :, :n].contiguous()])
+    # the first occupant of slot 0 froze its pools (small auxiliary pool, many outlier tokens) ...
+    torch.cuda.synchronize()
+    assert int(cache.frozen.view(torch.int32)[0].item()) == 1
+    # ... and is replaced by a shorter sequence with other data
+    n0 = 100
+    K[0], V[0] = K2[0], V2[0]
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    cache.prefill_sequence(0, [Kd[0, :, :n0].contiguous()], [Vd[0, :, :n0].contiguous()])
+    lengths[0] = n0
+
+    def check(lengths, step):
+        Q = S.layer_queries(w, 0, step, "peaky")
+        got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+        state = cache.seq_state.cpu().numpy()
+        for b, n in enumerate(lengths):
+            if n == 0:
+                assert not got[b].any()
+                continue
+            nq, nr = ragged_lengths_state(n, G, R)
+            assert (state[b, 0], state[b, 2]) == (nq, nr), (b, state[b])
+            units = [b * w.kv_heads + h for h in range(w.kv_heads)]
+            states = H.oracle_states(w, K, V, nq, units)
+            H.compare_state(cache, states, w, nq, units=units)
+            ref = H.oracle_attention(w, states, Q, K, V, nq, nr, units)
+            assert float(np.abs(got[b] - ref[b]).max()) <= ATT_TOL, (b, n, step)
+
+    check(lengths, 0)
+    for t in range(steps):                                    # the three live sequences grow together
+        cache.set_active([n > 0 for n in lengths])
+        rows_k = torch.stack([Kd[b, :, n] for b, n in enumerate(lengths)]).contiguous()
+        rows_v = torch.stack([Vd[b, :, n] for b, n in enumerate(lengths)]).contiguous()
+        cache.append(0, rows_k, rows_v)
+        cache.advance()
+        lengths = [n + 1 if n > 0 else 0 for n in lengths]
+    check(lengths, 1)
