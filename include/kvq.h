@@ -49,8 +49,12 @@ typedef struct kvq_config {
   int32_t group_k;        /* G: tokens per Key group and quantization cadence: 32, 64 or 128  */
   int32_t group_v;        /* channels per Value group: 32, 64 or 128                          */
   int32_t residual;       /* R >= 0: recent tokens kept in full precision                     */
-  int32_t outlier_budget; /* N >= 0 per unit; 0 disables tracing (the paper's layers 0 and 1) */
+  int32_t outlier_budget; /* N >= 0 per unit; 0 disables tracing                              */
   int32_t aux_capacity;   /* A >= 0: slots for tokens evicted from the outlier pool           */
+  int32_t untraced_layers; /* the first so many layers trace no outliers: their budget is 0   */
+                          /* whatever outlier_budget says (Experiments, "Details": layers 0   */
+                          /* and 1 of the paper's models; 0 <= untraced_layers <= layers).    */
+                          /* Buffer sizes do not depend on it                                 */
 } kvq_config;
 
 /* Sizes (bytes unless said otherwise) of every caller-allocated buffer. */

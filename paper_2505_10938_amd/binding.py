@@ -26,7 +26,7 @@ EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_
 class kvq_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("layers", "batch", "q_heads", "kv_heads", "head_dim", "max_seq", "bits", "group_k",
-                 "group_v", "residual", "outlier_budget", "aux_capacity")]
+                 "group_v", "residual", "outlier_budget", "aux_capacity", "untraced_layers")]
 
 
 class kvq_sizes(C.Structure):

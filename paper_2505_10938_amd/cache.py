@@ -12,9 +12,9 @@ from . import binding as B
 
 
 def make_config(layers, batch, q_heads, kv_heads, max_seq, bits=2, group_k=32, group_v=32, residual=128,
-                outlier_budget=8, aux_capacity=32, head_dim=128) -> B.kvq_config:
+                outlier_budget=8, aux_capacity=32, head_dim=128, untraced_layers=0) -> B.kvq_config:
     return B.kvq_config(layers, batch, q_heads, kv_heads, head_dim, max_seq, bits, group_k, group_v, residual,
-                        outlier_budget, aux_capacity)
+                        outlier_budget, aux_capacity, untraced_layers)
 
 
 class KVCache:

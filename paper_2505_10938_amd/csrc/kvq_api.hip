@@ -16,6 +16,7 @@ int32_t check_config(const kvq_config* c) {
   if (c->head_dim % c->group_v != 0) return KVQ_ERR_INVALID_ARG;
   if (c->max_seq < c->group_k || c->max_seq % c->group_k != 0) return KVQ_ERR_INVALID_ARG;
   if (c->residual < 0 || c->outlier_budget < 0 || c->aux_capacity < 0) return KVQ_ERR_INVALID_ARG;
+  if (c->untraced_layers < 0 || c->untraced_layers > c->layers) return KVQ_ERR_INVALID_ARG;
   if (c->residual > (1 << 20) || c->max_seq > (1 << 24)) return KVQ_ERR_INVALID_ARG;
   if (c->batch > 65535 || c->kv_heads > 32767) return KVQ_ERR_INVALID_ARG;   // grid y/z limits
   if (c->head_dim != kvq::kHeadDim) return KVQ_ERR_UNSUPPORTED;
@@ -71,7 +72,9 @@ Dims make_dims(const kvq_config* c, int32_t layer) {
   d.bits = c->bits;
   d.G = c->group_k;
   d.Gv = c->group_v;
-  d.N = c->outlier_budget;
+  // slots [0, outlier_budget) stay the outlier pool's in every layer (one layout for all buffers); a
+  // layer that traces nothing has budget 0: no competition, and its pool never has a member
+  d.N = layer < c->untraced_layers ? 0 : c->outlier_budget;
   d.A = c->aux_capacity;
   d.max_seq = c->max_seq;
   d.res_rows = (int32_t)res_rows_of(c);

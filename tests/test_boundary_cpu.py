@@ -225,3 +225,10 @@ def test_bad_sequence_prefill_arguments_rejected_before_launch():
     assert pf(stride=299 * 128) == B.KVQ_ERR_INVALID_ARG
     assert pf(k=264) == B.KVQ_ERR_INVALID_ARG
     assert lib.kvq_prefill_quantize_seq(None, 0, 0, 256, 256, 300 * 128, 300, pool, 256, qc, res, None) == B.KVQ_ERR_INVALID_ARG
+
+
+def test_untraced_layers_must_fit_the_layer_count():
+    assert P.load_library().kvq_query_sizes(C.byref(cfg(layers=3, untraced_layers=3)), C.byref(B.kvq_sizes())) == B.KVQ_OK
+    for bad in (-1, 4):
+        assert P.load_library().kvq_query_sizes(C.byref(cfg(layers=3, untraced_layers=bad)),
+                                                C.byref(B.kvq_sizes())) == B.KVQ_ERR_INVALID_ARG

@@ -215,6 +215,31 @@ def test_large_magnitudes_stay_in_the_fp16_range_of_the_operands():
     assert float(np.abs(got - ref).max()) <= 16 * ATT_TOL
 
 
+def test_first_layers_without_tracing():
+    """Three layers, the first two with outlier budget 0 by configuration (the paper's setting for
+    layers 0 and 1): they must equal plain group quantization, the third the traced cache."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    w = small("untraced", layers=3, batch=2, q_heads=4, kv_heads=2, context=32 * 10 + 50, residual=32, rho=0.05)
+    G = w.group_k
+    cfg = KC.make_config(w.layers, w.batch, w.q_heads, w.kv_heads, ((w.context + G - 1) // G) * G, w.bits, G,
+                         w.group_v, w.residual, w.outlier_budget, w.aux_capacity, w.head_dim, untraced_layers=2)
+    cache = KC.KVCache(cfg)
+    selected_any = []
+    for layer in range(3):
+        K, V = S.layer_kv(w, layer)
+        wl = w if layer >= 2 else w.with_(outlier_budget=0)
+        states = H.oracle_states(wl, K, V, w.n_quant)
+        H.gpu_cache(w, K, V, w.n_quant, w.n_res, layer=layer, cache=cache)
+        H.compare_state(cache, states, wl, w.n_quant, layer=layer)
+        selected_any.append(any(st.masked.any() for st in states))
+        Q = S.layer_queries(w, layer, 0, "peaky")
+        ref = H.oracle_attention(wl, states, Q, K, V, w.n_quant, w.n_res)
+        got = cache.decode(layer, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+        assert float(np.abs(got - ref).max()) <= ATT_TOL, layer
+    assert selected_any == [False, False, True]
+
+
 def test_whole_context_in_full_precision():
     # residual ring as long as the context: nothing is quantized, every row takes the full-precision
     # path (the fp16 attention the benchmark sets beside the quantized one), several rows per wavefront
