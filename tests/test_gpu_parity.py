@@ -110,10 +110,38 @@ def run_sampled(w: S.Workload, units, regimes=("peaky", "diffuse")):
     return cache
 
 
+def paged_copy(cache, seed=5, spare=100):
+    """The same cache contents in a paged cache whose pages are dealt at random."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    c = cache.cfg
+    groups = c.max_seq // c.group_k
+    other = KC.KVCache(c, n_pages=c.batch * groups + spare)
+    deal = np.random.default_rng(seed).permutation(other.n_pages)[:c.batch * groups].reshape(c.batch, groups)
+    other.page_table.copy_(torch.from_numpy(deal.astype(np.int32)))
+    table = other.page_table.long()
+    for name in ("k_codes", "k_meta", "v_codes", "v_meta", "mask"):
+        dense, pool = getattr(cache, name), getattr(other, name)
+        per_group = dense.numel() // (c.layers * c.batch * c.kv_heads * groups)
+        pages = pool[:c.layers * c.kv_heads * other.n_pages * per_group].view(c.layers, c.kv_heads, other.n_pages, per_group)
+        src = dense[:c.layers * c.batch * c.kv_heads * groups * per_group].view(c.layers, c.batch, c.kv_heads, groups, per_group)
+        pages[:, :, table] = src.permute(0, 2, 1, 3, 4)
+    for name in ("k_res", "v_res", "pool_k", "pool_v", "pool_idx", "pool_score", "pool_count", "aux_count", "frozen"):
+        getattr(other, name).copy_(getattr(cache, name))
+    other.n_quant, other.res_start, other.n_res = list(cache.n_quant), list(cache.res_start), list(cache.n_res)
+    return other
+
+
 def test_full_size_llama2_7b_4k_sampled_units():
     # the benchmark workload in the benchmark's launch shape (one workgroup of 8 wavefronts per unit)
+    import torch
     w = S.WORKLOADS["llama2_7b_4k"]
-    run_sampled(w, [0, 37, 130, 255])
+    cache = run_sampled(w, [0, 37, 130, 255])
+    # the same contents behind a page table (31 744 pages dealt at random): the same outputs, bit for bit
+    q = torch.from_numpy(S.layer_queries(w, 0, 0, "peaky")).cuda()
+    other = paged_copy(cache)
+    assert all(torch.equal(x, y[:x.numel()]) for x, y in zip(cache.dense_quantized(), other.dense_quantized()))
+    assert torch.equal(cache.decode(0, q), other.decode(0, q))
 
 
 def test_full_size_long_32k_sampled_units():
@@ -124,8 +152,11 @@ def test_full_size_long_32k_sampled_units():
 
 def test_full_size_llama3_8b_8k_sampled_units():
     # grouped queries at batch 16, context 8192: two workgroups per unit, four query heads each
+    import torch
     w = S.WORKLOADS["llama3_8b_8k_stream"]
-    run_sampled(w, [0, 77, 127], regimes=("peaky",))
+    cache = run_sampled(w, [0, 77, 127], regimes=("peaky",))
+    q = torch.from_numpy(S.layer_queries(w, 0, 0, "peaky")).cuda()
+    assert torch.equal(cache.decode(0, q), paged_copy(cache).decode(0, q))
 
 
 @pytest.mark.parametrize("bits", [2, 4])
