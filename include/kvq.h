@@ -10,8 +10,11 @@
  * Cache shape follows the paper's [num_layers, batch_size, num_heads,
  * sequence_length, head_dim] (Introduction).  A "unit" is one (layer, batch,
  * kv head); unit index u = (layer * batch + b) * kv_heads + h.  Every buffer
- * below is a dense array whose leading dimension is the unit.  Sequence
- * lengths are uniform over the batch.
+ * below is a dense array whose leading dimension is the unit; the quantized
+ * arrays may instead be a pool of pages shared by the sequences (kvq_qcache).
+ * Sequence lengths are uniform over the batch in the calls that take them as
+ * arguments; the *_ragged calls read each sequence's own state from a device
+ * array, and kvq_prefill_quantize_seq fills the slot of one sequence.
  *
  * Return value of every call: 0 (KVQ_OK) or a negative kvq_status.  Arguments
  * are validated on the host before anything is launched, so an error return
@@ -208,7 +211,8 @@ int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_i
  *              tokens to work on.  Likewise pool.pool_k / pool_v whenever outlier_budget +
  *              aux_capacity > 0 (every slot is loaded, filled or not) and pool_count, aux_count
  *   Range    : the products run on fp16 operands with fp32 accumulation.  Results are finite and within
- *              the stated tolerance while |q_c| * step_c < 32 000 for every channel c and Key group
+ *              2e-3 (absolute, for outputs of order 1) of the exact attention over the dequantized
+ *              cache while |q_c| * step_c < 32 000 for every channel c and Key group
  *              (step = the group's quantization step of that channel) and every Value step < 4000;
  *              beyond that an operand overflows fp16 and outputs become infinite or NaN
  *   out      : device fp16 [batch][q_heads][head_dim]
@@ -345,7 +349,7 @@ int32_t kvq_stream_read(const void* buf, size_t bytes, void* sink, void* stream)
 /* Static string for a kvq_status value. */
 const char* kvq_status_string(int32_t status);
 
-/* Library version, for the binding's load check. */
+/* Version of this interface (structure layouts and entry points), for the binding's load check: 2. */
 int32_t kvq_version(void);
 
 #ifdef __cplusplus

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "libkvq.so")
 
 KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH = 0, -1, -2, -3, -4
 
+INTERFACE_VERSION = 2       # kvq_version() of the library these structures and signatures match
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
            "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_prefill_quantize_seq", "kvq_decode_attention",
            "kvq_append_decode_attention", "kvq_append_trace_quantize_ragged", "kvq_seq_advance",
@@ -71,6 +72,9 @@ def load_library() -> C.CDLL:
     i32, i64, vp = C.c_int32, C.c_int64, C.c_void_p
     cfgp = C.POINTER(kvq_config)
     lib.kvq_version.restype = i32
+    if lib.kvq_version() != INTERFACE_VERSION:          # the structures below would not match the library's
+        raise RuntimeError(f"{LIB_PATH} has interface version {lib.kvq_version()}, this binding {INTERFACE_VERSION}: "
+                           "rebuild with `python -m paper_2505_10938_amd.build`")
     lib.kvq_status_string.restype = C.c_char_p
     lib.kvq_status_string.argtypes = [i32]
     lib.kvq_query_sizes.restype = i32

@@ -143,7 +143,7 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restric
 
 extern "C" {
 
-int32_t kvq_version(void) { return 1; }
+int32_t kvq_version(void) { return 2; }
 
 int32_t kvq_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {
   if (!buf || !sink || bytes == 0 || bytes % 16 != 0 || ((uintptr_t)buf & 15) != 0) return KVQ_ERR_INVALID_ARG;
