@@ -38,6 +38,54 @@ def algorithmic_bytes(w, n_quant, n_res, pool_rows):
     return dec_unit * w.units, quant_unit * w.units
 
 
+def stream_mode(args, w):
+    """Consecutive decode steps of one layer shape, the cadence of real decoding: every step appends a
+    token and attends; every G-th also traces and quantizes a group.  Eight copies of the cache take
+    turns (eight layers of a model, in effect), so that a step reads its cache from HBM."""
+    import torch
+    import kvq_synth as S
+    from paper_2505_10938_amd import cache as KC
+    G, steps, copies = w.group_k, args.stream, 8
+    K, V = S.layer_kv(w, 0, w.context + steps)
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ((w.context + steps + G - 1) // G) * G, w.bits, G,
+                         w.group_v, w.residual, w.outlier_budget, w.aux_capacity, w.head_dim)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    base = KC.KVCache(cfg)
+    base.prefill(0, Kd[:, :, :w.context].contiguous(), Vd[:, :, :w.context].contiguous())
+    inst = [base] + [base.clone() for _ in range(copies - 1)]
+    qd = torch.from_numpy(S.layer_queries(w, 0)).cuda()
+    rows = [(Kd[:, :, w.context + s].contiguous(), Vd[:, :, w.context + s].contiguous()) for s in range(steps)]
+    outs = [torch.empty_like(qd) for _ in inst]
+    torch.cuda.synchronize()
+    group_steps = 0
+    t0 = time.perf_counter()
+    for s in range(steps):
+        for c, o in zip(inst, outs):
+            before = c.n_quant[0]
+            c.step(0, rows[s][0], rows[s][1], qd, o)
+            group_steps += c.n_quant[0] != before
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    us = dt * 1e6 / (steps * copies)
+    n_mid = w.context + steps // 2
+    nq_mid = G * ((n_mid - w.residual) // G)
+    pool_rows = int(base.pool_count.view(torch.int32)[:w.units].sum().item()
+                    + base.aux_count.view(torch.int32)[:w.units].sum().item()) / w.units
+    dec_bytes, quant_bytes = algorithmic_bytes(w, nq_mid, n_mid - nq_mid, pool_rows)
+    step_bytes = dec_bytes + quant_bytes * group_steps / (steps * copies)
+    print(json.dumps({
+        "metric": "decode_attention_kv_GBps_2bit_1xMI355X" if w.bits == 2 else "decode_attention_kv_GBps",
+        "value": round(step_bytes / (us * 1e-6) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": steps * copies,
+        "warmup": 0, "ms_per_step": round(us * 1e-3, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {steps} consecutive decode steps from context {w.context} on each of "
+                               f"{copies} cache copies in turn (batch {w.batch}, {w.q_heads} q / {w.kv_heads} kv heads, "
+                               f"{w.bits}-bit, G={G}, R={w.residual}, N={w.outlier_budget}); {group_steps} of the "
+                               f"{steps * copies} steps traced and quantized a group"},
+        "tokens_per_s": round(w.batch / (us * 1e-6), 1),
+        "frac_of_hbm_peak": round(step_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -46,6 +94,10 @@ def main():
     ap.add_argument("--workload", default="llama2_7b_4k")
     ap.add_argument("--cpu-units", type=int, default=32, help="units of the workload the oracle is timed on")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--stream", type=int, default=0, metavar="STEPS",
+                    help="instead of the step benchmark: STEPS consecutive decode steps (append + attention, a group "
+                         "step whenever a ring fills) on each of 8 cache copies taken in turn, from a prompt of the "
+                         "workload's context quantized in one call")
     ap.add_argument("--decode-only", type=int, default=0, metavar="N",
                     help="profiling aid: after set-up run N decode-attention launches over the cache copies and exit")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -75,6 +127,9 @@ def main():
     w = S.WORKLOADS[args.workload]
     assert w.layers == 1, "bench.py times one layer; multi-layer workloads are run layer by layer elsewhere"
     G = w.group_k
+    if args.stream:
+        stream_mode(args, w)
+        return
     # the decode sees the context right after a group was quantized: the longest one of that kind
     # within the workload's context (for the default workload it is the workload's context itself)
     ctx = w.residual + G * ((w.context - w.residual) // G)

@@ -690,3 +690,49 @@ def test_sequences_join_a_running_batch_by_their_own_prefill(use_pages):
         cache.advance()
         lengths = [n + 1 if n > 0 else 0 for n in lengths]
     check(lengths, 1)
+
+
+def test_full_size_llama3_8b_8k_128_consecutive_steps_sampled_units():
+    """The third configuration as it is stated: batch 16, 32 query / 8 kv heads, context 8192, then 128
+    consecutive decode steps with the group step on every 32nd (KVCache.step: one launch on the other
+    steps).  The prompt is quantized in one call; sampled units are compared with the oracle streaming
+    the same tokens, the attention output at every 8th step and after every group step."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    w = S.WORKLOADS["llama3_8b_8k_stream"]
+    steps = 128
+    units = [0, 77, 127]
+    K, V = S.layer_kv(w, 0, w.context + steps)
+    G, R = w.group_k, w.residual
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ((w.context + steps + G - 1) // G) * G, w.bits, G,
+                         w.group_v, R, w.outlier_budget, w.aux_capacity, w.head_dim)
+    cache = KC.KVCache(cfg)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    cache.prefill(0, Kd[:, :, :w.context].contiguous(), Vd[:, :, :w.context].contiguous())
+    nq = w.n_quant
+    assert cache.n_quant[0] == nq and cache.n_res[0] == w.n_res
+    states = H.oracle_states(w, K, V, nq, units)
+    n, quantized, checked = w.context, 0, 0
+    for s in range(steps):
+        Q = S.layer_queries(w, 0, s, "peaky")
+        out = cache.step(0, Kd[:, :, n].contiguous(), Vd[:, :, n].contiguous(), torch.from_numpy(Q).cuda())
+        n += 1
+        closed = n - nq == R + G
+        if closed:
+            for ui, st in zip(units, states):
+                b, h = divmod(ui, w.kv_heads)
+                st.append_group(K[b, h, nq:nq + G], V[b, h, nq:nq + G])
+            nq += G
+            quantized += 1
+        assert cache.n_quant[0] == nq and cache.n_res[0] == n - nq
+        if closed or s % 8 == 0:
+            ref = H.oracle_attention(w, states, Q, K, V, nq, n - nq, units)
+            got = out.cpu().numpy().astype(np.float64)
+            g = w.q_heads // w.kv_heads
+            for ui in units:
+                b, h = divmod(ui, w.kv_heads)
+                err = float(np.abs(got[b, h * g:(h + 1) * g] - ref[b, h * g:(h + 1) * g]).max())
+                assert err <= ATT_TOL, (s, ui, err)
+            checked += 1
+    assert quantized == 4 and checked >= 16
+    H.compare_state(cache, states, w, nq, units=units)
