@@ -337,6 +337,22 @@ int32_t kvq_decode_attention_ragged(const kvq_config* cfg, int32_t layer, const 
                                     size_t workspace_bytes, void* stream);
 
 /*
+ * The quantized segment as fp16 rows, for consumers that need the cache as a matrix (attention of
+ * several query tokens at once, inspection): x^ = X_min + Q * q, the inverse of Eq. 2, evaluated in
+ * fp32 (the product is exact there, the sum rounds once) and rounded to nearest fp16.  A token that
+ * lives in the outlier or auxiliary pool comes out as its stored full-precision row (Method,
+ * "Decoding").  Tokens t0 .. t0+n-1 of every unit of `layer`:
+ *   n_quant      : quantized tokens of the layer (multiple of group_k, <= max_seq)
+ *   t0, n        : multiples of 32, n >= 32, t0 + n <= n_quant
+ *   k_out, v_out : device fp16, out; token t of unit (b,h) at element offset
+ *                  (b*kv_heads + h) * out_unit_stride + (t - t0) * head_dim
+ *   out_unit_stride : in fp16 elements, >= n * head_dim
+ * The pools are read only.  Not on the decode path: the decode entry points never form these rows.
+ */
+int32_t kvq_dequantize(const kvq_config* cfg, int32_t layer, kvq_qcache qcache, int32_t n_quant, kvq_pool pool,
+                       int32_t t0, int32_t n, void* k_out, void* v_out, int64_t out_unit_stride, void* stream);
+
+/*
  * Measurement aid, not part of the method: read `bytes` bytes (a multiple of 16) of device memory
  * at `buf` (16-byte aligned) once with 16-byte loads, in one launch that fills the chip, and fold
  * them into the 4 bytes at `sink` (device).  The benchmark times it over a buffer larger than the

@@ -229,6 +229,24 @@ class UnitState:
                 np.concatenate([vh, v_res.astype(np.float64)]))
 
 
+    def rows_fp16(self):
+        """The quantized segment as fp16 rows, as a consumer that wants the cache as a matrix
+        gets it: x_hat = X_min + Q * q (the inverse of Eq. 2) evaluated in fp32 - the product of a
+        code and an fp16 step is exact there, the sum rounds once - and rounded to nearest fp16;
+        pool / auxiliary tokens as their stored rows.  Returns (K, V), fp16 [n_quant, hd]."""
+        G, nq = self.G, self.n_quant
+        f32 = np.float32
+        kc = self.k_codes.reshape(-1, G, self.hd).astype(f32)
+        kh = (self.k_zero.astype(f32)[:, None, :] + kc * self.k_step.astype(f32)[:, None, :]).reshape(nq, self.hd)
+        vc = self.v_codes.reshape(nq, self.hd // self.Gv, self.Gv).astype(f32)
+        vh = (self.v_zero.astype(f32)[..., None] + vc * self.v_step.astype(f32)[..., None]).reshape(nq, self.hd)
+        kh, vh = kh.astype(np.float16), vh.astype(np.float16)
+        for m in self.pool + self.aux:
+            kh[m["idx"]] = m["k"]
+            vh[m["idx"]] = m["v"]
+        return kh, vh
+
+
 # --------------------------------------------------------------------------
 # Decode attention (Eq. 1)
 # --------------------------------------------------------------------------

@@ -20,7 +20,7 @@ INTERFACE_VERSION = 2       # kvq_version() of the library these structures and 
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
            "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_prefill_quantize_seq", "kvq_decode_attention",
            "kvq_append_decode_attention", "kvq_append_trace_quantize_ragged", "kvq_seq_advance",
-           "kvq_decode_attention_ragged", "kvq_stream_read",
+           "kvq_decode_attention_ragged", "kvq_dequantize", "kvq_stream_read",
            "kvq_status_string", "kvq_version"]
 
 
@@ -101,6 +101,8 @@ def load_library() -> C.CDLL:
                                                 vp, vp, C.c_size_t, vp]
     lib.kvq_append_trace_quantize_ragged.restype = i32
     lib.kvq_append_trace_quantize_ragged.argtypes = [cfgp, i32, vp, vp, kvq_residual, vp, kvq_pool, vp, kvq_qcache, vp]
+    lib.kvq_dequantize.restype = i32
+    lib.kvq_dequantize.argtypes = [cfgp, i32, kvq_qcache, i32, kvq_pool, i32, i32, vp, vp, i64, vp]
     lib.kvq_seq_advance.restype = i32
     lib.kvq_seq_advance.argtypes = [cfgp, vp, vp]
     lib.kvq_decode_attention_ragged.restype = i32
@@ -189,6 +191,14 @@ def kvq_prefill_quantize_seq(cfg, layer, seq, k_rows, v_rows, unit_stride, n_tok
                                                  n_tokens, pool, _ptr(selected), qcache, res, _stream(stream))
     if st != KVQ_OK:
         raise KvqError(st, "kvq_prefill_quantize_seq")
+
+
+def kvq_dequantize(cfg, layer, qcache: kvq_qcache, n_quant, pool: kvq_pool, t0, n, k_out, v_out, out_unit_stride,
+                   stream=None):
+    st = load_library().kvq_dequantize(C.byref(cfg), layer, qcache, n_quant, pool, t0, n, _ptr(k_out), _ptr(v_out),
+                                       out_unit_stride, _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_dequantize")
 
 
 def kvq_append_decode_attention(cfg, layer, q, k_new, v_new, qcache: kvq_qcache, n_quant, res: kvq_residual, res_start,

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libkvq.so")
 
-SOURCES = ["kvq_api.hip", "kvq_quantize.hip", "kvq_trace.hip", "kvq_decode.hip"]
+SOURCES = ["kvq_api.hip", "kvq_quantize.hip", "kvq_trace.hip", "kvq_decode.hip", "kvq_dequant.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

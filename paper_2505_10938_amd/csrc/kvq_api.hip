@@ -345,6 +345,25 @@ int32_t kvq_append_trace_quantize_ragged(const kvq_config* cfg, int32_t layer, c
                                          (hipStream_t)stream));
 }
 
+int32_t kvq_dequantize(const kvq_config* cfg, int32_t layer, kvq_qcache qc, int32_t n_quant, kvq_pool pool,
+                       int32_t t0, int32_t n, void* k_out, void* v_out, int64_t out_unit_stride, void* stream) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
+  if (n_quant < 0 || n_quant > cfg->max_seq || n_quant % cfg->group_k != 0) return KVQ_ERR_INVALID_ARG;
+  if (t0 < 0 || n < 1 || t0 % kvq::kBlockTokens != 0 || n % kvq::kBlockTokens != 0 || (int64_t)t0 + n > n_quant)
+    return KVQ_ERR_INVALID_ARG;
+  if (!k_out || !v_out || ((((uintptr_t)k_out) | ((uintptr_t)v_out)) & 1)) return KVQ_ERR_INVALID_ARG;
+  if (out_unit_stride < (int64_t)n * cfg->head_dim) return KVQ_ERR_INVALID_ARG;
+  if (!qcache_ok(cfg, qc) || !pool.pool_count || !pool.aux_count) return KVQ_ERR_INVALID_ARG;
+  if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v || !pool.pool_idx)) return KVQ_ERR_INVALID_ARG;
+  const Dims d = make_dims(cfg, layer, qc);
+  const int64_t n_blocks = n / kvq::kBlockTokens;
+  if (n_blocks * d.units_per_layer > 0x7FFFFFFFll) return KVQ_ERR_UNSUPPORTED;
+  return from_hip(kvq::launch_dequantize(d, t0 / kvq::kBlockTokens, (int32_t)n_blocks, qc, pool, (__half*)k_out,
+                                         (__half*)v_out, out_unit_stride, (hipStream_t)stream));
+}
+
 int32_t kvq_seq_advance(const kvq_config* cfg, int32_t* seq_state, void* stream) {
   const int32_t st = check_config(cfg);
   if (st != KVQ_OK) return st;

@@ -87,6 +87,8 @@ struct DecodeArgs {
 
 hipError_t launch_append(const Dims& d, const __half* k_new, const __half* v_new, __half* k_res, __half* v_res,
                          int32_t row, hipStream_t s);
+hipError_t launch_dequantize(const Dims& d, int32_t block0, int32_t n_blocks, const kvq_qcache& qc, const kvq_pool& pool,
+                             __half* k_out, __half* v_out, int64_t out_unit_stride, hipStream_t s);
 hipError_t launch_reset_pools(const Dims& d, const kvq_pool& pool, hipStream_t s);
 hipError_t launch_trace(const Dims& d, int32_t group_index, const __half* k_group, const __half* v_group,
                         int64_t unit_stride, const kvq_pool& pool, uint8_t* selected, hipStream_t s);

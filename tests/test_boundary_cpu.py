@@ -232,3 +232,20 @@ def test_untraced_layers_must_fit_the_layer_count():
     for bad in (-1, 4):
         assert P.load_library().kvq_query_sizes(C.byref(cfg(layers=3, untraced_layers=bad)),
                                                 C.byref(B.kvq_sizes())) == B.KVQ_ERR_INVALID_ARG
+
+
+def test_bad_dequantize_arguments_rejected_before_launch():
+    lib = P.load_library()
+    c = cfg()
+    qc = B.kvq_qcache(256, 256, 256, 256, 256)
+    pool = B.kvq_pool(256, 256, 256, 256, 256, 256, 256)
+    dq = lambda nq=256, t0=0, n=64, ko=256, stride=64 * 128, qc=qc, pool=pool: lib.kvq_dequantize(
+        C.byref(c), 0, qc, nq, pool, t0, n, ko, 256, stride, None)
+    bad = B.KVQ_ERR_INVALID_ARG
+    assert dq(nq=250) == bad                                  # not a multiple of the group size
+    assert dq(t0=16) == bad and dq(n=48) == bad and dq(n=0) == bad
+    assert dq(t0=224, n=64) == bad                            # window past the quantized segment
+    assert dq(ko=None) == bad and dq(ko=257) == bad
+    assert dq(stride=64 * 128 - 1) == bad
+    assert dq(qc=B.kvq_qcache(256, 0, 256, 256, 256)) == bad
+    assert dq(pool=B.kvq_pool(256, 256, 0, 256, 256, 256, 256)) == bad     # token indices are needed

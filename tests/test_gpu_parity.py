@@ -736,3 +736,36 @@ def test_full_size_llama3_8b_8k_128_consecutive_steps_sampled_units():
             checked += 1
     assert quantized == 4 and checked >= 16
     H.compare_state(cache, states, w, nq, units=units)
+
+
+@pytest.mark.parametrize("kw,use_pages", [
+    (dict(bits=2, group_k=32, group_v=32, residual=32, outlier_budget=8), False),
+    (dict(bits=4, group_k=64, group_v=128, residual=32, outlier_budget=3), False),
+    (dict(bits=2, group_k=128, group_v=64, residual=0, outlier_budget=4, rho=0.05), True),
+])
+def test_dequantized_rows_bit_exact(kw, use_pages):
+    """kvq_dequantize against the oracle's fp16 rows: every token of the quantized segment, tokens
+    held in the pools included (their stored rows), whole and as a window that starts inside it."""
+    import torch
+    from paper_2505_10938_amd import binding as B, cache as KC
+    w = small("dequant", batch=2, q_heads=2, kv_heads=2, context=128 * 5 + 70, **kw)
+    K, V = S.layer_kv(w, 0)
+    nq = w.n_quant
+    G = w.group_k
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ((w.context + G - 1) // G) * G, w.bits, G, w.group_v,
+                         w.residual, w.outlier_budget, w.aux_capacity, w.head_dim)
+    cache = H.gpu_cache(w, K, V, nq, w.n_res, cache=paged(cfg) if use_pages else KC.KVCache(cfg))
+    states = H.oracle_states(w, K, V, nq)
+    assert any(st.masked.any() for st in states)
+    units = w.batch * w.kv_heads
+    for t0, n in ((0, nq), (96, nq - 160)):
+        ko = torch.full((units, n + 8, w.head_dim), 7.0, dtype=torch.float16, device="cuda")   # padded stride
+        vo = torch.full_like(ko, 7.0)
+        B.kvq_dequantize(cfg, 0, cache.qcache, nq, cache.pool, t0, n, ko, vo, (n + 8) * w.head_dim)
+        torch.cuda.synchronize()
+        kg, vg = ko.cpu().numpy(), vo.cpu().numpy()
+        for ui, st in enumerate(states):
+            kr, vr = st.rows_fp16()
+            assert np.array_equal(kg[ui, :n].view(np.uint16), kr[t0:t0 + n].view(np.uint16)), (ui, t0)
+            assert np.array_equal(vg[ui, :n].view(np.uint16), vr[t0:t0 + n].view(np.uint16)), (ui, t0)
+        assert (kg[:, n:] == 7.0).all() and (vg[:, n:] == 7.0).all()      # nothing written past the window

@@ -171,3 +171,44 @@ def test_packer_against_hand_computed_positions_and_bijection():
     assert vm[1, 128 + (15 * 4 + 3) * 2 + 1] == -(4 * 63 + 3)                         # token 63 = block 1, pair 15, e = 1
     mk = np.zeros(64, bool); mk[0] = mk[33] = mk[63] = True
     assert O.mask_words(mk).tolist() == [1, (1 << 1) | (1 << 31)]
+
+
+# ---- the quantized segment as fp16 rows (inverse of Eq. 2) ----------------------------------------------
+
+@pytest.mark.parametrize("bits,G,Gv", [(2, 32, 32), (4, 64, 128), (2, 128, 64)])
+def test_fp16_rows_are_the_exact_reconstruction_rounded_once_more(bits, G, Gv):
+    st, K, V, nq = build(G * 6 + 40, N=4, G=G, R=32, bits=bits, Gv=Gv, seed=3)
+    kh, vh = st.rows_fp16()
+    ke, ve = st.effective_rows(K[nq:], V[nq:])                 # exact reconstruction, fp64 (pinned above)
+    for got, exact in ((kh, ke[:nq]), (vh, ve[:nq])):
+        assert got.dtype == np.float16 and got.shape == (nq, 128)
+        # fp16 spacing at the exact value; the fp32 sum adds at most 2^-24 relative before the final rounding
+        ulp = np.maximum(np.spacing(np.abs(exact).astype(np.float16)).astype(np.float64), 2.0 ** -24)
+        assert np.all(np.abs(got.astype(np.float64) - exact) <= 0.5 * ulp + 2.0 ** -24 * np.abs(exact))
+    # tokens in the pools come out as the input rows, bit for bit; the others within step/2 (+ rounding)
+    held = sorted(m["idx"] for m in st.pool + st.aux)
+    assert held and np.array_equal(kh[held].view(np.uint16), K[held].view(np.uint16))
+    assert np.array_equal(vh[held].view(np.uint16), V[held].view(np.uint16))
+    free = np.setdiff1d(np.arange(nq), held)
+    kstep = np.repeat(st.k_step.astype(np.float64), G, axis=0)
+    err = np.abs(kh[free].astype(np.float64) - K[free].astype(np.float64))
+    assert np.all(err <= 0.5 * kstep[free] + np.spacing(np.abs(K[free])).astype(np.float64))
+
+
+def test_fp16_rows_of_lattice_inputs_are_the_inputs():
+    # inputs that sit on the quantization lattice: every group spans [-1, 0.5] in steps of 0.5 (2-bit:
+    # zero -1, step 0.5), all exactly representable, so the reconstruction must return the inputs
+    g = rng(9)
+    G = 32
+    levels = np.array([-1.0, -0.5, 0.0, 0.5])
+    K = levels[g.integers(0, 4, (G * 3, 128))]
+    V = levels[g.integers(0, 4, (G * 3, 128))]
+    K[::G, :] = -1.0; K[1::G, :] = 0.5                         # every Key group (per channel) spans the range
+    V[:, ::32] = -1.0; V[:, 1::32] = 0.5                       # every Value group (per token) too
+    K, V = K.astype(np.float16), V.astype(np.float16)
+    st = O.UnitState(128, 2, G, 32, 0, 0)
+    for i in range(3):
+        st.append_group(K[i * G:(i + 1) * G], V[i * G:(i + 1) * G])
+    assert np.all(st.k_step == np.float16(0.5)) and np.all(st.v_zero == np.float16(-1.0))
+    kh, vh = st.rows_fp16()
+    assert np.array_equal(kh, K) and np.array_equal(vh, V)
