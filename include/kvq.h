@@ -227,6 +227,23 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
                              void* stream);
 
 /*
+ * The same attention for several consecutive query tokens at once (verification of drafted tokens,
+ * a short continuation of the prompt; the paper decodes one token per step): the q_tokens newest
+ * tokens of every sequence, whose Keys and Values are already in the cache.  Token i of them (0 = the
+ * oldest) attends to every token up to and including itself, i.e. to everything but the q_tokens - 1 - i
+ * newest residual rows.  The cache is read once for all of them.
+ *   q, out    : device fp16 [batch][q_tokens][q_heads][head_dim]
+ *   q_tokens  : q_tokens * (q_heads / kv_heads) must be 1, 2, 4 or 8 (KVQ_ERR_UNSUPPORTED otherwise);
+ *               n_res >= q_tokens - 1 (the tokens to hide must be residual rows)
+ *   workspace : at least q_tokens * kvq_sizes.workspace_bytes
+ * Everything else as kvq_decode_attention, which is the case q_tokens = 1.
+ */
+int32_t kvq_decode_attention_multi(const kvq_config* cfg, int32_t layer, const void* q, int32_t q_tokens,
+                                   kvq_qcache qcache, int32_t n_quant, kvq_residual res, int32_t res_start,
+                                   int32_t n_res, kvq_pool pool, void* out, void* workspace,
+                                   size_t workspace_bytes, void* stream);
+
+/*
  * Quantize a whole prompt of one layer in one call (Method, "Quantization", prefill phase: the
  * prompt's Keys and Values are quantized group by group, the last tokens stay in full precision).
  * The result is the state that appending the n_tokens tokens one by one would leave: groups

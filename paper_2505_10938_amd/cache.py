@@ -175,6 +175,19 @@ class KVCache:
                                self.workspace.numel(), stream)
         return out
 
+    def decode_multi(self, layer, q, out=None, stream=None):
+        """Attention outputs of the q.shape[1] newest tokens at once (q: fp16 [batch, tokens, q_heads,
+        head_dim]; their Keys and Values are in the cache already), each attending up to itself."""
+        if out is None:
+            out = torch.empty_like(q)
+        tokens = q.shape[1]
+        if self.workspace.numel() < tokens * self.sizes.workspace_bytes:
+            self.workspace = torch.zeros(int(tokens * self.sizes.workspace_bytes), dtype=torch.uint8, device=self.device)
+        B.kvq_decode_attention_multi(self.cfg, layer, q, tokens, self.qcache, self.n_quant[layer], self.res,
+                                     self.res_start[layer], self.n_res[layer], self.pool, out, self.workspace,
+                                     self.workspace.numel(), stream)
+        return out
+
     def step(self, layer, k_new, v_new, q, out=None, stream=None):
         """One decode step of `layer`: the new token joins the cache and the attention output (fp16
         [batch, q_heads, head_dim]) over the cache including it is returned.  Two launches on the steps

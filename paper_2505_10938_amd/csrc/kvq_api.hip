@@ -375,13 +375,31 @@ namespace {
 
 // The decode launch, shared by the two entry points: `seq_state` null = every sequence has the
 // state given; otherwise n_quant and n_res are upper bounds and each sequence brings its own.
-int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc, int32_t n_quant,
-                      kvq_residual res, int32_t res_start, int32_t n_res, const int32_t* seq_state,
+// Workspace of a decode launch whose kv heads have `rows` query rows each (rows = query heads per kv
+// head times query tokens): arrival counters, then partial results for the largest split the launch
+// shape can get.
+int64_t decode_workspace_bytes(const kvq_config* cfg, int64_t rows) {
+  const int64_t upl = (int64_t)cfg->batch * cfg->kv_heads, hd = cfg->head_dim;
+  const int64_t hp = head_parts_of((int)rows);
+  const int64_t slots = (int64_t)cfg->outlier_budget + cfg->aux_capacity;
+  const int64_t s_max =
+      decode_split(upl * hp, (int)(rows / hp), (int)(hd / cfg->group_v), cfg->max_seq, res_rows_of(cfg) + slots).splits;
+  return kCounterBytes(upl * hp) + upl * s_max * rows * (hd + 2) * 4;
+}
+
+int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, int32_t q_tokens, kvq_qcache qc,
+                      int32_t n_quant, kvq_residual res, int32_t res_start, int32_t n_res, const int32_t* seq_state,
                       const void* k_new, const void* v_new, kvq_pool pool, void* out, void* workspace,
                       size_t workspace_bytes, void* stream) {
   const int32_t st = check_config(cfg);
   if (st != KVQ_OK) return st;
   if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
+  const int32_t g = cfg->q_heads / cfg->kv_heads;
+  if (q_tokens < 1 || q_tokens > 8) return KVQ_ERR_INVALID_ARG;
+  const int32_t qrows = q_tokens * g;                    // query rows per kv head: 1, 2, 4 or 8
+  if (qrows != 1 && qrows != 2 && qrows != 4 && qrows != 8) return KVQ_ERR_UNSUPPORTED;
+  // a token must not see the tokens after it: those are hidden as the newest residual rows
+  if (q_tokens > 1 && (seq_state || k_new || n_res < q_tokens - 1)) return KVQ_ERR_INVALID_ARG;
   if (!q || !out) return KVQ_ERR_INVALID_ARG;
   // rows are read 16 bytes at a time (the query rows too: they stand in for rows past the last pool slot)
   if ((((uintptr_t)q) | ((uintptr_t)res.k_res) | ((uintptr_t)res.v_res) | ((uintptr_t)pool.pool_k) |
@@ -405,10 +423,8 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, kvq_q
   if (!pool.pool_count || !pool.aux_count) return KVQ_ERR_INVALID_ARG;
   // every pool slot is read, filled or not, so the rows must exist whenever there are slots
   if (cfg->outlier_budget + cfg->aux_capacity > 0 && (!pool.pool_k || !pool.pool_v)) return KVQ_ERR_INVALID_ARG;
-  kvq_sizes sz;
-  kvq_query_sizes(cfg, &sz);
   if (!workspace || ((uintptr_t)workspace & 255) != 0) return KVQ_ERR_WORKSPACE;
-  if ((int64_t)workspace_bytes < sz.workspace_bytes) return KVQ_ERR_WORKSPACE;
+  if ((int64_t)workspace_bytes < decode_workspace_bytes(cfg, qrows)) return KVQ_ERR_WORKSPACE;
 
   kvq::DecodeArgs a;
   a.d = make_dims(cfg, layer, qc);
@@ -426,15 +442,17 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, kvq_q
   a.aux_count = pool.aux_count;
   a.out = (__half*)out;
   a.counters = (int32_t*)workspace;
-  a.partials = (float*)((unsigned char*)workspace + kCounterBytes((int64_t)a.d.units_per_layer * head_parts_of(a.d.g)));
+  a.partials = (float*)((unsigned char*)workspace + kCounterBytes((int64_t)a.d.units_per_layer * head_parts_of(qrows)));
   a.n_quant = n_quant;
   a.res_start = res_start;
   a.n_res = n_res;
   a.seq = seq_state;
   a.k_new = (const __half*)k_new;
   a.v_new = (const __half*)v_new;
-  a.head_parts = head_parts_of(a.d.g);
-  const Split sp = decode_split((int64_t)a.d.units_per_layer * a.head_parts, a.d.g / a.head_parts, a.d.vgroups, n_quant,
+  a.head_parts = head_parts_of(qrows);
+  a.q_tokens = q_tokens;
+  a.g_shift = g == 1 ? 0 : g == 2 ? 1 : g == 4 ? 2 : 3;
+  const Split sp = decode_split((int64_t)a.d.units_per_layer * a.head_parts, qrows / a.head_parts, a.d.vgroups, n_quant,
                                 (int64_t)n_res + (k_new ? 1 : 0) + a.d.pool_slots);
   a.splits = sp.splits;
   a.nw = sp.nw;
@@ -447,8 +465,16 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, kvq_q
 int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc, int32_t n_quant,
                              kvq_residual res, int32_t res_start, int32_t n_res, kvq_pool pool, void* out,
                              void* workspace, size_t workspace_bytes, void* stream) {
-  return decode_common(cfg, layer, q, qc, n_quant, res, res_start, n_res, nullptr, nullptr, nullptr, pool, out,
+  return decode_common(cfg, layer, q, 1, qc, n_quant, res, res_start, n_res, nullptr, nullptr, nullptr, pool, out,
                        workspace, workspace_bytes, stream);
+}
+
+int32_t kvq_decode_attention_multi(const kvq_config* cfg, int32_t layer, const void* q, int32_t q_tokens,
+                                   kvq_qcache qc, int32_t n_quant, kvq_residual res, int32_t res_start,
+                                   int32_t n_res, kvq_pool pool, void* out, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  return decode_common(cfg, layer, q, q_tokens, qc, n_quant, res, res_start, n_res, nullptr, nullptr, nullptr, pool,
+                       out, workspace, workspace_bytes, stream);
 }
 
 int32_t kvq_append_decode_attention(const kvq_config* cfg, int32_t layer, const void* q, const void* k_new,
@@ -456,7 +482,7 @@ int32_t kvq_append_decode_attention(const kvq_config* cfg, int32_t layer, const 
                                     int32_t res_start, int32_t n_res, kvq_pool pool, void* out, void* workspace,
                                     size_t workspace_bytes, void* stream) {
   if (!k_new || !v_new) return KVQ_ERR_INVALID_ARG;
-  return decode_common(cfg, layer, q, qc, n_quant, res, res_start, n_res, nullptr, k_new, v_new, pool, out,
+  return decode_common(cfg, layer, q, 1, qc, n_quant, res, res_start, n_res, nullptr, k_new, v_new, pool, out,
                        workspace, workspace_bytes, stream);
 }
 
@@ -465,7 +491,7 @@ int32_t kvq_decode_attention_ragged(const kvq_config* cfg, int32_t layer, const 
                                     int32_t max_n_res, kvq_pool pool, void* out, void* workspace,
                                     size_t workspace_bytes, void* stream) {
   if (!seq_state || (((uintptr_t)seq_state) & 15)) return KVQ_ERR_INVALID_ARG;
-  return decode_common(cfg, layer, q, qc, max_n_quant, res, 0, max_n_res, seq_state, nullptr, nullptr, pool, out,
+  return decode_common(cfg, layer, q, 1, qc, max_n_quant, res, 0, max_n_res, seq_state, nullptr, nullptr, pool, out,
                        workspace, workspace_bytes, stream);
 }
 

@@ -571,9 +571,17 @@ __device__ __forceinline__ bool fp_row_ok(const DecodeArgs& a, const Seq& sq, in
 
 template <int GQ, int NV>
 __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, NV>& L, const DecodeArgs& a,
-                                           const Seq& sq, int n_pool, int n_aux, int lane) {
+                                           const Seq& sq, int n_pool, int n_aux, int r0, int lane) {
   const int m16 = lane & 15, r = lane >> 4;
   const bool okk = fp_row_ok(a, sq, X.row0 + m16, n_pool, n_aux);
+  // Several query tokens at once: token i of q_tokens does not see the q_tokens - 1 - i tokens after it,
+  // which are the newest residual rows (one query token: nothing is hidden).  Row j of this workgroup
+  // belongs to token (r0 + j) >> g_shift.
+  auto seen_by = [&](int j) {
+    const int after = a.q_tokens - 1 - ((r0 + j) >> a.g_shift);
+    const int row = X.row0 + m16;
+    return okk && !(row < sq.n_res && row >= sq.n_res - after);
+  };
   // which of the 16 rows hold a token, as a wave-uniform bit mask (lanes 0..15 are rows 0..15):
   // asking row by row costs some 25 scalar instructions per row
   const uint32_t ok_rows = (uint32_t)__ballot(okk) & 0xFFFFu;
@@ -585,8 +593,8 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
     D = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.q0[arow], cb * 64 + r * 16),
                                                 __builtin_bit_cast(half8, X.kf[cb]), D, 0, 0, 0);
   wave_sync();                                                     // earlier readers of sc are done
-  if (2 * r < GQ) L.sc[2 * r][m16] = okk ? D[0] + D[1] : kNegBig;
-  if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][m16] = okk ? D[2] + D[3] : kNegBig;
+  if (2 * r < GQ) L.sc[2 * r][m16] = seen_by(2 * r) ? D[0] + D[1] : kNegBig;
+  if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][m16] = seen_by(2 * r + 1) ? D[2] + D[3] : kNegBig;
   wave_sync();
   float alpha[GQ], x[GQ], red[GQ];
 #pragma unroll
@@ -640,7 +648,8 @@ decode_kernel(DecodeArgs a) {
                "s"(d.bpg_shift), "s"(d.block_bytes), "s"(d.blocks_per_unit), "s"(d.groups_per_unit), "s"(a.q),
                "s"(a.k_codes), "s"(a.k_meta), "s"(a.v_codes), "s"(a.v_meta), "s"(a.mask), "s"(a.k_res), "s"(a.v_res),
                "s"(a.pool_k), "s"(a.pool_v), "s"(a.pool_count), "s"(a.aux_count), "s"(a.seq));
-  asm volatile("" ::"s"(a.k_new), "s"(a.v_new), "s"(d.page_table), "s"(d.table_stride), "s"(d.n_pages), "s"(d.plane0));
+  asm volatile("" ::"s"(a.k_new), "s"(a.v_new), "s"(d.page_table), "s"(d.table_stride), "s"(d.n_pages), "s"(d.plane0),
+               "s"(a.q_tokens), "s"(a.g_shift));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -654,11 +663,17 @@ decode_kernel(DecodeArgs a) {
   const int b = blockIdx.z;
   const int ul = b * d.kv_heads + h;                     // the unit whose cache is read
   const int wl = ul * a.head_parts + part;               // its slice of the workspace
-  const int hq0 = (h * a.head_parts + part) * GQ;        // first query head handled here
+  // The rows handled here: GQ consecutive (query token, query head) pairs of the kv head, token-major
+  // (a plain decode step has one token: the rows are the kv head's query heads).
+  const int r0 = part * GQ;
+  auto row_elem = [&](int j) -> int64_t {                // element offset of row j's query and output row
+    const int r = r0 + j, tj = r >> a.g_shift, hj = r & ((1 << a.g_shift) - 1);
+    return (((int64_t)b * a.q_tokens + tj) * d.q_heads + (h << a.g_shift) + hj) * kHeadDim;
+  };
   const int64_t u = d.unit0 + ul;
   const float qscale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
   WaveLds<GQ, NV>& L = ((WaveLds<GQ, NV>*)smem)[wave];
-  const __half* qbase = a.q + ((int64_t)b * d.q_heads + hq0) * kHeadDim;
+  const __half* qbase = a.q + row_elem(0);               // also stands in for rows that do not exist
   const int n_splits = a.splits;
   // A batch of sequences of different lengths: each sequence's own state, read from memory.  The
   // arguments' values bound it (the host has checked them against the buffers), so that whatever
@@ -694,7 +709,7 @@ decode_kernel(DecodeArgs a) {
   // on: the query, the wave's first group of full-precision rows, its first quantized mini-chunk.
   uint32_t qw[GQ];
 #pragma unroll
-  for (int j = 0; j < GQ; ++j) qw[j] = ((const uint32_t*)(qbase + j * kHeadDim))[lane];
+  for (int j = 0; j < GQ; ++j) qw[j] = ((const uint32_t*)(a.q + row_elem(j)))[lane];
   // The rows of the token being decoded, if they come with the call: one wavefront of the unit
   // stores them in the ring at the end (every wavefront loads them, so that all issue the same
   // loads; without such rows the query row is read instead).
@@ -769,10 +784,10 @@ decode_kernel(DecodeArgs a) {
   if (has_fp) {
     n_pool = __builtin_amdgcn_readfirstlane(n_pool);
     n_aux = __builtin_amdgcn_readfirstlane(n_aux);
-    fp_compute<GQ, NV>(X, F, L, a, sq, n_pool, n_aux, lane);
+    fp_compute<GQ, NV>(X, F, L, a, sq, n_pool, n_aux, r0, lane);
     for (rg += unit_waves; rg < n_rg; rg += unit_waves) {          // further groups (short quantized segment)
       fp_load(X, a, sq, u, qbase, rg * 16, lane);
-      fp_compute<GQ, NV>(X, F, L, a, sq, n_pool, n_aux, lane);
+      fp_compute<GQ, NV>(X, F, L, a, sq, n_pool, n_aux, r0, lane);
     }
   }
 
@@ -856,7 +871,7 @@ decode_kernel(DecodeArgs a) {
       l += mg.l[w * GQ + j] * f;
     }
     if (n_splits == 1) {
-      a.out[((int64_t)b * d.q_heads + hq0 + j) * kHeadDim + c] = __float2half_rn(l > 0.f ? o / l : 0.f);
+      a.out[row_elem(j) + c] = __float2half_rn(l > 0.f ? o / l : 0.f);
     } else {
       coherent_store(&part_out[j * (kHeadDim + 2) + 2 + c], o);
       if (c == 0) {
@@ -910,7 +925,7 @@ decode_kernel(DecodeArgs a) {
         }
         m = mb;
       }
-      a.out[((int64_t)b * d.q_heads + hq0 + j) * kHeadDim + c] = __float2half_rn(l > 0.f ? o / l : 0.f);
+      a.out[row_elem(j) + c] = __float2half_rn(l > 0.f ? o / l : 0.f);
     }
     if (tid == 0)                                        // leave the counter as it was found
       __hip_atomic_store(&a.counters[wl], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -965,7 +980,7 @@ int decode_wave_lds_bytes(int g, int nv) {
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s) {
   const dim3 grid(a.splits, a.d.kv_heads * a.head_parts, a.d.batch);
-  switch (a.d.g / a.head_parts) {
+  switch ((a.q_tokens << a.g_shift) / a.head_parts) {
     case 1: launch_bits<1>(a, grid, s); break;
     case 2: launch_bits<2>(a, grid, s); break;
     default: launch_bits<4>(a, grid, s); break;

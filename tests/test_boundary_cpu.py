@@ -249,3 +249,19 @@ def test_bad_dequantize_arguments_rejected_before_launch():
     assert dq(stride=64 * 128 - 1) == bad
     assert dq(qc=B.kvq_qcache(256, 0, 256, 256, 256)) == bad
     assert dq(pool=B.kvq_pool(256, 256, 0, 256, 256, 256, 256)) == bad     # token indices are needed
+
+
+def test_bad_multi_token_decode_arguments_rejected_before_launch():
+    lib = P.load_library()
+    c = cfg()                                                  # 8 query heads on 2 kv heads: g = 4
+    qc = B.kvq_qcache(256, 256, 256, 256, 256)
+    pool = B.kvq_pool(256, 256, 256, 256, 256, 256, 256)
+    res = B.kvq_residual(256, 256)
+    ws = P.kvq_query_sizes(c).workspace_bytes
+    dm = lambda t, n_res=10, wsb=8 * ws: lib.kvq_decode_attention_multi(C.byref(c), 0, 256, t, qc, 64, res, 0, n_res,
+                                                                        pool, 256, 512, wsb, None)
+    assert dm(0) == B.KVQ_ERR_INVALID_ARG and dm(9) == B.KVQ_ERR_INVALID_ARG
+    assert dm(3) == B.KVQ_ERR_UNSUPPORTED                     # 12 rows per kv head
+    assert dm(4) == B.KVQ_ERR_UNSUPPORTED                     # 16 rows per kv head
+    assert dm(2, n_res=0) == B.KVQ_ERR_INVALID_ARG            # the token to hide must be a residual row
+    assert dm(2, wsb=ws // 2) == B.KVQ_ERR_WORKSPACE

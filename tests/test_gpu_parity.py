@@ -769,3 +769,40 @@ def test_dequantized_rows_bit_exact(kw, use_pages):
             assert np.array_equal(kg[ui, :n].view(np.uint16), kr[t0:t0 + n].view(np.uint16)), (ui, t0)
             assert np.array_equal(vg[ui, :n].view(np.uint16), vr[t0:t0 + n].view(np.uint16)), (ui, t0)
         assert (kg[:, n:] == 7.0).all() and (vg[:, n:] == 7.0).all()      # nothing written past the window
+
+
+@pytest.mark.parametrize("g,tokens,kw", [
+    (1, 2, dict()),
+    (1, 4, dict(bits=4, group_k=64, group_v=64, residual=32, outlier_budget=3)),
+    (2, 2, dict(group_v=128)),
+    (1, 8, dict(residual=32)),                               # eight rows per kv head: two workgroup rows
+    (4, 2, dict(residual=7, context=32 * 30 + 20)),          # the same, with grouped queries
+    (2, 4, dict(context=8192 + 100, batch=1, kv_heads=2)),   # a long unit: several workgroups and the merge
+])
+def test_several_query_tokens_at_once(g, tokens, kw):
+    """kvq_decode_attention_multi: the `tokens` newest tokens of every sequence attend in one launch, each
+    up to itself.  Every token's output is compared with the oracle's attention over the cache without
+    the residual rows that follow the token."""
+    import torch
+    base = dict(batch=2, kv_heads=2, context=1024 + 77)
+    base.update(kw)
+    base["q_heads"] = g * base["kv_heads"]
+    w = small("multi", **base)
+    K, V = S.layer_kv(w, 0)
+    nq, nr = w.n_quant, w.n_res
+    assert nr >= tokens - 1
+    states = H.oracle_states(w, K, V, nq)
+    cache = H.gpu_cache(w, K, V, nq, nr)
+    Q = np.stack([S.layer_queries(w, 0, i, "peaky" if i % 2 == 0 else "diffuse") for i in range(tokens)], axis=1)
+    out = cache.decode_multi(0, torch.from_numpy(np.ascontiguousarray(Q)).cuda())
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    assert got.shape == (w.batch, tokens, w.q_heads, w.head_dim) and np.isfinite(got).all()
+    for i in range(tokens):
+        seen = nr - (tokens - 1 - i)
+        ref = H.oracle_attention(w, states, Q[:, i], K, V, nq, seen)
+        err = float(np.abs(got[:, i] - ref).max())
+        assert err <= ATT_TOL, (i, err)
+    # one query token through the same entry point is the plain decode step, bit for bit
+    q1 = torch.from_numpy(np.ascontiguousarray(Q[:, -1])).cuda()
+    assert torch.equal(cache.decode_multi(0, q1[:, None].contiguous())[:, 0], cache.decode(0, q1))
