@@ -129,17 +129,19 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
   // mean replacement: per-channel mean of the original rows of all G tokens, exact fp64 sum,
   // scaled by the power of two 1/G, rounded to fp32 then fp16.
   if (any) {
-    if (tid < 256) {
-      const int c = tid & 127;
-      unsigned char* rows = (tid < 128) ? sk : sv;
-      double sum = 0.0;
+    // four adjacent lanes per (matrix, channel), each summing every fourth token (the adds are exact,
+    // so the split changes nothing), then each replacing the flagged ones among its own tokens
+    const int part = tid & 3, c = (tid >> 2) & 127;
+    unsigned char* rows = (tid < 512) ? sk : sv;
+    double sum = 0.0;
 #pragma unroll 8
-      for (int t = 0; t < G; ++t) sum += (double)half_at(rows + t * kRowB + 2 * c);
-      const float m32 = (float)(sum / (double)G);
-      const __half m16 = __float2half_rn(m32);
-      for (int t = 0; t < G; ++t)
-        if (ssel[t]) *(__half*)(rows + t * kRowB + 2 * c) = m16;
-    }
+    for (int t = part; t < G; t += 4) sum += (double)half_at(rows + t * kRowB + 2 * c);
+    sum += __shfl_xor(sum, 1, 64);
+    sum += __shfl_xor(sum, 2, 64);
+    const float m32 = (float)(sum / (double)G);
+    const __half m16 = __float2half_rn(m32);
+    for (int t = part; t < G; t += 4)
+      if (ssel[t]) *(__half*)(rows + t * kRowB + 2 * c) = m16;
     __syncthreads();
   }
 
@@ -358,9 +360,10 @@ __global__ void __launch_bounds__(kQuantThreads) group_step_kernel(
     const trace_core::UnitPool p =
         trace_core::unit_pool(d, u, pool_k, pool_v, pool_idx, pool_score, pool_count, aux_count, frozen);
     trace_core::Loaded<G> in;
-    trace_core::load<G>(in, d, p, gk, tid);
+    const bool ahead = d.N <= trace_core::kPoolRowsAhead;
+    trace_core::load<G>(in, d, p, gk, tid, ahead);
     rows_to_lds<G>(rows, L, tid);
-    trace_core::compete<G>(in, d, group_index, p, gk, gv, sel, L.ssel, tid);
+    trace_core::compete<G>(in, d, group_index, p, gk, gv, sel, L.ssel, tid, L.sk, L.sv, kRowB, ahead);
   } else {
     rows_to_lds<G>(rows, L, tid);
     if (tid < G) {

@@ -61,12 +61,18 @@ struct Loaded {
   double old_score;
   int32_t old_idx;
   uint4 kr[G / 16];      // Key rows 16p + team, this lane's 8 channels (threads below kWorkers)
+  uint4 pool_kr, pool_vr;   // pool slot `team`'s Key and Value row, same 8 channels (see kPoolRowsAhead)
 };
+
+// A budget of at most this many tokens has its pool rows fetched with the first loads, so that a
+// member that falls out can be moved to the auxiliary pool without a second trip to memory.
+constexpr int kPoolRowsAhead = 16;
 
 // Issue every load of the first phase (state, stored scores, the group's Key rows); nothing is
 // waited for here.  Rows are handled by teams of 16 lanes (16 bytes per lane).  Requires N > 0.
 template <int G>
-__device__ __forceinline__ void load(Loaded<G>& in, const Dims& d, const UnitPool& p, const __half* gk, int tid) {
+__device__ __forceinline__ void load(Loaded<G>& in, const Dims& d, const UnitPool& p, const __half* gk, int tid,
+                                     bool pool_rows_ahead = false) {
   in.is_frozen = *p.frozen;
   in.n_old = *p.pool_count;
   in.n_aux = *p.aux_count;
@@ -80,6 +86,10 @@ __device__ __forceinline__ void load(Loaded<G>& in, const Dims& d, const UnitPoo
   if (tid < kWorkers) {
 #pragma unroll
     for (int q = 0; q < G / 16; ++q) in.kr[q] = *(const uint4*)(gk + (q * 16 + team) * kHeadDim + sub * 8);
+    if (pool_rows_ahead && team < d.N) {               // d.N <= kPoolRowsAhead: one slot per team
+      in.pool_kr = *(const uint4*)(p.pk + (int64_t)team * kHeadDim + sub * 8);
+      in.pool_vr = *(const uint4*)(p.pv + (int64_t)team * kHeadDim + sub * 8);
+    }
   }
 }
 
@@ -87,9 +97,15 @@ __device__ __forceinline__ void load(Loaded<G>& in, const Dims& d, const UnitPoo
 // barriers); the work is done by threads 0 .. kWorkers-1.  Writes the group's selected flags to
 // `sel` (global, may be null) and `sel_lds` (LDS, may be null), and leaves the unit's new state
 // (frozen flag, member counts) in `in`.  Requires N > 0.
+// `staged_k`, `staged_v` (may be null): the group's rows in LDS, row t at byte t * staged_pitch; with them,
+// and with the pool rows fetched ahead (`pool_rows_ahead`, as passed to load()), no moving row is read
+// from memory.
 template <int G>
 __device__ __forceinline__ void compete(Loaded<G>& in, const Dims& d, int group_index, const UnitPool& p,
-                                        const __half* gk, const __half* gv, uint8_t* sel, uint8_t* sel_lds, int tid) {
+                                        const __half* gk, const __half* gv, uint8_t* sel, uint8_t* sel_lds, int tid,
+                                        const unsigned char* staged_k = nullptr, const unsigned char* staged_v = nullptr,
+                                        int staged_pitch = 0, bool pool_rows_ahead = false) {
+  __shared__ uint4 s_pool_k[kPoolRowsAhead][16], s_pool_v[kPoolRowsAhead][16];
   __shared__ double c_score[kMaxCand];
   __shared__ int32_t c_idx[kMaxCand];
   __shared__ int32_t c_rank[kMaxCand];
@@ -120,6 +136,10 @@ __device__ __forceinline__ void compete(Loaded<G>& in, const Dims& d, int group_
     c_idx[tid] = in.old_idx;
   }
   if (tid < n_cand) c_rank[tid] = 0;
+  if (worker && pool_rows_ahead && team < N) {
+    s_pool_k[team][sub] = in.pool_kr;
+    s_pool_v[team][sub] = in.pool_vr;
+  }
   if (worker) {
 #pragma unroll
     for (int q = 0; q < G / 16; ++q) {
@@ -206,15 +226,26 @@ __device__ __forceinline__ void compete(Loaded<G>& in, const Dims& d, int group_
     const int m = q * 16 + team;
     if (worker && m < n_moves) {
       const int src = mv_src[m];
-      const __half* rk = src >= 0 ? p.pk + (int64_t)src * kHeadDim : gk + (int64_t)(-src - 1) * kHeadDim;
-      const __half* rv = src >= 0 ? p.pv + (int64_t)src * kHeadDim : gv + (int64_t)(-src - 1) * kHeadDim;
-      mk[q] = *(const uint4*)(rk + sub * 8);
-      mvv[q] = *(const uint4*)(rv + sub * 8);
+      if (src >= 0 && pool_rows_ahead) {               // a member that falls out: its row was fetched ahead
+        mk[q] = s_pool_k[src][sub];
+        mvv[q] = s_pool_v[src][sub];
+      } else if (src < 0 && staged_k) {                // a new member: its row is staged in LDS
+        mk[q] = *(const uint4*)(staged_k + (-src - 1) * staged_pitch + sub * 16);
+        mvv[q] = *(const uint4*)(staged_v + (-src - 1) * staged_pitch + sub * 16);
+      } else {
+        const __half* rk = src >= 0 ? p.pk + (int64_t)src * kHeadDim : gk + (int64_t)(-src - 1) * kHeadDim;
+        const __half* rv = src >= 0 ? p.pv + (int64_t)src * kHeadDim : gv + (int64_t)(-src - 1) * kHeadDim;
+        mk[q] = *(const uint4*)(rk + sub * 8);
+        mvv[q] = *(const uint4*)(rv + sub * 8);
+      }
     }
   }
-  // a destination may be another move's source: every load must have returned before any store
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
+  // A destination may be another move's source: every load from memory must have returned before any
+  // store.  Rows taken from LDS copies have no such hazard (uniform over the workgroup).
+  if (!(pool_rows_ahead && staged_k)) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
 #pragma unroll
   for (int q = 0; q < kMaxMovesPerTeam; ++q) {
     const int m = q * 16 + team;
