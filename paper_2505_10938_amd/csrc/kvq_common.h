@@ -108,6 +108,28 @@ hipError_t launch_seq_advance(const Dims& d, int32_t* seq, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
 int decode_wave_lds_bytes(int g, int vgroups);   // LDS one decode wavefront needs
 
+// ---- exchanges inside a row of 16 lanes on the DPP path (no LDS traffic) -----------------------
+// Step s of a butterfly over 2, 4, 8, 16 adjacent lanes: the value of lane ^ 1, of lane ^ 2, then of
+// the mirror lane inside 8 and inside 16.  The mirrors pair a lane with one of the other half; they
+// stand for lane ^ 4 and lane ^ 8 in a reduction because by then all lanes of a half hold the same
+// partial result.  Any commutative, associative and exact combination (min, max, exact sums) may use it.
+template <int STEP>
+__device__ __forceinline__ uint32_t row_partner_u32(uint32_t v) {
+  constexpr int ctrl = STEP == 0 ? 0xB1 /* quad_perm [1,0,3,2] */ : STEP == 1 ? 0x4E /* quad_perm [2,3,0,1] */
+                       : STEP == 2 ? 0x141 /* row_half_mirror */ : 0x140 /* row_mirror */;
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ctrl, 0xf, 0xf, false);
+}
+template <int STEP>
+__device__ __forceinline__ float row_partner(float v) {
+  return __uint_as_float(row_partner_u32<STEP>(__float_as_uint(v)));
+}
+template <int STEP>
+__device__ __forceinline__ double row_partner(double v) {
+  const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+  const unsigned long long lo = row_partner_u32<STEP>((uint32_t)b), hi = row_partner_u32<STEP>((uint32_t)(b >> 32));
+  return __longlong_as_double((long long)((hi << 32) | lo));
+}
+
 // ---- packed layout ---------------------------------------------------------------------------
 // Byte offset (inside a block) of the u32 word that holds field f of lane l, and the bit
 // offset of code x = 2v + e inside that word.  A code occupies bits code_bit .. code_bit + bits - 1

@@ -58,9 +58,17 @@ constexpr int kQuantThreads = 1024;
 
 // Minimum and maximum over groups of `n` adjacent lanes (n = 4, 8 or 16).
 __device__ inline void team_minmax(float& mn, float& mx, int n) {
-  for (int off = 1; off < n; off <<= 1) {
-    mn = fminf(mn, __shfl_xor(mn, off, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  mn = fminf(mn, row_partner<0>(mn));
+  mx = fmaxf(mx, row_partner<0>(mx));
+  mn = fminf(mn, row_partner<1>(mn));
+  mx = fmaxf(mx, row_partner<1>(mx));
+  if (n > 4) {
+    mn = fminf(mn, row_partner<2>(mn));
+    mx = fmaxf(mx, row_partner<2>(mx));
+  }
+  if (n > 8) {
+    mn = fminf(mn, row_partner<3>(mn));
+    mx = fmaxf(mx, row_partner<3>(mx));
   }
 }
 
@@ -136,8 +144,8 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
     double sum = 0.0;
 #pragma unroll 8
     for (int t = part; t < G; t += 4) sum += (double)half_at(rows + t * kRowB + 2 * c);
-    sum += __shfl_xor(sum, 1, 64);
-    sum += __shfl_xor(sum, 2, 64);
+    sum += row_partner<0>(sum);
+    sum += row_partner<1>(sum);
     const float m32 = (float)(sum / (double)G);
     const __half m16 = __float2half_rn(m32);
     for (int t = part; t < G; t += 4)
@@ -250,7 +258,7 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
       for (int x = 0; x < 8; ++x)
         word |= place_code(quant_code(val[x], hi_half(ms[x]), lo_half(ms[x]), kLevels), code_bit(BITS, ff, x));
     }
-    if (kFieldsPerWord == 2) word |= __shfl_xor(word, 1, 64);      // the word's other field
+    if (kFieldsPerWord == 2) word |= row_partner_u32<0>(word);      // the word's other field (the adjacent lane)
     if (ff == 0) {
       const int64_t boff = (u * d.blocks_per_unit + first_block + blk) * (int64_t)d.block_bytes;
       ((uint32_t*)((kv ? v_codes : k_codes) + boff))[wi] = word;

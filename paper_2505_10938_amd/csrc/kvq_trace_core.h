@@ -15,7 +15,10 @@ constexpr int kMaxMovesPerTeam = (64 + 64) / 16;   // at most N evicted + N new 
 // Sum over the 16 lanes of a row team.  fp64 adds of multiples of 2^-24 below 2^23 are exact,
 // so the order does not matter.
 __device__ inline double team_sum_f64(double v) {
-  for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  v += row_partner<0>(v);
+  v += row_partner<1>(v);
+  v += row_partner<2>(v);
+  v += row_partner<3>(v);
   return v;
 }
 
