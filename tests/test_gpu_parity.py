@@ -806,3 +806,21 @@ def test_several_query_tokens_at_once(g, tokens, kw):
     # one query token through the same entry point is the plain decode step, bit for bit
     q1 = torch.from_numpy(np.ascontiguousarray(Q[:, -1])).cuda()
     assert torch.equal(cache.decode_multi(0, q1[:, None].contiguous())[:, 0], cache.decode(0, q1))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_seeded_random_configurations(seed):
+    """Hyper-parameters, shapes and lengths drawn from a seeded generator (ragged tails, budgets from 0 to
+    more than a group, every group size and bit width, every query-head ratio)."""
+    g = np.random.default_rng(1000 + seed)
+    G = int(g.choice([32, 64, 128]))
+    kv_heads = int(g.choice([1, 2, 3]))
+    ratio = int(g.choice([1, 2, 4, 8]))
+    N = int(g.choice([0, 1, 3, 8, 17, 40]))
+    kw = dict(bits=int(g.choice([2, 4])), group_k=G, group_v=int(g.choice([32, 64, 128])),
+              residual=int(g.choice([0, 1, 31, 32, 100, 128])), outlier_budget=N,
+              aux_capacity=int(g.choice([0, 4, 32, 64])) if N else 0,
+              batch=int(g.choice([1, 2, 3])), kv_heads=kv_heads, q_heads=kv_heads * ratio,
+              context=int(g.integers(1, 6 * G + 200)), rho=float(g.choice([0.0, 0.02, 0.1])))
+    w = S.Workload(f"random{seed}", 1, seed=seed, **kw)
+    run_case(w, regimes=("peaky",) if seed % 2 else ("diffuse",))
