@@ -824,3 +824,19 @@ def test_seeded_random_configurations(seed):
               context=int(g.integers(1, 6 * G + 200)), rho=float(g.choice([0.0, 0.02, 0.1])))
     w = S.Workload(f"random{seed}", 1, seed=seed, **kw)
     run_case(w, regimes=("peaky",) if seed % 2 else ("diffuse",))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_seeded_random_ragged_batches(seed):
+    """Ragged batches with drawn lengths and hyper-parameters, on a dense or a paged cache."""
+    from paper_2505_10938_amd import cache as KC
+    g = np.random.default_rng(2000 + seed)
+    G = int(g.choice([32, 64]))
+    kw = dict(bits=int(g.choice([2, 4])), group_k=G, group_v=int(g.choice([32, 128])),
+              residual=int(g.choice([0, 16, 32, 64])), outlier_budget=int(g.choice([0, 2, 6])),
+              q_heads=int(g.choice([2, 4, 8])), rho=0.05)
+    lengths = [int(x) for x in g.integers(0, 5 * G + 60, size=int(g.choice([2, 3, 5])))]
+    if max(lengths) == 0:
+        lengths[0] = 1
+    make = (lambda cfg: paged(cfg, seed=seed, kind=KC.RaggedKVCache)) if seed % 2 else None
+    run_ragged(kw, lengths, make_cache=make)
