@@ -63,13 +63,14 @@ def quantize_groups(x: np.ndarray, bits: int):
                 division so the integer decision is the same on every IEEE
                 machine.
     A group whose stored step is zero (constant group, or step underflow) gets
-    all codes 0.
+    all codes 0.  A minimum of zero is stored as +0: fp16 has two zeros that are
+    the same number, and the stored pattern has to be one of them.
 
     Returns (codes uint8 [..., m], step fp16 [...], zero fp16 [...]).
     """
     assert x.dtype == np.float16
     levels = (1 << bits) - 1
-    mn = x.min(axis=-1)
+    mn = x.min(axis=-1) + np.float16(0.0)                        # -0 + +0 = +0; every other value unchanged
     mx = x.max(axis=-1)
     d = mx.astype(np.float32) - mn.astype(np.float32)            # fl32
     s32 = (d * inv_levels_f32(bits)).astype(np.float32)          # fl32

@@ -164,6 +164,7 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
       mx = fmaxf(mx, x);
     }
     team_minmax(mn, mx, 8);
+    mn += 0.0f;                                        // a zero minimum is stored as +0 (-0 + +0 = +0)
     if (part == 0) {
       const __half st = step_of(mn, mx, BITS);
       skm[c] = (uint32_t)__half_as_ushort(st) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
@@ -189,6 +190,7 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
         mx = fmaxf(mx, fmaxf(x0, x1));
       }
       team_minmax(mn, mx, lanes);
+      mn += 0.0f;                                      // a zero minimum is stored as +0
       if ((c8 & (lanes - 1)) == 0) {
         const int j = (c8 * 8) >> gv_shift;
         const __half st = step_of(mn, mx, BITS);

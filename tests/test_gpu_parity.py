@@ -840,3 +840,34 @@ def test_seeded_random_ragged_batches(seed):
         lengths[0] = 1
     make = (lambda cfg: paged(cfg, seed=seed, kind=KC.RaggedKVCache)) if seed % 2 else None
     run_ragged(kw, lengths, make_cache=make)
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_degenerate_groups(bits):
+    """Groups whose range is zero (step 0, every code 0), fp16 subnormals, signed zeros, a channel and a
+    token of large values: the quantizer's decisions must still be the oracle's bit for bit and the
+    attention finite and within tolerance."""
+    import torch
+    w = small("degenerate", batch=1, q_heads=2, kv_heads=2, context=32 * 8 + 40, residual=32, bits=bits,
+              outlier_budget=2)
+    K, V = S.layer_kv(w, 0)
+    K, V = K.copy(), V.copy()
+    K[:, :, 32:64, :] = np.float16(0.5)                       # a Key group that is constant in every channel
+    K[:, :, 64:96, 5] = np.float16(-3.0)                      # one constant channel in the next group
+    V[:, :, 40:44, :] = np.float16(1.25)                      # Value rows that are constant
+    V[:, :, 100, 32:64] = np.float16(0.0)                     # one constant value group of one token
+    K[:, :, 96:128, 7] = np.float16(6e-8) * (np.arange(32) % 3).astype(np.float16)     # subnormal range
+    V[:, :, 130, :] = np.where(np.arange(128) % 2 == 0, np.float16(0.0), -np.float16(0.0))   # signed zeros
+    K[:, :, 160:192, 9] = (np.arange(32) * 30 - 400).astype(np.float16)                 # a wide channel
+    V[:, :, 170, :] = (np.arange(128) * 4 - 250).astype(np.float16)                     # a wide token
+    states = H.oracle_states(w, K, V, w.n_quant)
+    assert any((st.k_step == 0).any() for st in states) and any((st.v_step == 0).any() for st in states)
+    cache = H.gpu_cache(w, K, V, w.n_quant, w.n_res)
+    H.compare_state(cache, states, w, w.n_quant)
+    for regime in ("peaky", "diffuse"):
+        Q = S.layer_queries(w, 0, 0, regime)
+        ref = H.oracle_attention(w, states, Q, K, V, w.n_quant, w.n_res)
+        got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all()
+        scale = max(1.0, float(np.abs(ref).max()))           # the wide token can dominate an output row
+        assert float(np.abs(got - ref).max()) <= ATT_TOL * scale, regime

@@ -165,3 +165,14 @@ def test_kv_group_axes_and_independence():
     # V channel groups: token 0's group 1 = channels 32..63
     cc, ss, zz = O.quantize_groups(v[0, 32:64][None], 2)
     assert np.array_equal(cc[0], q0["v_codes"][0, 32:64]) and ss[0] == q0["v_step"][0, 1]
+
+
+def test_zero_minimum_is_stored_as_plus_zero():
+    # fp16 has two zeros; the stored zero point of a group whose minimum is zero must be the same
+    # pattern whichever of them the group holds (and a negative minimum keeps its sign)
+    x = np.array([[0.0, -0.0, 1.0, 2.0], [-0.0, -0.0, -0.0, -0.0], [-0.0, 3.0, 0.0, 1.5], [-1.0, 0.0, -0.0, 2.0]],
+                 dtype=np.float16)
+    codes, step, zero = O.quantize_groups(x, 2)
+    assert zero.view(np.uint16).tolist() == [0x0000, 0x0000, 0x0000, 0xBC00]
+    assert codes[1].tolist() == [0, 0, 0, 0] and step[1] == 0
+    assert codes[0].tolist() == [0, 0, 2, 3] and codes[2].tolist() == [0, 3, 0, 2]
