@@ -127,7 +127,11 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restric
   for (; base + run <= n16; base += (size_t)gridDim.x * run) {
     uint4 v[kReadUnroll];
 #pragma unroll
-    for (int k = 0; k < kReadUnroll; ++k) v[k] = p[base + k * 256 + threadIdx.x];
+    for (int k = 0; k < kReadUnroll; ++k) {             // non-temporal: the data is read once
+      typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+      const u4v t = __builtin_nontemporal_load((const u4v*)(p + base + k * 256 + threadIdx.x));
+      v[k] = make_uint4(t.x, t.y, t.z, t.w);
+    }
 #pragma unroll
     for (int k = 0; k < kReadUnroll; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
   }

@@ -269,9 +269,19 @@ struct UnitPtrs {
     pbl = stored_block((uint32_t)min(mc * 4 + (lane >> 4), last_block), e.of_lane);
   }
 };
+// The cache is read once per launch: its loads are non-temporal, which keeps them from displacing each
+// other in the caches on their way through (measured: a plain streaming read reaches 7.0 TB/s with
+// such loads against 6.2 TB/s without, and the kernel gains 8-12 %).
 template <typename T>
-__device__ __forceinline__ T ld(const unsigned char* base, uint32_t off) {
-  return *(const T*)(base + off);
+__device__ __forceinline__ T ld(const unsigned char* base, uint32_t off);
+template <>
+__device__ __forceinline__ uint32_t ld<uint32_t>(const unsigned char* base, uint32_t off) {
+  return __builtin_nontemporal_load((const uint32_t*)(base + off));
+}
+template <>
+__device__ __forceinline__ uint4 ld<uint4>(const unsigned char* base, uint32_t off) {
+  const u32x4 t = __builtin_nontemporal_load((const u32x4*)(base + off));
+  return make_uint4(t[0], t[1], t[2], t[3]);
 }
 
 // Loads of one mini-chunk, in the four parts the compute phases consume.  A block past the end of
@@ -281,8 +291,10 @@ template <int BITS, int NV, class PT>
 __device__ __forceinline__ void load_k_meta_block(McRegs<BITS, NV>& R, const PT& P, int mc, int i, int lane) {
   // uniform base (scalar registers) + one lane offset shared by all loads
   const unsigned char* gp = P.km + (P.block(mc, i) >> P.bpg_shift) * 512u;
-  R.ksp[i] = ld<uint32_t>(gp, lane * 4u);
-  R.ksz[i] = ld<uint32_t>(gp + 256, lane * 4u);
+  // (ordinary loads: with groups of more than 32 tokens the blocks of a mini-chunk share these rows, and
+  // non-temporal loads were measured slower here even without sharing)
+  R.ksp[i] = *(const uint32_t*)(gp + lane * 4u);
+  R.ksz[i] = *(const uint32_t*)(gp + 256 + lane * 4u);
 }
 template <int BITS, int NV, class PT>
 __device__ __forceinline__ void load_k_meta(McRegs<BITS, NV>& R, const PT& P, int mc, int lane) {
@@ -554,12 +566,12 @@ __device__ __forceinline__ void fp_load(FpRegs& X, const DecodeArgs& a, const Se
   const __half *kp, *vp_unused;
   locate(row0 + m16, kp, vp_unused);
 #pragma unroll
-  for (int cb = 0; cb < 4; ++cb) X.kf[cb] = *(const uint4*)(kp + cb * 32 + r * 8);
+  for (int cb = 0; cb < 4; ++cb) X.kf[cb] = ld<uint4>((const unsigned char*)(kp + cb * 32 + r * 8), 0u);
 #pragma unroll
   for (int t = 0; t < 16; ++t) {
     const __half *kp_unused, *vp;
     locate(row0 + t, kp_unused, vp);                               // uniform over the wave
-    X.vw[t] = ((const uint32_t*)vp)[lane];
+    X.vw[t] = ld<uint32_t>((const unsigned char*)vp, lane * 4u);
   }
 }
 
