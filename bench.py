@@ -24,7 +24,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, vendor figure
 # HBM bytes per decode launch from the FETCH_SIZE / WRITE_SIZE counters, scaled by what the same
 # counters read for a plain device copy of known size (profiles/decode_kernel_<workload>.md).
-MEASURED_TRAFFIC = {"llama2_7b_4k": 120_290_000}
+MEASURED_TRAFFIC = {"llama2_7b_4k": 120_440_000}
 
 
 def algorithmic_bytes(w, n_quant, n_res, pool_rows):
