@@ -265,3 +265,16 @@ def test_bad_multi_token_decode_arguments_rejected_before_launch():
     assert dm(4) == B.KVQ_ERR_UNSUPPORTED                     # 16 rows per kv head
     assert dm(2, n_res=0) == B.KVQ_ERR_INVALID_ARG            # the token to hide must be a residual row
     assert dm(2, wsb=ws // 2) == B.KVQ_ERR_WORKSPACE
+
+
+def test_header_is_plain_c_and_cxx():
+    """include/kvq.h compiles on its own as C99 and as C++11 (no torch or HIP types in the boundary)."""
+    import shutil
+    import subprocess
+    header = os.path.join(ROOT, "include", "kvq.h")
+    if shutil.which("gcc") is None:
+        pytest.skip("no host compiler")
+    for cmd in (["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c", header],
+                ["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", header]):
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
