@@ -235,9 +235,12 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
  *   q, out    : device fp16 [batch][q_tokens][q_heads][head_dim]
  *   q_tokens  : q_tokens * (q_heads / kv_heads) must be 1, 2, 4 or 8 (KVQ_ERR_UNSUPPORTED otherwise);
  *               n_res >= q_tokens - 1 (the tokens to hide must be residual rows)
- *   workspace : at least q_tokens * kvq_sizes.workspace_bytes
+ *   workspace : at least kvq_decode_workspace_bytes(cfg, q_tokens) (host only; a negative kvq_status
+ *               for a configuration or token count that is not supported); for q_tokens = 1 that is
+ *               kvq_sizes.workspace_bytes
  * Everything else as kvq_decode_attention, which is the case q_tokens = 1.
  */
+int64_t kvq_decode_workspace_bytes(const kvq_config* cfg, int32_t q_tokens);
 int32_t kvq_decode_attention_multi(const kvq_config* cfg, int32_t layer, const void* q, int32_t q_tokens,
                                    kvq_qcache qcache, int32_t n_quant, kvq_residual res, int32_t res_start,
                                    int32_t n_res, kvq_pool pool, void* out, void* workspace,

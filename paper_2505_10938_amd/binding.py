@@ -20,7 +20,7 @@ INTERFACE_VERSION = 2       # kvq_version() of the library these structures and 
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
            "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_prefill_quantize_seq", "kvq_decode_attention",
            "kvq_append_decode_attention", "kvq_append_trace_quantize_ragged", "kvq_seq_advance",
-           "kvq_decode_attention_ragged", "kvq_decode_attention_multi", "kvq_dequantize", "kvq_stream_read",
+           "kvq_decode_attention_ragged", "kvq_decode_attention_multi", "kvq_decode_workspace_bytes", "kvq_dequantize", "kvq_stream_read",
            "kvq_status_string", "kvq_version"]
 
 
@@ -101,6 +101,8 @@ def load_library() -> C.CDLL:
                                                 vp, vp, C.c_size_t, vp]
     lib.kvq_append_trace_quantize_ragged.restype = i32
     lib.kvq_append_trace_quantize_ragged.argtypes = [cfgp, i32, vp, vp, kvq_residual, vp, kvq_pool, vp, kvq_qcache, vp]
+    lib.kvq_decode_workspace_bytes.restype = i64
+    lib.kvq_decode_workspace_bytes.argtypes = [cfgp, i32]
     lib.kvq_decode_attention_multi.restype = i32
     lib.kvq_decode_attention_multi.argtypes = [cfgp, i32, vp, i32, kvq_qcache, i32, kvq_residual, i32, i32, kvq_pool,
                                                vp, vp, C.c_size_t, vp]
@@ -194,6 +196,13 @@ def kvq_prefill_quantize_seq(cfg, layer, seq, k_rows, v_rows, unit_stride, n_tok
                                                  n_tokens, pool, _ptr(selected), qcache, res, _stream(stream))
     if st != KVQ_OK:
         raise KvqError(st, "kvq_prefill_quantize_seq")
+
+
+def kvq_decode_workspace_bytes(cfg, q_tokens) -> int:
+    n = load_library().kvq_decode_workspace_bytes(C.byref(cfg), q_tokens)
+    if n < 0:
+        raise KvqError(int(n), "kvq_decode_workspace_bytes")
+    return int(n)
 
 
 def kvq_decode_attention_multi(cfg, layer, q, q_tokens, qcache: kvq_qcache, n_quant, res: kvq_residual, res_start,

@@ -181,8 +181,9 @@ class KVCache:
         if out is None:
             out = torch.empty_like(q)
         tokens = q.shape[1]
-        if self.workspace.numel() < tokens * self.sizes.workspace_bytes:
-            self.workspace = torch.zeros(int(tokens * self.sizes.workspace_bytes), dtype=torch.uint8, device=self.device)
+        need = B.kvq_decode_workspace_bytes(self.cfg, tokens)
+        if self.workspace.numel() < need:
+            self.workspace = torch.zeros(need, dtype=torch.uint8, device=self.device)
         B.kvq_decode_attention_multi(self.cfg, layer, q, tokens, self.qcache, self.n_quant[layer], self.res,
                                      self.res_start[layer], self.n_res[layer], self.pool, out, self.workspace,
                                      self.workspace.numel(), stream)

@@ -59,9 +59,9 @@ Split decode_split(int64_t units_per_layer, int g, int vgroups, int64_t n_quant,
   return s;
 }
 constexpr int64_t kCounterBytes(int64_t upl) { return ((upl * 4 + 255) / 256) * 256; }
-// Eight query heads per kv head run as two workgroup rows of four (the same kernel instance as
-// g = 4; both rows read the unit's cache): eight at once do not fit the registers.
-constexpr int head_parts_of(int g) { return g == 8 ? 2 : 1; }
+// Eight query rows per kv head run at once with 2-bit codes; with 4-bit codes, whose instance would not
+// fit the registers, as two workgroup rows of four (the instance of four rows; both read the unit's cache).
+constexpr int head_parts_of(int rows, int bits) { return rows == 8 && bits == 4 ? 2 : 1; }
 
 Dims make_dims(const kvq_config* c, int32_t layer) {
   Dims d;
@@ -191,7 +191,7 @@ int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out) {
   out->counter_bytes = units * 4;
   out->selected_bytes = upl * cfg->group_k;
   // the split count grows with the amount of work: the largest is the one of a full cache
-  const int hp = head_parts_of((int)g);
+  const int hp = head_parts_of((int)g, cfg->bits);
   const int64_t s_max = decode_split(upl * hp, (int)g / hp, (int)(hd / cfg->group_v), cfg->max_seq, out->res_rows + slots).splits;
   out->workspace_bytes = kCounterBytes(upl * hp) + upl * s_max * g * (hd + 2) * 4;
   out->prefill_selected_bytes = upl * cfg->max_seq;
@@ -384,7 +384,7 @@ namespace {
 // shape can get.
 int64_t decode_workspace_bytes(const kvq_config* cfg, int64_t rows) {
   const int64_t upl = (int64_t)cfg->batch * cfg->kv_heads, hd = cfg->head_dim;
-  const int64_t hp = head_parts_of((int)rows);
+  const int64_t hp = head_parts_of((int)rows, cfg->bits);
   const int64_t slots = (int64_t)cfg->outlier_budget + cfg->aux_capacity;
   const int64_t s_max =
       decode_split(upl * hp, (int)(rows / hp), (int)(hd / cfg->group_v), cfg->max_seq, res_rows_of(cfg) + slots).splits;
@@ -446,14 +446,14 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, int32
   a.aux_count = pool.aux_count;
   a.out = (__half*)out;
   a.counters = (int32_t*)workspace;
-  a.partials = (float*)((unsigned char*)workspace + kCounterBytes((int64_t)a.d.units_per_layer * head_parts_of(qrows)));
+  a.partials = (float*)((unsigned char*)workspace + kCounterBytes((int64_t)a.d.units_per_layer * head_parts_of(qrows, cfg->bits)));
   a.n_quant = n_quant;
   a.res_start = res_start;
   a.n_res = n_res;
   a.seq = seq_state;
   a.k_new = (const __half*)k_new;
   a.v_new = (const __half*)v_new;
-  a.head_parts = head_parts_of(qrows);
+  a.head_parts = head_parts_of(qrows, cfg->bits);
   a.q_tokens = q_tokens;
   a.g_shift = g == 1 ? 0 : g == 2 ? 1 : g == 4 ? 2 : 3;
   const Split sp = decode_split((int64_t)a.d.units_per_layer * a.head_parts, qrows / a.head_parts, a.d.vgroups, n_quant,
@@ -471,6 +471,15 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
                              void* workspace, size_t workspace_bytes, void* stream) {
   return decode_common(cfg, layer, q, 1, qc, n_quant, res, res_start, n_res, nullptr, nullptr, nullptr, pool, out,
                        workspace, workspace_bytes, stream);
+}
+
+int64_t kvq_decode_workspace_bytes(const kvq_config* cfg, int32_t q_tokens) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  const int64_t rows = (int64_t)q_tokens * (cfg->q_heads / cfg->kv_heads);
+  if (q_tokens < 1 || q_tokens > 8) return KVQ_ERR_INVALID_ARG;
+  if (rows != 1 && rows != 2 && rows != 4 && rows != 8) return KVQ_ERR_UNSUPPORTED;
+  return decode_workspace_bytes(cfg, rows);
 }
 
 int32_t kvq_decode_attention_multi(const kvq_config* cfg, int32_t layer, const void* q, int32_t q_tokens,

@@ -100,6 +100,19 @@ __device__ inline float from_lane63(float v) {
   }
 KVQ_WAVE_REDUCE(wave_max, "v_max_f32_dpp")
 KVQ_WAVE_REDUCE(wave_sum, "v_add_f32_dpp")
+// eight values: two chains of four
+#define KVQ_WAVE_REDUCE8(NAME)                                              \
+  __device__ inline void NAME(float (&v)[8]) {                                \
+    float a[4] = {v[0], v[1], v[2], v[3]}, b[4] = {v[4], v[5], v[6], v[7]};   \
+    NAME(a);                                                                  \
+    NAME(b);                                                                  \
+    for (int i = 0; i < 4; ++i) {                                             \
+      v[i] = a[i];                                                            \
+      v[4 + i] = b[i];                                                        \
+    }                                                                         \
+  }
+KVQ_WAVE_REDUCE8(wave_max)
+KVQ_WAVE_REDUCE8(wave_sum)
 
 // fp16 hi/lo split of two floats: hi = fp16(x), lo = fp16(x - hi), both rounded to nearest, so that
 // hi + lo = x (1 + e) with |e| <= 2^-22 and no bias (truncating hi instead leaves 2^-21, one-sided);
@@ -986,6 +999,7 @@ int decode_wave_lds_bytes(int g, int nv) {
   switch (g) {
     case 1: return of_g(std::integral_constant<int, 1>{});
     case 2: return of_g(std::integral_constant<int, 2>{});
+    case 8: return of_g(std::integral_constant<int, 8>{});
     default: return of_g(std::integral_constant<int, 4>{});
   }
 }
@@ -995,6 +1009,7 @@ hipError_t launch_decode(const DecodeArgs& a, hipStream_t s) {
   switch ((a.q_tokens << a.g_shift) / a.head_parts) {
     case 1: launch_bits<1>(a, grid, s); break;
     case 2: launch_bits<2>(a, grid, s); break;
+    case 8: launch_nv<8, 2>(a, grid, s); break;          // eight rows at once fit the registers with 2-bit codes only
     default: launch_bits<4>(a, grid, s); break;
   }
   return hipGetLastError();

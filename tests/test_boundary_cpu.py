@@ -258,6 +258,9 @@ def test_bad_multi_token_decode_arguments_rejected_before_launch():
     pool = B.kvq_pool(256, 256, 256, 256, 256, 256, 256)
     res = B.kvq_residual(256, 256)
     ws = P.kvq_query_sizes(c).workspace_bytes
+    assert P.kvq_decode_workspace_bytes(c, 1) == ws and P.kvq_decode_workspace_bytes(c, 2) >= ws
+    assert lib.kvq_decode_workspace_bytes(C.byref(c), 3) == B.KVQ_ERR_UNSUPPORTED
+    assert lib.kvq_decode_workspace_bytes(C.byref(c), 0) == B.KVQ_ERR_INVALID_ARG
     dm = lambda t, n_res=10, wsb=8 * ws: lib.kvq_decode_attention_multi(C.byref(c), 0, 256, t, qc, 64, res, 0, n_res,
                                                                         pool, 256, 512, wsb, None)
     assert dm(0) == B.KVQ_ERR_INVALID_ARG and dm(9) == B.KVQ_ERR_INVALID_ARG
