@@ -190,23 +190,33 @@ struct McRegs {
 };
 
 // LDS of one wavefront.  The first group of arrays is used while scores are formed, the second
-// afterwards; they share storage.
+// afterwards; they share storage.  The scores of a mini-chunk are written while the first group is in
+// use and read before the second buffer of the p*step rows is first written: they lie behind the
+// first group, over that second buffer.
 template <int GQ, int NV>
 struct WaveLds {
+  struct KeyPart {
+    unsigned char aop[2][2 * GQ][kRowBytes];      // q*step rows of one block; two buffers, taken in turn
+    unsigned char zk[4][kRowBytes];               // Key zeros per block, 128 channels
+  };
+  struct ValuePart {
+    unsigned char pp[2 * GQ][kRowBytes];          // p rows (hi/lo per head), 128 tokens
+    unsigned char zv[NV + 1][kRowBytes];          // Value zeros per value group, 128 tokens; row NV = ones
+    unsigned char ps[2][2 * GQ][kRowBytes];       // p*step rows of one value group; two buffers, taken in turn
+  };
+  static constexpr int kSecondBuffer = (2 * GQ + NV + 1 + 2 * GQ) * kRowBytes;   // offset of ps[1]
+  static constexpr int kScores = (int)sizeof(KeyPart) > kSecondBuffer ? (int)sizeof(KeyPart) : kSecondBuffer;
+  static constexpr int kSharedBytes =
+      (int)sizeof(ValuePart) > kScores + GQ * 128 * 4 ? (int)sizeof(ValuePart) : kScores + GQ * 128 * 4;
   unsigned char q0[2 * GQ][kRowBytes];            // q rows (hi/lo per head), no step; written once
   union {
-    struct {
-      unsigned char aop[2][2 * GQ][kRowBytes];    // q*step rows of one block; two buffers, taken in turn
-      unsigned char zk[4][kRowBytes];             // Key zeros per block, 128 channels
-    } k;
-    struct {
-      unsigned char pp[2 * GQ][kRowBytes];        // p rows (hi/lo per head), 128 tokens
-      unsigned char ps[2][2 * GQ][kRowBytes];     // p*step rows of one value group; two buffers, taken in turn
-      unsigned char zv[NV + 1][kRowBytes];        // Value zeros per value group, 128 tokens; row NV = ones
-    } v;
+    KeyPart k;
+    ValuePart v;
+    unsigned char shared[kSharedBytes];
   };
-  float sc[GQ][128];                              // scores of the 128 tokens
   float qz[4][GQ];                                // sum_c q_c z_c per (block, head)
+  // scores of the 128 tokens, [GQ][128]
+  __device__ __forceinline__ float (&sc())[GQ][128] { return *(float (*)[GQ][128])(shared + kScores); }
 };
 
 // Results handed to the workgroup merge, laid over the wavefronts' storage once they are done
@@ -420,12 +430,12 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
     if (more) load_codes_block<BITS>(R.kc, P.kc, P, mc_next, i, lane);
     const int tl = i * 32 + m16;
     if (2 * r < GQ) {
-      L.sc[2 * r][tl] = D0[0] + D0[1];
-      L.sc[2 * r][tl + 16] = D1[0] + D1[1];
+      L.sc()[2 * r][tl] = D0[0] + D0[1];
+      L.sc()[2 * r][tl + 16] = D1[0] + D1[1];
     }
     if (2 * r + 1 < GQ) {
-      L.sc[(2 * r + 1) % GQ][tl] = D0[2] + D0[3];
-      L.sc[(2 * r + 1) % GQ][tl + 16] = D1[2] + D1[3];
+      L.sc()[(2 * r + 1) % GQ][tl] = D0[2] + D0[3];
+      L.sc()[(2 * r + 1) % GQ][tl + 16] = D1[2] + D1[3];
     }
     wave_sync();                        // the next block's rows, at last the scores, are visible
   }
@@ -458,7 +468,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
     bool rescale = false;
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
-      const float2 s2 = *(const float2*)&L.sc[j][2 * lane];
+      const float2 s2 = *(const float2*)&L.sc()[j][2 * lane];
       const float qz = L.qz[bi][j];
       x0[j] = ok0 ? __builtin_fmaf(s2.x, post_k, qz) : kNegBig;
       x1[j] = ok1 ? __builtin_fmaf(s2.y, post_k, qz) : kNegBig;
@@ -618,12 +628,12 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
     D = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.q0[arow], cb * 64 + r * 16),
                                                 __builtin_bit_cast(half8, X.kf[cb]), D, 0, 0, 0);
   wave_sync();                                                     // earlier readers of sc are done
-  if (2 * r < GQ) L.sc[2 * r][m16] = seen_by(2 * r) ? D[0] + D[1] : kNegBig;
-  if (2 * r + 1 < GQ) L.sc[(2 * r + 1) % GQ][m16] = seen_by(2 * r + 1) ? D[2] + D[3] : kNegBig;
+  if (2 * r < GQ) L.sc()[2 * r][m16] = seen_by(2 * r) ? D[0] + D[1] : kNegBig;
+  if (2 * r + 1 < GQ) L.sc()[(2 * r + 1) % GQ][m16] = seen_by(2 * r + 1) ? D[2] + D[3] : kNegBig;
   wave_sync();
   float alpha[GQ], x[GQ], red[GQ];
 #pragma unroll
-  for (int j = 0; j < GQ; ++j) red[j] = x[j] = L.sc[j][lane & 15];   // every lane: the 16 scores, 4 times over
+  for (int j = 0; j < GQ; ++j) red[j] = x[j] = L.sc()[j][lane & 15];   // every lane: the 16 scores, 4 times over
   wave_max(red);
 #pragma unroll
   for (int j = 0; j < GQ; ++j) {
@@ -632,7 +642,7 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
     F.m[j] = m;
     x[j] = x[j] > 0.5f * kNegBig ? __builtin_amdgcn_exp2f(x[j] - m) : 0.f;   // now p
     red[j] = lane < 16 ? x[j] : 0.f;
-    if (lane < 16) L.sc[j][16 + lane] = x[j];
+    if (lane < 16) L.sc()[j][16 + lane] = x[j];
   }
   wave_sum(red);
 #pragma unroll
@@ -649,7 +659,7 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
     const float v0 = h2f_bits(vw & 0xFFFFu), v1 = h2f_bits(vw >> 16);
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
-      const float p = L.sc[j][16 + t];
+      const float p = L.sc()[j][16 + t];
       F.o[j][0] += p * v0;
       F.o[j][1] += p * v1;
     }
