@@ -59,9 +59,10 @@ Split decode_split(int64_t units_per_layer, int g, int vgroups, int64_t n_quant,
   return s;
 }
 constexpr int64_t kCounterBytes(int64_t upl) { return ((upl * 4 + 255) / 256) * 256; }
-// Eight query rows per kv head run at once with 2-bit codes; with 4-bit codes, whose instance would not
-// fit the registers, as two workgroup rows of four (the instance of four rows; both read the unit's cache).
-constexpr int head_parts_of(int rows, int bits) { return rows == 8 && bits == 4 ? 2 : 1; }
+// Workgroup rows that share the query rows of a kv head.  Every supported count (1, 2, 4, 8) has a kernel
+// instance of its own, so it is 1; the kernel still takes any divisor (a count without an instance would
+// run as several rows of a smaller one, all reading the unit's cache).
+constexpr int head_parts_of(int rows, int bits) { return (void)rows, (void)bits, 1; }
 
 Dims make_dims(const kvq_config* c, int32_t layer) {
   Dims d;

@@ -1019,7 +1019,7 @@ hipError_t launch_decode(const DecodeArgs& a, hipStream_t s) {
   switch ((a.q_tokens << a.g_shift) / a.head_parts) {
     case 1: launch_bits<1>(a, grid, s); break;
     case 2: launch_bits<2>(a, grid, s); break;
-    case 8: launch_nv<8, 2>(a, grid, s); break;          // eight rows at once fit the registers with 2-bit codes only
+    case 8: launch_bits<8>(a, grid, s); break;
     default: launch_bits<4>(a, grid, s); break;
   }
   return hipGetLastError();
