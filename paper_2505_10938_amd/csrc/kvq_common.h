@@ -81,7 +81,7 @@ struct DecodeArgs {
   const __half* v_new;  // attended as the newest residual row, and stored in the ring by the launch), or null
   int32_t splits;       // workgroups per unit
   int32_t nw;           // wavefronts per workgroup
-  int32_t head_parts;   // workgroup rows that share a kv head's query rows (1, or 2 when there are 8)
+  int32_t head_parts;   // workgroup rows that share a kv head's query rows (the host passes 1: every row count has its instance)
   int32_t q_tokens;     // consecutive query tokens attended at once (1 in a plain decode step); the rows of a
   int32_t g_shift;      // kv head are its q_tokens * g (token, query head) pairs, token-major; g = 1 << g_shift
   int32_t mc_per_split; // 128-token mini-chunks of the quantized segment per workgroup
