@@ -275,7 +275,7 @@ def test_header_is_plain_c_and_cxx():
     import shutil
     import subprocess
     header = os.path.join(ROOT, "include", "kvq.h")
-    if shutil.which("gcc") is None:
+    if shutil.which("gcc") is None or shutil.which("g++") is None:
         pytest.skip("no host compiler")
     for cmd in (["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c", header],
                 ["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", header]):
