@@ -110,7 +110,9 @@ typedef struct kvq_sizes {
  * have the sizes kvq_query_sizes gives for the same configuration with batch = 1 and
  * max_seq = n_pages * group_k.  Key group j (tokens j*group_k ...) of sequence b is stored as group
  * page_table[b * table_stride + j] of its planes.  The table is device memory, int32, read by the
- * kernels when they run; table_stride >= max_seq / group_k, 0 < n_pages <= 2^20.  An entry outside
+ * kernels when they run; table_stride >= max_seq / group_k, 0 < n_pages <= 2^20 and
+ * n_pages * (group_k / 32) * 512 * bits < 2^32 (the codes of one plane stay below 4 GiB: the kernels
+ * address them with 32-bit offsets); otherwise KVQ_ERR_INVALID_ARG.  An entry outside
  * [0, n_pages) is clamped to that range by the kernels (results are then wrong, accesses stay inside
  * the arrays); entries of groups that no call touches are not read, with one exception: entry 0 of
  * a sequence is read even while the sequence has no quantized token.  Two sequences must not name
@@ -245,6 +247,22 @@ int32_t kvq_decode_attention_multi(const kvq_config* cfg, int32_t layer, const v
                                    kvq_qcache qcache, int32_t n_quant, kvq_residual res, int32_t res_start,
                                    int32_t n_res, kvq_pool pool, void* out, void* workspace,
                                    size_t workspace_bytes, void* stream);
+
+/*
+ * How kvq_decode_attention (and its variants) would split a launch, host only: the quantized tokens
+ * of a unit go to the wavefronts of `splits` workgroups of `waves` wavefronts each in mini-chunks of
+ * 128 tokens, `minichunks_per_split` per workgroup; with splits > 1 the workgroups of a unit exchange
+ * partial results (m, l, o) through the workspace and the last one to arrive merges them (the
+ * chunk-wise form of Eq. 1's softmax: the result does not depend on the split).  For tests and
+ * benchmarks that must know which launch shape they exercise; the kernels need no such call.
+ *   q_tokens : as in kvq_decode_attention_multi (1 for a plain decode step)
+ *   n_quant  : quantized tokens (multiple of group_k, <= max_seq)
+ *   fp_rows  : full-precision rows the launch reads per unit: n_res (+ 1 with k_new) + outlier_budget
+ *              + aux_capacity
+ * Returns KVQ_OK or the status kvq_decode_attention would return for the same cfg / q_tokens / n_quant.
+ */
+int32_t kvq_decode_launch_shape(const kvq_config* cfg, int32_t q_tokens, int32_t n_quant, int32_t fp_rows,
+                                int32_t* splits, int32_t* waves, int32_t* minichunks_per_split);
 
 /*
  * Quantize a whole prompt of one layer in one call (Method, "Quantization", prefill phase: the

@@ -20,7 +20,8 @@ INTERFACE_VERSION = 2       # kvq_version() of the library these structures and 
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
            "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_prefill_quantize_seq", "kvq_decode_attention",
            "kvq_append_decode_attention", "kvq_append_trace_quantize_ragged", "kvq_seq_advance",
-           "kvq_decode_attention_ragged", "kvq_decode_attention_multi", "kvq_decode_workspace_bytes", "kvq_dequantize", "kvq_stream_read",
+           "kvq_decode_attention_ragged", "kvq_decode_attention_multi", "kvq_decode_workspace_bytes",
+           "kvq_decode_launch_shape", "kvq_dequantize", "kvq_stream_read",
            "kvq_status_string", "kvq_version"]
 
 
@@ -103,6 +104,8 @@ def load_library() -> C.CDLL:
     lib.kvq_append_trace_quantize_ragged.argtypes = [cfgp, i32, vp, vp, kvq_residual, vp, kvq_pool, vp, kvq_qcache, vp]
     lib.kvq_decode_workspace_bytes.restype = i64
     lib.kvq_decode_workspace_bytes.argtypes = [cfgp, i32]
+    lib.kvq_decode_launch_shape.restype = i32
+    lib.kvq_decode_launch_shape.argtypes = [cfgp, i32, i32, i32] + [C.POINTER(i32)] * 3
     lib.kvq_decode_attention_multi.restype = i32
     lib.kvq_decode_attention_multi.argtypes = [cfgp, i32, vp, i32, kvq_qcache, i32, kvq_residual, i32, i32, kvq_pool,
                                                vp, vp, C.c_size_t, vp]
@@ -203,6 +206,16 @@ def kvq_decode_workspace_bytes(cfg, q_tokens) -> int:
     if n < 0:
         raise KvqError(int(n), "kvq_decode_workspace_bytes")
     return int(n)
+
+
+def kvq_decode_launch_shape(cfg, q_tokens, n_quant, fp_rows):
+    """(splits, waves, minichunks_per_split) of the decode launch for this state."""
+    a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
+    st = load_library().kvq_decode_launch_shape(C.byref(cfg), q_tokens, n_quant, fp_rows, C.byref(a), C.byref(b),
+                                                C.byref(c))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_decode_launch_shape")
+    return a.value, b.value, c.value
 
 
 def kvq_decode_attention_multi(cfg, layer, q, q_tokens, qcache: kvq_qcache, n_quant, res: kvq_residual, res_start,

@@ -100,8 +100,10 @@ Dims make_dims(const kvq_config* c, int32_t layer) {
 bool qcache_ok(const kvq_config* c, const kvq_qcache& qc) {
   if (!qc.k_codes || !qc.k_meta || !qc.v_codes || !qc.v_meta || !qc.mask) return false;
   if (!qc.page_table) return true;
-  return qc.n_pages > 0 && qc.n_pages <= (1 << 20) && qc.table_stride >= c->max_seq / c->group_k &&
-         (((uintptr_t)qc.page_table) & 3) == 0;
+  // the kernels address the blocks of a plane with 32-bit byte offsets: a plane's codes stay below 4 GiB
+  const int64_t plane_code_bytes = (int64_t)qc.n_pages * (c->group_k / 32) * 512 * c->bits;
+  return qc.n_pages > 0 && qc.n_pages <= (1 << 20) && plane_code_bytes < (1ll << 32) &&
+         qc.table_stride >= c->max_seq / c->group_k && (((uintptr_t)qc.page_table) & 3) == 0;
 }
 // Dims of a launch that reads or writes the quantized cache `qc`.
 Dims make_dims(const kvq_config* c, int32_t layer, const kvq_qcache& qc) {
@@ -481,6 +483,24 @@ int64_t kvq_decode_workspace_bytes(const kvq_config* cfg, int32_t q_tokens) {
   if (q_tokens < 1 || q_tokens > 8) return KVQ_ERR_INVALID_ARG;
   if (rows != 1 && rows != 2 && rows != 4 && rows != 8) return KVQ_ERR_UNSUPPORTED;
   return decode_workspace_bytes(cfg, rows);
+}
+
+int32_t kvq_decode_launch_shape(const kvq_config* cfg, int32_t q_tokens, int32_t n_quant, int32_t fp_rows,
+                                int32_t* splits, int32_t* waves, int32_t* minichunks_per_split) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  if (!splits || !waves || !minichunks_per_split) return KVQ_ERR_INVALID_ARG;
+  if (q_tokens < 1 || q_tokens > 8 || fp_rows < 0) return KVQ_ERR_INVALID_ARG;
+  const int32_t qrows = q_tokens * (cfg->q_heads / cfg->kv_heads);
+  if (qrows != 1 && qrows != 2 && qrows != 4 && qrows != 8) return KVQ_ERR_UNSUPPORTED;
+  if (n_quant < 0 || n_quant > cfg->max_seq || n_quant % cfg->group_k != 0) return KVQ_ERR_INVALID_ARG;
+  const int hp = head_parts_of(qrows, cfg->bits);
+  const Split sp = decode_split((int64_t)cfg->batch * cfg->kv_heads * hp, qrows / hp, cfg->head_dim / cfg->group_v,
+                                n_quant, fp_rows);
+  *splits = sp.splits;
+  *waves = sp.nw;
+  *minichunks_per_split = sp.mc_per_split;
+  return KVQ_OK;
 }
 
 int32_t kvq_decode_attention_multi(const kvq_config* cfg, int32_t layer, const void* q, int32_t q_tokens,

@@ -920,7 +920,12 @@ decode_kernel(DecodeArgs a) {
   // ---- the last workgroup of the unit to arrive merges the unit's partials ---------------------------
   // Partials and the counter are accessed with device-scope atomic operations (they go to the
   // point where the compute dies' L2 caches agree), so no cache write-back or invalidate is
-  // needed; the fences below only wait for this thread's own stores and keep the order.
+  // needed.  What orders them is explicit: every thread waits until its own partial stores have
+  // been acknowledged at that point (vector-memory counter at zero), then the barrier, then one
+  // thread bumps the counter.  A workgroup that finds the counter at n_splits - 1 therefore finds
+  // every other workgroup's partials in place; its loads are device-scope too and are issued after
+  // the barrier that follows the counter's return.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (tid == 0) {

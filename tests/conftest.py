@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    config.addinivalue_line("markers", "relaxed_share(x): share of attention outputs this test may judge on the "
+                                       "fp16-ulp branch of the tolerance (default 0.001)")
 
 
 def pytest_collection_modifyitems(config, items):

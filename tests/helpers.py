@@ -8,6 +8,68 @@ import kvq_synth as S
 from oracle import kvq_oracle as O
 
 
+ATT_TOL = 2e-3          # the bar on the attention output: max abs error against the oracle's fp64 result
+ATT_ABS_LIMIT = 3.5     # |reference| up to which that bar is applied as it stands
+
+
+class AttStats:
+    """What the attention checks of one test saw."""
+
+    def __init__(self):
+        self.reset()
+
+    def reset(self):
+        self.n = self.relaxed = 0
+        self.max_abs = self.worst_ulps = 0.0
+
+
+ATT_STATS = AttStats()
+
+
+def att_err(got, ref, stats: AttStats = ATT_STATS):
+    """Error of an attention output (`got`: the kernel's fp16 values as float64, `ref`: the oracle's
+    fp64 values), in units in which ATT_TOL is the bar.
+
+    Where |ref| <= 3.5 it is the plain absolute error.  fp16 cannot hold a larger value to 2e-3 (half
+    an ulp is 1.95e-3 in [4, 8)), so there the output is compared with the oracle's own result rounded
+    to fp16 and must lie within one fp16 ulp of it: the error is counted in ulps and scaled so that
+    one ulp equals ATT_TOL.  `stats` counts how many elements each branch judged; the tests bound the
+    second branch's share."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    big = np.abs(ref) > ATT_ABS_LIMIT
+    err_abs = np.abs(got - ref)
+    stats.n += int(ref.size)
+    stats.relaxed += int(big.sum())
+    worst = float(err_abs[~big].max()) if (~big).any() else 0.0
+    stats.max_abs = max(stats.max_abs, worst)
+    if big.any():
+        ref16 = ref[big].astype(np.float32).astype(np.float16)
+        ulps = np.abs(got[big] - ref16.astype(np.float64)) / np.spacing(np.abs(ref16)).astype(np.float64)
+        stats.worst_ulps = max(stats.worst_ulps, float(ulps.max()))
+        worst = max(worst, float(ulps.max()) * ATT_TOL)
+    return worst
+
+
+def merged_partials(cache, w: S.Workload, n_quant: int, fp_rows: int):
+    """The decode launch's result BEFORE the rounding of the output to fp16: the fp32 partial results
+    (m, l, o) that the workgroups of a unit exchange through the workspace, merged here in fp64.  Only
+    for launches that split a unit over several workgroups (they leave the partials in the workspace).
+    Returns float64 [batch, q_heads, head_dim]."""
+    import torch
+    from paper_2505_10938_amd import binding as B
+    splits, _, _ = B.kvq_decode_launch_shape(cache.cfg, 1, n_quant, fp_rows)
+    assert splits > 1, "one workgroup per unit: no partials are written"
+    upl, g, hd = w.batch * w.kv_heads, w.q_heads // w.kv_heads, w.head_dim
+    off = ((upl * 4 + 255) // 256) * 256
+    raw = cache.workspace[off:off + upl * splits * g * (hd + 2) * 4].view(torch.float32).cpu().numpy()
+    part = raw.astype(np.float64).reshape(upl, splits, g, hd + 2)
+    m, l, o = part[..., 0], part[..., 1], part[..., 2:]
+    scale = np.exp2(m - m.max(axis=1, keepdims=True))               # scores are kept in the log2 domain
+    out = (o * scale[..., None]).sum(axis=1) / (l * scale).sum(axis=1)[..., None]
+    return out.reshape(w.batch, w.kv_heads * g, hd)
+
+
 def oracle_states(w: S.Workload, K: np.ndarray, V: np.ndarray, n_quant: int, units=None):
     """K, V: fp16 [batch, kv_heads, n, hd] of one layer.  Streams the first n_quant tokens of
     every unit (or of the units listed, as indices b * kv_heads + h) through the oracle group

@@ -188,6 +188,19 @@ def test_bad_page_tables_rejected_before_launch():
         assert call(paged(pages=(1 << 20) + 1)) == B.KVQ_ERR_INVALID_ARG
         assert call(paged(stride=groups - 1)) == B.KVQ_ERR_INVALID_ARG  # a table row shorter than a sequence can get
         assert call(paged(table=258)) == B.KVQ_ERR_INVALID_ARG          # int32 entries
+    # a plane's codes must stay below 4 GiB (the kernels' block offsets are 32-bit): with 128-token groups
+    # and 4-bit codes a page is 8 KiB of codes per plane, so 2^19 pages are one too many
+    big = cfg(group_k=128, group_v=128, bits=4, max_seq=1024)
+    ws_big = P.kvq_query_sizes(big).workspace_bytes
+    for pages, want_ok in (((1 << 19) - 1, True), (1 << 19, False), (1 << 20, False)):
+        qc = B.kvq_qcache(256, 256, 256, 256, 256, 256, big.max_seq // big.group_k, pages)
+        # (a null workspace is looked at after the cache: it tells an accepted cache from a rejected one, no launch)
+        st = lib.kvq_decode_attention(C.byref(big), 0, 256, qc, 128, res, 0, 10, pool, 256, 0, ws_big, None)
+        assert st == (B.KVQ_ERR_WORKSPACE if want_ok else B.KVQ_ERR_INVALID_ARG), (pages, st)
+    small_pages = cfg(group_k=32, bits=2)
+    qc = B.kvq_qcache(256, 256, 256, 256, 256, 256, small_pages.max_seq // 32, 1 << 20)    # 1 GiB per plane: fine
+    assert lib.kvq_decode_attention(C.byref(small_pages), 0, 256, qc, 64, res, 0, 10, pool, 256, 0, ws, None) == \
+        B.KVQ_ERR_WORKSPACE
     # the quantized arrays are needed even with nothing quantized: the first block is always loaded
     assert lib.kvq_decode_attention(C.byref(c), 0, 256, B.kvq_qcache(0, 256, 256, 256, 256), 0, res, 0, 10, pool, 256,
                                     512, ws, None) == B.KVQ_ERR_INVALID_ARG

@@ -6,19 +6,31 @@ import numpy as np
 import pytest
 
 import kvq_synth as S
+from paper_2505_10938_amd import binding as B
 from tests import helpers as H
 
 pytestmark = pytest.mark.gpu
 
-ATT_TOL = 2e-3
+ATT_TOL = H.ATT_TOL
+att_err = H.att_err          # absolute error where |ref| <= 3.5, fp16 ulps of the rounded oracle result beyond
 
 
-def att_err(got, ref):
-    """Largest attention error, in units in which ATT_TOL is the bar: absolute for outputs up to 3.5 in
-    magnitude, relative to |ref| / 3.5 beyond.  fp16 cannot hold larger values to 2e-3 (half an ulp is
-    1.95e-3 in [4, 8)), so the bar grows with the magnitude there; the synthetic workloads' outputs
-    are almost all below 3.5."""
-    return float((np.abs(got - ref) / np.maximum(1.0, np.abs(ref) / 3.5)).max())
+@pytest.fixture(autouse=True)
+def relaxed_share(request):
+    """Every test states how many output elements were judged on the relaxed branch of att_err (|ref| >
+    3.5: within one fp16 ulp of the oracle's rounded result) and keeps that share below 0.1 % (a test
+    whose inputs are scaled up on purpose says so with the `relaxed_share` marker; a test with few
+    outputs may have three such elements)."""
+    H.ATT_STATS.reset()
+    yield
+    st = H.ATT_STATS
+    marker = request.node.get_closest_marker("relaxed_share")
+    limit = marker.args[0] if marker else 1e-3
+    if st.n:
+        print(f"\n[attention check] {request.node.name}: {st.n} elements; max abs err {st.max_abs:.3e} on |ref| <= "
+              f"{H.ATT_ABS_LIMIT}; {st.relaxed} elements ({100.0 * st.relaxed / st.n:.4f} %) beyond, worst "
+              f"{st.worst_ulps:.2f} fp16 ulp from the rounded oracle result")
+        assert st.relaxed <= max(3, limit * st.n), (st.relaxed, st.n)
 
 
 def run_case(w: S.Workload, regimes=("peaky", "diffuse")):
@@ -154,26 +166,95 @@ def test_full_size_llama2_7b_4k_sampled_units():
 
 def test_full_size_long_32k_sampled_units():
     # long context, grouped queries, N = G: several workgroups per unit and the last-arrival merge
+    import torch
     w = S.WORKLOADS["long_32k"]
-    run_sampled(w, [0, 31], regimes=("peaky",))
+    cache = run_sampled(w, [0, 31])
+    assert B.kvq_decode_launch_shape(cache.cfg, 1, w.n_quant, w.n_res + 64)[0] == 8      # workgroups per unit
+    # the result before the output is rounded to fp16, from the partial results the workgroups exchange
+    units = [0, 13, 31]
+    K, V = S.layer_kv(w, 0)
+    states = H.oracle_states(w, K, V, w.n_quant, units)
+    for regime in ("peaky", "diffuse"):
+        Q = S.layer_queries(w, 0, 0, regime)
+        ref = H.oracle_attention(w, states, Q, K, V, w.n_quant, w.n_res, units)
+        cache.decode(0, torch.from_numpy(Q).cuda())
+        torch.cuda.synchronize()
+        pre = H.merged_partials(cache, w, w.n_quant, w.n_res + 64)
+        rows = np.isfinite(ref).all(axis=-1)
+        err = float(np.abs(pre[rows] - ref[rows]).max())
+        print(f"\n[before output rounding] long_32k {regime}: max abs err {err:.3e}")
+        assert err <= 0.5 * ATT_TOL, (regime, err)
 
 
 def test_full_size_llama3_8b_8k_sampled_units():
     # grouped queries at batch 16, context 8192: two workgroups per unit, four query heads each
     import torch
     w = S.WORKLOADS["llama3_8b_8k_stream"]
-    cache = run_sampled(w, [0, 77, 127], regimes=("peaky",))
+    cache = run_sampled(w, [0, 77, 127])
+    assert B.kvq_decode_launch_shape(cache.cfg, 1, w.n_quant, w.n_res + 40)[:2] == (2, 8)
     q = torch.from_numpy(S.layer_queries(w, 0, 0, "peaky")).cuda()
     assert torch.equal(cache.decode(0, q), paged_copy(cache).decode(0, q))
+    # the result before the output is rounded to fp16 (two workgroups per unit leave their partial results)
+    units = [0, 77, 127]
+    K, V = S.layer_kv(w, 0)
+    states = H.oracle_states(w, K, V, w.n_quant, units)
+    for regime in ("peaky", "diffuse"):
+        Q = S.layer_queries(w, 0, 0, regime)
+        ref = H.oracle_attention(w, states, Q, K, V, w.n_quant, w.n_res, units)
+        cache.decode(0, torch.from_numpy(Q).cuda())
+        torch.cuda.synchronize()
+        pre = H.merged_partials(cache, w, w.n_quant, w.n_res + 40)
+        rows = np.isfinite(ref).all(axis=-1)
+        err = float(np.abs(pre[rows] - ref[rows]).max())
+        print(f"\n[before output rounding] llama3_8b_8k {regime}: max abs err {err:.3e}")
+        assert err <= 0.5 * ATT_TOL, (regime, err)
 
 
 @pytest.mark.parametrize("bits", [2, 4])
-def test_batch_128_layer_shape_sampled_units(bits):
-    # the 32-layer configuration's layer shape (8 kv heads, 4 query heads each, 2 wavefronts per
-    # unit) at a quarter of its batch and a shorter context
+def test_batch_32_layer_shape_sampled_units(bits):
+    # the 32-layer configuration's layer shape (8 kv heads, 4 query heads each) at a quarter of its batch
+    # and a shorter context: 256 units, one workgroup of 8 wavefronts per unit
     w = S.WORKLOADS["mistral_7b_b128_4k_layer"].with_(name=f"b32_layer_{bits}bit", batch=32, context=1024 + 128,
                                                       bits=bits)
-    run_sampled(w, [0, 100, 255], regimes=("peaky",))
+    cache = run_sampled(w, [0, 100, 255], regimes=("peaky",))
+    assert B.kvq_decode_launch_shape(cache.cfg, 1, w.n_quant, w.n_res + 40)[:2] == (1, 8)
+
+
+@pytest.mark.parametrize("bits,context", [(2, 4096), (4, 1024 + 128 + 19)])
+def test_batch_128_stack_layer_sampled_units(bits, context):
+    """The 32-layer, batch-128 configuration in the launch shape the benchmark times: 1024 units per layer, so
+    every unit is one workgroup of TWO wavefronts that share its mini-chunks (2-bit: the full context of
+    4096 tokens, 16 and 15 mini-chunks per wavefront).  The cache has four layers and the last one is used,
+    so unit and plane offsets beyond the first layers are exercised.  Every unit runs on the GPU; units
+    sampled across the batch are checked against the oracle, state bit for bit and attention in both query
+    regimes."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    layer = 3
+    w = S.WORKLOADS["mistral_7b_b128_4k"].with_(name=f"b128_stack_{bits}bit", layers=4, bits=bits, context=context)
+    G = w.group_k
+    cfg = KC.make_config(w.layers, w.batch, w.q_heads, w.kv_heads, ((w.n_quant + G - 1) // G) * G, w.bits, G, w.group_v,
+                         w.residual, w.outlier_budget, w.aux_capacity, w.head_dim)
+    assert B.kvq_decode_launch_shape(cfg, 1, w.n_quant, w.n_res + 40)[:2] == (1, 2)
+    units = [0, 7, 8 * 63 + 2, 8 * 100 + 5, 1023]
+    K, V = S.layer_kv(w, layer)
+    cache = KC.KVCache(cfg)
+    cache.prefill(layer, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
+    torch.cuda.synchronize()
+    states = H.oracle_states(w, K, V, w.n_quant, units)
+    H.compare_state(cache, states, w, w.n_quant, layer=layer, units=units)
+    g = w.q_heads // w.kv_heads
+    for regime in ("peaky", "diffuse"):
+        Q = S.layer_queries(w, layer, 0, regime)
+        ref = H.oracle_attention(w, states, Q, K, V, w.n_quant, w.n_res, units)
+        got = cache.decode(layer, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all()
+        for ui in units:
+            b, h = divmod(ui, w.kv_heads)
+            err = att_err(got[b, h * g:(h + 1) * g], ref[b, h * g:(h + 1) * g])
+            assert err <= ATT_TOL, (bits, regime, ui, err)
+    # the other layers of the cache were not touched
+    assert not cache.pool_count.view(torch.int32)[:3 * w.units].any()
 
 
 def test_four_bit_full_batch_sampled_units():
@@ -234,6 +315,7 @@ def test_fused_group_step_configurations(kw):
     run_streaming(w, 2 * w.group_k + 5, True, check_every=17)
 
 
+@pytest.mark.relaxed_share(1.0)
 def test_large_magnitudes_stay_in_the_fp16_range_of_the_operands():
     """Keys 8 times and queries 4 times the usual size: Key steps of several hundred, |q| * step up
     to about 10^4, a quarter of what the fp16 operand rows can hold; Values 16 times the usual size."""
@@ -250,8 +332,9 @@ def test_large_magnitudes_stay_in_the_fp16_range_of_the_operands():
     ref = H.oracle_attention(w, states, Q, K, V, w.n_quant, w.n_res)
     got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
     assert np.isfinite(got).all()
-    # outputs are 16 times larger than usual, and so is the rounding of the fp16 result
-    assert att_err(got, ref) <= 16 * ATT_TOL
+    # outputs are 16 times larger than usual: most exceed 3.5 and are held to one fp16 ulp of the oracle's
+    # rounded result, the others to the plain 2e-3
+    assert att_err(got, ref) <= ATT_TOL
 
 
 def test_first_layers_without_tracing():
