@@ -36,7 +36,8 @@ typedef enum kvq_status {
   KVQ_ERR_INVALID_ARG = -1, /* null pointer, out-of-range or inconsistent argument        */
   KVQ_ERR_UNSUPPORTED = -2, /* meaningful for the method but not built (e.g. head_dim 64) */
   KVQ_ERR_WORKSPACE = -3,   /* workspace smaller than kvq_query_sizes reports             */
-  KVQ_ERR_LAUNCH = -4       /* the HIP runtime refused a launch                           */
+  KVQ_ERR_LAUNCH = -4,      /* the HIP runtime refused a launch                           */
+  KVQ_ERR_SCRATCH = -5      /* too large for the library's static scratch buffer          */
 } kvq_status;
 
 /* Hyper-parameters in the paper's notation (Experiments, "Details"): bit width b,
@@ -247,6 +248,25 @@ int32_t kvq_decode_attention_multi(const kvq_config* cfg, int32_t layer, const v
                                    kvq_qcache qcache, int32_t n_quant, kvq_residual res, int32_t res_start,
                                    int32_t n_res, kvq_pool pool, void* out, void* workspace,
                                    size_t workspace_bytes, void* stream);
+
+/*
+ * kvq_decode_attention for callers that cannot allocate or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  The launch's workspace (arrival
+ * counters and partial results of units that are split over several workgroups) is a 4 MiB array
+ * inside the library, one per device, held from its first use until the process ends.  The call
+ * allocates nothing and frees nothing; its first call on a device looks up the array's address once.
+ *   arguments : as kvq_decode_attention, without workspace and workspace_bytes; `stream` must be a
+ *               stream of the current device
+ *   limit     : kvq_decode_workspace_bytes(cfg, 1) <= 4 MiB (4 194 304), else KVQ_ERR_SCRATCH and
+ *               nothing is launched
+ * The result equals kvq_decode_attention's bit for bit.  All calls on one device share the array:
+ * calls that overlap in time on one device (different streams, different threads) race on it; calls
+ * on one stream, or otherwise ordered, do not.  What must start at zero (the counters) is cleared by
+ * the call itself, with a small fill kernel ahead of the decode launch when a unit is split.
+ */
+int32_t kvq_decode_attention_static(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qcache,
+                                    int32_t n_quant, kvq_residual res, int32_t res_start, int32_t n_res,
+                                    kvq_pool pool, void* out, void* stream);
 
 /*
  * How kvq_decode_attention (and its variants) would split a launch, host only: the quantized tokens

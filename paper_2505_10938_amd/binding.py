@@ -14,14 +14,14 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libkvq.so")
 
-KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH = 0, -1, -2, -3, -4
+KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH, KVQ_ERR_SCRATCH = 0, -1, -2, -3, -4, -5
 
 INTERFACE_VERSION = 2       # kvq_version() of the library these structures and signatures match
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
            "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_prefill_quantize_seq", "kvq_decode_attention",
            "kvq_append_decode_attention", "kvq_append_trace_quantize_ragged", "kvq_seq_advance",
            "kvq_decode_attention_ragged", "kvq_decode_attention_multi", "kvq_decode_workspace_bytes",
-           "kvq_decode_launch_shape", "kvq_dequantize", "kvq_stream_read",
+           "kvq_decode_launch_shape", "kvq_decode_attention_static", "kvq_dequantize", "kvq_stream_read",
            "kvq_status_string", "kvq_version"]
 
 
@@ -97,6 +97,8 @@ def load_library() -> C.CDLL:
     lib.kvq_decode_attention.restype = i32
     lib.kvq_decode_attention.argtypes = [cfgp, i32, vp, kvq_qcache, i32, kvq_residual, i32, i32, kvq_pool,
                                          vp, vp, C.c_size_t, vp]
+    lib.kvq_decode_attention_static.restype = i32
+    lib.kvq_decode_attention_static.argtypes = [cfgp, i32, vp, kvq_qcache, i32, kvq_residual, i32, i32, kvq_pool, vp, vp]
     lib.kvq_append_decode_attention.restype = i32
     lib.kvq_append_decode_attention.argtypes = [cfgp, i32, vp, vp, vp, kvq_qcache, i32, kvq_residual, i32, i32, kvq_pool,
                                                 vp, vp, C.c_size_t, vp]
@@ -206,6 +208,14 @@ def kvq_decode_workspace_bytes(cfg, q_tokens) -> int:
     if n < 0:
         raise KvqError(int(n), "kvq_decode_workspace_bytes")
     return int(n)
+
+
+def kvq_decode_attention_static(cfg, layer, q, qcache: kvq_qcache, n_quant, res: kvq_residual, res_start, n_res,
+                                pool: kvq_pool, out, stream=None):
+    st = load_library().kvq_decode_attention_static(C.byref(cfg), layer, _ptr(q), qcache, n_quant, res, res_start,
+                                                    n_res, pool, _ptr(out), _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_decode_attention_static")
 
 
 def kvq_decode_launch_shape(cfg, q_tokens, n_quant, fp_rows):

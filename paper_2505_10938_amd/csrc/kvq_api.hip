@@ -1,6 +1,8 @@
 // Host side of the C ABI: argument validation, buffer sizes, launches.
 #include "kvq_common.h"
 
+#include <mutex>
+
 namespace {
 
 using kvq::Dims;
@@ -166,6 +168,7 @@ const char* kvq_status_string(int32_t status) {
     case KVQ_ERR_UNSUPPORTED: return "configuration not supported by this build";
     case KVQ_ERR_WORKSPACE: return "workspace too small";
     case KVQ_ERR_LAUNCH: return "HIP launch failed";
+    case KVQ_ERR_SCRATCH: return "problem too large for the library's static scratch buffer";
     default: return "unknown status";
   }
 }
@@ -380,6 +383,35 @@ int32_t kvq_seq_advance(const kvq_config* cfg, int32_t* seq_state, void* stream)
 
 namespace {
 
+// Scratch of kvq_decode_attention_static: the decode launch's workspace (arrival counters, partial
+// results) for callers that cannot hand one over.  One array per device, held until the process ends;
+// its device address is looked up once per device and kept.  In host code the array's NAME is not
+// a device address: only the looked-up pointer is ever passed to a kernel.
+constexpr size_t kScratchBytes = 4u << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int32_t scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KVQ_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return KVQ_ERR_LAUNCH;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return KVQ_OK;
+}
+
+// (a fill kernel and not a memset: a memset node in a captured graph has replayed wrongly on this stack)
+__global__ void zero_words_kernel(uint32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
 // The decode launch, shared by the two entry points: `seq_state` null = every sequence has the
 // state given; otherwise n_quant and n_res are upper bounds and each sequence brings its own.
 // Workspace of a decode launch whose kv heads have `rows` query rows each (rows = query heads per kv
@@ -397,7 +429,7 @@ int64_t decode_workspace_bytes(const kvq_config* cfg, int64_t rows) {
 int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, int32_t q_tokens, kvq_qcache qc,
                       int32_t n_quant, kvq_residual res, int32_t res_start, int32_t n_res, const int32_t* seq_state,
                       const void* k_new, const void* v_new, kvq_pool pool, void* out, void* workspace,
-                      size_t workspace_bytes, void* stream) {
+                      size_t workspace_bytes, void* stream, bool static_scratch = false) {
   const int32_t st = check_config(cfg);
   if (st != KVQ_OK) return st;
   if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
@@ -430,6 +462,12 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, int32
   if (!pool.pool_count || !pool.aux_count) return KVQ_ERR_INVALID_ARG;
   // every pool slot is read, filled or not, so the rows must exist whenever there are slots
   if (cfg->outlier_budget + cfg->aux_capacity > 0 && (!pool.pool_k || !pool.pool_v)) return KVQ_ERR_INVALID_ARG;
+  if (static_scratch) {                                  // the library's own array stands in for the workspace
+    if (decode_workspace_bytes(cfg, qrows) > (int64_t)kScratchBytes) return KVQ_ERR_SCRATCH;
+    const int32_t got = scratch_of_current_device(&workspace);
+    if (got != KVQ_OK) return got;
+    workspace_bytes = kScratchBytes;
+  }
   if (!workspace || ((uintptr_t)workspace & 255) != 0) return KVQ_ERR_WORKSPACE;
   if ((int64_t)workspace_bytes < decode_workspace_bytes(cfg, qrows)) return KVQ_ERR_WORKSPACE;
 
@@ -464,6 +502,14 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, int32
   a.splits = sp.splits;
   a.nw = sp.nw;
   a.mc_per_split = sp.mc_per_split;
+  if (static_scratch && sp.splits > 1) {
+    // The array is shared by every call on this device, whatever its shape: where this launch keeps its
+    // arrival counters an earlier one may have left partial results.  They must start at zero.
+    const int words = (int)(kCounterBytes((int64_t)a.d.units_per_layer * a.head_parts) / 4);
+    hipLaunchKernelGGL(zero_words_kernel, dim3((words + 255) / 256), dim3(256), 0, (hipStream_t)stream,
+                       (uint32_t*)workspace, words);
+    if (hipGetLastError() != hipSuccess) return KVQ_ERR_LAUNCH;
+  }
   return from_hip(kvq::launch_decode(a, (hipStream_t)stream));
 }
 
@@ -474,6 +520,13 @@ int32_t kvq_decode_attention(const kvq_config* cfg, int32_t layer, const void* q
                              void* workspace, size_t workspace_bytes, void* stream) {
   return decode_common(cfg, layer, q, 1, qc, n_quant, res, res_start, n_res, nullptr, nullptr, nullptr, pool, out,
                        workspace, workspace_bytes, stream);
+}
+
+int32_t kvq_decode_attention_static(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc, int32_t n_quant,
+                                    kvq_residual res, int32_t res_start, int32_t n_res, kvq_pool pool, void* out,
+                                    void* stream) {
+  return decode_common(cfg, layer, q, 1, qc, n_quant, res, res_start, n_res, nullptr, nullptr, nullptr, pool, out,
+                       nullptr, 0, stream, true);
 }
 
 int64_t kvq_decode_workspace_bytes(const kvq_config* cfg, int32_t q_tokens) {
