@@ -207,12 +207,15 @@ int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_i
  *   q        : device fp16 [batch][q_heads][head_dim], 16-byte aligned (as must be the code arrays,
  *              the residual ring and the pool rows; steps/zeros and mask words 4-byte aligned)
  *   n_quant  : multiple of G, <= max_seq
- *   res_start, n_res : live part of the residual ring, n_res <= res_rows;
- *              n_quant + n_res >= 1
+ *   res_start, n_res : live part of the residual ring, n_res <= res_rows; res_start a multiple of 16
+ *              (it is a multiple of group_k under the schedule of kvq_append_trace_quantize): the
+ *              residual rows are read 16 at a time, and such a run must not wrap; n_quant + n_res >= 1
  *   qcache   : all five arrays must be valid device memory of the sizes kvq_query_sizes gives, also
  *              when n_quant == 0: every workgroup loads a first block whether or not it has quantized
  *              tokens to work on.  Likewise pool.pool_k / pool_v whenever outlier_budget +
- *              aux_capacity > 0 (every slot is loaded, filled or not) and pool_count, aux_count
+ *              aux_capacity > 0 (every slot is loaded, filled or not, 16 slots at a time: up to 15 rows
+ *              past a unit's last slot are read, never used; kvq_sizes.pool_rows_bytes includes those
+ *              15 rows behind the last unit) and pool_count, aux_count
  *   Range    : the products run on fp16 operands with fp32 accumulation.  Results are finite and within
  *              2e-3 (absolute, for outputs of order 1) of the exact attention over the dequantized
  *              cache while |q_c| * step_c < 32 000 for every channel c and Key group
@@ -423,7 +426,7 @@ int32_t kvq_stream_read(const void* buf, size_t bytes, void* sink, void* stream)
 /* Static string for a kvq_status value. */
 const char* kvq_status_string(int32_t status);
 
-/* Version of this interface (structure layouts and entry points), for the binding's load check: 2. */
+/* Version of this interface (structure layouts and entry points), for the binding's load check: 3. */
 int32_t kvq_version(void);
 
 #ifdef __cplusplus

@@ -70,6 +70,7 @@ WORKLOADS["llama2_7b_4k_g128"] = WORKLOADS["llama2_7b_4k"].with_(name="llama2_7b
 WORKLOADS["llama2_7b_4k_4bit"] = WORKLOADS["llama2_7b_4k"].with_(name="llama2_7b_4k_4bit", bits=4)
 WORKLOADS["llama3_8b_4k_gqa"] = WORKLOADS["llama2_7b_4k"].with_(name="llama3_8b_4k_gqa", batch=32, kv_heads=8)
 WORKLOADS["llama2_7b_4k_b1"] = WORKLOADS["llama2_7b_4k"].with_(name="llama2_7b_4k_b1", batch=1)
+WORKLOADS["mistral_7b_b128_4k_4bit"] = WORKLOADS["mistral_7b_b128_4k"].with_(name="mistral_7b_b128_4k_4bit", bits=4)
 # One of the 32 identical layers of the fourth configuration (a decode step over the stack is 32
 # such launches on 32 such caches), 2-bit and 4-bit.
 WORKLOADS["mistral_7b_b128_4k_layer"] = WORKLOADS["mistral_7b_b128_4k"].with_(name="mistral_7b_b128_4k_layer", layers=1)

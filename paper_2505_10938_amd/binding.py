@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(HERE, "libkvq.so")
 
 KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH, KVQ_ERR_SCRATCH = 0, -1, -2, -3, -4, -5
 
-INTERFACE_VERSION = 2       # kvq_version() of the library these structures and signatures match
+INTERFACE_VERSION = 3       # kvq_version() of the library these structures and signatures match
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
            "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_prefill_quantize_seq", "kvq_decode_attention",
            "kvq_append_decode_attention", "kvq_append_trace_quantize_ragged", "kvq_seq_advance",

@@ -152,7 +152,7 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restric
 
 extern "C" {
 
-int32_t kvq_version(void) { return 2; }
+int32_t kvq_version(void) { return 3; }
 
 int32_t kvq_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {
   if (!buf || !sink || bytes == 0 || bytes % 16 != 0 || ((uintptr_t)buf & 15) != 0) return KVQ_ERR_INVALID_ARG;
@@ -191,7 +191,8 @@ int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out) {
   out->v_meta_bytes = units * cfg->max_seq * (hd / cfg->group_v) * 4;
   out->mask_bytes = units * (cfg->max_seq / 32) * 4;
   out->res_bytes = units * out->res_rows * hd * 2;
-  out->pool_rows_bytes = units * slots * hd * 2;
+  // the decode kernel reads the pool slots 16 at a time: up to 15 rows past the last unit's last slot
+  out->pool_rows_bytes = slots > 0 ? (units * slots + 15) * hd * 2 : 0;
   out->pool_idx_bytes = units * slots * 4;
   out->pool_score_bytes = units * slots * 8;
   out->counter_bytes = units * 4;
@@ -449,6 +450,7 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, int32
   if (n_quant < 0 || n_quant > cfg->max_seq || n_quant % cfg->group_k != 0) return KVQ_ERR_INVALID_ARG;
   const int32_t rows = (int32_t)res_rows_of(cfg);
   if (n_res < 0 || n_res > rows || res_start < 0 || res_start >= rows) return KVQ_ERR_INVALID_ARG;
+  if (res_start % 16 != 0) return KVQ_ERR_INVALID_ARG;     // residual rows are read 16 at a time, without wrapping
   if (n_quant + n_res + (k_new ? 1 : 0) < 1) return KVQ_ERR_INVALID_ARG;
   if ((k_new != nullptr) != (v_new != nullptr)) return KVQ_ERR_INVALID_ARG;
   if (k_new) {                                          // the new token must leave the ring short of full

@@ -113,6 +113,29 @@ KVQ_WAVE_REDUCE(wave_sum, "v_add_f32_dpp")
   }
 KVQ_WAVE_REDUCE8(wave_max)
 KVQ_WAVE_REDUCE8(wave_sum)
+// The same inside each row of 16 lanes only (the first four steps): every lane of a row ends up with the
+// row's result (the mirrors stand for lane ^ 4 and lane ^ 8 because by then the lanes of a half hold the
+// same partial result), which needs no broadcast.
+#define KVQ_DPP_ROW(STEP, OP) STEP(OP, KVQ_DPP_CTRL0) STEP(OP, KVQ_DPP_CTRL1) STEP(OP, KVQ_DPP_CTRL2) STEP(OP, KVQ_DPP_CTRL3)
+#define KVQ_ROW_REDUCE(NAME, OP)                                                                       \
+  __device__ inline void NAME(float (&v)[1]) { asm(KVQ_DPP_ROW(KVQ_DPP_STEP1, OP) : "+v"(v[0])); }     \
+  __device__ inline void NAME(float (&v)[2]) {                                                         \
+    asm("s_nop 0\n\t" KVQ_DPP_ROW(KVQ_DPP_STEP2, OP) : "+v"(v[0]), "+v"(v[1]));                        \
+  }                                                                                                    \
+  __device__ inline void NAME(float (&v)[4]) {                                                         \
+    asm("s_nop 1\n\t" KVQ_DPP_ROW(KVQ_DPP_STEP4, OP) : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3])); \
+  }                                                                                                    \
+  __device__ inline void NAME(float (&v)[8]) {                                                         \
+    float a[4] = {v[0], v[1], v[2], v[3]}, b[4] = {v[4], v[5], v[6], v[7]};                            \
+    NAME(a);                                                                                           \
+    NAME(b);                                                                                           \
+    for (int i = 0; i < 4; ++i) {                                                                      \
+      v[i] = a[i];                                                                                     \
+      v[4 + i] = b[i];                                                                                 \
+    }                                                                                                  \
+  }
+KVQ_ROW_REDUCE(row16_max, "v_max_f32_dpp")
+KVQ_ROW_REDUCE(row16_sum, "v_add_f32_dpp")
 
 // fp16 hi/lo split of two floats: hi = fp16(x), lo = fp16(x - hi), both rounded to nearest, so that
 // hi + lo = x (1 + e) with |e| <= 2^-22 and no bias (truncating hi instead leaves 2^-21, one-sided);
@@ -558,67 +581,89 @@ struct Seq {
 };
 
 struct FpRegs {
-  uint4 kf[4];       // K row of token row0 + (lane & 15): channels 32cb + 8(lane >> 4) ..
+  uint4 kf[4];       // K row of token first + (lane & 15): channels 32cb + 8(lane >> 4) ..
   uint32_t vw[16];   // V rows of the 16 tokens: this lane's channel pair
-  int row0;
+  int group;
 };
 
-// Issue the loads of one group of 16 full-precision rows.  Every pool slot is read, filled or
-// not (the slot counts are looked at only when the data is used, so that these loads do not wait
-// for them); a row past the last slot reads the query row instead (always valid memory).
-__device__ __forceinline__ void fp_load(FpRegs& X, const DecodeArgs& a, const Seq& sq, int64_t u, const __half* qbase,
-                                        int row0, int lane) {
-  const Dims& d = a.d;
-  const int m16 = lane & 15, r = lane >> 4;
-  const int64_t new_off = (u - d.unit0) * kHeadDim;                // the unit's row of k_new / v_new
-  const __half* kres = a.k_res + u * d.res_rows * kHeadDim;
-  const __half* vres = a.v_res + u * d.res_rows * kHeadDim;
-  const __half* kpool = a.pool_k + u * d.pool_slots * kHeadDim;
-  const __half* vpool = a.pool_v + u * d.pool_slots * kHeadDim;
-  auto locate = [&](int row, const __half*& kp, const __half*& vp) {
-    const bool in_res = row < sq.n_res;
-    int ring = sq.res_start + row;
-    ring -= ring >= d.res_rows ? d.res_rows : 0;
-    const int slot = row - sq.n_res;
-    const bool in_pool = slot < d.pool_slots;
-    const bool in_ring = row < sq.n_ring;
-    kp = in_ring ? kres + ring * kHeadDim : in_res ? a.k_new + new_off : (in_pool ? kpool + slot * kHeadDim : qbase);
-    vp = in_ring ? vres + ring * kHeadDim : in_res ? a.v_new + new_off : (in_pool ? vpool + slot * kHeadDim : qbase);
-  };
-  X.row0 = row0;
-  const __half *kp, *vp_unused;
-  locate(row0 + m16, kp, vp_unused);
-#pragma unroll
-  for (int cb = 0; cb < 4; ++cb) X.kf[cb] = ld<uint4>((const unsigned char*)(kp + cb * 32 + r * 8), 0u);
-#pragma unroll
-  for (int t = 0; t < 16; ++t) {
-    const __half *kp_unused, *vp;
-    locate(row0 + t, kp_unused, vp);                               // uniform over the wave
-    X.vw[t] = ld<uint32_t>((const unsigned char*)vp, lane * 4u);
-  }
+// The full-precision rows of a unit, in groups of 16 that are each one contiguous run of rows in memory,
+// so that a group is loaded from one base address with constant offsets (no work per row):
+//   groups 0 .. ring_groups-1 : the residual tokens in ring order, 16 per group.  The ring starts at a
+//       multiple of 16 and has a multiple of 16 rows, so a group never wraps; the last group may reach past
+//       the newest token (those rows are ring rows that hold no live token and are masked).  The token
+//       being decoded, if it comes with the call, is the newest of them: its ring row is not written yet,
+//       its Key row is read from the caller's buffer by the lanes that own it and its Value words are put
+//       in place from the registers every wavefront has loaded them into.
+//   then pool_groups groups  : the outlier-pool and auxiliary-pool slots, 16 per group; the last group may
+//       reach up to 15 rows past the unit's last slot (the next unit's slots, or the padding behind the
+//       last unit's: kvq_query_sizes counts it), masked as well.
+struct FpLayout {
+  int ring_groups, pool_groups;
+  int new_group, new_t;    // where the token being decoded sits (new_group < 0: it does not come with the call)
+  __device__ __forceinline__ int groups() const { return ring_groups + pool_groups; }
+};
+__device__ __forceinline__ FpLayout fp_layout(const DecodeArgs& a, const Seq& sq) {
+  FpLayout f;
+  f.ring_groups = (sq.n_res + 15) >> 4;
+  f.pool_groups = (a.d.pool_slots + 15) >> 4;
+  f.new_group = sq.n_res > sq.n_ring ? sq.n_ring >> 4 : -1;
+  f.new_t = sq.n_ring & 15;
+  return f;
 }
 
-// Does full-precision row `row` of the unit hold a token?
-__device__ __forceinline__ bool fp_row_ok(const DecodeArgs& a, const Seq& sq, int row, int n_pool, int n_aux) {
-  const int slot = row - sq.n_res;
-  return row < sq.n_res || (slot < a.d.N ? (slot < n_pool) : (slot < a.d.pool_slots && slot - a.d.N < n_aux));
+// Issue the loads of group g (a wavefront without a group passes one that exists: the same loads are then
+// in flight on every path; the ring always has a first group of 16 rows).  Every pool slot is read, filled or
+// not: the slot counts are looked at only when the data is used, so that these loads do not wait for them.
+__device__ __forceinline__ void fp_load(FpRegs& X, const DecodeArgs& a, const Seq& sq, const FpLayout& f, int64_t u,
+                                        const __half* k_new_row, int g, int lane) {
+  const Dims& d = a.d;
+  const int m16 = lane & 15, r = lane >> 4;
+  const bool is_ring = g < f.ring_groups;                            // uniform
+  int ring0 = sq.res_start + 16 * (is_ring ? g : 0);
+  ring0 -= ring0 >= d.res_rows ? d.res_rows : 0;
+  const int slot0 = 16 * (g - f.ring_groups);
+  const int64_t row0 = is_ring ? u * d.res_rows + ring0 : u * d.pool_slots + slot0;
+  const unsigned char* kb = (const unsigned char*)((is_ring ? a.k_res : a.pool_k) + row0 * kHeadDim);
+  const unsigned char* vb = (const unsigned char*)((is_ring ? a.v_res : a.pool_v) + row0 * kHeadDim);
+  X.group = g;
+  // Keys: lane (row m16, quarter r) reads its 16 bytes of each 64-byte run of its row
+  const bool is_new = g == f.new_group && m16 == f.new_t;
+  const unsigned char* kp = is_new ? (const unsigned char*)k_new_row + r * 16 : kb + m16 * (2 * kHeadDim) + r * 16;
+#pragma unroll
+  for (int cb = 0; cb < 4; ++cb) X.kf[cb] = ld<uint4>(kp, cb * 64u);
+  // Values: every lane its channel pair of each of the 16 rows
+  const unsigned char* vp = vb + lane * 4;
+#pragma unroll
+  for (int t = 0; t < 16; ++t) X.vw[t] = ld<uint32_t>(vp, t * (2u * kHeadDim));
+}
+
+// Does row m16 of group g hold a token?
+__device__ __forceinline__ bool fp_row_ok(const DecodeArgs& a, const Seq& sq, const FpLayout& f, int g, int m16,
+                                          int n_pool, int n_aux) {
+  if (g < f.ring_groups) return 16 * g + m16 < sq.n_res;
+  const int slot = 16 * (g - f.ring_groups) + m16;
+  return slot < a.d.N ? (slot < n_pool) : (slot < a.d.pool_slots && slot - a.d.N < n_aux);
 }
 
 template <int GQ, int NV>
-__device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, NV>& L, const DecodeArgs& a,
-                                           const Seq& sq, int n_pool, int n_aux, int r0, int lane) {
+__device__ __forceinline__ void fp_compute(FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, NV>& L, const DecodeArgs& a,
+                                           const Seq& sq, const FpLayout& f, int n_pool, int n_aux, int r0,
+                                           uint32_t v_new_word, int lane) {
   const int m16 = lane & 15, r = lane >> 4;
-  const bool okk = fp_row_ok(a, sq, X.row0 + m16, n_pool, n_aux);
+  const bool okk = fp_row_ok(a, sq, f, X.group, m16, n_pool, n_aux);
+  if (X.group == f.new_group) {                                    // uniform, one group of the unit
+#pragma unroll
+    for (int t = 0; t < 16; ++t) X.vw[t] = t == f.new_t ? v_new_word : X.vw[t];
+  }
   // Several query tokens at once: token i of q_tokens does not see the q_tokens - 1 - i tokens after it,
   // which are the newest residual rows (one query token: nothing is hidden).  Row j of this workgroup
   // belongs to token (r0 + j) >> g_shift.
   auto seen_by = [&](int j) {
     const int after = a.q_tokens - 1 - ((r0 + j) >> a.g_shift);
-    const int row = X.row0 + m16;
-    return okk && !(row < sq.n_res && row >= sq.n_res - after);
+    const int row = 16 * X.group + m16;                              // its place among the residual tokens
+    return okk && !(X.group < f.ring_groups && row >= sq.n_res - after);
   };
-  // which of the 16 rows hold a token, as a wave-uniform bit mask (lanes 0..15 are rows 0..15):
-  // asking row by row costs some 25 scalar instructions per row
+  // which of the 16 rows hold a token, as a wave-uniform bit mask (lanes 0..15 are rows 0..15)
   const uint32_t ok_rows = (uint32_t)__ballot(okk) & 0xFFFFu;
   constexpr int R2 = 2 * GQ;
   const int arow = m16 % R2;
@@ -630,21 +675,27 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
   wave_sync();                                                     // earlier readers of sc are done
   if (2 * r < GQ) L.sc()[2 * r][m16] = seen_by(2 * r) ? D[0] + D[1] : kNegBig;
   if (2 * r + 1 < GQ) L.sc()[(2 * r + 1) % GQ][m16] = seen_by(2 * r + 1) ? D[2] + D[3] : kNegBig;
+  // a row that holds no token may hold anything, a NaN too: its Value words are cleared (most groups are
+  // full: one uniform test)
+  if (ok_rows != 0xFFFFu) {
+#pragma unroll
+    for (int t = 0; t < 16; ++t) X.vw[t] = ((ok_rows >> t) & 1u) ? X.vw[t] : 0u;
+  }
   wave_sync();
   float alpha[GQ], x[GQ], red[GQ];
 #pragma unroll
-  for (int j = 0; j < GQ; ++j) red[j] = x[j] = L.sc()[j][lane & 15];   // every lane: the 16 scores, 4 times over
-  wave_max(red);
+  for (int j = 0; j < GQ; ++j) red[j] = x[j] = L.sc()[j][m16];      // every row of 16 lanes: the 16 scores
+  row16_max(red);
 #pragma unroll
   for (int j = 0; j < GQ; ++j) {
     const float m = fmaxf(F.m[j], red[j]);
     alpha[j] = __builtin_amdgcn_exp2f(F.m[j] - m);
     F.m[j] = m;
     x[j] = x[j] > 0.5f * kNegBig ? __builtin_amdgcn_exp2f(x[j] - m) : 0.f;   // now p
-    red[j] = lane < 16 ? x[j] : 0.f;
+    red[j] = x[j];
     if (lane < 16) L.sc()[j][16 + lane] = x[j];
   }
-  wave_sum(red);
+  row16_sum(red);
 #pragma unroll
   for (int j = 0; j < GQ; ++j) F.l[j] = F.l[j] * alpha[j] + red[j];
   wave_sync();
@@ -653,10 +704,10 @@ __device__ __forceinline__ void fp_compute(const FpRegs& X, FpAcc<GQ>& F, WaveLd
     F.o[j][0] *= alpha[j];
     F.o[j][1] *= alpha[j];
   }
+  // (newest row first: loads return in order, so the wait for the last row's word covers all of them)
 #pragma unroll
-  for (int t = 0; t < 16; ++t) {
-    const uint32_t vw = ((ok_rows >> t) & 1u) ? X.vw[t] : 0u;     // uniform; an empty slot may hold anything
-    const float v0 = h2f_bits(vw & 0xFFFFu), v1 = h2f_bits(vw >> 16);
+  for (int t = 15; t >= 0; --t) {
+    const float v0 = h2f_bits(X.vw[t] & 0xFFFFu), v1 = h2f_bits(X.vw[t] >> 16);
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
       const float p = L.sc()[j][16 + t];
@@ -718,7 +769,7 @@ decode_kernel(DecodeArgs a) {
   if (a.seq) {
     const int4 own = *(const int4*)(a.seq + 4 * b);        // uniform: one scalar load
     sq.n_quant = min(max(own.x, 0), a.n_quant) & ~(kBlockTokens - 1);
-    sq.res_start = (own.y >= 0 && own.y < d.res_rows) ? own.y : 0;
+    sq.res_start = (own.y >= 0 && own.y < d.res_rows) ? own.y & ~15 : 0;   // (a row group of 16 must not wrap)
     sq.n_res = min(max(own.z, 0), a.n_res);
     sq.n_ring = sq.n_res;
   }
@@ -755,8 +806,8 @@ decode_kernel(DecodeArgs a) {
 
   // full-precision row groups go to the unit's wavefronts from the last one backwards (the
   // first wavefronts of a workgroup are the ones that may hold one more mini-chunk)
-  const int fp_rows = sq.n_res + d.pool_slots;
-  const int n_rg = (fp_rows + 15) >> 4;
+  const FpLayout fl = fp_layout(a, sq);
+  const int n_rg = fl.groups();
   const int unit_waves = n_splits * nw;
   int rg = unit_waves - 1 - (split * nw + wave);
   const bool has_fp = rg < n_rg;                         // uniform over the wave
@@ -764,15 +815,17 @@ decode_kernel(DecodeArgs a) {
   // a scalar load in flight would hold up the next wait on the scalar side, which comes before
   // the quantized loads below.
   // Every wavefront issues the same loads, whether or not it has rows or a mini-chunk to work on
-  // (the loaders fall back on addresses that are always valid: the query row, the unit's last
-  // block): only then are the loads in flight the same on every path, and only then can the
+  // (a wavefront without a row group loads the unit's first one, one without a mini-chunk the unit's
+  // last block): only then are the loads in flight the same on every path, and only then can the
   // waits leave the younger ones in flight.
   FpRegs X;
   int64_t uv = u;
   asm("" : "+v"(uv));                                    // a vector address: a vector load
   int n_pool = a.pool_count[uv];
   int n_aux = a.aux_count[uv];
-  fp_load(X, a, sq, u, qbase, rg * 16, lane);
+  if (n_rg > 0) {                                        // (no residual token and no pool slot at all: nothing to load)
+    fp_load(X, a, sq, fl, u, k_new_row, has_fp ? rg : 0, lane);
+  }
 
   // Quantized arrays: a dense cache keeps the blocks of unit u together, a paged one those of the
   // plane (layer, kv head); there d.blocks_per_unit and d.groups_per_unit are the plane's.
@@ -819,10 +872,10 @@ decode_kernel(DecodeArgs a) {
   if (has_fp) {
     n_pool = __builtin_amdgcn_readfirstlane(n_pool);
     n_aux = __builtin_amdgcn_readfirstlane(n_aux);
-    fp_compute<GQ, NV>(X, F, L, a, sq, n_pool, n_aux, r0, lane);
-    for (rg += unit_waves; rg < n_rg; rg += unit_waves) {          // further groups (short quantized segment)
-      fp_load(X, a, sq, u, qbase, rg * 16, lane);
-      fp_compute<GQ, NV>(X, F, L, a, sq, n_pool, n_aux, r0, lane);
+    fp_compute<GQ, NV>(X, F, L, a, sq, fl, n_pool, n_aux, r0, v_new_word, lane);
+    for (rg += unit_waves; rg < n_rg; rg += unit_waves) {          // the wavefront's further groups
+      fp_load(X, a, sq, fl, u, k_new_row, rg, lane);
+      fp_compute<GQ, NV>(X, F, L, a, sq, fl, n_pool, n_aux, r0, v_new_word, lane);
     }
   }
 
