@@ -488,7 +488,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
 #pragma unroll
     for (int jv = 0; jv < NV; ++jv) vs[jv] = as_half2(R.vsp[jv]) * half2v{fv, fv};
     float alpha[GQ], x0[GQ], x1[GQ], mx[GQ];
-    bool rescale = false;
+    bool above = false;                                 // does a score here exceed its head's running maximum?
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
       const float2 s2 = *(const float2*)&L.sc()[j][2 * lane];
@@ -496,14 +496,24 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
       x0[j] = ok0 ? __builtin_fmaf(s2.x, post_k, qz) : kNegBig;
       x1[j] = ok1 ? __builtin_fmaf(s2.y, post_k, qz) : kNegBig;
       mx[j] = fmaxf(x0[j], x1[j]);
+      above |= mx[j] > S.m[j];
+      alpha[j] = 1.f;
     }
-    wave_max(mx);
+    // The wave-wide maxima are needed only if some score exceeds a running maximum (always in a
+    // wavefront's first mini-chunk, ever more rarely afterwards): otherwise nothing moves.
+    const bool rescale = __any(above);                  // wave-uniform
+    if (rescale) {
+      wave_max(mx);
+#pragma unroll
+      for (int j = 0; j < GQ; ++j) {
+        const float m = fmaxf(S.m[j], mx[j]);
+        alpha[j] = __builtin_amdgcn_exp2f(S.m[j] - m);
+        S.m[j] = m;
+      }
+    }
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
-      const float m = fmaxf(S.m[j], mx[j]);
-      alpha[j] = __builtin_amdgcn_exp2f(S.m[j] - m);
-      rescale |= m > S.m[j];
-      S.m[j] = m;
+      const float m = S.m[j];
       const float p0 = ok0 ? __builtin_amdgcn_exp2f(x0[j] - m) : 0.f;
       const float p1 = ok1 ? __builtin_amdgcn_exp2f(x1[j] - m) : 0.f;
       uint32_t hi, lo;
