@@ -33,7 +33,7 @@ DEFAULT_WORKLOAD = "mistral_7b_b128_4k"
 # HBM bytes per decode launch from the FETCH_SIZE / WRITE_SIZE counters, scaled by what the same counters
 # read for a plain device copy of known size; recorded values (profiles/decode_kernel_<workload>.md), the
 # benchmark itself does not read hardware counters.
-RECORDED_TRAFFIC = {}
+RECORDED_TRAFFIC = {"mistral_7b_b128_4k": 488_200_000, "llama2_7b_4k": 120_440_000}
 PAPER_CONTEXT = ("the paper reports 6.4x lower peak memory (A100 40G) and up to 2.3x end-to-end decoding throughput "
                  "(A800 80G) against fp16 for LLaMA-2-7B, no kernel-level figure")
 
