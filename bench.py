@@ -171,10 +171,6 @@ def run_stack(w, layers, steps, warmup, samples, pool, cpu_budget, label):
                          w.aux_capacity, w.head_dim)
     t_setup = time.time()
     jobs = None
-    if pool is not None and samples:
-        wd = {f: getattr(w, f) for f in w.__dataclass_fields__}
-        jobs = pool.map_async(_oracle_job, [dict(workload=wd, layer=l, b=b, h=h, n0=n0, n_steps=total,
-                                                 budget=cpu_budget) for (l, b, h) in samples], chunksize=1)
     cache = KC.KVCache(cfg, device=dev)
     synth = DeviceSynth(w, dev)
     by_layer = {}
@@ -248,8 +244,13 @@ def run_stack(w, layers, steps, warmup, samples, pool, cpu_budget, label):
     if grp_steps:
         res["group_step_ms"] = sum(step_ms[i] for i in grp_steps) / len(grp_steps)
         res["plain_step_ms"] = sum(step_ms[i] for i in plain) / len(plain)
-    if jobs is not None:
+    if pool is not None and samples:
+        # the oracle's processes start only now: while they run they take every host core, and the launches
+        # of the timed region above must not wait for the host
         got1 = out.cpu().numpy().astype(np.float64)
+        wd = {f: getattr(w, f) for f in w.__dataclass_fields__}
+        jobs = pool.map_async(_oracle_job, [dict(workload=wd, layer=l, b=b, h=h, n0=n0, n_steps=total,
+                                                 budget=cpu_budget) for (l, b, h) in samples], chunksize=1)
         results = jobs.get()
         from tests import helpers as H
         stats = H.AttStats()
