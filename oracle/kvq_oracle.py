@@ -24,6 +24,10 @@ What follows the paper, by passage:
   tokens" (Method, "Quantization").
 * `decode_attention`                - Eq. 1 over the three cache kinds (Method,
   "Decoding").
+* `PerStepValueUnit`                - the other schedule the paper measures itself
+  against (Experiments, "Details": the Keys are compressed every G steps, the
+  Values at each step; Efficiency comparison: that per-step compression is what
+  the method saves).  Same quantizer, no tracing.
 
 Readings taken where the paper is silent are listed in the repository's design
 document; each is also stated at the function that implements it.
@@ -249,6 +253,97 @@ class UnitState:
 
 
 # --------------------------------------------------------------------------
+# The per-step Value schedule (the comparison schedule of Experiments, "Details")
+# --------------------------------------------------------------------------
+
+def quantize_value_rows(v_rows: np.ndarray, bits: int, group_v: int):
+    """Token-wise quantization of Value rows on their own (Eq. 2 per token and per
+    `group_v` consecutive channels: a token's groups do not involve other tokens).
+
+    v_rows: fp16 [n, hd].  Returns (codes u8 [n, hd], step fp16 [n, hd/group_v],
+    zero fp16 [n, hd/group_v], v_hat fp16 [n, hd]) where v_hat = zero + code * step
+    evaluated in fp32 (the product is exact, the sum rounds once) and rounded to
+    nearest fp16: the row as a cache that holds dequantized rows in fp16 keeps it."""
+    n, hd = v_rows.shape
+    vc, vs, vz = quantize_groups(v_rows.reshape(n, hd // group_v, group_v), bits)
+    f32 = np.float32
+    v_hat = (vz.astype(f32)[..., None] + vc.astype(f32) * vs.astype(f32)[..., None]).reshape(n, hd)
+    return vc.reshape(n, hd), vs, vz, v_hat.astype(np.float16)
+
+
+class PerStepValueUnit(UnitState):
+    """A unit whose Values are quantized at each step and whose Keys every G steps.
+
+    Reading taken (the paper only names the schedule): with n tokens in the cache,
+        Keys   : tokens below n_quant = G * floor((n - R) / G) are quantized in groups
+                 of G, exactly as in `UnitState` (same ring rule);
+        Values : tokens below n - R are quantized, token-wise, each at the step at
+                 which it leaves the window of the R most recent tokens.
+    No outlier tracing (the schedule belongs to the method without it): N = 0.
+    A token's Value codes do not depend on when they are computed, so once its Key
+    group closes the unit holds exactly what `UnitState` with N = 0 holds.  In
+    between (Keys still in full precision, Values already quantized) the token is
+    attended with its full-precision Key row and its dequantized Value row held in
+    fp16 (`quantize_value_rows`: v_hat)."""
+
+    def __init__(self, head_dim: int, bits: int, group_k: int, group_v: int):
+        super().__init__(head_dim, bits, group_k, group_v, 0, 0)
+        self.v_hat = np.zeros((0, head_dim), np.float16)    # dequantized rows, all quantized tokens
+
+    @property
+    def n_quant_v(self):
+        return self.v_codes.shape[0]
+
+    def quantize_values(self, v_rows: np.ndarray):
+        """The next tokens (in order) leave the window: quantize their Value rows."""
+        vc, vs, vz, v_hat = quantize_value_rows(v_rows, self.bits, self.Gv)
+        self.v_codes = np.concatenate([self.v_codes, vc])
+        self.v_step = np.concatenate([self.v_step, vs])
+        self.v_zero = np.concatenate([self.v_zero, vz])
+        self.v_hat = np.concatenate([self.v_hat, v_hat])
+
+    def append_key_group(self, k_group: np.ndarray):
+        """Close the next Key group: channel-wise quantization of its G rows.  Its
+        tokens' Values must already be quantized."""
+        assert self.n_quant + self.G <= self.n_quant_v, "Values of the group are quantized before its Keys"
+        kc, ks, kz = quantize_groups(np.ascontiguousarray(k_group.T), self.bits)
+        self.k_codes = np.concatenate([self.k_codes, np.ascontiguousarray(kc.T)])
+        self.k_step = np.concatenate([self.k_step, ks[None]])
+        self.k_zero = np.concatenate([self.k_zero, kz[None]])
+        self.masked = np.concatenate([self.masked, np.zeros(self.G, bool)])
+
+    def append_group(self, k_group, v_group, trace: bool = True):
+        raise TypeError("per-step schedule: use quantize_values and append_key_group")
+
+    def advance_to(self, K: np.ndarray, V: np.ndarray, n: int, residual: int):
+        """Bring the unit to the state it has with tokens 0 .. n-1 in the cache
+        (K, V: fp16 [>= n, hd], the unit's rows from token 0 on)."""
+        nv = max(0, n - residual)
+        if nv > self.n_quant_v:
+            self.quantize_values(V[self.n_quant_v:nv])
+        nk = self.G * ((n - residual) // self.G) if n >= residual + self.G else 0
+        while self.n_quant < nk:
+            self.append_key_group(K[self.n_quant:self.n_quant + self.G])
+
+    def effective_rows(self, k_res: np.ndarray, v_res: np.ndarray):
+        """k_res, v_res: the original rows of tokens n_quant .. n-1.  Tokens below
+        n_quant: dequantized Keys and Values (exact, as in `UnitState`); tokens
+        n_quant .. n_quant_v - 1: original Key row, v_hat as Value row; the rest:
+        original rows."""
+        G, nq, nqv = self.G, self.n_quant, self.n_quant_v
+        kh = dequantize(self.k_codes.reshape(-1, G, self.hd).transpose(0, 2, 1),
+                        self.k_step, self.k_zero).transpose(0, 2, 1).reshape(nq, self.hd)
+        vh = dequantize(self.v_codes[:nq].reshape(nq, self.hd // self.Gv, self.Gv),
+                        self.v_step[:nq], self.v_zero[:nq]).reshape(nq, self.hd)
+        v_tail = v_res.astype(np.float64).copy()
+        v_tail[:nqv - nq] = self.v_hat[nq:nqv].astype(np.float64)
+        return np.concatenate([kh, k_res.astype(np.float64)]), np.concatenate([vh, v_tail])
+
+    def rows_fp16(self):
+        raise TypeError("not defined for the per-step schedule")
+
+
+# --------------------------------------------------------------------------
 # Decode attention (Eq. 1)
 # --------------------------------------------------------------------------
 
@@ -353,7 +448,8 @@ def mask_words(masked: np.ndarray) -> np.ndarray:
 
 
 def packed_unit(state: UnitState):
-    """Packed image of one unit's quantized cache, as the HIP path must produce it."""
+    """Packed image of one unit's quantized cache, as the HIP path must produce it (the tokens
+    below n_quant: a per-step unit's further Value tokens are not part of it)."""
     nb = state.n_quant // 32
     kc = np.stack([pack_k_block(state.k_codes[32 * i:32 * i + 32], state.bits) for i in range(nb)]) \
         if nb else np.zeros((0, 512 * state.bits), np.uint8)
@@ -361,5 +457,5 @@ def packed_unit(state: UnitState):
         if nb else np.zeros((0, 512 * state.bits), np.uint8)
     return dict(k_codes=kc, v_codes=vc,
                 k_meta=pack_k_meta(state.k_step, state.k_zero),
-                v_meta=pack_v_meta(state.v_step, state.v_zero),
+                v_meta=pack_v_meta(state.v_step[:state.n_quant], state.v_zero[:state.n_quant]),
                 mask=mask_words(state.masked))
