@@ -145,9 +145,10 @@ class DeviceSynth:
         return K.to(torch.float16), V.to(torch.float16)
 
 
-def run_stack(w, layers, steps, warmup, samples, pool, cpu_budget, label):
+def run_stack(w, layers, steps, warmup, samples, pool, cpu_budget, label, value_per_step=0):
     """Consecutive decode steps over `layers` layer caches of workload w.  `samples`: (layer, b, h) units
-    drawn on the host and checked against the oracle (through `pool`, a multiprocessing pool, or None)."""
+    drawn on the host and checked against the oracle (through `pool`, a multiprocessing pool, or None).
+    `value_per_step`: the schedule that quantizes Values at each step (needs a workload without tracing)."""
     import numpy as np
     import torch
     import kvq_synth as S
@@ -166,9 +167,9 @@ def run_stack(w, layers, steps, warmup, samples, pool, cpu_budget, label):
     n_res0 = R + (G - 1 - fill_at) % G
     n0 = nq0 + n_res0
     assert nq0 >= 0 and n_res0 + fill_at % G + 1 == R + G
-    max_seq = max(G, nq_final)
+    max_seq = max(G, nq_final) + (G if value_per_step else 0)   # Values are quantized up to G - 1 tokens ahead of the Keys
     cfg = KC.make_config(layers, w.batch, w.q_heads, w.kv_heads, max_seq, w.bits, G, w.group_v, R, w.outlier_budget,
-                         w.aux_capacity, w.head_dim)
+                         w.aux_capacity, w.head_dim, value_per_step=value_per_step)
     t_setup = time.time()
     jobs = None
     cache = KC.KVCache(cfg, device=dev)
@@ -472,6 +473,25 @@ def main():
         if w.name == DEFAULT_WORKLOAD:                         # the single-layer MHA configuration, on copies
             w2 = S.WORKLOADS["llama2_7b_4k"]
             extras.append((w2, copies_for(w2)))
+            # The two schedules the paper sets side by side (Experiments, "Details"; Efficiency comparison): Keys and
+            # Values quantized together every G steps, against Values quantized at each step.  Same stack, same
+            # data, no tracing in either (the per-step schedule is the one of the method without it).
+            w0 = w.with_(name=w.name + "_no_tracing", outlier_budget=0, aux_capacity=0)
+            ab = {}
+            for key, vps in (("every_G_steps", 0), ("values_at_each_step", 1)):
+                r = run_stack(w0, w.layers, args.steps, args.warmup, [], None, 0.0, key, value_per_step=vps)
+                ab[key] = {"ms_per_step": round(r["ms_per_step"], 5), "tokens_per_s": round(r["tokens_per_s"], 1),
+                           "step_without_group_quantize_ms": round(r.get("plain_step_ms", 0.0), 4),
+                           "step_with_group_quantize_ms": round(r.get("group_step_ms", 0.0), 4),
+                           "launches_per_layer_and_plain_step": 1 + vps}
+            ab["slowdown_of_values_at_each_step"] = round(ab["values_at_each_step"]["ms_per_step"]
+                                                          / ab["every_G_steps"]["ms_per_step"], 4)
+            ab["value_launch_us_per_layer_and_step"] = round(
+                (ab["values_at_each_step"]["step_without_group_quantize_ms"]
+                 - ab["every_G_steps"]["step_without_group_quantize_ms"]) * 1e3 / w.layers, 3)
+            ab["note"] = ("outlier_budget 0 in both; values_at_each_step adds one launch of kvq_quantize_value_tokens "
+                          "per layer and step and its group steps quantize Keys only")
+            result["value_schedule_ab"] = ab
         for (we, le) in extras:
             r = run_stack(we, le, args.steps, args.warmup, [], None, 0.0, we.name)
             result.setdefault("other_workloads", {})[we.name] = {

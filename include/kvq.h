@@ -59,6 +59,15 @@ typedef struct kvq_config {
                           /* whatever outlier_budget says (Experiments, "Details": layers 0   */
                           /* and 1 of the paper's models; 0 <= untraced_layers <= layers).    */
                           /* Buffer sizes do not depend on it                                 */
+  int32_t value_per_step; /* 0: Keys and Values of a group are quantized together when the    */
+                          /* ring fills, every G steps (the paper's schedule).  1: the        */
+                          /* schedule the paper compares itself with (Experiments, "Details": */
+                          /* Keys every G steps, Values at each step): a token's Values are   */
+                          /* quantized, token-wise, when the token leaves the window of the R */
+                          /* most recent tokens (kvq_quantize_value_tokens), and the group    */
+                          /* steps quantize Keys only.  Needs outlier_budget == 0 and         */
+                          /* residual >= 1 (KVQ_ERR_UNSUPPORTED otherwise); the *_ragged and  */
+                          /* *_seq entry points do not support it.  Buffer sizes are the same */
 } kvq_config;
 
 /* Sizes (bytes unless said otherwise) of every caller-allocated buffer. */
@@ -196,6 +205,31 @@ int32_t kvq_trace_outliers(const kvq_config* cfg, int32_t layer, int32_t group_i
 int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_index, const void* k_group,
                            const void* v_group, int64_t unit_stride, const uint8_t* selected,
                            kvq_qcache qcache, void* stream);
+
+/*
+ * Per-step Value quantization (cfg->value_per_step == 1; the schedule of the paper's comparison,
+ * Experiments, "Details": "compressing the Values at each step").  Tokens first_token ..
+ * first_token + count - 1 of every sequence, which live in ring rows ring_row, ring_row + 1, ...
+ * (mod res_rows) of the Value ring, are quantized token-wise with Eq. 2 (one step and zero per
+ * group_v channels of the token, exactly what kvq_quantize_group computes for the same row): their
+ * codes, steps and zeros are stored at their places in v_codes / v_meta (other tokens' bits of the
+ * same words are kept), and each ring row is overwritten with its dequantized row, zero + code * step
+ * evaluated in fp32 and rounded to fp16.  From then on the decode calls, which read those tokens from
+ * the ring until their Key group is quantized, attend them with their quantized Values.  A decode
+ * step under this schedule: this call for the one token that leaves the window (token n - R - 1 with
+ * n tokens in the cache after the append, once n > R), then the step's other calls as usual;
+ * kvq_quantize_group, kvq_append_trace_quantize and kvq_prefill_quantize's group pass then leave the
+ * Value arrays alone, and kvq_prefill_quantize ends with this call for the tokens between the last
+ * whole group and the window.
+ *   first_token, count : 0 <= first_token, 1 <= count <= res_rows, first_token + count <= max_seq
+ *   ring_row           : in [0, res_rows)
+ *   v_res              : device fp16 ring of the Values (read and written), 4-byte aligned
+ *   qcache             : dense or paged (the pages of the tokens' groups must be in the table)
+ * Tokens of one call are processed in order by one workgroup per unit; two calls that touch tokens
+ * of the same 32-token block must not overlap in time.
+ */
+int32_t kvq_quantize_value_tokens(const kvq_config* cfg, int32_t layer, int32_t first_token, int32_t count,
+                                  void* v_res, int32_t ring_row, kvq_qcache qcache, void* stream);
 
 /*
  * Decode-step attention of one layer (Eq. 1) over the three cache kinds (Method,

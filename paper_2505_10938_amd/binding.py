@@ -16,19 +16,19 @@ LIB_PATH = os.path.join(HERE, "libkvq.so")
 
 KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH, KVQ_ERR_SCRATCH = 0, -1, -2, -3, -4, -5
 
-INTERFACE_VERSION = 3       # kvq_version() of the library these structures and signatures match
+INTERFACE_VERSION = 4       # kvq_version() of the library these structures and signatures match
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
            "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_prefill_quantize_seq", "kvq_decode_attention",
            "kvq_append_decode_attention", "kvq_append_trace_quantize_ragged", "kvq_seq_advance",
            "kvq_decode_attention_ragged", "kvq_decode_attention_multi", "kvq_decode_workspace_bytes",
            "kvq_decode_launch_shape", "kvq_decode_attention_static", "kvq_dequantize", "kvq_stream_read",
-           "kvq_status_string", "kvq_version"]
+           "kvq_quantize_value_tokens", "kvq_status_string", "kvq_version"]
 
 
 class kvq_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("layers", "batch", "q_heads", "kv_heads", "head_dim", "max_seq", "bits", "group_k",
-                 "group_v", "residual", "outlier_budget", "aux_capacity", "untraced_layers")]
+                 "group_v", "residual", "outlier_budget", "aux_capacity", "untraced_layers", "value_per_step")]
 
 
 class kvq_sizes(C.Structure):
@@ -88,6 +88,8 @@ def load_library() -> C.CDLL:
     lib.kvq_trace_outliers.argtypes = [cfgp, i32, i32, vp, vp, i64, kvq_pool, vp, vp]
     lib.kvq_quantize_group.restype = i32
     lib.kvq_quantize_group.argtypes = [cfgp, i32, i32, vp, vp, i64, vp, kvq_qcache, vp]
+    lib.kvq_quantize_value_tokens.restype = i32
+    lib.kvq_quantize_value_tokens.argtypes = [cfgp, i32, i32, i32, vp, i32, kvq_qcache, vp]
     lib.kvq_prefill_quantize.restype = i32
     lib.kvq_prefill_quantize.argtypes = [cfgp, i32, vp, vp, i64, i32, kvq_pool, vp, kvq_qcache, kvq_residual, vp]
     lib.kvq_prefill_quantize_seq.restype = i32
@@ -177,6 +179,13 @@ def kvq_quantize_group(cfg, layer, group_index, k_group, v_group, unit_stride, s
                                            unit_stride, _ptr(selected), qcache, _stream(stream))
     if st != KVQ_OK:
         raise KvqError(st, "kvq_quantize_group")
+
+
+def kvq_quantize_value_tokens(cfg, layer, first_token, count, v_res, ring_row, qcache: kvq_qcache, stream=None):
+    st = load_library().kvq_quantize_value_tokens(C.byref(cfg), layer, first_token, count, _ptr(v_res), ring_row,
+                                                  qcache, _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_quantize_value_tokens")
 
 
 def kvq_append_trace_quantize(cfg, layer, k_new, v_new, res: kvq_residual, res_start, n_res, n_quant, pool: kvq_pool,

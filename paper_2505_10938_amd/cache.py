@@ -12,9 +12,9 @@ from . import binding as B
 
 
 def make_config(layers, batch, q_heads, kv_heads, max_seq, bits=2, group_k=32, group_v=32, residual=128,
-                outlier_budget=8, aux_capacity=32, head_dim=128, untraced_layers=0) -> B.kvq_config:
+                outlier_budget=8, aux_capacity=32, head_dim=128, untraced_layers=0, value_per_step=0) -> B.kvq_config:
     return B.kvq_config(layers, batch, q_heads, kv_heads, head_dim, max_seq, bits, group_k, group_v, residual,
-                        outlier_budget, aux_capacity, untraced_layers)
+                        outlier_budget, aux_capacity, untraced_layers, value_per_step)
 
 
 class KVCache:
@@ -40,7 +40,7 @@ class KVCache:
         if n_pages is not None:      # the pool is laid out as the dense cache of one sequence of n_pages groups
             qsz = B.kvq_query_sizes(make_config(cfg.layers, 1, cfg.kv_heads, cfg.kv_heads, n_pages * cfg.group_k,
                                                 cfg.bits, cfg.group_k, cfg.group_v, cfg.residual, cfg.outlier_budget,
-                                                cfg.aux_capacity, cfg.head_dim))
+                                                cfg.aux_capacity, cfg.head_dim, 0, cfg.value_per_step))
             self.page_table = torch.zeros(cfg.batch, cfg.max_seq // cfg.group_k, dtype=torch.int32, device=dev)
         self.k_codes, self.k_meta = raw(qsz.k_codes_bytes), raw(qsz.k_meta_bytes)
         self.v_codes, self.v_meta = raw(qsz.v_codes_bytes), raw(qsz.v_meta_bytes)
@@ -99,12 +99,26 @@ class KVCache:
         return self.k_res.data_ptr() + off, self.v_res.data_ptr() + off, self.sizes.res_rows * hd
 
     # ---- the schedule --------------------------------------------------------------------------------
+    def _value_leaves_window(self, layer, stream=None):
+        """The per-step Value schedule (cfg.value_per_step; Experiments, "Details": Values compressed at
+        each step): ahead of a step's append, the Values of the token that the append pushes out of the
+        window of the R most recent tokens are quantized."""
+        cfg = self.cfg
+        if not cfg.value_per_step:
+            return
+        tok = self.n_quant[layer] + self.n_res[layer] - cfg.residual
+        if tok < 0:
+            return
+        row = (self.res_start[layer] + tok - self.n_quant[layer]) % self.sizes.res_rows
+        B.kvq_quantize_value_tokens(cfg, layer, tok, 1, self.v_res, row, self.qcache, stream)
+
     def append(self, layer, k_new, v_new, stream=None, trace=True, fused=True):
         """Append one token (fp16 [batch, kv_heads, head_dim] each); when the ring then holds R + G
         tokens, trace and quantize the oldest G (in the same launch if `fused`, else with the three
         separate calls).  Returns True if a group was quantized."""
         cfg = self.cfg
         G = cfg.group_k
+        self._value_leaves_window(layer, stream)
         fills = self.n_res[layer] + 1 == cfg.residual + G
         if fills and fused and trace:
             B.kvq_append_trace_quantize(cfg, layer, k_new, v_new, self.res, self.res_start[layer], self.n_res[layer],
@@ -192,12 +206,14 @@ class KVCache:
     def step(self, layer, k_new, v_new, q, out=None, stream=None):
         """One decode step of `layer`: the new token joins the cache and the attention output (fp16
         [batch, q_heads, head_dim]) over the cache including it is returned.  Two launches on the steps
-        on which the ring fills (group step, then attention), one on all others."""
+        on which the ring fills (group step, then attention), one on all others; under the per-step
+        Value schedule one more, ahead of them (the Values of the token that leaves the window)."""
         if out is None:
             out = torch.empty_like(q)
         if self.n_res[layer] + 1 == self.cfg.residual + self.cfg.group_k:
             self.append(layer, k_new, v_new, stream)
             return self.decode(layer, q, out, stream)
+        self._value_leaves_window(layer, stream)
         B.kvq_append_decode_attention(self.cfg, layer, q, k_new, v_new, self.qcache, self.n_quant[layer], self.res,
                                       self.res_start[layer], self.n_res[layer], self.pool, out, self.workspace,
                                       self.workspace.numel(), stream)

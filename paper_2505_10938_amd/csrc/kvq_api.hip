@@ -25,6 +25,10 @@ int32_t check_config(const kvq_config* c) {
   const int g = c->q_heads / c->kv_heads;
   if (g != 1 && g != 2 && g != 4 && g != 8) return KVQ_ERR_UNSUPPORTED;
   if (c->outlier_budget > 64 || c->aux_capacity > 64) return KVQ_ERR_UNSUPPORTED;
+  if (c->value_per_step != 0 && c->value_per_step != 1) return KVQ_ERR_INVALID_ARG;
+  // the per-step Value schedule is the one of the method without tracing; a token must be in the ring
+  // when it leaves the window
+  if (c->value_per_step && (c->outlier_budget != 0 || c->residual < 1)) return KVQ_ERR_UNSUPPORTED;
   return KVQ_OK;
 }
 
@@ -95,6 +99,7 @@ Dims make_dims(const kvq_config* c, int32_t layer) {
   d.n_pages = 0;
   d.plane0 = (int64_t)layer * c->kv_heads;
   d.seq0 = 0;
+  d.keys_only = c->value_per_step;
   return d;
 }
 
@@ -152,7 +157,7 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restric
 
 extern "C" {
 
-int32_t kvq_version(void) { return 3; }
+int32_t kvq_version(void) { return 4; }
 
 int32_t kvq_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {
   if (!buf || !sink || bytes == 0 || bytes % 16 != 0 || ((uintptr_t)buf & 15) != 0) return KVQ_ERR_INVALID_ARG;
@@ -277,7 +282,14 @@ int32_t prefill_common(const kvq_config* cfg, int32_t layer, int32_t seq, const 
     return KVQ_ERR_INVALID_ARG;
   if (n_groups > 0 && (!selected || !qcache_ok(cfg, qc))) return KVQ_ERR_INVALID_ARG;
   if (n_groups > 65535) return KVQ_ERR_UNSUPPORTED;                    // grid limit of the quantization launch
-  Dims d = n_groups > 0 ? make_dims(cfg, layer, qc) : make_dims(cfg, layer);
+  // per-step Value schedule: the Values of the tokens between the last whole group and the window of R
+  // tokens are quantized as well (from the ring, after the tail rows are there)
+  const int32_t n_more_values = cfg->value_per_step ? (n_tokens - R) - n_groups * G : 0;
+  if (n_more_values > 0 && !qcache_ok(cfg, qc)) return KVQ_ERR_INVALID_ARG;
+  if (cfg->value_per_step && seq >= 0) return KVQ_ERR_UNSUPPORTED;
+  if (n_more_values > 0 && n_tokens - R > cfg->max_seq) return KVQ_ERR_INVALID_ARG;
+  Dims d = (n_groups > 0 || n_more_values > 0) ? make_dims(cfg, layer, qc) : make_dims(cfg, layer);
+  d.keys_only = 0;                                       // whole groups: Keys and Values in one pass
   hipStream_t s = (hipStream_t)stream;
   if (seq >= 0) {                                        // the launches cover the units of this sequence only
     d.unit0 += (int64_t)seq * cfg->kv_heads;
@@ -293,8 +305,11 @@ int32_t prefill_common(const kvq_config* cfg, int32_t layer, int32_t seq, const 
                              (int64_t)n_groups * G, qc, s);
     if (e != hipSuccess) return KVQ_ERR_LAUNCH;
   }
-  return from_hip(kvq::launch_tail_copy(d, (const __half*)k_rows, (const __half*)v_rows, unit_stride, n_groups * G,
-                                        n_tokens - n_groups * G, (__half*)res.k_res, (__half*)res.v_res, s));
+  hipError_t e = kvq::launch_tail_copy(d, (const __half*)k_rows, (const __half*)v_rows, unit_stride, n_groups * G,
+                                       n_tokens - n_groups * G, (__half*)res.k_res, (__half*)res.v_res, s);
+  if (e == hipSuccess && n_more_values > 0)
+    e = kvq::launch_value_tokens(d, n_groups * G, n_more_values, (__half*)res.v_res, 0, qc, s);
+  return from_hip(e);
 }
 
 }  // namespace
@@ -342,6 +357,7 @@ int32_t kvq_append_trace_quantize_ragged(const kvq_config* cfg, int32_t layer, c
   const int32_t st = check_config(cfg);
   if (st != KVQ_OK) return st;
   if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
+  if (cfg->value_per_step) return KVQ_ERR_UNSUPPORTED;
   if (!k_new || !v_new || !res.k_res || !res.v_res || !seq_state) return KVQ_ERR_INVALID_ARG;
   if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 3) return KVQ_ERR_INVALID_ARG;
   if (((uintptr_t)seq_state) & 15) return KVQ_ERR_INVALID_ARG;
@@ -354,6 +370,22 @@ int32_t kvq_append_trace_quantize_ragged(const kvq_config* cfg, int32_t layer, c
   return from_hip(kvq::launch_group_step(d, 0, (const __half*)k_new, (const __half*)v_new, (__half*)res.k_res,
                                          (__half*)res.v_res, 0, 0, seq_state, pool, selected, qc,
                                          (hipStream_t)stream));
+}
+
+int32_t kvq_quantize_value_tokens(const kvq_config* cfg, int32_t layer, int32_t first_token, int32_t count,
+                                  void* v_res, int32_t ring_row, kvq_qcache qc, void* stream) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  if (!cfg->value_per_step) return KVQ_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
+  const int32_t rows = (int32_t)res_rows_of(cfg);
+  if (first_token < 0 || count < 1 || count > rows || (int64_t)first_token + count > cfg->max_seq)
+    return KVQ_ERR_INVALID_ARG;
+  if (ring_row < 0 || ring_row >= rows) return KVQ_ERR_INVALID_ARG;
+  if (!v_res || (((uintptr_t)v_res) & 3)) return KVQ_ERR_INVALID_ARG;
+  if (!qcache_ok(cfg, qc)) return KVQ_ERR_INVALID_ARG;
+  const Dims d = make_dims(cfg, layer, qc);
+  return from_hip(kvq::launch_value_tokens(d, first_token, count, (__half*)v_res, ring_row, qc, (hipStream_t)stream));
 }
 
 int32_t kvq_dequantize(const kvq_config* cfg, int32_t layer, kvq_qcache qc, int32_t n_quant, kvq_pool pool,

@@ -42,6 +42,8 @@ struct Dims {
   int64_t plane0;                             // layer * kv_heads
   // A launch over the units of ONE sequence (units_per_layer = kv_heads, unit0 includes the sequence):
   int32_t seq0;                               // that sequence (0 for launches over the whole batch)
+  int32_t keys_only;                          // group quantization leaves the Value arrays alone (Values are
+                                              // quantized token by token, at each step)
 };
 
 // Where group `group` of local unit ul = b * kv_heads + h is stored: `row` indexes runs of
@@ -105,6 +107,8 @@ hipError_t launch_group_step(const Dims& d, int32_t group_index, const __half* k
                              __half* v_res, int32_t append_row, int32_t group_row0, const int32_t* seq,
                              const kvq_pool& pool, uint8_t* selected, const kvq_qcache& qc, hipStream_t s);
 hipError_t launch_seq_advance(const Dims& d, int32_t* seq, hipStream_t s);
+hipError_t launch_value_tokens(const Dims& d, int32_t first_token, int32_t count, __half* v_res, int32_t ring_row,
+                               const kvq_qcache& qc, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
 int decode_wave_lds_bytes(int g, int vgroups);   // LDS one decode wavefront needs
 

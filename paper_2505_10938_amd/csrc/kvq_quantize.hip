@@ -175,7 +175,7 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
     }
   }
   // V meta: Gv / 8 adjacent lanes share a (token, channel group), 8 channels each.
-  {
+  if (!d.keys_only) {
     const int lanes = d.Gv >> 3;                       // 4, 8 or 16
 #pragma unroll 1
     for (int e = tid; e < G * 16; e += kQuantThreads) {
@@ -215,8 +215,9 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
   constexpr int nblk = G / kBlockTokens;
   constexpr int kItems = 2 * nblk * kWordsPerBlock * kFieldsPerWord;   // a multiple of 1024
   const int first_block = group_index * nblk;
+  const int n_items = d.keys_only ? kItems / 2 : kItems;          // Key words first, then Value words
 #pragma unroll 1
-  for (int e = tid; e < kItems; e += kQuantThreads) {
+  for (int e = tid; e < n_items; e += kQuantThreads) {
     const int kv = e / (kItems / 2);
     const int wf = e % (kItems / 2);
     const int i = wf / kFieldsPerWord, ff = wf % kFieldsPerWord;
@@ -455,6 +456,92 @@ hipError_t launch_group_step_bits(const Dims& d, int32_t group_index, const __ha
 }
 
 }  // namespace
+
+// ---- per-step Value quantization ---------------------------------------------------------------
+// One workgroup of 128 threads (thread = channel) per unit; the tokens of the call one after the
+// other.  Per token: minimum and maximum of each group of Gv channels, step and zero, codes (Eq. 2,
+// the same device functions as the group quantization), the dequantized row back into the ring, the
+// steps and zeros to their places in the block's meta, and the token's 2 or 4 bits of 64 or 128
+// packed words replaced (the words also hold the block's other tokens of the same 8).
+template <int BITS>
+__global__ void __launch_bounds__(128) value_tokens_kernel(Dims d, int32_t first_token, int32_t count,
+                                                           __half* __restrict__ v_res, int32_t ring_row,
+                                                           uint8_t* __restrict__ v_codes,
+                                                           uint32_t* __restrict__ v_meta) {
+  constexpr int kLevels = (1 << BITS) - 1;
+  constexpr int kWords = 32 * BITS;                     // packed words that hold one token's codes
+  __shared__ float s_mn[2], s_mx[2];
+  __shared__ uint32_t s_words[kWords];
+  const int ul = blockIdx.x;
+  const int64_t u = d.unit0 + ul;
+  const int c = threadIdx.x;                            // channel
+  const int gv_shift = 31 - __clz(d.Gv);
+  const int nblk_shift = d.bpg_shift;                   // blocks per Key group
+  __half* ring = v_res + u * d.res_rows * kHeadDim;
+  for (int i = 0; i < count; ++i) {
+    const int tok = first_token + i;
+    int row = ring_row + i;
+    row -= row >= d.res_rows ? d.res_rows : 0;
+    const float x = __half2float(ring[row * kHeadDim + c]);
+    float mn = x, mx = x;
+    const int team = d.Gv < 64 ? d.Gv : 64;
+    for (int off = 1; off < team; off <<= 1) {
+      mn = fminf(mn, __shfl_xor(mn, off));
+      mx = fmaxf(mx, __shfl_xor(mx, off));
+    }
+    if (d.Gv == 128) {                                  // the group spans both wavefronts
+      if ((c & 63) == 0) {
+        s_mn[c >> 6] = mn;
+        s_mx[c >> 6] = mx;
+      }
+      __syncthreads();
+      mn = fminf(s_mn[0], s_mn[1]);
+      mx = fmaxf(s_mx[0], s_mx[1]);
+    }
+    mn += 0.0f;                                         // a zero minimum is stored as +0
+    const __half st = step_of(mn, mx, BITS);
+    const float stf = __half2float(st);
+    const uint32_t code = quant_code(x, mn, stf, kLevels);
+    const float prod = (float)code * stf;               // exact
+    ring[row * kHeadDim + c] = __float2half_rn(mn + prod);
+    // where the token's block is stored
+    const GroupPlace at = place_of_group(d, ul, tok / d.G);
+    const int64_t blk = at.row * d.blocks_per_unit + ((int64_t)at.slot << nblk_shift) + ((tok % d.G) >> 5);
+    const int tb = tok & 31;
+    if ((c & (d.Gv - 1)) == 0) {
+      const int j = c >> gv_shift;
+      __half* gm = (__half*)(v_meta + blk * 32 * d.vgroups);
+      gm[((tb >> 1) * d.vgroups + j) * 2 + (tb & 1)] = st;
+      gm[32 * d.vgroups + ((tb >> 1) * d.vgroups + j) * 2 + (tb & 1)] = __float2half_rn(mn);
+    }
+    // codes: channel c = 16 f + n of token tb = 8 r + xx lives in lane 16 r + n, field f, code xx
+    const int n = c & 15, f = c >> 4, xx = tb & 7, r = tb >> 3;
+    const int slot = BITS == 2 ? n * 4 + (f >> 1) : (f >> 2) * 64 + n * 4 + (f & 3);
+    __syncthreads();                                    // the previous token's words have been used
+    if (c < kWords) s_words[c] = 0;
+    __syncthreads();
+    atomicOr(&s_words[slot], place_code(code, code_bit(BITS, f, xx)));
+    __syncthreads();
+    if (c < kWords) {
+      const int half = BITS == 2 ? 0 : c >> 6, nn = (c & 63) >> 2, w = c & 3;
+      const uint32_t clear = BITS == 2 ? (place_code(3u, code_bit(2, 0, xx)) | place_code(3u, code_bit(2, 1, xx)))
+                                       : place_code(15u, code_bit(4, 0, xx));
+      uint32_t* gw = (uint32_t*)(v_codes + blk * d.block_bytes + 1024 * half + 16 * (16 * r + nn) + 4 * w);
+      *gw = (*gw & ~clear) | s_words[c];
+    }
+  }
+}
+
+hipError_t launch_value_tokens(const Dims& d, int32_t first_token, int32_t count, __half* v_res, int32_t ring_row,
+                               const kvq_qcache& qc, hipStream_t s) {
+  if (d.bits == 2)
+    hipLaunchKernelGGL(value_tokens_kernel<2>, dim3(d.units_per_layer), dim3(128), 0, s, d, first_token, count, v_res,
+                       ring_row, (uint8_t*)qc.v_codes, (uint32_t*)qc.v_meta);
+  else
+    hipLaunchKernelGGL(value_tokens_kernel<4>, dim3(d.units_per_layer), dim3(128), 0, s, d, first_token, count, v_res,
+                       ring_row, (uint8_t*)qc.v_codes, (uint32_t*)qc.v_meta);
+  return hipGetLastError();
+}
 
 // The state of every active sequence after one token has been appended to it (and its oldest group
 // quantized if that filled its ring): the rule group_step_kernel applies, applied to the array.

@@ -247,6 +247,33 @@ def test_untraced_layers_must_fit_the_layer_count():
                                                 C.byref(B.kvq_sizes())) == B.KVQ_ERR_INVALID_ARG
 
 
+def test_per_step_value_schedule_configuration_and_arguments():
+    lib = P.load_library()
+    sz = B.kvq_sizes()
+    ok = cfg(outlier_budget=0, aux_capacity=0, value_per_step=1)
+    assert lib.kvq_query_sizes(C.byref(ok), C.byref(sz)) == B.KVQ_OK
+    assert sz.v_codes_bytes == P.kvq_query_sizes(cfg(outlier_budget=0, aux_capacity=0)).v_codes_bytes
+    assert lib.kvq_query_sizes(C.byref(cfg(outlier_budget=0, value_per_step=2)), C.byref(sz)) == B.KVQ_ERR_INVALID_ARG
+    # the schedule of the method without tracing; the token that leaves the window must be in the ring
+    assert lib.kvq_query_sizes(C.byref(cfg(value_per_step=1)), C.byref(sz)) == B.KVQ_ERR_UNSUPPORTED
+    assert lib.kvq_query_sizes(C.byref(cfg(outlier_budget=0, residual=0, value_per_step=1)), C.byref(sz)) == B.KVQ_ERR_UNSUPPORTED
+    qc = B.kvq_qcache(256, 256, 256, 256, 256)
+    call = lambda c=ok, first=0, count=1, v=256, row=0, qc=qc: lib.kvq_quantize_value_tokens(
+        C.byref(c), 0, first, count, v, row, qc, None)
+    bad = B.KVQ_ERR_INVALID_ARG
+    assert call(c=cfg(outlier_budget=0)) == bad                # the configuration quantizes Values with their group
+    assert call(first=-1) == bad and call(count=0) == bad and call(count=161) == bad
+    assert call(first=1024) == bad and call(first=1000, count=25) == bad   # past the quantized capacity
+    assert call(row=-1) == bad and call(row=160) == bad
+    assert call(v=None) == bad and call(v=258) == bad
+    assert call(qc=B.kvq_qcache(256, 256, 0, 256, 256)) == bad
+    # entry points that do not support the schedule
+    pool = B.kvq_pool(256, 256, 256, 256, 256, 256, 256)
+    res = B.kvq_residual(256, 256)
+    assert lib.kvq_append_trace_quantize_ragged(C.byref(ok), 0, 256, 256, res, 256, pool, None, qc, None) == B.KVQ_ERR_UNSUPPORTED
+    assert lib.kvq_prefill_quantize_seq(C.byref(ok), 0, 0, 256, 256, 512 * 128, 512, pool, 256, qc, res, None) == B.KVQ_ERR_UNSUPPORTED
+
+
 def test_bad_dequantize_arguments_rejected_before_launch():
     lib = P.load_library()
     c = cfg()

@@ -964,3 +964,127 @@ def test_degenerate_groups(bits):
         got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
         assert np.isfinite(got).all()
         assert att_err(got, ref) <= ATT_TOL, regime                 # the wide token can dominate an output row
+
+
+# ---- the per-step Value schedule (the paper's comparison: Keys every G steps, Values at each step) ----
+
+def per_step_states(w, K, V, n):
+    """Oracle units of the per-step schedule with n tokens in the cache, every unit of the layer."""
+    from oracle import kvq_oracle as O
+    states = []
+    for ui in range(w.batch * w.kv_heads):
+        b, h = divmod(ui, w.kv_heads)
+        st = O.PerStepValueUnit(w.head_dim, w.bits, w.group_k, w.group_v)
+        st.advance_to(K[b, h], V[b, h], n, w.residual)
+        states.append(st)
+    return states
+
+
+def compare_per_step_values(cache, states, w, n, layer=0):
+    """Bit-exact: the Value codes, steps and zeros of the tokens between the last closed Key group
+    and the window (tokens n_quant .. n - R - 1, inside partly written blocks), and the ring's Value
+    rows of those tokens, which hold the dequantized rows."""
+    from oracle import kvq_oracle as O
+    cfg, sz = cache.cfg, cache.sizes
+    nq, nqv = states[0].n_quant, states[0].n_quant_v
+    assert nqv == max(0, n - w.residual) and cache.n_quant[layer] == nq
+    if nqv == nq:
+        return
+    bb, nv = 512 * w.bits, w.head_dim // w.group_v
+    nblk = cfg.max_seq // 32
+    _, _, v_codes, v_meta, _ = (t.cpu().numpy() for t in cache.dense_quantized())
+    vc = v_codes[:sz.units * nblk * bb].reshape(sz.units, nblk, bb)
+    vm = v_meta.view(np.uint16)[:sz.units * nblk * 64 * nv].reshape(sz.units, nblk, 64 * nv)
+    ring = cache.res_view("v").cpu().numpy()
+    levels = (1 << w.bits) - 1
+    u0 = layer * w.batch * w.kv_heads
+    for i, st in enumerate(states):
+        u = u0 + i
+        for blk in range(nq // 32, (nqv + 31) // 32):
+            t0, t1 = 32 * blk, min(32 * blk + 32, nqv)
+            codes = np.zeros((32, w.head_dim), np.uint8)
+            codes[:t1 - t0] = st.v_codes[t0:t1]
+            written = np.zeros((32, w.head_dim), np.uint8)
+            written[:t1 - t0] = levels
+            want, bits_written = O.pack_v_block(codes, w.bits), O.pack_v_block(written, w.bits)
+            assert np.array_equal(vc[u, blk] & bits_written, want), f"v_codes unit {i} block {blk}"
+            step = np.zeros((32, nv), np.float16)
+            zero = np.zeros((32, nv), np.float16)
+            step[:t1 - t0], zero[:t1 - t0] = st.v_step[t0:t1], st.v_zero[t0:t1]
+            meta = O.pack_v_meta(step, zero).view(np.uint16)[0]
+            there = O.pack_v_meta(np.where(written[:, :nv] > 0, 1, 0).astype(np.float16),
+                                  np.where(written[:, :nv] > 0, 1, 0).astype(np.float16)).view(np.uint16)[0] != 0
+            assert np.array_equal(vm[u, blk][there], meta[there]), f"v_meta unit {i} block {blk}"
+        for t in range(nq, nqv):
+            row = (cache.res_start[layer] + t - nq) % sz.res_rows
+            assert np.array_equal(ring[u, row].view(np.uint16), st.v_hat[t].view(np.uint16)), f"ring row of token {t}"
+
+
+@pytest.mark.parametrize("kw", [
+    dict(bits=2, group_k=32, group_v=32, residual=32, q_heads=4, kv_heads=2),
+    dict(bits=4, group_k=32, group_v=64, residual=40, q_heads=2, kv_heads=2),
+    dict(bits=2, group_k=64, group_v=128, residual=1, q_heads=8, kv_heads=1),
+    dict(bits=4, group_k=128, group_v=32, residual=128, q_heads=2, kv_heads=2),
+])
+def test_per_step_value_schedule_streaming(kw):
+    """Prefill, then decode steps under the per-step Value schedule: the attention of every step
+    against the oracle's, the Value codes written token by token and the ring rows that hold
+    dequantized Values bit for bit, and at the end the closed groups bit for bit - which are those of
+    the every-G-steps schedule without tracing."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    w = small("per_step", batch=2, outlier_budget=0, aux_capacity=0, context=300, **kw)
+    G, R = w.group_k, w.residual
+    steps = 2 * G + 9
+    n0 = w.context
+    K, V = S.layer_kv(w, 0, n0 + steps)
+    ms = ((n0 + steps + G - 1) // G) * G
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ms, w.bits, G, w.group_v, R, 0, 0, w.head_dim,
+                         value_per_step=1)
+    cache = KC.KVCache(cfg)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    cache.prefill(0, Kd[:, :, :n0].contiguous(), Vd[:, :, :n0].contiguous())
+    torch.cuda.synchronize()
+    compare_per_step_values(cache, per_step_states(w, K, V, n0), w, n0)
+    worst = 0.0
+    for s in range(steps):
+        n = n0 + s + 1
+        Q = S.layer_queries(w, 0, s, "peaky" if s % 2 else "diffuse")
+        got = cache.step(0, Kd[:, :, n - 1].contiguous(), Vd[:, :, n - 1].contiguous(), torch.from_numpy(Q).cuda())
+        states = per_step_states(w, K, V, n)
+        nq = states[0].n_quant
+        assert cache.n_quant[0] == nq and cache.n_res[0] == n - nq
+        ref = H.oracle_attention(w, states, Q, K, V, nq, n - nq)
+        worst = max(worst, att_err(got.cpu().numpy().astype(np.float64), ref))
+        if s % 7 == 0 or s == steps - 1:
+            compare_per_step_values(cache, states, w, n)
+    assert worst <= ATT_TOL, worst
+    # the closed groups: what the every-G-steps schedule leaves without tracing
+    H.compare_state(cache, states, w, nq)
+    plain = H.oracle_states(w, K, V, nq)
+    H.compare_state(cache, plain, w, nq)
+
+
+def test_per_step_value_schedule_from_an_empty_cache():
+    """No prompt: the first tokens stay inside the window, then Values start to leave it one by one
+    before any Key group closes."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    w = small("per_step_empty", batch=1, q_heads=4, kv_heads=2, outlier_budget=0, aux_capacity=0, residual=16,
+              context=0)
+    G, R = w.group_k, w.residual
+    steps = R + G + 5
+    K, V = S.layer_kv(w, 0, steps)
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, 4 * G, w.bits, G, w.group_v, R, 0, 0, w.head_dim,
+                         value_per_step=1)
+    cache = KC.KVCache(cfg)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    for s in range(steps):
+        n = s + 1
+        Q = S.layer_queries(w, 0, s, "peaky")
+        got = cache.step(0, Kd[:, :, s].contiguous(), Vd[:, :, s].contiguous(), torch.from_numpy(Q).cuda())
+        states = per_step_states(w, K, V, n)
+        nq = states[0].n_quant
+        ref = H.oracle_attention(w, states, Q, K, V, nq, n - nq)
+        assert att_err(got.cpu().numpy().astype(np.float64), ref) <= ATT_TOL, s
+        compare_per_step_values(cache, states, w, n)
