@@ -265,7 +265,8 @@ class RaggedKVCache(KVCache):
         G, R = cfg.group_k, cfg.residual
         nq = G * ((n - R) // G) if n >= R + G else 0
         if getattr(self, "prefill_selected", None) is None:
-            self.prefill_selected = torch.zeros(max(cfg.kv_heads * cfg.max_seq, 16), dtype=torch.uint8, device=self.device)
+            self.prefill_selected = torch.zeros(max(int(self.sizes.prefill_selected_bytes), 16), dtype=torch.uint8,
+                                                device=self.device)
         for layer in range(cfg.layers):
             k, v = k_rows[layer], v_rows[layer]
             assert k.shape == (cfg.kv_heads, n, cfg.head_dim) and k.is_contiguous() and v.is_contiguous()

@@ -70,6 +70,12 @@ constexpr int64_t kCounterBytes(int64_t upl) { return ((upl * 4 + 255) / 256) * 
 // run as several rows of a smaller one, all reading the unit's cache).
 constexpr int head_parts_of(int rows, int bits) { return (void)rows, (void)bits, 1; }
 
+// The prompt scratch: selected flags [units of a layer][max_seq] uint8, then, from this offset on, the
+// tokens' fp64 scores.
+int64_t prefill_scores_offset(const kvq_config* c) {
+  return (((int64_t)c->batch * c->kv_heads * c->max_seq + 255) / 256) * 256;
+}
+
 Dims make_dims(const kvq_config* c, int32_t layer) {
   Dims d;
   d.batch = c->batch;
@@ -206,7 +212,7 @@ int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out) {
   const int hp = head_parts_of((int)g, cfg->bits);
   const int64_t s_max = decode_split(upl * hp, (int)g / hp, (int)(hd / cfg->group_v), cfg->max_seq, out->res_rows + slots).splits;
   out->workspace_bytes = kCounterBytes(upl * hp) + upl * s_max * g * (hd + 2) * 4;
-  out->prefill_selected_bytes = upl * cfg->max_seq;
+  out->prefill_selected_bytes = prefill_scores_offset(cfg) + upl * cfg->max_seq * 8;
   return KVQ_OK;
 }
 
@@ -280,7 +286,7 @@ int32_t prefill_common(const kvq_config* cfg, int32_t layer, int32_t seq, const 
   if (!pool.pool_count || !pool.aux_count || !pool.frozen) return KVQ_ERR_INVALID_ARG;
   if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v || !pool.pool_idx || !pool.pool_score))
     return KVQ_ERR_INVALID_ARG;
-  if (n_groups > 0 && (!selected || !qcache_ok(cfg, qc))) return KVQ_ERR_INVALID_ARG;
+  if (n_groups > 0 && (!selected || (((uintptr_t)selected) & 7) || !qcache_ok(cfg, qc))) return KVQ_ERR_INVALID_ARG;
   if (n_groups > 65535) return KVQ_ERR_UNSUPPORTED;                    // grid limit of the quantization launch
   // per-step Value schedule: the Values of the tokens between the last whole group and the window of R
   // tokens are quantized as well (from the ring, after the tail rows are there)
@@ -299,7 +305,7 @@ int32_t prefill_common(const kvq_config* cfg, int32_t layer, int32_t seq, const 
   }
   if (n_groups > 0) {
     hipError_t e = kvq::launch_prefill_trace(d, n_groups, (const __half*)k_rows, (const __half*)v_rows, unit_stride,
-                                             pool, selected, s);
+                                             pool, selected, (double*)(selected + prefill_scores_offset(cfg)), s);
     if (e != hipSuccess) return KVQ_ERR_LAUNCH;
     e = kvq::launch_quantize(d, 0, n_groups, (const __half*)k_rows, (const __half*)v_rows, unit_stride, selected,
                              (int64_t)n_groups * G, qc, s);

@@ -37,6 +37,33 @@ __device__ inline uint32_t quant_code(float x, float mn, float step, int levels)
   return code;
 }
 
+// The same decision as quant_code, as a binary search: code k is reached when fl32(x - mn) >= (2k - 1) * h
+// with h = step / 2 (exact products again: 2k - 1 has 5 bits, h 11).  Returns 2 * code as a float.  A group
+// whose step is zero passes h = +infinity: no threshold is reached, the code is 0.
+template <int BITS>
+__device__ __forceinline__ float quant_code_twice(float x, float mn, float h) {
+  const float t = x - mn;
+  float acc = 0.0f;
+#pragma unroll
+  for (int l = BITS - 1; l >= 0; --l) {
+    const float c = (float)(2 << l);
+    const float w = acc + (c - 1.0f);
+    acc = (t >= w * h) ? acc + c : acc;
+  }
+  return acc;
+}
+__device__ __forceinline__ float half_step_of(__half st) {
+  const float s = __half2float(st);
+  return s == 0.0f ? __uint_as_float(0x7F800000u) : 0.5f * s;
+}
+// 2 * code (as returned above) put at bit position p of a packed word (a compile-time position of the
+// first field of a word; bits beyond 31 wrap around)
+template <int BITS>
+__device__ __forceinline__ uint32_t place_twice(float acc, int p) {
+  const uint32_t b = (uint32_t)acc;
+  return (b << (p - 1)) | (p + BITS > 32 ? b >> (33 - p) : 0u);
+}
+
 // fp16 step from a group's min and max: fl32(fl32(max - min) * c_b) rounded to nearest even.
 __device__ inline __half step_of(float mn, float mx, int bits) {
   const float c = bits == 2 ? __uint_as_float(0x3EAAAAABu) : __uint_as_float(0x3D888889u);  // 1/3, 1/15
@@ -77,19 +104,19 @@ template <int G>
 struct QuantLds {
   unsigned char* sk;     // [G] rows of kRowB bytes
   unsigned char* sv;     // [G] rows
-  uint32_t* skm;         // [128] K meta: step | zero << 16
-  uint32_t* svm;         // [vgroups][G] V meta
+  float2* skm;           // [128] K meta: {zero, step / 2 (+infinity for a zero step)}
+  float2* svm;           // [vgroups][G] V meta, the same pair
   uint8_t* ssel;         // [G] selected flags
   __device__ QuantLds(unsigned char* smem, int vgroups) {
     sk = smem;
     sv = sk + G * kRowB;
-    skm = (uint32_t*)(sv + G * kRowB);
+    skm = (float2*)(sv + G * kRowB);
     svm = skm + kHeadDim;
     ssel = (uint8_t*)(svm + G * vgroups);
   }
 };
 template <int G>
-size_t quant_lds_bytes(int vgroups) { return (size_t)2 * G * kRowB + kHeadDim * 4 + (size_t)G * vgroups * 4 + G; }
+size_t quant_lds_bytes(int vgroups) { return (size_t)2 * G * kRowB + kHeadDim * 8 + (size_t)G * vgroups * 8 + G; }
 
 // The group's rows, 16 bytes per thread: K rows first, then V rows.
 template <int G>
@@ -127,8 +154,8 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
                                               uint32_t* __restrict__ v_meta, uint32_t* __restrict__ mask, int tid) {
   unsigned char* sk = L.sk;
   unsigned char* sv = L.sv;
-  uint32_t* skm = L.skm;
-  uint32_t* svm = L.svm;
+  float2* skm = L.skm;
+  float2* svm = L.svm;
   uint8_t* ssel = L.ssel;
   const int gv_shift = 31 - __clz(d.Gv);             // Gv is a power of two
   if (tid < G) ssel[tid] = flag;
@@ -167,7 +194,7 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
     mn += 0.0f;                                        // a zero minimum is stored as +0 (-0 + +0 = +0)
     if (part == 0) {
       const __half st = step_of(mn, mx, BITS);
-      skm[c] = (uint32_t)__half_as_ushort(st) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
+      skm[c] = make_float2(mn, half_step_of(st));      // (mn is an fp16 value)
       // global layout of a group's Key meta: fp16 step[128], then fp16 zero[128]
       __half* gm = (__half*)(k_meta + (u * d.groups_per_unit + group_index) * kHeadDim);
       gm[c] = st;
@@ -194,7 +221,7 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
       if ((c8 & (lanes - 1)) == 0) {
         const int j = (c8 * 8) >> gv_shift;
         const __half st = step_of(mn, mx, BITS);
-        svm[j * G + t] = (uint32_t)__half_as_ushort(st) | ((uint32_t)__half_as_ushort(__float2half_rn(mn)) << 16);
+        svm[j * G + t] = make_float2(mn, half_step_of(st));
         // global layout of a 32-token block's Value meta (NV = value groups per token):
         // fp16 step[16 token pairs][NV][2], then fp16 zero[16 token pairs][NV][2]
         const int64_t tok = (int64_t)group_index * G + t;
@@ -209,7 +236,6 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
 
   // codes: one field (8 codes) of one packed u32 word of K or V per thread step.  Word w of lane l
   // of block blk holds 4/BITS fields; with two fields per word, adjacent lanes hold them.
-  constexpr int kLevels = (1 << BITS) - 1;
   constexpr int kWordsPerBlock = 128 * BITS;          // 512*BITS bytes / 4
   constexpr int kFieldsPerWord = 4 / BITS;            // 2 (2-bit) or 1 (4-bit)
   constexpr int nblk = G / kBlockTokens;
@@ -235,32 +261,40 @@ __device__ __forceinline__ void quantize_body(const Dims& d, int64_t u, int32_t 
     }
     const int r = lane >> 4, mn_ = lane & 15;
     const int f = f0 + ff;
+    // the word as if the field were the first of its word; the second field of a 2-bit word sits 8 bits up
     uint32_t word = 0;
+    float2 ms[8];
+    float val[8];
     if (kv == 0) {  // Key: lane = 16 r + m, field = 4 th + cb: 8 consecutive channels of one token
       const int t = 16 * (f >> 2) + mn_;
       const int c0 = 32 * (f & 3) + 8 * r;
       const uint4 xv = *(const uint4*)(sk + (blk * kBlockTokens + t) * kRowB + 2 * c0);
-      const uint4 m0 = *(const uint4*)(skm + c0), m1 = *(const uint4*)(skm + c0 + 4);
       const uint32_t xs[4] = {xv.x, xv.y, xv.z, xv.w};
-      const uint32_t ms[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
 #pragma unroll
-      for (int x = 0; x < 8; ++x) {
-        const float val = (x & 1) ? hi_half(xs[x >> 1]) : lo_half(xs[x >> 1]);
-        word |= place_code(quant_code(val, hi_half(ms[x]), lo_half(ms[x]), kLevels), code_bit(BITS, ff, x));
+      for (int x = 0; x < 8; x += 2) {
+        const float4 m2 = *(const float4*)(skm + c0 + x);
+        ms[x] = make_float2(m2.x, m2.y);
+        ms[x + 1] = make_float2(m2.z, m2.w);
       }
+#pragma unroll
+      for (int x = 0; x < 8; ++x) val[x] = (x & 1) ? hi_half(xs[x >> 1]) : lo_half(xs[x >> 1]);
     } else {        // Value: lane = 16 r + n, field = ct: one channel of 8 consecutive tokens
       const int c = 16 * f + mn_;
       const int t0 = blk * kBlockTokens + 8 * r;
-      const uint32_t* pm = svm + (c >> gv_shift) * G + t0;
-      const uint4 m0 = *(const uint4*)pm, m1 = *(const uint4*)(pm + 4);
-      const uint32_t ms[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
-      float val[8];
+      const float2* pm = svm + (c >> gv_shift) * G + t0;
+#pragma unroll
+      for (int x = 0; x < 8; x += 2) {
+        const float4 m2 = *(const float4*)(pm + x);
+        ms[x] = make_float2(m2.x, m2.y);
+        ms[x + 1] = make_float2(m2.z, m2.w);
+      }
 #pragma unroll
       for (int x = 0; x < 8; ++x) val[x] = half_at(sv + (t0 + x) * kRowB + 2 * c);
-#pragma unroll
-      for (int x = 0; x < 8; ++x)
-        word |= place_code(quant_code(val[x], hi_half(ms[x]), lo_half(ms[x]), kLevels), code_bit(BITS, ff, x));
     }
+#pragma unroll
+    for (int x = 0; x < 8; ++x)
+      word |= place_twice<BITS>(quant_code_twice<BITS>(val[x], ms[x].x, ms[x].y), code_bit(BITS, 0, x));
+    if (ff) word = (word << 8) | (word >> 24);
     if (kFieldsPerWord == 2) word |= row_partner_u32<0>(word);      // the word's other field (the adjacent lane)
     if (ff == 0) {
       const int64_t boff = (u * d.blocks_per_unit + first_block + blk) * (int64_t)d.block_bytes;
@@ -291,7 +325,6 @@ __global__ void __launch_bounds__(kQuantThreads) quantize_kernel(
   const QuantLds<G> L(smem, d.vgroups);
   const int tid = threadIdx.x;
   const int ul = blockIdx.x, gy = blockIdx.y;
-  const int64_t u = d.unit0 + ul;
   GroupRows<G> rows;
   const int64_t row0 = (int64_t)ul * unit_stride + (int64_t)gy * G * kHeadDim;
   rows_issue<G>(rows, k_group + row0, v_group + row0, tid);
