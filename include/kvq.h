@@ -87,8 +87,7 @@ typedef struct kvq_sizes {
   int64_t counter_bytes;    /* each of pool_count, aux_count, frozen: [units] int32           */
   int64_t selected_bytes;   /* [batch*kv_heads][G] uint8, one layer                           */
   int64_t workspace_bytes;  /* decode-attention workspace for one layer                       */
-  int64_t prefill_selected_bytes; /* scratch of kvq_prefill_quantize: flags [batch*kv_heads][max_seq] uint8, */
-                                  /* then (256-byte aligned) the tokens' fp64 scores                        */
+  int64_t prefill_selected_bytes; /* [batch*kv_heads][max_seq/G][G] uint8: flags of a whole prompt */
 } kvq_sizes;
 
 /*
@@ -334,11 +333,12 @@ int32_t kvq_decode_launch_shape(const kvq_config* cfg, int32_t q_tokens, int32_t
  *                    offset (b*kv_heads + h) * unit_stride; 16-byte aligned
  *   unit_stride    : in fp16 elements, >= n_tokens * head_dim, multiple of 8
  *   n_tokens       : 1 .. max_seq + R + G - 1, with n_q <= max_seq
- *   selected       : device scratch of kvq_sizes.prefill_selected_bytes, 8-byte aligned; on return
+ *   selected       : device uint8 scratch of kvq_sizes.prefill_selected_bytes; on return
  *                    selected[(unit * (n_q/G) + group) * G + t] = 1 if token t of that group entered
- *                    the pool at its competition (the rest of the buffer holds the tokens' scores)
- * The tokens' scores are computed in parallel, the competitions of a unit then run in order in one
- * wavefront on those scores, and the groups are quantized in parallel over units and groups.
+ *                    the pool at its competition
+ * The competitions of a unit run in order in one wavefront, on scores that the other wavefronts of its
+ * workgroup compute a stretch of tokens ahead; the groups are then quantized in parallel over units and
+ * groups.
  */
 int32_t kvq_prefill_quantize(const kvq_config* cfg, int32_t layer, const void* k_rows, const void* v_rows,
                              int64_t unit_stride, int32_t n_tokens, kvq_pool pool, uint8_t* selected,

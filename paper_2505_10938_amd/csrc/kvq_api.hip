@@ -70,12 +70,6 @@ constexpr int64_t kCounterBytes(int64_t upl) { return ((upl * 4 + 255) / 256) * 
 // run as several rows of a smaller one, all reading the unit's cache).
 constexpr int head_parts_of(int rows, int bits) { return (void)rows, (void)bits, 1; }
 
-// The prompt scratch: selected flags [units of a layer][max_seq] uint8, then, from this offset on, the
-// tokens' fp64 scores.
-int64_t prefill_scores_offset(const kvq_config* c) {
-  return (((int64_t)c->batch * c->kv_heads * c->max_seq + 255) / 256) * 256;
-}
-
 Dims make_dims(const kvq_config* c, int32_t layer) {
   Dims d;
   d.batch = c->batch;
@@ -212,7 +206,7 @@ int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out) {
   const int hp = head_parts_of((int)g, cfg->bits);
   const int64_t s_max = decode_split(upl * hp, (int)g / hp, (int)(hd / cfg->group_v), cfg->max_seq, out->res_rows + slots).splits;
   out->workspace_bytes = kCounterBytes(upl * hp) + upl * s_max * g * (hd + 2) * 4;
-  out->prefill_selected_bytes = prefill_scores_offset(cfg) + upl * cfg->max_seq * 8;
+  out->prefill_selected_bytes = upl * cfg->max_seq;
   return KVQ_OK;
 }
 
@@ -286,7 +280,7 @@ int32_t prefill_common(const kvq_config* cfg, int32_t layer, int32_t seq, const 
   if (!pool.pool_count || !pool.aux_count || !pool.frozen) return KVQ_ERR_INVALID_ARG;
   if (cfg->outlier_budget > 0 && (!pool.pool_k || !pool.pool_v || !pool.pool_idx || !pool.pool_score))
     return KVQ_ERR_INVALID_ARG;
-  if (n_groups > 0 && (!selected || (((uintptr_t)selected) & 7) || !qcache_ok(cfg, qc))) return KVQ_ERR_INVALID_ARG;
+  if (n_groups > 0 && (!selected || !qcache_ok(cfg, qc))) return KVQ_ERR_INVALID_ARG;
   if (n_groups > 65535) return KVQ_ERR_UNSUPPORTED;                    // grid limit of the quantization launch
   // per-step Value schedule: the Values of the tokens between the last whole group and the window of R
   // tokens are quantized as well (from the ring, after the tail rows are there)
@@ -305,14 +299,17 @@ int32_t prefill_common(const kvq_config* cfg, int32_t layer, int32_t seq, const 
   }
   if (n_groups > 0) {
     hipError_t e = kvq::launch_prefill_trace(d, n_groups, (const __half*)k_rows, (const __half*)v_rows, unit_stride,
-                                             pool, selected, (double*)(selected + prefill_scores_offset(cfg)), s);
+                                             pool, selected, s);
     if (e != hipSuccess) return KVQ_ERR_LAUNCH;
+    // (the rows behind the last group go to the ring in the same launch)
     e = kvq::launch_quantize(d, 0, n_groups, (const __half*)k_rows, (const __half*)v_rows, unit_stride, selected,
-                             (int64_t)n_groups * G, qc, s);
+                             (int64_t)n_groups * G, qc, s, n_tokens - n_groups * G, (__half*)res.k_res,
+                             (__half*)res.v_res);
     if (e != hipSuccess) return KVQ_ERR_LAUNCH;
   }
-  hipError_t e = kvq::launch_tail_copy(d, (const __half*)k_rows, (const __half*)v_rows, unit_stride, n_groups * G,
-                                       n_tokens - n_groups * G, (__half*)res.k_res, (__half*)res.v_res, s);
+  hipError_t e = n_groups > 0 ? hipSuccess
+                              : kvq::launch_tail_copy(d, (const __half*)k_rows, (const __half*)v_rows, unit_stride, 0,
+                                                      n_tokens, (__half*)res.k_res, (__half*)res.v_res, s);
   if (e == hipSuccess && n_more_values > 0)
     e = kvq::launch_value_tokens(d, n_groups * G, n_more_values, (__half*)res.v_res, 0, qc, s);
   return from_hip(e);

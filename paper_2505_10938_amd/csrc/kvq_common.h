@@ -98,10 +98,10 @@ hipError_t launch_trace(const Dims& d, int32_t group_index, const __half* k_grou
                         int64_t unit_stride, const kvq_pool& pool, uint8_t* selected, hipStream_t s);
 hipError_t launch_quantize(const Dims& d, int32_t group_index, int32_t n_groups, const __half* k_group,
                            const __half* v_group, int64_t unit_stride, const uint8_t* selected,
-                           int64_t selected_unit_stride, const kvq_qcache& qc, hipStream_t s);
+                           int64_t selected_unit_stride, const kvq_qcache& qc, hipStream_t s, int32_t tail_n = 0,
+                           __half* k_res = nullptr, __half* v_res = nullptr);
 hipError_t launch_prefill_trace(const Dims& d, int32_t n_groups, const __half* k_rows, const __half* v_rows,
-                                int64_t unit_stride, const kvq_pool& pool, uint8_t* selected, double* scores,
-                                hipStream_t s);
+                                int64_t unit_stride, const kvq_pool& pool, uint8_t* selected, hipStream_t s);
 hipError_t launch_tail_copy(const Dims& d, const __half* k_rows, const __half* v_rows, int64_t unit_stride, int32_t n0,
                             int32_t n, __half* k_res, __half* v_res, hipStream_t s);
 hipError_t launch_group_step(const Dims& d, int32_t group_index, const __half* k_new, const __half* v_new, __half* k_res,

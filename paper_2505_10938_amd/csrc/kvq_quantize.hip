@@ -318,13 +318,27 @@ __global__ void __launch_bounds__(kQuantThreads) quantize_kernel(
     Dims d, int32_t group_index, const __half* __restrict__ k_group, const __half* __restrict__ v_group,
     int64_t unit_stride, const uint8_t* __restrict__ selected, int64_t selected_unit_stride,
     uint8_t* __restrict__ k_codes, uint32_t* __restrict__ k_meta, uint8_t* __restrict__ v_codes,
-    uint32_t* __restrict__ v_meta, uint32_t* __restrict__ mask) {
-  // grid (units, groups): workgroup (ul, gy) quantizes the G rows from row gy * G of the unit's
-  // rows as group group_index + gy; its flags are selected[ul * selected_unit_stride + gy * G ..]
+    uint32_t* __restrict__ v_meta, uint32_t* __restrict__ mask, int32_t n_groups, int32_t tail_n,
+    __half* __restrict__ k_res, __half* __restrict__ v_res) {
+  // grid (units, groups + tail blocks): workgroup (ul, gy) with gy < n_groups quantizes the G rows from row
+  // gy * G of the unit's rows as group group_index + gy; its flags are
+  // selected[ul * selected_unit_stride + gy * G ..].  The workgroups behind them copy the tail_n rows that
+  // follow the last group into ring rows 0 .. of the unit (a whole prompt: the rows that stay in full
+  // precision), 16 bytes of K and of V per thread.
   extern __shared__ __align__(16) unsigned char smem[];
   const QuantLds<G> L(smem, d.vgroups);
   const int tid = threadIdx.x;
   const int ul = blockIdx.x, gy = blockIdx.y;
+  if (gy >= n_groups) {
+    const int i = (gy - n_groups) * kQuantThreads + tid;
+    if (i < tail_n * 16) {
+      const int64_t src = (int64_t)ul * unit_stride + (int64_t)n_groups * G * kHeadDim;
+      const int64_t dst = (d.unit0 + ul) * d.res_rows * kHeadDim;
+      ((uint4*)(k_res + dst))[i] = ((const uint4*)(k_group + src))[i];
+      ((uint4*)(v_res + dst))[i] = ((const uint4*)(v_group + src))[i];
+    }
+    return;
+  }
   GroupRows<G> rows;
   const int64_t row0 = (int64_t)ul * unit_stride + (int64_t)gy * G * kHeadDim;
   rows_issue<G>(rows, k_group + row0, v_group + row0, tid);
@@ -423,27 +437,31 @@ __global__ void __launch_bounds__(kQuantThreads) group_step_kernel(
 template <int BITS, int G>
 hipError_t launch_quantize_one(const Dims& d, int32_t group_index, int32_t n_groups, const __half* k_group,
                                const __half* v_group, int64_t unit_stride, const uint8_t* selected,
-                               int64_t selected_unit_stride, const kvq_qcache& qc, hipStream_t s) {
+                               int64_t selected_unit_stride, const kvq_qcache& qc, int32_t tail_n, __half* k_res,
+                               __half* v_res, hipStream_t s) {
   const size_t smem = quant_lds_bytes<G>(d.vgroups);
   if (smem > 48 * 1024) {  // more than the default limit of dynamic LDS per workgroup
     hipError_t e = hipFuncSetAttribute((const void*)quantize_kernel<BITS, G>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)smem);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((quantize_kernel<BITS, G>), dim3(d.units_per_layer, n_groups), dim3(kQuantThreads), smem, s, d,
-                     group_index, k_group, v_group, unit_stride, selected, selected_unit_stride, (uint8_t*)qc.k_codes, (uint32_t*)qc.k_meta, (uint8_t*)qc.v_codes,
-                     (uint32_t*)qc.v_meta, (uint32_t*)qc.mask);
+  const int tail_blocks = (tail_n * 16 + kQuantThreads - 1) / kQuantThreads;
+  hipLaunchKernelGGL((quantize_kernel<BITS, G>), dim3(d.units_per_layer, n_groups + tail_blocks), dim3(kQuantThreads),
+                     smem, s, d, group_index, k_group, v_group, unit_stride, selected, selected_unit_stride,
+                     (uint8_t*)qc.k_codes, (uint32_t*)qc.k_meta, (uint8_t*)qc.v_codes, (uint32_t*)qc.v_meta,
+                     (uint32_t*)qc.mask, n_groups, tail_n, k_res, v_res);
   return hipGetLastError();
 }
 
 template <int BITS>
 hipError_t launch_quantize_bits(const Dims& d, int32_t group_index, int32_t n_groups, const __half* k_group,
                                 const __half* v_group, int64_t unit_stride, const uint8_t* selected,
-                                int64_t selected_unit_stride, const kvq_qcache& qc, hipStream_t s) {
+                                int64_t selected_unit_stride, const kvq_qcache& qc, int32_t tail_n, __half* k_res,
+                                __half* v_res, hipStream_t s) {
   switch (d.G) {
-    case 32: return launch_quantize_one<BITS, 32>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, s);
-    case 64: return launch_quantize_one<BITS, 64>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, s);
-    default: return launch_quantize_one<BITS, 128>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, s);
+    case 32: return launch_quantize_one<BITS, 32>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, tail_n, k_res, v_res, s);
+    case 64: return launch_quantize_one<BITS, 64>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, tail_n, k_res, v_res, s);
+    default: return launch_quantize_one<BITS, 128>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, tail_n, k_res, v_res, s);
   }
 }
 
@@ -610,9 +628,10 @@ hipError_t launch_group_step(const Dims& d, int32_t group_index, const __half* k
 
 hipError_t launch_quantize(const Dims& d, int32_t group_index, int32_t n_groups, const __half* k_group,
                            const __half* v_group, int64_t unit_stride, const uint8_t* selected,
-                           int64_t selected_unit_stride, const kvq_qcache& qc, hipStream_t s) {
-  return d.bits == 2 ? launch_quantize_bits<2>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, s)
-                     : launch_quantize_bits<4>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, s);
+                           int64_t selected_unit_stride, const kvq_qcache& qc, hipStream_t s, int32_t tail_n,
+                           __half* k_res, __half* v_res) {
+  return d.bits == 2 ? launch_quantize_bits<2>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, tail_n, k_res, v_res, s)
+                     : launch_quantize_bits<4>(d, group_index, n_groups, k_group, v_group, unit_stride, selected, selected_unit_stride, qc, tail_n, k_res, v_res, s);
 }
 
 hipError_t launch_tail_copy(const Dims& d, const __half* k_rows, const __half* v_rows, int64_t unit_stride, int32_t n0,

@@ -32,34 +32,14 @@ __global__ void __launch_bounds__(trace_core::kWorkers) trace_kernel(
 }
 
 // ---- the competitions of a whole prompt -----------------------------------------------------------
-// Three steps.  (1) The L1 scores of all tokens, in parallel over units and tokens.  (2) Per unit, ONE
-// wavefront walks the groups in order on those scores: the pool is a sorted list held one entry per
-// lane, a group is looked at with one comparison per token against the pool's largest key, and only
-// tokens below it are inserted, one at a time (the N smallest of pool and group do not depend on the
-// order of insertion).  No barrier, no memory round trip between groups.  (3) The same wavefront then
-// copies the rows of the final members from the prompt.  The result is the state the group-by-group
-// competitions leave: same index sets, scores, rows, counts and flags (slot order is not part of it).
-
-// (1) fp64 L1 score of every token below n_tok: 16 lanes per row, 16 rows per pass of a 256-thread workgroup.
-__global__ void __launch_bounds__(256) prefill_scores_kernel(Dims d, int32_t n_tok, const __half* __restrict__ k_rows,
-                                                             int64_t unit_stride, double* __restrict__ scores) {
-  const int ul = blockIdx.x;
-  const int team = threadIdx.x >> 4, sub = threadIdx.x & 15;
-  const __half* rows = k_rows + (int64_t)ul * unit_stride;
-  const int t0 = blockIdx.y * 64;
-  uint4 w[4];
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int t = min(t0 + q * 16 + team, n_tok - 1);
-    w[q] = *(const uint4*)(rows + (int64_t)t * kHeadDim + sub * 8);
-  }
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int t = t0 + q * 16 + team;
-    const double sc = trace_core::team_sum_f64(trace_core::abs_sum8(w[q]));
-    if (sub == 0 && t < n_tok) scores[(int64_t)ul * n_tok + t] = sc;
-  }
-}
+// One workgroup of 4 wavefronts per unit.  The L1 scores of the tokens are computed 1024 tokens at a time
+// into one of two LDS buffers; ONE wavefront walks the groups of a chunk in order on those scores while
+// the other three compute the next chunk's.  The pool is a sorted list held one entry per lane of that
+// wavefront; a stretch of tokens is looked at with one comparison per token against the pool's largest
+// key, and only tokens below it are inserted, one at a time (the N smallest of pool and group do not
+// depend on the order of insertion).  At the end the wavefront copies the rows of the final members from
+// the prompt.  The result is the state the group-by-group competitions leave: same index sets, scores,
+// rows, counts and flags (slot order is not part of it).
 
 __device__ inline double lane_value(double v, int l) {     // v of lane l (uniform l)
   const unsigned long long b = (unsigned long long)__double_as_longlong(v);
@@ -81,34 +61,55 @@ __device__ inline bool key_less(double as, int ai, double bs, int bi) { return a
 
 constexpr int kScoreChunk = 1024;                      // scores staged in LDS at a time
 
-// (2) + (3): one wavefront per unit.  Requires empty pools on entry (a prompt starts a sequence).
+// Requires empty pools on entry (a prompt starts a sequence).
 template <int G>
-__global__ void __launch_bounds__(64) prefill_compete_kernel(
-    Dims d, int32_t n_groups, const double* __restrict__ scores, const __half* __restrict__ k_rows,
-    const __half* __restrict__ v_rows, int64_t unit_stride, __half* pool_k, __half* pool_v, int32_t* pool_idx,
-    double* pool_score, int32_t* pool_count, int32_t* aux_count, int32_t* frozen, uint8_t* __restrict__ selected) {
-  __shared__ double s_sc[kScoreChunk];
+__global__ void __launch_bounds__(256) prefill_trace_kernel(
+    Dims d, int32_t n_groups, const __half* __restrict__ k_rows, const __half* __restrict__ v_rows,
+    int64_t unit_stride, __half* pool_k, __half* pool_v, int32_t* pool_idx, double* pool_score, int32_t* pool_count,
+    int32_t* aux_count, int32_t* frozen, uint8_t* __restrict__ selected) {
+  __shared__ double s_buf[2][kScoreChunk];
   __shared__ double s_aux_score[64];
   __shared__ int32_t s_aux_idx[64];
-  const int lane = threadIdx.x;
+  __shared__ int32_t s_stop[2];                         // set by the wavefront that holds the pool; slot = chunk parity
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ul = blockIdx.x;
   const int64_t u = d.unit0 + ul;
   const int n_tok = n_groups * G;
   uint8_t* sel = selected + (int64_t)ul * n_tok;
   const int N = d.N, A = d.A;
   if (N == 0) {                                        // no pool: nothing is ever selected
-    for (int i = lane; i < n_tok; i += 64) sel[i] = 0;
+    for (int i = tid; i < n_tok; i += 256) sel[i] = 0;
     return;
   }
-  const double* sc_u = scores + (int64_t)ul * n_tok;
   constexpr int kRounds = (G + 63) / 64;               // a group is looked at 64 tokens at a time
   constexpr int kPer = kScoreChunk / 64;
-  double pre[kPer];
-  auto issue = [&](int c0) {
+  // fp64 L1 scores of the chunk's tokens into `buf`, by the wavefronts w0 .. 3: 16 lanes per row, 4 rows
+  // per load instruction, eight of them in flight per wavefront
+  const __half* rows = k_rows + (int64_t)ul * unit_stride;
+  auto score_chunk = [&](int c0, double* buf, int w0) {
+    const int nw = 4 - w0;
+    const int n_here = min(kScoreChunk, n_tok - c0);
+    const int team = lane >> 4, sub = lane & 15;
+    for (int i0 = 0; ((wave - w0) + nw * i0) * 4 < n_here; i0 += 8) {
+      uint4 w[8];
 #pragma unroll
-    for (int k = 0; k < kPer; ++k) pre[k] = sc_u[min(c0 + k * 64 + lane, n_tok - 1)];
+      for (int q = 0; q < 8; ++q) {
+        const int r = min(((wave - w0) + nw * (i0 + q)) * 4 + team, n_here - 1);
+        w[q] = *(const uint4*)(rows + (int64_t)(c0 + r) * kHeadDim + sub * 8);
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int r = ((wave - w0) + nw * (i0 + q)) * 4 + team;
+        const double sc = trace_core::team_sum_f64(trace_core::abs_sum8(w[q]));
+        if (sub == 0 && r < n_here) buf[r] = sc;
+      }
+    }
   };
-  issue(0);
+  if (tid < 2) s_stop[tid] = 0;
+  score_chunk(0, s_buf[0], 0);
+  __syncthreads();
   const double kInf = __longlong_as_double(0x7FF0000000000000ll);
   double ps = kInf;                                    // the pool, ascending by key: entry `lane`, lanes below P
   int pi = 0x7FFFFFFF;
@@ -117,7 +118,7 @@ __global__ void __launch_bounds__(64) prefill_compete_kernel(
   int gi = 0;                                          // the next group
   // One group on the sorted pool: tokens that belong to the N smallest keys seen so far are inserted one
   // at a time, the largest key falling out each time the pool is full.
-  auto do_group = [&](int gl) {
+  auto do_group = [&](int gl, const double* s_sc) {
     const int first = gi * G;                          // the group's first token
     const double ps0 = ps;                             // the pool before the group, should tracing stop here
     const int pi0 = pi, P0 = P;
@@ -187,12 +188,8 @@ __global__ void __launch_bounds__(64) prefill_compete_kernel(
   };
   constexpr int kSpanTok = G > 64 ? G : 64;            // tokens that are ruled out together: whole groups, whole masks
   constexpr int kMasksPerSpan = kSpanTok / 64, kGroupsPerSpan = kSpanTok / G;
-  for (int c0 = 0; c0 < n_tok && !stopped; c0 += kScoreChunk) {
-    __syncthreads();                                   // (one wavefront: orders its LDS reads and writes)
-#pragma unroll
-    for (int k = 0; k < kPer; ++k) s_sc[k * 64 + lane] = pre[k];
-    if (c0 + kScoreChunk < n_tok) issue(c0 + kScoreChunk);
-    __syncthreads();
+  // the groups of one chunk (the wavefront that holds the pool)
+  auto compete_chunk = [&](int c0, const double* s_sc) {
     const int here = min(kScoreChunk, n_tok - c0) / G;
     // Which tokens of the chunk lie below the pool's largest key as it is now (64 per mask, mask k kept by
     // lane k): that key only falls, so tokens that are not below it now cannot change anything later, and
@@ -231,12 +228,28 @@ __global__ void __launch_bounds__(64) prefill_compete_kernel(
         gi += n_here;
         continue;
       }
-      for (int g2 = 0; g2 < n_here && !stopped; ++g2) do_group(gl + g2);
+      for (int g2 = 0; g2 < n_here && !stopped; ++g2) do_group(gl + g2, s_sc);
       gl += n_here;
     }
+  };
+  int buf = 0;
+  for (int c0 = 0; c0 < n_tok; c0 += kScoreChunk, buf ^= 1) {
+    if (wave == 0) {
+      compete_chunk(c0, s_buf[buf]);
+      if (stopped && lane == 0) s_stop[buf] = 1;
+    } else if (c0 + kScoreChunk < n_tok) {
+      score_chunk(c0 + kScoreChunk, s_buf[buf ^ 1], 1);
+    }
+    __syncthreads();
+    if (s_stop[buf]) break;                            // (written before the barrier; the slot is not written again
+                                                       // before every wavefront has passed the next one)
   }
+  if (wave != 0) return;
   for (int i = gi * G + lane; i < n_tok; i += 64) sel[i] = 0;      // groups after the stop select nothing
-  __syncthreads();
+  // lane 0's writes of the auxiliary list, read by the other lanes below
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   // the unit's state
   const int64_t slot0 = u * d.pool_slots;
   if (lane < P) {
@@ -284,21 +297,16 @@ __global__ void __launch_bounds__(64) prefill_compete_kernel(
 }  // namespace
 
 hipError_t launch_prefill_trace(const Dims& d, int32_t n_groups, const __half* k_rows, const __half* v_rows,
-                                int64_t unit_stride, const kvq_pool& pool, uint8_t* selected, double* scores,
-                                hipStream_t s) {
-  const int32_t n_tok = n_groups * d.G;
-  if (d.N > 0)
-    hipLaunchKernelGGL(prefill_scores_kernel, dim3(d.units_per_layer, (n_tok + 63) / 64), dim3(256), 0, s, d, n_tok,
-                       k_rows, unit_stride, scores);
+                                int64_t unit_stride, const kvq_pool& pool, uint8_t* selected, hipStream_t s) {
   auto go = [&](auto kern) {
-    hipLaunchKernelGGL(kern, dim3(d.units_per_layer), dim3(64), 0, s, d, n_groups, (const double*)scores, k_rows,
-                       v_rows, unit_stride, (__half*)pool.pool_k, (__half*)pool.pool_v, pool.pool_idx, pool.pool_score,
-                       pool.pool_count, pool.aux_count, pool.frozen, selected);
+    hipLaunchKernelGGL(kern, dim3(d.units_per_layer), dim3(256), 0, s, d, n_groups, k_rows, v_rows, unit_stride,
+                       (__half*)pool.pool_k, (__half*)pool.pool_v, pool.pool_idx, pool.pool_score, pool.pool_count,
+                       pool.aux_count, pool.frozen, selected);
   };
   switch (d.G) {
-    case 32: go(prefill_compete_kernel<32>); break;
-    case 64: go(prefill_compete_kernel<64>); break;
-    default: go(prefill_compete_kernel<128>); break;
+    case 32: go(prefill_trace_kernel<32>); break;
+    case 64: go(prefill_trace_kernel<64>); break;
+    default: go(prefill_trace_kernel<128>); break;
   }
   return hipGetLastError();
 }
