@@ -433,6 +433,37 @@ int32_t kvq_decode_attention_ragged(const kvq_config* cfg, int32_t layer, const 
                                     size_t workspace_bytes, void* stream);
 
 /*
+ * kvq_decode_attention_ragged sizes its launch by the longest sequence, so it lasts as long as that
+ * sequence's units.  A launch PLAN deals the workgroups by length instead: every sequence gets a number
+ * of workgroups in proportion to its tokens and full-precision rows (at least one), all of them resident
+ * at once; the workgroups of a sequence share its quantized tokens equally and merge their partial
+ * results (m, l, o) like the splits of kvq_decode_attention.
+ *   kvq_seq_plan_bytes : host only; size of a plan for cfg, or KVQ_ERR_UNSUPPORTED when the batch has more
+ *                than 1024 sequences or more sequences than workgroups fit per kv head on the device
+ *   kvq_seq_plan : one small launch; writes the plan for the sequences' CURRENT state (a copy of it is
+ *                part of the plan).  Call it after kvq_seq_advance, once per decode step, before the
+ *                step's kvq_decode_attention_planned calls of all layers (the state is the same for all)
+ *     seq_state, max_n_quant, max_n_res : as in kvq_decode_attention_ragged
+ *     plan      : device int32, kvq_seq_plan_bytes(cfg) bytes, 16-byte aligned.  Word 0: entries in use;
+ *                from word 8 on, 8 words per entry (= per workgroup of a kv head): {sequence, split,
+ *                splits of the sequence, first mini-chunk of 128 quantized tokens, n_quant, res_start,
+ *                n_res, end of the mini-chunks}
+ *   kvq_decode_attention_planned : kvq_decode_attention_ragged on the state the plan holds
+ *     plan      : as written by kvq_seq_plan with the same cfg and bounds.  Its entries are clamped to the
+ *                bounds like seq_state's; a plan that is inconsistent (not written by kvq_seq_plan) gives
+ *                wrong or missing outputs, no access outside the buffers and no hang
+ *     workspace : at least kvq_sizes.workspace_bytes (which covers this launch shape too)
+ *   other arguments and errors as kvq_decode_attention_ragged.
+ */
+int64_t kvq_seq_plan_bytes(const kvq_config* cfg);
+int32_t kvq_seq_plan(const kvq_config* cfg, const int32_t* seq_state, int32_t max_n_quant, int32_t max_n_res,
+                     int32_t* plan, void* stream);
+int32_t kvq_decode_attention_planned(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qcache,
+                                     kvq_residual res, const int32_t* plan, int32_t max_n_quant,
+                                     int32_t max_n_res, kvq_pool pool, void* out, void* workspace,
+                                     size_t workspace_bytes, void* stream);
+
+/*
  * The quantized segment as fp16 rows, for consumers that need the cache as a matrix (attention of
  * several query tokens at once, inspection): x^ = X_min + Q * q, the inverse of Eq. 2, evaluated in
  * fp32 (the product is exact there, the sum rounds once) and rounded to nearest fp16.  A token that
@@ -461,7 +492,7 @@ int32_t kvq_stream_read(const void* buf, size_t bytes, void* sink, void* stream)
 /* Static string for a kvq_status value. */
 const char* kvq_status_string(int32_t status);
 
-/* Version of this interface (structure layouts and entry points), for the binding's load check: 3. */
+/* Version of this interface (structure layouts and entry points), for the binding's load check: 5. */
 int32_t kvq_version(void);
 
 #ifdef __cplusplus

@@ -16,13 +16,14 @@ LIB_PATH = os.path.join(HERE, "libkvq.so")
 
 KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH, KVQ_ERR_SCRATCH = 0, -1, -2, -3, -4, -5
 
-INTERFACE_VERSION = 4       # kvq_version() of the library these structures and signatures match
+INTERFACE_VERSION = 5       # kvq_version() of the library these structures and signatures match
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
            "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_prefill_quantize_seq", "kvq_decode_attention",
            "kvq_append_decode_attention", "kvq_append_trace_quantize_ragged", "kvq_seq_advance",
            "kvq_decode_attention_ragged", "kvq_decode_attention_multi", "kvq_decode_workspace_bytes",
            "kvq_decode_launch_shape", "kvq_decode_attention_static", "kvq_dequantize", "kvq_stream_read",
-           "kvq_quantize_value_tokens", "kvq_status_string", "kvq_version"]
+           "kvq_quantize_value_tokens", "kvq_seq_plan_bytes", "kvq_seq_plan", "kvq_decode_attention_planned",
+           "kvq_status_string", "kvq_version"]
 
 
 class kvq_config(C.Structure):
@@ -120,6 +121,13 @@ def load_library() -> C.CDLL:
     lib.kvq_decode_attention_ragged.restype = i32
     lib.kvq_decode_attention_ragged.argtypes = [cfgp, i32, vp, kvq_qcache, kvq_residual, vp, i32, i32, kvq_pool,
                                                 vp, vp, C.c_size_t, vp]
+    lib.kvq_seq_plan_bytes.restype = i64
+    lib.kvq_seq_plan_bytes.argtypes = [cfgp]
+    lib.kvq_seq_plan.restype = i32
+    lib.kvq_seq_plan.argtypes = [cfgp, vp, i32, i32, vp, vp]
+    lib.kvq_decode_attention_planned.restype = i32
+    lib.kvq_decode_attention_planned.argtypes = [cfgp, i32, vp, kvq_qcache, kvq_residual, vp, i32, i32, kvq_pool,
+                                                 vp, vp, C.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -285,6 +293,28 @@ def kvq_decode_attention_ragged(cfg, layer, q, qcache: kvq_qcache, res: kvq_resi
                                                     workspace_bytes, _stream(stream))
     if st != KVQ_OK:
         raise KvqError(st, "kvq_decode_attention_ragged")
+
+
+def kvq_seq_plan_bytes(cfg) -> int:
+    n = load_library().kvq_seq_plan_bytes(C.byref(cfg))
+    if n < 0:
+        raise KvqError(int(n), "kvq_seq_plan_bytes")
+    return int(n)
+
+
+def kvq_seq_plan(cfg, seq_state, max_n_quant, max_n_res, plan, stream=None):
+    st = load_library().kvq_seq_plan(C.byref(cfg), _ptr(seq_state), max_n_quant, max_n_res, _ptr(plan), _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_seq_plan")
+
+
+def kvq_decode_attention_planned(cfg, layer, q, qcache: kvq_qcache, res: kvq_residual, plan, max_n_quant, max_n_res,
+                                 pool: kvq_pool, out, workspace, workspace_bytes, stream=None):
+    st = load_library().kvq_decode_attention_planned(C.byref(cfg), layer, _ptr(q), qcache, res, _ptr(plan),
+                                                     max_n_quant, max_n_res, pool, _ptr(out), _ptr(workspace),
+                                                     workspace_bytes, _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_decode_attention_planned")
 
 
 def kvq_stream_read(buf, nbytes, sink, stream=None):

@@ -281,6 +281,14 @@ class RaggedKVCache(KVCache):
         B.kvq_seq_advance(self.cfg, self.seq_state, stream)
         self.longest += 1
 
+    def make_plan(self, stream=None):
+        """Deal the decode launches of the next step by the sequences' current lengths (once per step,
+        after advance(); then decode(..., planned=True) for every layer)."""
+        if getattr(self, "plan", None) is None:
+            self.plan = torch.zeros(B.kvq_seq_plan_bytes(self.cfg) // 4, dtype=torch.int32, device=self.device)
+        nq, nr = self.bounds()
+        B.kvq_seq_plan(self.cfg, self.seq_state, nq, nr, self.plan, stream)
+
     def bounds(self):
         """(max_n_quant, max_n_res) over all sequences, from the host's bound of the longest one."""
         G, R = self.cfg.group_k, self.cfg.residual
@@ -288,10 +296,14 @@ class RaggedKVCache(KVCache):
         nq = G * ((n - R) // G) if n >= R + G else 0
         return min(nq, self.cfg.max_seq), min(n, R + G - 1)
 
-    def decode(self, layer, q, out=None, stream=None):
+    def decode(self, layer, q, out=None, stream=None, planned=False):
         if out is None:
             out = torch.empty_like(q)
         nq, nr = self.bounds()
+        if planned:
+            B.kvq_decode_attention_planned(self.cfg, layer, q, self.qcache, self.res, self.plan, nq, nr, self.pool, out,
+                                           self.workspace, self.workspace.numel(), stream)
+            return out
         B.kvq_decode_attention_ragged(self.cfg, layer, q, self.qcache, self.res, self.seq_state, nq, nr, self.pool, out,
                                       self.workspace, self.workspace.numel(), stream)
         return out

@@ -65,10 +65,58 @@ Split decode_split(int64_t units_per_layer, int g, int vgroups, int64_t n_quant,
   return s;
 }
 constexpr int64_t kCounterBytes(int64_t upl) { return ((upl * 4 + 255) / 256) * 256; }
+
+// Shape of a planned decode launch (sequences of different lengths dealt by length): wavefronts per
+// workgroup and workgroups ("entries") per kv head.  All workgroups are to be resident at once, and there
+// should be at least twice as many per kv head as sequences, so that a long sequence can have several
+// while a short one has one: the workgroups are made smaller until that holds.  (Measured on 32 sequences
+// of 128 .. 8192 tokens with 8 kv heads: 41.4 us with as many workgroups as sequences, 36.7 with twice,
+// 36.8 with four times, 46.2 with eight times as many; sharing a large workgroup between several short
+// sequences, one after the other, 61.8 us: every sequence then waits for its own first loads.)
+// entries == 0: no such shape (more sequences than workgroups fit per kv head, or more than 1024).
+struct PlanShape {
+  int32_t nw, entries;
+};
+PlanShape plan_shape(const kvq_config* c) {
+  const int g = c->q_heads / c->kv_heads;
+  int64_t waves_per_cu = kvq::kLdsPerComputeUnit / kvq::decode_wave_lds_bytes(g, c->head_dim / c->group_v);
+  const int64_t by_registers = 4 * kvq::kDecodeWavesPerSimd;
+  if (waves_per_cu > by_registers) waves_per_cu = by_registers;
+  if (waves_per_cu < 1) waves_per_cu = 1;
+  PlanShape best = {0, 0};
+  if (c->batch > 1024) return best;
+  for (int nw = (int)waves_per_cu; nw >= 1; nw >>= 1) {
+    const int64_t entries = kvq::kComputeUnits * (waves_per_cu / nw) / c->kv_heads;
+    if (entries < c->batch) continue;
+    best.nw = nw;
+    best.entries = (int32_t)(entries > 4096 ? 4096 : entries);
+    if (entries >= 2 * (int64_t)c->batch) break;
+  }
+  return best;
+}
+constexpr int64_t kPlanEntryWords = 8;
 // Workgroup rows that share the query rows of a kv head.  Every supported count (1, 2, 4, 8) has a kernel
 // instance of its own, so it is 1; the kernel still takes any divisor (a count without an instance would
 // run as several rows of a smaller one, all reading the unit's cache).
 constexpr int head_parts_of(int rows, int bits) { return (void)rows, (void)bits, 1; }
+
+// Workspace of a decode launch whose kv heads have `rows` query rows each (rows = query heads per kv
+// head times query tokens): arrival counters, then partial results for the largest split the launch
+// shape can get.
+int64_t decode_workspace_bytes(const kvq_config* cfg, int64_t rows) {
+  const int64_t upl = (int64_t)cfg->batch * cfg->kv_heads, hd = cfg->head_dim;
+  const int64_t hp = head_parts_of((int)rows, cfg->bits);
+  const int64_t slots = (int64_t)cfg->outlier_budget + cfg->aux_capacity;
+  const int64_t s_max =
+      decode_split(upl * hp, (int)(rows / hp), (int)(hd / cfg->group_v), cfg->max_seq, res_rows_of(cfg) + slots).splits;
+  int64_t slots_needed = upl * s_max;
+  if (cfg->batch <= 1024) {                              // a planned launch: items per kv head
+    const int64_t planned = (int64_t)plan_shape(cfg).entries * cfg->kv_heads;
+    if (planned > slots_needed) slots_needed = planned;
+  }
+  return kCounterBytes(upl * hp) + slots_needed * rows * (hd + 2) * 4;
+}
+
 
 Dims make_dims(const kvq_config* c, int32_t layer) {
   Dims d;
@@ -157,7 +205,7 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restric
 
 extern "C" {
 
-int32_t kvq_version(void) { return 4; }
+int32_t kvq_version(void) { return 5; }
 
 int32_t kvq_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {
   if (!buf || !sink || bytes == 0 || bytes % 16 != 0 || ((uintptr_t)buf & 15) != 0) return KVQ_ERR_INVALID_ARG;
@@ -205,7 +253,7 @@ int32_t kvq_query_sizes(const kvq_config* cfg, kvq_sizes* out) {
   // the split count grows with the amount of work: the largest is the one of a full cache
   const int hp = head_parts_of((int)g, cfg->bits);
   const int64_t s_max = decode_split(upl * hp, (int)g / hp, (int)(hd / cfg->group_v), cfg->max_seq, out->res_rows + slots).splits;
-  out->workspace_bytes = kCounterBytes(upl * hp) + upl * s_max * g * (hd + 2) * 4;
+  out->workspace_bytes = decode_workspace_bytes(cfg, g);
   out->prefill_selected_bytes = upl * cfg->max_seq;
   return KVQ_OK;
 }
@@ -450,22 +498,11 @@ __global__ void zero_words_kernel(uint32_t* p, int n) {
 
 // The decode launch, shared by the two entry points: `seq_state` null = every sequence has the
 // state given; otherwise n_quant and n_res are upper bounds and each sequence brings its own.
-// Workspace of a decode launch whose kv heads have `rows` query rows each (rows = query heads per kv
-// head times query tokens): arrival counters, then partial results for the largest split the launch
-// shape can get.
-int64_t decode_workspace_bytes(const kvq_config* cfg, int64_t rows) {
-  const int64_t upl = (int64_t)cfg->batch * cfg->kv_heads, hd = cfg->head_dim;
-  const int64_t hp = head_parts_of((int)rows, cfg->bits);
-  const int64_t slots = (int64_t)cfg->outlier_budget + cfg->aux_capacity;
-  const int64_t s_max =
-      decode_split(upl * hp, (int)(rows / hp), (int)(hd / cfg->group_v), cfg->max_seq, res_rows_of(cfg) + slots).splits;
-  return kCounterBytes(upl * hp) + upl * s_max * rows * (hd + 2) * 4;
-}
-
 int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, int32_t q_tokens, kvq_qcache qc,
                       int32_t n_quant, kvq_residual res, int32_t res_start, int32_t n_res, const int32_t* seq_state,
                       const void* k_new, const void* v_new, kvq_pool pool, void* out, void* workspace,
-                      size_t workspace_bytes, void* stream, bool static_scratch = false) {
+                      size_t workspace_bytes, void* stream, bool static_scratch = false,
+                      const int32_t* plan = nullptr) {
   const int32_t st = check_config(cfg);
   if (st != KVQ_OK) return st;
   if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
@@ -539,6 +576,17 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, int32
   a.splits = sp.splits;
   a.nw = sp.nw;
   a.mc_per_split = sp.mc_per_split;
+  a.plan = nullptr;
+  a.plan_entries = 0;
+  if (plan) {                                            // the plan's own shape; splits are per sequence
+    const PlanShape ps = plan_shape(cfg);
+    if (ps.entries == 0 || q_tokens != 1 || k_new) return KVQ_ERR_UNSUPPORTED;
+    a.plan = plan;
+    a.plan_entries = ps.entries;
+    a.nw = ps.nw;
+    a.splits = 1;
+    a.seq = nullptr;
+  }
   if (static_scratch && sp.splits > 1) {
     // The array is shared by every call on this device, whatever its shape: where this launch keeps its
     // arrival counters an earlier one may have left partial results.  They must start at zero.
@@ -608,6 +656,36 @@ int32_t kvq_append_decode_attention(const kvq_config* cfg, int32_t layer, const 
   if (!k_new || !v_new) return KVQ_ERR_INVALID_ARG;
   return decode_common(cfg, layer, q, 1, qc, n_quant, res, res_start, n_res, nullptr, k_new, v_new, pool, out,
                        workspace, workspace_bytes, stream);
+}
+
+int64_t kvq_seq_plan_bytes(const kvq_config* cfg) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  const PlanShape ps = plan_shape(cfg);
+  if (ps.entries == 0) return KVQ_ERR_UNSUPPORTED;
+  return (8 + kPlanEntryWords * (int64_t)ps.entries) * 4;
+}
+
+int32_t kvq_seq_plan(const kvq_config* cfg, const int32_t* seq_state, int32_t max_n_quant, int32_t max_n_res,
+                     int32_t* plan, void* stream) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  const PlanShape ps = plan_shape(cfg);
+  if (ps.entries == 0) return KVQ_ERR_UNSUPPORTED;
+  if (!seq_state || (((uintptr_t)seq_state) & 15) || !plan || (((uintptr_t)plan) & 15)) return KVQ_ERR_INVALID_ARG;
+  if (max_n_quant < 0 || max_n_quant > cfg->max_seq || max_n_quant % cfg->group_k != 0) return KVQ_ERR_INVALID_ARG;
+  if (max_n_res < 0 || max_n_res > (int32_t)res_rows_of(cfg)) return KVQ_ERR_INVALID_ARG;
+  return from_hip(kvq::launch_seq_plan(make_dims(cfg, 0), seq_state, max_n_quant, max_n_res, ps.entries, plan,
+                                       (hipStream_t)stream));
+}
+
+int32_t kvq_decode_attention_planned(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc,
+                                     kvq_residual res, const int32_t* plan, int32_t max_n_quant, int32_t max_n_res,
+                                     kvq_pool pool, void* out, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+  if (!plan || (((uintptr_t)plan) & 15)) return KVQ_ERR_INVALID_ARG;
+  return decode_common(cfg, layer, q, 1, qc, max_n_quant, res, 0, max_n_res, nullptr, nullptr, nullptr, pool, out,
+                       workspace, workspace_bytes, stream, false, plan);
 }
 
 int32_t kvq_decode_attention_ragged(const kvq_config* cfg, int32_t layer, const void* q, kvq_qcache qc,

@@ -87,6 +87,13 @@ struct DecodeArgs {
   int32_t q_tokens;     // consecutive query tokens attended at once (1 in a plain decode step); the rows of a
   int32_t g_shift;      // kv head are its q_tokens * g (token, query head) pairs, token-major; g = 1 << g_shift
   int32_t mc_per_split; // 128-token mini-chunks of the quantized segment per workgroup
+  // A launch plan (sequences of different lengths dealt by length), or null.  int32: [0] = entries in use;
+  // from [8] on the entries, 8 words each: {sequence, split, splits of the sequence, first mini-chunk,
+  // n_quant, res_start, n_res, end of the mini-chunks}.  The entries of a sequence are consecutive.  With a
+  // plan the grid is (plan_entries, kv heads, 1): workgroup x does entry x; `seq`, `splits` and
+  // `mc_per_split` are not used.
+  const int32_t* plan;
+  int32_t plan_entries;     // entries the plan has room for (the grid's x extent)
 };
 
 hipError_t launch_append(const Dims& d, const __half* k_new, const __half* v_new, __half* k_res, __half* v_res,
@@ -108,6 +115,8 @@ hipError_t launch_group_step(const Dims& d, int32_t group_index, const __half* k
                              __half* v_res, int32_t append_row, int32_t group_row0, const int32_t* seq,
                              const kvq_pool& pool, uint8_t* selected, const kvq_qcache& qc, hipStream_t s);
 hipError_t launch_seq_advance(const Dims& d, int32_t* seq, hipStream_t s);
+hipError_t launch_seq_plan(const Dims& d, const int32_t* seq, int32_t max_n_quant, int32_t max_n_res, int32_t entries,
+                           int32_t* plan, hipStream_t s);
 hipError_t launch_value_tokens(const Dims& d, int32_t first_token, int32_t count, __half* v_res, int32_t ring_row,
                                const kvq_qcache& qc, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);

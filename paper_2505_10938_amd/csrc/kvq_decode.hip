@@ -727,14 +727,12 @@ __device__ __forceinline__ void fp_compute(FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, 
   }
 }
 
-// grid (splits, kv_heads * head_parts, batch), 64 * a.nw threads (a.nw at most what one compute unit
-// holds of this instance), a.nw * sizeof(WaveLds) bytes of dynamic LDS
-
+// One unit (or one split of it) on the calling workgroup.  `entry` < 0: the grid's coordinates say which;
+// otherwise entry `entry` of the launch plan does (a batch of sequences of different lengths dealt by
+// length).  The plan is device data: what is read from it is clamped to bounds the host has checked
+// against the buffers.
 template <int GQ, int BITS, int NV, bool PAGED>
-__global__ void __launch_bounds__(64 * 4 * kDecodeWavesPerSimd) __attribute__((amdgpu_waves_per_eu(kDecodeWavesPerSimd)))
-decode_kernel(DecodeArgs a) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int s_last;
+__device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* smem, int& s_last, int entry) {
   const Dims& d = a.d;
   // Every argument the loads below depend on is fetched here, in one round trip (left to
   // itself the compiler fetches an argument where it is first used, and each such place waits
@@ -752,11 +750,24 @@ decode_kernel(DecodeArgs a) {
   const int nw = a.nw;
   const int nthreads = nw * 64;
   const int m16 = lane & 15, r = lane >> 4;
-  const int split = blockIdx.x;
   // the query heads of a kv head may be dealt to `head_parts` workgroup rows (part-major in
   // blockIdx.y, so that the parts of one kv head tend to land on the same compute die)
   const int h = blockIdx.y % d.kv_heads, part = blockIdx.y / d.kv_heads;
-  const int b = blockIdx.z;
+  int split = blockIdx.x, b = blockIdx.z, n_splits = a.splits;
+  int64_t part_first = -1;                               // first slot of the unit's partial results (plan only)
+  int4 planned = {0, 0, 0, 0};
+  int plan_mc_begin = 0, plan_mc_end = 0;
+  if (entry >= 0) {
+    const int32_t* e = a.plan + 8 + 8 * entry;
+    const int4 e0 = *(const int4*)e;
+    planned = *(const int4*)(e + 4);
+    b = min(max(e0.x, 0), d.batch - 1);
+    n_splits = min(max(e0.z, 1), a.plan_entries);
+    split = min(max(e0.y, 0), n_splits - 1);
+    plan_mc_begin = e0.w;
+    plan_mc_end = planned.w;
+    part_first = (int64_t)blockIdx.y * a.plan_entries + min(max(entry - split, 0), a.plan_entries - n_splits);
+  }
   const int ul = b * d.kv_heads + h;                     // the unit whose cache is read
   const int wl = ul * a.head_parts + part;               // its slice of the workspace
   // The rows handled here: GQ consecutive (query token, query head) pairs of the kv head, token-major
@@ -770,14 +781,13 @@ decode_kernel(DecodeArgs a) {
   const float qscale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
   WaveLds<GQ, NV>& L = ((WaveLds<GQ, NV>*)smem)[wave];
   const __half* qbase = a.q + row_elem(0);               // also stands in for rows that do not exist
-  const int n_splits = a.splits;
   // A batch of sequences of different lengths: each sequence's own state, read from memory.  The
   // arguments' values bound it (the host has checked them against the buffers), so that whatever
   // the array holds every access below stays inside the buffers.
   Seq sq = {a.n_quant, a.res_start, a.n_res, a.n_res};
   if (a.k_new) sq.n_res += 1;                            // the token being decoded: the newest residual row
-  if (a.seq) {
-    const int4 own = *(const int4*)(a.seq + 4 * b);        // uniform: one scalar load
+  if (a.seq || entry >= 0) {
+    const int4 own = entry >= 0 ? planned : *(const int4*)(a.seq + 4 * b);   // uniform: one scalar load
     sq.n_quant = min(max(own.x, 0), a.n_quant) & ~(kBlockTokens - 1);
     sq.res_start = (own.y >= 0 && own.y < d.res_rows) ? own.y & ~15 : 0;   // (a row group of 16 must not wrap)
     sq.n_res = min(max(own.z, 0), a.n_res);
@@ -791,7 +801,11 @@ decode_kernel(DecodeArgs a) {
   P.block_bytes = (uint32_t)d.block_bytes;
   P.table = PAGED ? d.page_table + (int64_t)b * d.table_stride : nullptr;
   P.n_pages = d.n_pages;
-  int mc = split * a.mc_per_split + wave;
+  // the mini-chunks of the quantized segment that are this workgroup's: [mc_begin, mc_end)
+  const int n_mc = (sq.n_quant + kMiniChunk - 1) / kMiniChunk;
+  const int mc_begin = entry >= 0 ? min(max(plan_mc_begin, 0), n_mc) : split * a.mc_per_split;
+  const int mc_end = entry >= 0 ? min(max(plan_mc_end, mc_begin), n_mc) : min(n_mc, (split + 1) * a.mc_per_split);
+  int mc = mc_begin + wave;
   // A paged cache: the page numbers of the wave's first two mini-chunks are asked for before
   // everything else, so that the loads of the first mini-chunk can follow as soon as possible
   // (from then on the entries of a mini-chunk are fetched one mini-chunk ahead of its loads).
@@ -845,8 +859,6 @@ decode_kernel(DecodeArgs a) {
   P.km = (const unsigned char*)(a.k_meta + uq * d.groups_per_unit * kHeadDim);
   P.vm = (const unsigned char*)a.v_meta + uq * d.blocks_per_unit * (int64_t)(128 * NV);
   P.mask = (const unsigned char*)(a.mask + uq * d.blocks_per_unit);
-  const int n_mc = (sq.n_quant + kMiniChunk - 1) / kMiniChunk;
-  const int mc_end = min(n_mc, (split + 1) * a.mc_per_split);
   const bool has_q = mc < mc_end;                        // uniform over the wave
   McRegs<BITS, NV> R;
   if constexpr (PAGED) P.resolve(mc, pages_now, lane);
@@ -970,7 +982,8 @@ decode_kernel(DecodeArgs a) {
 
   // ---- merge the 2 nw results: the output itself if this workgroup is the unit's only one, else its partial
   __syncthreads();
-  float* part_out = a.partials + ((int64_t)wl * n_splits + split) * GQ * (kHeadDim + 2);
+  const int64_t part_slot0 = part_first >= 0 ? part_first : (int64_t)wl * n_splits;
+  float* part_out = a.partials + (part_slot0 + split) * GQ * (kHeadDim + 2);
   for (int i = tid; i < GQ * kHeadDim; i += nthreads) {
     const int j = i / kHeadDim, c = i % kHeadDim;
     const int jv = c / (kHeadDim / NV);
@@ -1017,7 +1030,7 @@ decode_kernel(DecodeArgs a) {
   __syncthreads();
   if (s_last) {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    const float* pu = a.partials + (int64_t)wl * n_splits * GQ * (kHeadDim + 2);
+    const float* pu = a.partials + part_slot0 * GQ * (kHeadDim + 2);
     constexpr int kBatch = 8;                            // partials fetched per round trip
     for (int i = tid; i < GQ * kHeadDim; i += nthreads) {
       const int j = i / kHeadDim, c = i % kHeadDim;
@@ -1052,6 +1065,21 @@ decode_kernel(DecodeArgs a) {
     if (tid == 0)                                        // leave the counter as it was found
       __hip_atomic_store(&a.counters[wl], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+}
+
+// grid (splits, kv_heads * head_parts, batch), or with a launch plan (entries, kv_heads, 1); 64 * a.nw threads
+// (a.nw at most what one compute unit holds of this instance), a.nw * sizeof(WaveLds) bytes of dynamic LDS.
+template <int GQ, int BITS, int NV, bool PAGED>
+__global__ void __launch_bounds__(64 * 4 * kDecodeWavesPerSimd) __attribute__((amdgpu_waves_per_eu(kDecodeWavesPerSimd)))
+decode_kernel(DecodeArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int s_last;
+  int entry = -1;
+  if (a.plan) {
+    entry = blockIdx.x;
+    if (entry >= min(a.plan[0], a.plan_entries)) return;
+  }
+  decode_item<GQ, BITS, NV, PAGED>(a, smem, s_last, entry);
 }
 
 template <int GQ, int BITS, int NV, bool PAGED>
@@ -1102,7 +1130,7 @@ int decode_wave_lds_bytes(int g, int nv) {
 }
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s) {
-  const dim3 grid(a.splits, a.d.kv_heads * a.head_parts, a.d.batch);
+  const dim3 grid(a.plan ? a.plan_entries : a.splits, a.d.kv_heads * a.head_parts, a.plan ? 1 : a.d.batch);
   switch ((a.q_tokens << a.g_shift) / a.head_parts) {
     case 1: launch_bits<1>(a, grid, s); break;
     case 2: launch_bits<2>(a, grid, s); break;

@@ -613,6 +613,83 @@ __global__ void seq_advance_kernel(Dims d, int32_t* seq) {
   *(int4*)(seq + 4 * b) = own;
 }
 
+// A launch plan for the decode attention of sequences of different lengths: `entries` workgroups per kv
+// head are dealt to the sequences by the work each has (mini-chunks of quantized tokens, groups of
+// full-precision rows at half a mini-chunk each), every sequence at least one; a sequence's workgroups
+// share its mini-chunks equally.  The share m of one workgroup is the smallest for which the sequences'
+// workgroups, ceil(work / m) each, are at most `entries` in all (found by bisection: that count does not
+// grow with m).  One workgroup, one thread per sequence.
+__global__ void __launch_bounds__(1024) seq_plan_kernel(Dims d, const int32_t* __restrict__ seq, int32_t max_nq,
+                                                         int32_t max_nres, int32_t entries, int32_t* __restrict__ plan) {
+  __shared__ int s_acc;
+  __shared__ int s_wave[16];
+  const int b = threadIdx.x;
+  const bool live = b < d.batch;
+  int nq = 0, rs = 0, nr = 0, w = 0, mc = 0;
+  if (live) {
+    const int4 own = *(const int4*)(seq + 4 * b);
+    nq = min(max(own.x, 0), max_nq) & ~(kBlockTokens - 1);
+    rs = (own.y >= 0 && own.y < d.res_rows) ? own.y & ~15 : 0;
+    nr = min(max(own.z, 0), max_nres);
+    mc = (nq + kMiniChunk - 1) / kMiniChunk;
+    w = 2 * mc + ((nr + kFpGroupRows - 1) / kFpGroupRows) + ((d.pool_slots + kFpGroupRows - 1) / kFpGroupRows);
+  }
+  auto block_sum = [&](int v) {
+    if (threadIdx.x == 0) s_acc = 0;
+    __syncthreads();
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    if ((threadIdx.x & 63) == 0) atomicAdd(&s_acc, v);
+    __syncthreads();
+    const int r = s_acc;
+    __syncthreads();
+    return r;
+  };
+  auto block_max = [&](int v) {
+    if (threadIdx.x == 0) s_acc = 0;
+    __syncthreads();
+    for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off));
+    if ((threadIdx.x & 63) == 0) atomicMax(&s_acc, v);
+    __syncthreads();
+    const int r = s_acc;
+    __syncthreads();
+    return r;
+  };
+  auto splits_for = [&](int m) { return live ? min(max((w + m - 1) / m, 1), max(mc, 1)) : 0; };
+  int lo = 1, hi = max(block_max(w), 1);                // at m = hi every sequence has one workgroup: entries >= batch
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (block_sum(splits_for(mid)) <= entries) hi = mid;
+    else lo = mid + 1;
+  }
+  const int sp = splits_for(lo);
+  // exclusive prefix of the sequences' workgroup counts
+  int incl = sp;
+  for (int off = 1; off < 64; off <<= 1) {
+    const int up = __shfl_up(incl, off);
+    if ((threadIdx.x & 63) >= off) incl += up;
+  }
+  if ((threadIdx.x & 63) == 63) s_wave[threadIdx.x >> 6] = incl;
+  __syncthreads();
+  int before = 0;
+  for (int k = 0; k < (int)(threadIdx.x >> 6); ++k) before += s_wave[k];
+  const int first = before + incl - sp;
+  if (threadIdx.x == 1023) plan[0] = min(first + sp, entries);
+  if (live) {
+    const int per = (mc + sp - 1) / sp;                  // mini-chunks per workgroup of this sequence
+    for (int k = 0; k < sp && first + k < entries; ++k) {
+      int4* e = (int4*)(plan + 8 + 8 * (first + k));
+      e[0] = make_int4(b, k, sp, min(k * per, mc));
+      e[1] = make_int4(nq, rs, nr, min((k + 1) * per, mc));
+    }
+  }
+}
+
+hipError_t launch_seq_plan(const Dims& d, const int32_t* seq, int32_t max_n_quant, int32_t max_n_res, int32_t entries,
+                           int32_t* plan, hipStream_t s) {
+  hipLaunchKernelGGL(seq_plan_kernel, dim3(1), dim3(1024), 0, s, d, seq, max_n_quant, max_n_res, entries, plan);
+  return hipGetLastError();
+}
+
 hipError_t launch_seq_advance(const Dims& d, int32_t* seq, hipStream_t s) {
   hipLaunchKernelGGL(seq_advance_kernel, dim3((d.batch + 255) / 256), dim3(256), 0, s, d, seq);
   return hipGetLastError();

@@ -463,7 +463,7 @@ def test_ragged_batch_streaming(kw, lengths):
     run_ragged(kw, lengths)
 
 
-def run_ragged(kw, lengths, make_cache=None):
+def run_ragged(kw, lengths, make_cache=None, planned=False):
     """Sequences of different lengths in one batch: tokens are appended step by step to the
     sequences that are still growing (one launch per step and layer, the state kept on the device),
     then one decode launch serves all of them.  Every unit is compared with the oracle run on its
@@ -487,7 +487,9 @@ def run_ragged(kw, lengths, make_cache=None):
     torch.cuda.synchronize()
     state = cache.seq_state.cpu().numpy()
     Q = S.layer_queries(w, 0, 0, "peaky")
-    got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+    if planned:                                              # workgroups dealt by length
+        cache.make_plan()
+    got = cache.decode(0, torch.from_numpy(Q).cuda(), planned=planned).cpu().numpy().astype(np.float64)
     assert np.isfinite(got).all()
     g = w.q_heads // w.kv_heads
     rows = cache.sizes.res_rows
@@ -504,6 +506,57 @@ def run_ragged(kw, lengths, make_cache=None):
         ref = H.oracle_attention(w, states, Q, K, V, nq, nr, units)
         err = att_err(got[b], ref[b])
         assert err <= ATT_TOL, (b, n, err)
+
+
+@pytest.mark.parametrize("kw,lengths", [
+    (dict(bits=2, group_k=32, group_v=32, residual=32, outlier_budget=4), [45, 3000, 161, 96]),
+    (dict(bits=4, group_k=64, group_v=64, residual=32, outlier_budget=3, q_heads=8), [1, 4000, 95, 960, 33, 2048]),
+    (dict(bits=2, group_k=32, group_v=128, residual=0, outlier_budget=4), [32, 31, 2570, 0]),
+])
+def test_ragged_batch_with_a_launch_plan(kw, lengths):
+    """The same batches through kvq_seq_plan + kvq_decode_attention_planned: the long sequences are split
+    over several workgroups, the short ones have one, and every unit still matches the oracle."""
+    run_ragged(kw, lengths, planned=True)
+
+
+def test_launch_plan_contents():
+    """What the plan holds: every sequence has consecutive entries, numbered 0 .. n-1, which together cover
+    its mini-chunks exactly once and carry a copy of its state; there are no more entries than the launch has
+    workgroups per kv head; longer sequences have more of them."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    lengths = [128 + (8192 - 128) * i // 31 for i in range(32)]
+    G, R = 32, 128
+    cfg = KC.make_config(1, 32, 32, 8, 8192, 2, G, 32, R, 8, 32)
+    cache = KC.RaggedKVCache(cfg)
+    st = torch.zeros(32, 4, dtype=torch.int32)
+    for b, n in enumerate(lengths):
+        nq, nr = ragged_lengths_state(n, G, R)
+        st[b] = torch.tensor([nq, nq % cache.sizes.res_rows, nr, 1])
+    cache.seq_state.copy_(st)
+    cache.longest = max(lengths)
+    cache.make_plan()
+    plan = cache.plan.cpu().numpy()
+    room = (len(plan) - 8) // 8
+    n_entries = int(plan[0])
+    assert 32 <= n_entries <= room
+    entries = plan[8:8 + 8 * n_entries].reshape(n_entries, 8)
+    per_seq = {}
+    for i, e in enumerate(entries):
+        b, split, n_splits, mc0, nq, rs, nr, mc1 = (int(x) for x in e)
+        assert (nq, rs, nr) == tuple(int(x) for x in st[b, :3])
+        per_seq.setdefault(b, []).append((split, n_splits, mc0, mc1, i))
+    assert sorted(per_seq) == list(range(32))
+    counts = []
+    for b in range(32):
+        parts = per_seq[b]
+        n_mc = (int(st[b, 0]) + 127) // 128
+        assert [p[0] for p in parts] == list(range(len(parts))) and all(p[1] == len(parts) for p in parts)
+        assert [p[4] for p in parts] == list(range(parts[0][4], parts[0][4] + len(parts)))     # consecutive entries
+        assert parts[0][2] == 0 and parts[-1][3] == n_mc
+        assert all(parts[i][3] == parts[i + 1][2] for i in range(len(parts) - 1))              # no gap, no overlap
+        counts.append(len(parts))
+    assert counts == sorted(counts) and counts[0] == 1 and counts[-1] >= 2                      # lengths ascend with b
 
 
 def test_ragged_equals_uniform_when_lengths_agree():
