@@ -274,6 +274,31 @@ def test_per_step_value_schedule_configuration_and_arguments():
     assert lib.kvq_prefill_quantize_seq(C.byref(ok), 0, 0, 256, 256, 512 * 128, 512, pool, 256, qc, res, None) == B.KVQ_ERR_UNSUPPORTED
 
 
+def test_launch_plan_sizes_and_arguments():
+    lib = P.load_library()
+    c = cfg(batch=32, q_heads=32, kv_heads=8, max_seq=8192)
+    # 256 compute units x 2 workgroups of 4 wavefronts / 8 kv heads = 64 entries, twice the sequences
+    assert B.kvq_seq_plan_bytes(c) == (8 + 8 * 64) * 4
+    assert B.kvq_seq_plan_bytes(cfg(batch=2, q_heads=8, kv_heads=2)) == (8 + 8 * 128) * 4
+    big = cfg(batch=2000, q_heads=8, kv_heads=8)
+    assert lib.kvq_seq_plan_bytes(C.byref(big)) == B.KVQ_ERR_UNSUPPORTED           # more than 1024 sequences
+    assert lib.kvq_seq_plan_bytes(C.byref(cfg(batch=600, q_heads=8, kv_heads=8))) == B.KVQ_ERR_UNSUPPORTED  # do not fit
+    plan = lambda seq=256, nq=8192, nr=128, pl=512: lib.kvq_seq_plan(C.byref(c), seq, nq, nr, pl, None)
+    bad = B.KVQ_ERR_INVALID_ARG
+    assert plan(seq=None) == bad and plan(seq=260) == bad and plan(pl=None) == bad and plan(pl=520) == bad
+    assert plan(nq=8200) == bad and plan(nq=8224) == bad and plan(nr=161) == bad and plan(nr=-1) == bad
+    # the workspace the sizes report covers the planned launch: one partial result per entry and kv head
+    s = P.kvq_query_sizes(c)
+    assert s.workspace_bytes >= 64 * 8 * 4 * (128 + 2) * 4
+    qc = B.kvq_qcache(256, 256, 256, 256, 256)
+    pool = B.kvq_pool(256, 256, 256, 256, 256, 256, 256)
+    res = B.kvq_residual(256, 256)
+    dec = lambda pl=512, ws=s.workspace_bytes: lib.kvq_decode_attention_planned(
+        C.byref(c), 0, 256, qc, res, pl, 8192, 128, pool, 256, 256, ws, None)
+    assert dec(pl=None) == bad and dec(pl=516) == bad
+    assert dec(ws=s.workspace_bytes - 1) == B.KVQ_ERR_WORKSPACE
+
+
 def test_bad_dequantize_arguments_rejected_before_launch():
     lib = P.load_library()
     c = cfg()
