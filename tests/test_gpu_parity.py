@@ -1078,6 +1078,8 @@ def compare_per_step_values(cache, states, w, n, layer=0):
     dict(bits=4, group_k=32, group_v=64, residual=40, q_heads=2, kv_heads=2),
     dict(bits=2, group_k=64, group_v=128, residual=1, q_heads=8, kv_heads=1),
     dict(bits=4, group_k=128, group_v=32, residual=128, q_heads=2, kv_heads=2),
+    dict(bits=2, group_k=32, group_v=32, residual=32, q_heads=4, kv_heads=2, paged_cache=True),
+    dict(bits=4, group_k=64, group_v=64, residual=20, q_heads=2, kv_heads=2, paged_cache=True),
 ])
 def test_per_step_value_schedule_streaming(kw):
     """Prefill, then decode steps under the per-step Value schedule: the attention of every step
@@ -1086,6 +1088,8 @@ def test_per_step_value_schedule_streaming(kw):
     the every-G-steps schedule without tracing."""
     import torch
     from paper_2505_10938_amd import cache as KC
+    kw = dict(kw)
+    paged_cache = kw.pop("paged_cache", False)
     w = small("per_step", batch=2, outlier_budget=0, aux_capacity=0, context=300, **kw)
     G, R = w.group_k, w.residual
     steps = 2 * G + 9
@@ -1094,7 +1098,7 @@ def test_per_step_value_schedule_streaming(kw):
     ms = ((n0 + steps + G - 1) // G) * G
     cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ms, w.bits, G, w.group_v, R, 0, 0, w.head_dim,
                          value_per_step=1)
-    cache = KC.KVCache(cfg)
+    cache = paged(cfg) if paged_cache else KC.KVCache(cfg)       # (paged: the Value words go through the page table)
     Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
     cache.prefill(0, Kd[:, :, :n0].contiguous(), Vd[:, :, :n0].contiguous())
     torch.cuda.synchronize()
