@@ -221,7 +221,9 @@ int32_t kvq_quantize_group(const kvq_config* cfg, int32_t layer, int32_t group_i
  * kvq_quantize_group, kvq_append_trace_quantize and kvq_prefill_quantize's group pass then leave the
  * Value arrays alone, and kvq_prefill_quantize ends with this call for the tokens between the last
  * whole group and the window.
- *   first_token, count : 0 <= first_token, 1 <= count <= res_rows, first_token + count <= max_seq
+ *   first_token, count : 0 <= first_token, 1 <= count <= res_rows, first_token + count <= max_seq (under
+ *                        this schedule max_seq must cover n - R tokens: Values run up to group_k - 1
+ *                        tokens ahead of the Keys)
  *   ring_row           : in [0, res_rows)
  *   v_res              : device fp16 ring of the Values (read and written), 4-byte aligned
  *   qcache             : dense or paged (the pages of the tokens' groups must be in the table)
