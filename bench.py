@@ -160,7 +160,9 @@ def run_stack(w, layers, steps, warmup, samples, pool, cpu_budget, label, value_
     total = steps + warmup
     # start state: the rings fill (a group step in every layer) in the middle of the timed steps, and the
     # quantized length right after it is the workload's
-    fill_at = warmup + steps // 2                              # index of the step that fills the rings
+    # index of the step that fills the rings (a single timed step: right after it, so that the step timed is one
+    # of the steps the roofline figure is taken from)
+    fill_at = warmup + steps // 2 if steps >= 2 else warmup + 1
     nq_final = G * ((w.context - R) // G)
     n_fills = len([s for s in range(total) if s % G == fill_at % G])
     nq0 = nq_final - G * n_fills
