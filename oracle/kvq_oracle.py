@@ -29,8 +29,8 @@ What follows the paper, by passage:
   Values at each step; Efficiency comparison: that per-step compression is what
   the method saves).  Same quantizer, no tracing.
 
-Readings taken where the paper is silent are listed in the repository's design
-document; each is also stated at the function that implements it.
+Where the paper is silent or ambiguous a reading is taken; each is stated at the
+function that implements it.
 
 Pins: every function here is pinned by tests/test_oracle_*.py (closed forms,
 brute force on tiny inputs, invariants, library routines).  The paper prints no
