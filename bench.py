@@ -317,6 +317,73 @@ def fp16_attention(w, layers=3):
     return {"us_per_launch": round(us, 3), "algorithmic_bytes": int(nbytes), "GBps": round(nbytes / (us * 1e-6) / 1e9, 1)}
 
 
+def ragged_batch(copies=6):
+    """A batch whose sequences differ in length (32 sequences of 128 .. 8192 tokens, 8 kv heads of 4 query
+    heads, 2-bit): one decode-attention launch sized by the longest sequence, the same with a launch plan
+    that deals the workgroups by length, and a batch of 32 sequences of the mean length for comparison.
+    Each figure is the mean over `copies` caches taken in turn (more than the last-level cache holds)."""
+    import torch
+    import kvq_synth as S
+    from paper_2505_10938_amd import cache as KC
+    dev = torch.device("cuda:0")
+    G, R, batch, qh, kvh = 32, 128, 32, 32, 8
+    lengths = [128 + (8192 - 128) * i // (batch - 1) for i in range(batch)]
+    mean_len = sum(lengths) // batch
+    w = S.Workload("ragged_128_8192", layers=1, batch=batch, q_heads=qh, kv_heads=kvh, context=max(lengths), bits=2,
+                   group_k=G, group_v=32, residual=R, outlier_budget=8, aux_capacity=32)
+    synth = DeviceSynth(w, dev)
+    K, V = synth.rows(0, max(lengths))
+
+    def build(lens):
+        cfg = KC.make_config(1, batch, qh, kvh, ((max(lens) + G - 1) // G) * G, 2, G, 32, R, 8, 32)
+        caches = []
+        for _ in range(copies):
+            c = KC.RaggedKVCache(cfg, device=dev)
+            for b, n in enumerate(lens):
+                c.prefill_sequence(b, [K[b, :, :n].contiguous()], [V[b, :, :n].contiguous()])
+            caches.append(c)
+        return caches
+
+    def timed(caches, planned):
+        q = torch.randn((batch, qh, 128), device=dev).to(torch.float16)
+        out = torch.empty_like(q)
+        for c in caches:
+            if planned:
+                c.make_plan()
+            c.decode(0, q, out, planned=planned)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 5
+        e0.record()
+        for _ in range(reps):
+            for c in caches:
+                c.decode(0, q, out, planned=planned)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * len(caches))
+
+    def nbytes(lens):
+        tot = 0
+        for n in lens:
+            nq = G * ((n - R) // G) if n >= R + G else 0
+            tot += decode_bytes(w.with_(batch=1), nq, n - nq, 8)
+        return tot
+
+    ragged = build(lengths)
+    t_plain, t_plan = timed(ragged, False), timed(ragged, True)
+    del ragged
+    torch.cuda.empty_cache()
+    uniform = build([mean_len] * batch)
+    t_mean = timed(uniform, False)
+    del uniform, K, V
+    torch.cuda.empty_cache()
+    return {"sequences": batch, "tokens": f"{min(lengths)} .. {max(lengths)} (mean {mean_len})",
+            "algorithmic_bytes": int(nbytes(lengths)),
+            "decode_us_sized_by_the_longest": round(t_plain, 3), "decode_us_with_a_launch_plan": round(t_plan, 3),
+            "decode_us_all_sequences_of_the_mean_length": round(t_mean, 3),
+            "planned_over_mean_length": round(t_plan / t_mean, 3)}
+
+
 def read_ceiling():
     """Read bandwidth a trivial 16-byte-load kernel reaches on this device over a buffer larger than the
     last-level cache (context for the roofline fraction, which stays quoted against 8 TB/s)."""
@@ -494,6 +561,7 @@ def main():
             ab["note"] = ("outlier_budget 0 in both; values_at_each_step adds one launch of kvq_quantize_value_tokens "
                           "per layer and step and its group steps quantize Keys only")
             result["value_schedule_ab"] = ab
+            result["ragged_batch"] = ragged_batch()
         for (we, le) in extras:
             r = run_stack(we, le, args.steps, args.warmup, [], None, 0.0, we.name)
             result.setdefault("other_workloads", {})[we.name] = {
