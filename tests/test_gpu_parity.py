@@ -423,6 +423,44 @@ def test_prefill_equals_streaming(kw):
     run_prefill(S.Workload("prefill", 1, **base))
 
 
+@pytest.mark.parametrize("G,N,A", [(128, 64, 64), (64, 64, 20), (32, 5, 64), (128, 1, 0)])
+def test_prefill_with_tied_scores_and_large_budgets(G, N, A):
+    """The prompt's competitions on keys with many equal L1 scores (rows repeated, rows with permuted
+    channels, signs flipped), so that the order falls back on the token index again and again, with
+    budgets up to the largest supported and groups of up to two 64-token passes: the pools, flags,
+    stop rule and codes are still those of the group-by-group competition."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    w = S.Workload("prefill_ties", 1, batch=2, q_heads=2, kv_heads=2, context=G * 9 + 40, bits=2, group_k=G,
+                   group_v=32, residual=32, outlier_budget=N, aux_capacity=A)
+    K, V = S.layer_kv(w, 0)
+    rng = np.random.default_rng(5)
+    for b in range(w.batch):
+        for h in range(w.kv_heads):
+            base_rows = K[b, h, :7].copy()
+            for t in range(7, w.context):
+                kind = rng.integers(0, 4)
+                if kind == 0:
+                    K[b, h, t] = base_rows[rng.integers(0, 7)]                       # the same row again
+                elif kind == 1:
+                    K[b, h, t] = -base_rows[rng.integers(0, 7)][rng.permutation(128)]  # same magnitudes
+                elif kind == 2:
+                    K[b, h, t] = K[b, h, t] * np.float16(0.05)                         # a small one
+    nq, nr = w.n_quant, w.n_res
+    states = H.oracle_states(w, K, V, nq)
+    if N >= 64:                                               # members with equal scores: the index decided
+        assert any(len({m["score"] for m in st.pool + st.aux}) < len(st.pool + st.aux) for st in states)
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, nq, w.bits, G, w.group_v, w.residual, N, A, w.head_dim)
+    cache = KC.KVCache(cfg)
+    cache.prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
+    torch.cuda.synchronize()
+    H.compare_state(cache, states, w, nq)
+    Q = S.layer_queries(w, 0, 0, "diffuse")
+    ref = H.oracle_attention(w, states, Q, K, V, nq, nr)
+    got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+    assert att_err(got, ref) <= ATT_TOL
+
+
 def test_prefill_then_stream():
     # a prompt quantized in one call, then tokens appended one by one (fused group steps)
     import torch
