@@ -597,6 +597,58 @@ def test_launch_plan_contents():
     assert counts == sorted(counts) and counts[0] == 1 and counts[-1] >= 2                      # lengths ascend with b
 
 
+def test_full_size_ragged_batch_with_a_launch_plan_sampled_units():
+    """The batch the benchmark's ragged lines run: 32 sequences of 128 .. 8192 tokens, 8 kv heads of 4 query
+    heads, each sequence prefilled on its own.  Sampled units (the shortest, the longest, some between; one to
+    four workgroups each under the plan) against the oracle, with and without the launch plan, in both query
+    regimes; the two launches differ by no more than the rounding of the output."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    G, R, batch = 32, 128, 32
+    lengths = [128 + (8192 - 128) * i // (batch - 1) for i in range(batch)]
+    w = S.Workload("ragged_full", 1, batch=batch, q_heads=32, kv_heads=8, context=max(lengths), bits=2, group_k=G,
+                   group_v=32, residual=R, outlier_budget=8, aux_capacity=32)
+    cfg = KC.make_config(1, batch, w.q_heads, w.kv_heads, max(lengths), 2, G, 32, R, 8, 32)
+    cache = KC.RaggedKVCache(cfg)
+    sampled = [(0, 0), (0, 7), (9, 3), (16, 5), (24, 1), (31, 0), (31, 6)]       # (sequence, kv head)
+    host = {}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    for b, n in enumerate(lengths):
+        k = torch.randn((w.kv_heads, n, 128), generator=gen, device="cuda", dtype=torch.float32).to(torch.float16)
+        v = torch.randn((w.kv_heads, n, 128), generator=gen, device="cuda", dtype=torch.float32).to(torch.float16)
+        for (sb, h) in sampled:
+            if sb == b:                                   # units the oracle sees: kvq_synth's rows
+                kh, vh = S.unit_kv(w.seed, 0, b, h, n, 128, w.rho)
+                k[h].copy_(torch.from_numpy(kh))
+                v[h].copy_(torch.from_numpy(vh))
+                host[(b, h)] = (kh, vh)
+        cache.prefill_sequence(b, [k.contiguous()], [v.contiguous()])
+    cache.make_plan()
+    plan = cache.plan.cpu().numpy()
+    splits_of = {int(e[0]): int(e[2]) for e in plan[8:8 + 8 * int(plan[0])].reshape(-1, 8)}
+    assert splits_of[0] == 1 and splits_of[31] >= 2
+    g = w.q_heads // w.kv_heads
+    from oracle import kvq_oracle as O
+    for regime in ("peaky", "diffuse"):
+        Q = S.layer_queries(w, 0, 0, regime)
+        qd = torch.from_numpy(Q).cuda()
+        plain = cache.decode(0, qd).cpu().numpy().astype(np.float64)
+        planned = cache.decode(0, qd, planned=True).cpu().numpy().astype(np.float64)
+        assert np.isfinite(planned).all()
+        # (different splits of a sequence, different summation order: at most the output's rounding apart)
+        assert np.abs(plain - planned).max() <= np.maximum(ATT_TOL, 2 * np.spacing(np.float16(np.abs(plain).max())))
+        for (b, h), (kh, vh) in host.items():
+            n = lengths[b]
+            nq, nr = ragged_lengths_state(n, G, R)
+            st = O.UnitState(128, 2, G, 32, 8, 32)
+            for i in range(nq // G):
+                st.append_group(kh[i * G:(i + 1) * G], vh[i * G:(i + 1) * G])
+            ref, _ = O.decode_attention(Q[b, h * g:(h + 1) * g], st, kh[nq:n], vh[nq:n])
+            for got in (plain, planned):
+                assert att_err(got[b, h * g:(h + 1) * g], ref) <= ATT_TOL, (regime, b, h)
+
+
 def test_ragged_equals_uniform_when_lengths_agree():
     """The ragged entry points on a batch whose sequences all have the same state give the bytes and
     the outputs of the uniform ones."""
