@@ -1212,6 +1212,73 @@ def test_per_step_value_schedule_streaming(kw):
     H.compare_state(cache, plain, w, nq)
 
 
+def test_per_step_value_schedule_batch_128_layer_sampled_units():
+    """The schedule comparison's stack shape (batch 128, 8 kv heads of 4 query heads, no tracing: 1024 units
+    per layer, one workgroup of two wavefronts each), second layer of two: a prompt, then steps through a
+    group step; sampled units against the oracle, attention at every step, Value words and ring rows at
+    the end."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    layer = 1
+    w = S.WORKLOADS["mistral_7b_b128_4k"].with_(name="b128_per_step", layers=2, context=1024 + 128 + 25, outlier_budget=0,
+                                                aux_capacity=0)
+    G, R = w.group_k, w.residual
+    steps = 12
+    n0 = w.context
+    K, V = S.layer_kv(w, layer, n0 + steps)
+    ms = ((n0 + steps + G - 1) // G) * G
+    cfg = KC.make_config(2, w.batch, w.q_heads, w.kv_heads, ms, w.bits, G, w.group_v, R, 0, 0, w.head_dim, value_per_step=1)
+    assert B.kvq_decode_launch_shape(cfg, 1, w.n_quant, w.n_res)[:2] == (1, 2)
+    cache = KC.KVCache(cfg)
+    Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+    cache.prefill(layer, Kd[:, :, :n0].contiguous(), Vd[:, :, :n0].contiguous())
+    units = [0, 7, 8 * 63 + 2, 1023]
+    from oracle import kvq_oracle as O
+    g = w.q_heads // w.kv_heads
+    states = {}
+    for ui in units:
+        b, h = divmod(ui, w.kv_heads)
+        states[ui] = O.PerStepValueUnit(w.head_dim, w.bits, G, w.group_v)
+    group_steps = 0
+    for s in range(steps):
+        n = n0 + s + 1
+        Q = S.layer_queries(w, layer, s, "peaky" if s % 2 else "diffuse")
+        nq_before = cache.n_quant[layer]
+        got = cache.step(layer, Kd[:, :, n - 1].contiguous(), Vd[:, :, n - 1].contiguous(),
+                         torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+        group_steps += cache.n_quant[layer] != nq_before
+        for ui in units:
+            b, h = divmod(ui, w.kv_heads)
+            st = states[ui]
+            st.advance_to(K[b, h], V[b, h], n, R)
+            assert cache.n_quant[layer] == st.n_quant
+            ref, _ = O.decode_attention(Q[b, h * g:(h + 1) * g], st, K[b, h, st.n_quant:n], V[b, h, st.n_quant:n])
+            assert att_err(got[b, h * g:(h + 1) * g], ref) <= ATT_TOL, (s, ui)
+    assert group_steps == 1
+    # the state at the end: closed groups, the Value words written token by token, the ring rows that hold
+    # dequantized Values
+    nq, nqv = states[units[0]].n_quant, states[units[0]].n_quant_v
+    H.compare_state(cache, [states[ui] for ui in units], w, nq, layer=layer, units=units)
+    sz = cache.sizes
+    ring = cache.res_view("v").cpu().numpy()
+    _, _, v_codes, _, _ = (t.cpu().numpy() for t in cache.dense_quantized())
+    bb = 512 * w.bits
+    vc = v_codes[:sz.units * (cfg.max_seq // 32) * bb].reshape(sz.units, cfg.max_seq // 32, bb)
+    for ui in units:
+        st = states[ui]
+        u = layer * w.units + ui
+        for t in range(nq, nqv):
+            row = (cache.res_start[layer] + t - nq) % sz.res_rows
+            assert np.array_equal(ring[u, row].view(np.uint16), st.v_hat[t].view(np.uint16)), (ui, t)
+        blk = nq // 32
+        codes = np.zeros((32, w.head_dim), np.uint8)
+        written = np.zeros((32, w.head_dim), np.uint8)
+        codes[:nqv - nq] = st.v_codes[nq:nqv]
+        written[:nqv - nq] = (1 << w.bits) - 1
+        assert np.array_equal(vc[u, blk] & O.pack_v_block(written, w.bits), O.pack_v_block(codes, w.bits)), ui
+    assert not cache.v_codes[:w.units * (cfg.max_seq // 32) * bb].any()        # the first layer was not touched
+
+
 def test_per_step_value_schedule_from_an_empty_cache():
     """No prompt: the first tokens stay inside the window, then Values start to leave it one by one
     before any Key group closes."""
