@@ -67,6 +67,9 @@ WORKLOADS = {
 # tokens) and its 4-bit and grouped-query relatives; same shapes otherwise.
 WORKLOADS["llama2_7b_4k_g128"] = WORKLOADS["llama2_7b_4k"].with_(name="llama2_7b_4k_g128", group_k=128, group_v=128,
                                                                  residual=32, outlier_budget=3)
+# the paper's main setting on the batch-128 stack of grouped-query models (one layer, timed on copies)
+WORKLOADS["mistral_7b_b128_4k_g128_layer"] = WORKLOADS["mistral_7b_b128_4k"].with_(
+    name="mistral_7b_b128_4k_g128_layer", layers=1, group_k=128, group_v=128, residual=32, outlier_budget=3)
 WORKLOADS["llama2_7b_4k_4bit"] = WORKLOADS["llama2_7b_4k"].with_(name="llama2_7b_4k_4bit", bits=4)
 WORKLOADS["llama3_8b_4k_gqa"] = WORKLOADS["llama2_7b_4k"].with_(name="llama3_8b_4k_gqa", batch=32, kv_heads=8)
 WORKLOADS["llama2_7b_4k_b1"] = WORKLOADS["llama2_7b_4k"].with_(name="llama2_7b_4k_b1", batch=1)
