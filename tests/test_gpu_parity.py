@@ -550,6 +550,7 @@ def run_ragged(kw, lengths, make_cache=None, planned=False):
     (dict(bits=2, group_k=32, group_v=32, residual=32, outlier_budget=4), [45, 3000, 161, 96]),
     (dict(bits=4, group_k=64, group_v=64, residual=32, outlier_budget=3, q_heads=8), [1, 4000, 95, 960, 33, 2048]),
     (dict(bits=2, group_k=32, group_v=128, residual=0, outlier_budget=4), [32, 31, 2570, 0]),
+    (dict(bits=2, group_k=128, group_v=128, residual=32, outlier_budget=3), [130, 2900, 700, 33, 161]),
 ])
 def test_ragged_batch_with_a_launch_plan(kw, lengths):
     """The same batches through kvq_seq_plan + kvq_decode_attention_planned: the long sequences are split
@@ -1015,6 +1016,8 @@ def test_dequantized_rows_bit_exact(kw, use_pages):
     (1, 8, dict(residual=32)),                               # eight rows per kv head: two workgroup rows
     (4, 2, dict(residual=7, context=32 * 30 + 20)),          # the same, with grouped queries
     (2, 4, dict(context=8192 + 100, batch=1, kv_heads=2)),   # a long unit: several workgroups and the merge
+    (2, 2, dict(bits=2, group_k=128, group_v=128, residual=32, outlier_budget=3, context=128 * 9 + 50)),  # one Key group per mini-chunk
+    (1, 4, dict(bits=4, group_k=128, group_v=32, residual=32, outlier_budget=3, context=128 * 5 + 40)),
 ])
 def test_several_query_tokens_at_once(g, tokens, kw):
     """kvq_decode_attention_multi: the `tokens` newest tokens of every sequence attend in one launch, each
