@@ -475,9 +475,8 @@ def main():
     main_res = run_stack(w, layers, args.steps, args.warmup, samples if pool else [], pool, budget, w.name)
 
     frac = main_res["dec_bytes"] / (main_res["dec_us"] * 1e-6) / 1e9 / HBM_PEAK_GBPS
-    # template arguments: query rows per kv head, bits, Value groups per token, paged cache, Key groups of 128 tokens
-    kern = (f"decode_kernel<{w.q_heads // w.kv_heads},{w.bits},{w.head_dim // w.group_v},false,"
-            f"{'true' if w.group_k == 128 else 'false'}>")
+    # template arguments: query rows per kv head, bits, Value groups per token, paged cache, blocks per Key group
+    kern = f"decode_kernel<{w.q_heads // w.kv_heads},{w.bits},{w.head_dim // w.group_v},false,{w.group_k // 32}>"
     what = (f"{w.name}: {layers} layers" if stacked else f"{w.name}: {layers} independent copies of the layer")
     result = {
         "metric": "decode_attention_kv_GBps_2bit_1xMI355X" if w.bits == 2 else "decode_attention_kv_GBps",

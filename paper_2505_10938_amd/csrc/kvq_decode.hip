@@ -342,12 +342,13 @@ __device__ __forceinline__ void load_k_meta_block(McRegs<BITS, NV>& R, const PT&
   R.ksp[i] = *(const uint32_t*)(gp + lane * 4u);
   R.ksz[i] = *(const uint32_t*)(gp + 256 + lane * 4u);
 }
-// (SH: the four blocks of a mini-chunk lie in one Key group - groups of 128 tokens - and share its steps
-// and zeros: they are loaded, and the operand rows made of them are formed, once per mini-chunk)
-template <int BITS, int NV, bool SH, class PT>
+// (SB: how many consecutive blocks of a mini-chunk lie in one Key group - 1, 2 or 4 for groups of 32, 64 or
+// 128 tokens - and share its steps and zeros: those are loaded, and the operand rows made of them are
+// formed, once per group, by the group's first block)
+template <int BITS, int NV, int SB, class PT>
 __device__ __forceinline__ void load_k_meta(McRegs<BITS, NV>& R, const PT& P, int mc, int lane) {
 #pragma unroll
-  for (int i = 0; i < (SH ? 1 : 4); ++i) load_k_meta_block(R, P, mc, i, lane);
+  for (int i = 0; i < 4; i += SB) load_k_meta_block(R, P, mc, i, lane);
 }
 template <int BITS, class PT>
 __device__ __forceinline__ void load_codes_block(uint32_t (&w)[4][2 * BITS], const unsigned char* codes,
@@ -392,7 +393,7 @@ struct WaveAcc {
   float m[GQ];       // running maximum per head (log2 domain)
 };
 
-template <int GQ, int BITS, int NV, bool SH, bool more, class PT>
+template <int GQ, int BITS, int NV, int SB, bool more, class PT>
 __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<GQ>& S, WaveLds<GQ, NV>& L,
                                                   const half2v (&qh)[GQ], const half2v (&ql)[GQ], int lane,
                                                   const PT& P, int mc_next) {
@@ -408,19 +409,19 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
   const int m16 = lane & 15, r = lane >> 4;
   constexpr int R2 = 2 * GQ;
   const int arow = m16 % R2;          // rows beyond 2*GQ repeat valid rows (their results are unused)
-  auto key_rows = [&](int i) {          // q*step (hi/lo per head) of block i
+  auto key_rows = [&](int i) {          // q*step (hi/lo per head) of the Key group that block i begins
 #pragma unroll
     for (int j = 0; j < GQ; ++j) {
       uint32_t hi, lo;
       mul_split(qh[j], ql[j], as_half2(R.ksp[i]), hi, lo);
-      ((uint32_t*)L.k.aop[i & 1][2 * j])[lane] = hi;
-      ((uint32_t*)L.k.aop[i & 1][2 * j + 1])[lane] = lo;
+      ((uint32_t*)L.k.aop[(i / SB) & 1][2 * j])[lane] = hi;
+      ((uint32_t*)L.k.aop[(i / SB) & 1][2 * j + 1])[lane] = lo;
     }
   };
 
   wave_sync();                          // the previous mini-chunk is done with the shared storage
 #pragma unroll
-  for (int i = 0; i < (SH ? 1 : 4); ++i) ((uint32_t*)L.k.zk[i])[lane] = R.ksz[i];
+  for (int i = 0; i < 4; i += SB) ((uint32_t*)L.k.zk[i])[lane] = R.ksz[i];
   key_rows(0);
   if (more) load_k_meta_block(R, P, mc_next, 0, lane);
   wave_sync();
@@ -431,7 +432,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
       Dq = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds_operand(L.q0[arow], cb * 64 + r * 16),
-                                                  lds_operand(L.k.zk[SH ? 0 : (m16 & 3)], cb * 64 + r * 16), Dq, 0, 0, 0);
+                                                  lds_operand(L.k.zk[(m16 & 3) & ~(SB - 1)], cb * 64 + r * 16), Dq, 0, 0, 0);
     if (m16 < 4) {
       if (2 * r < GQ) L.qz[m16][2 * r] = Dq[0] + Dq[1];
       if (2 * r + 1 < GQ) L.qz[m16][(2 * r + 1) % GQ] = Dq[2] + Dq[3];
@@ -440,7 +441,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
   // ---- scores (left in units of 2^-(24 - kShK); the softmax scales them) -----------------------------
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    if (i + 1 < 4 && !SH) {
+    if (i + 1 < 4 && (i + 1) % SB == 0) {
       key_rows(i + 1);
       if (more) load_k_meta_block(R, P, mc_next, i + 1, lane);
     }
@@ -448,7 +449,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
     float4v D0 = {0.f, 0.f, 0.f, 0.f}, D1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb) {
-      const half8 aq = lds_operand(L.k.aop[SH ? 0 : (i & 1)][arow], cb * 64 + r * 16);
+      const half8 aq = lds_operand(L.k.aop[(i / SB) & 1][arow], cb * 64 + r * 16);
       D0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq, field_operand<BITS>(R.kc[i], cb), D0, 0, 0, 0);
       D1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(aq, field_operand<BITS>(R.kc[i], 4 + cb), D1, 0, 0, 0);
     }
@@ -462,7 +463,7 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
       L.sc()[(2 * r + 1) % GQ][tl] = D0[2] + D0[3];
       L.sc()[(2 * r + 1) % GQ][tl + 16] = D1[2] + D1[3];
     }
-    if (!SH || i == 3) wave_sync();     // the next block's rows, at last the scores, are visible
+    if ((i + 1) % SB == 0) wave_sync();  // the next group's rows, at last the scores, are visible
   }
 
   // ---- softmax numerators of the 128 tokens against the running maximum; operand rows ---------------
@@ -733,7 +734,7 @@ __device__ __forceinline__ void fp_compute(FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, 
 // otherwise entry `entry` of the launch plan does (a batch of sequences of different lengths dealt by
 // length).  The plan is device data: what is read from it is clamped to bounds the host has checked
 // against the buffers.
-template <int GQ, int BITS, int NV, bool PAGED, bool SH>
+template <int GQ, int BITS, int NV, bool PAGED, int SB>
 __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* smem, int& s_last, int entry) {
   const Dims& d = a.d;
   // Every argument the loads below depend on is fetched here, in one round trip (left to
@@ -864,7 +865,7 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* 
   const bool has_q = mc < mc_end;                        // uniform over the wave
   McRegs<BITS, NV> R;
   if constexpr (PAGED) P.resolve(mc, pages_now, lane);
-  load_k_meta<BITS, NV, SH>(R, P, mc, lane);
+  load_k_meta<BITS, NV, SB>(R, P, mc, lane);
   load_codes<BITS>(R.kc, P.kc, P, mc, lane);
   load_v_meta(R, P, mc, lane);
   load_codes<BITS>(R.vc, P.vc, P, mc, lane);
@@ -945,9 +946,9 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* 
         P.resolve(mc + nw, pages_next, lane);
         pages_next = pages_after;
       }
-      compute_minichunk<GQ, BITS, NV, SH, true>(R, S, L, qh, ql, lane, P, mc + nw);
+      compute_minichunk<GQ, BITS, NV, SB, true>(R, S, L, qh, ql, lane, P, mc + nw);
     }
-    compute_minichunk<GQ, BITS, NV, SH, false>(R, S, L, qh, ql, lane, P, mc);
+    compute_minichunk<GQ, BITS, NV, SB, false>(R, S, L, qh, ql, lane, P, mc);
   }
   const float post_v = __builtin_amdgcn_exp2f((float)(24 - kShV));
   if (a.k_new && split == 0 && part == 0 && wave == 0) {     // append: the ring row after the live ones
@@ -1071,7 +1072,7 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* 
 
 // grid (splits, kv_heads * head_parts, batch), or with a launch plan (entries, kv_heads, 1); 64 * a.nw threads
 // (a.nw at most what one compute unit holds of this instance), a.nw * sizeof(WaveLds) bytes of dynamic LDS.
-template <int GQ, int BITS, int NV, bool PAGED, bool SH>
+template <int GQ, int BITS, int NV, bool PAGED, int SB>
 __global__ void __launch_bounds__(64 * 4 * kDecodeWavesPerSimd) __attribute__((amdgpu_waves_per_eu(kDecodeWavesPerSimd)))
 decode_kernel(DecodeArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -1081,23 +1082,24 @@ decode_kernel(DecodeArgs a) {
     entry = blockIdx.x;
     if (entry >= min(a.plan[0], a.plan_entries)) return;
   }
-  decode_item<GQ, BITS, NV, PAGED, SH>(a, smem, s_last, entry);
+  decode_item<GQ, BITS, NV, PAGED, SB>(a, smem, s_last, entry);
 }
 
-template <int GQ, int BITS, int NV, bool PAGED, bool SH>
+template <int GQ, int BITS, int NV, bool PAGED, int SB>
 void launch_shared(const DecodeArgs& a, dim3 grid, hipStream_t s) {
   const size_t lds = (size_t)a.nw * sizeof(WaveLds<GQ, NV>);
   static_assert(merge_bytes_per_wave<GQ, NV>() <= (int)sizeof(WaveLds<GQ, NV>), "merge view must fit");
   if (lds > 48 * 1024)     // more than the default limit of dynamic LDS: raise it (cheap, idempotent)
-    (void)hipFuncSetAttribute((const void*)decode_kernel<GQ, BITS, NV, PAGED, SH>,
+    (void)hipFuncSetAttribute((const void*)decode_kernel<GQ, BITS, NV, PAGED, SB>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  hipLaunchKernelGGL((decode_kernel<GQ, BITS, NV, PAGED, SH>), grid, dim3(64 * a.nw), lds, s, a);
+  hipLaunchKernelGGL((decode_kernel<GQ, BITS, NV, PAGED, SB>), grid, dim3(64 * a.nw), lds, s, a);
 }
 template <int GQ, int BITS, int NV, bool PAGED>
 void launch_paged(const DecodeArgs& a, dim3 grid, hipStream_t s) {
-  // Key groups of 128 tokens: a mini-chunk is one group (mini-chunks start at multiples of 128 tokens)
-  if (a.d.bpg_shift == 2) launch_shared<GQ, BITS, NV, PAGED, true>(a, grid, s);
-  else launch_shared<GQ, BITS, NV, PAGED, false>(a, grid, s);
+  // blocks per Key group: a mini-chunk (four blocks, starting at a multiple of 128 tokens) is four, two or one group
+  if (a.d.bpg_shift == 2) launch_shared<GQ, BITS, NV, PAGED, 4>(a, grid, s);
+  else if (a.d.bpg_shift == 1) launch_shared<GQ, BITS, NV, PAGED, 2>(a, grid, s);
+  else launch_shared<GQ, BITS, NV, PAGED, 1>(a, grid, s);
 }
 template <int GQ, int BITS, int NV>
 void launch_one(const DecodeArgs& a, dim3 grid, hipStream_t s) {
