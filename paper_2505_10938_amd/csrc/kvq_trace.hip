@@ -3,6 +3,8 @@
 #include "kvq_common.h"
 #include "kvq_trace_core.h"
 
+#include <type_traits>
+
 namespace kvq {
 
 namespace {
@@ -126,8 +128,9 @@ __global__ void __launch_bounds__(256) prefill_trace_kernel(
     unsigned long long selm[kRounds];
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) selm[r] = 0;
-#pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
+    // (the rounds as calls with a constant round number: as a loop around the insertions it is not unrolled)
+    auto round = [&](auto round_number) {
+      constexpr int r = decltype(round_number)::value;
       const int t = r * 64 + lane;
       const double s = s_sc[gl * G + min(t, G - 1)];
       const int idx = first + t;
@@ -170,7 +173,9 @@ __global__ void __launch_bounds__(256) prefill_trace_kernel(
         if (P < N) ++P;
         selm[r] |= 1ull << l;
       }
-    }
+    };
+    round(std::integral_constant<int, 0>{});
+    if constexpr (kRounds > 1) round(std::integral_constant<int, 1>{});
     if (aux_n + E > A) {                               // they do not fit: tracing stops, nothing changes
       ps = ps0;
       pi = pi0;
