@@ -211,7 +211,7 @@ def run_stack(w, layers, steps, warmup, samples, pool, cpu_budget, label, value_
         step(s)
     torch.cuda.synchronize()
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
-    step_bytes, step_kind = [], []
+    step_bytes, step_kind, step_state = [], [], []
     t0 = time.perf_counter()
     for i in range(steps):
         marks[i].record()
@@ -219,6 +219,7 @@ def run_stack(w, layers, steps, warmup, samples, pool, cpu_budget, label, value_
         step(warmup + i)
         grp = cache.n_quant[0] != nq_before
         step_kind.append(grp)
+        step_state.append((cache.n_quant[0], cache.n_res[0]))
         step_bytes.append(layers * (decode_bytes(w, cache.n_quant[0], cache.n_res[0], pool_rows)
                                     + (group_step_bytes(w) if grp else 0)))
     marks[steps].record()
@@ -230,6 +231,7 @@ def run_stack(w, layers, steps, warmup, samples, pool, cpu_budget, label, value_
     # dominant kernel: the decode-attention launch.  A step without a group step is `layers` such launches
     # back to back and nothing else, so its duration / layers is the average launch (events on the launch stream)
     dec_us = sum(step_ms[i] for i in plain) * 1e3 / (len(plain) * layers)
+    per_step_us = sorted(step_ms[i] * 1e3 / layers for i in plain)           # average launch of each such step
     dec_bytes = sum(step_bytes[i] for i in plain) / (len(plain) * layers)
     grp_steps = [i for i in range(steps) if step_kind[i]]
     assert cache.n_quant[0] == nq_final
@@ -243,6 +245,9 @@ def run_stack(w, layers, steps, warmup, samples, pool, cpu_budget, label, value_
             getattr(cache, a).numel() for a in ("k_codes", "k_meta", "v_codes", "v_meta", "mask", "k_res", "v_res",
                                                  "pool_k", "pool_v")) / 1e9, 2),
         "launch_shape": KB.kvq_decode_launch_shape(cfg, 1, nq_final, R + 1 + w.outlier_budget + w.aux_capacity),
+        "per_step": [(step_state[i][0], step_state[i][1], round(step_ms[i] * 1e3 / layers, 2), bool(step_kind[i]))
+                     for i in range(steps)],
+        "dec_us_median": per_step_us[len(per_step_us) // 2], "dec_us_min": per_step_us[0], "dec_us_max": per_step_us[-1],
     }
     if grp_steps:
         res["group_step_ms"] = sum(step_ms[i] for i in grp_steps) / len(grp_steps)
@@ -499,7 +504,10 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(frac, 4),
                      "traffic": RECORDED_TRAFFIC.get(w.name),
                      "traffic_source": "recorded from rocprofv3 counter runs (profiles/), not measured in this run",
-                     "algorithmic_bytes": int(main_res["dec_bytes"]), "us_per_launch": round(main_res["dec_us"], 3)},
+                     "algorithmic_bytes": int(main_res["dec_bytes"]), "us_per_launch": round(main_res["dec_us"], 3),
+                     "us_per_launch_by_step": {"median": round(main_res["dec_us_median"], 3),
+                                               "min": round(main_res["dec_us_min"], 3),
+                                               "max": round(main_res["dec_us_max"], 3)}},
         "setup_s": round(main_res["setup_s"], 1),
     }
     if "group_step_ms" in main_res:
