@@ -28,6 +28,11 @@ What follows the paper, by passage:
   against (Experiments, "Details": the Keys are compressed every G steps, the
   Values at each step; Efficiency comparison: that per-step compression is what
   the method saves).  Same quantizer, no tracing.
+* `rope_rotate`                     - NOT from the paper: the rotary position
+  embedding (Su et al., "RoFormer", Eq. 34, in the half-split pairing of the
+  LLaMA-family models the paper evaluates) that a serving stack applies to the
+  query and the new Key before they reach the cache; here so that a decode launch
+  that applies it itself can be checked.
 
 Where the paper is silent or ambiguous a reading is taken; each is stated at the
 function that implements it.
@@ -363,6 +368,34 @@ def decode_attention(q_heads: np.ndarray, state: UnitState, k_res: np.ndarray, v
     K, V = state.effective_rows(k_res, v_res)
     out = np.stack([softmax_attention(q, K, V) for q in q_heads])
     return out, out.astype(np.float32).astype(np.float16)
+
+
+# --------------------------------------------------------------------------
+# Rotary position embedding (not part of the paper's method; see the header)
+# --------------------------------------------------------------------------
+
+def rope_rotate(x: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
+    """Rotate rows x[..., hd] (fp16) by the angles of one position.
+
+    Channel i < hd/2 is paired with channel i + hd/2; the pair is the point
+    (x_i, x_{i+hd/2}) of a plane, turned counter-clockwise by the angle whose
+    cosine and sine are cos[i], sin[i] (fp32, the caller's table: frequencies,
+    base and scaling are the caller's):
+        y_i        = x_i cos_i - x_{i+hd/2} sin_i
+        y_{i+hd/2} = x_{i+hd/2} cos_i + x_i sin_i
+    Precision (a reading: the arithmetic decides stored fp16 Key rows, so it is
+    fixed): each product and the sum are rounded to fp32 separately (no fused
+    multiply-add), the result once more to fp16, nearest-even."""
+    x = np.asarray(x)
+    assert x.dtype == np.float16
+    hd = x.shape[-1]
+    c = np.asarray(cos, dtype=np.float32).reshape(hd // 2)
+    s = np.asarray(sin, dtype=np.float32).reshape(hd // 2)
+    a = x[..., : hd // 2].astype(np.float32)
+    b = x[..., hd // 2:].astype(np.float32)
+    ya = (a * c).astype(np.float32) - (b * s).astype(np.float32)
+    yb = (b * c).astype(np.float32) + (a * s).astype(np.float32)
+    return np.concatenate([ya.astype(np.float32), yb.astype(np.float32)], axis=-1).astype(np.float16)
 
 
 # --------------------------------------------------------------------------
