@@ -397,6 +397,42 @@ int32_t kvq_append_decode_attention(const kvq_config* cfg, int32_t layer, const 
                                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same step for callers that hand over the query and the new Key BEFORE their rotary position
+ * embedding: the launch rotates both, then does what kvq_append_decode_attention does with the
+ * rotated rows (the rotated Key row is what the ring receives; Values are not rotated).  Not part of
+ * the paper's method: it is the step its models (LLaMA-2/3, Mistral) apply ahead of the cache
+ * (Su et al., "RoFormer", Eq. 34), fused here so that a decode step stays one launch.
+ * Channel i < head_dim/2 is paired with channel i + head_dim/2:
+ *     y_i = x_i cos_i - x_{i+hd/2} sin_i        y_{i+hd/2} = x_{i+hd/2} cos_i + x_i sin_i
+ * each product and the sum rounded to fp32 on its own, the result to fp16 (nearest-even).
+ *   q, k_new         : as kvq_append_decode_attention, unrotated; neither buffer is written
+ *   rope             : device fp32, 16-byte aligned: for the new token's position the head_dim/2
+ *                      cosines, then the head_dim/2 sines (frequencies, base and scaling are the
+ *                      caller's).  Sequence b reads the head_dim floats at rope + b * rope_stride
+ *   rope_stride      : elements (floats) between the rows of consecutive sequences: 0 (every
+ *                      sequence is at the same position and shares one row) or a multiple of 4
+ *                      that is >= head_dim
+ *   other arguments, workspace and errors as kvq_append_decode_attention.
+ */
+int32_t kvq_append_decode_attention_rope(const kvq_config* cfg, int32_t layer, const void* q, const void* k_new,
+                                         const void* v_new, const float* rope, int64_t rope_stride,
+                                         kvq_qcache qcache, int32_t n_quant, kvq_residual res, int32_t res_start,
+                                         int32_t n_res, kvq_pool pool, void* out, void* workspace,
+                                         size_t workspace_bytes, void* stream);
+
+/*
+ * The rotation of kvq_append_decode_attention_rope on its own, for the steps on which the new Key
+ * goes through kvq_append_trace_quantize first (the ring fills): rotate k_new and q with it, then
+ * call the unrotated entry points.  Same pairing and the same arithmetic, bit for bit.
+ *   x, out           : device fp16 [batch][heads][head_dim], 4-byte aligned; out may be x
+ *   heads            : rows per sequence (q_heads for a query, kv_heads for Keys)
+ *   rope, rope_stride: as above
+ * Errors: KVQ_ERR_INVALID_ARG (NULL or misaligned pointers, heads < 1, a bad stride).
+ */
+int32_t kvq_rope_rotate(const kvq_config* cfg, const void* x, int32_t heads, const float* rope, int64_t rope_stride,
+                        void* out, void* stream);
+
+/*
  * Batches whose sequences differ in length (the paper's runs use one length per batch; a serving
  * loop does not).  The per-sequence state lives in device memory so that a step needs no host
  * decision:
@@ -494,7 +530,7 @@ int32_t kvq_stream_read(const void* buf, size_t bytes, void* sink, void* stream)
 /* Static string for a kvq_status value. */
 const char* kvq_status_string(int32_t status);
 
-/* Version of this interface (structure layouts and entry points), for the binding's load check: 5. */
+/* Version of this interface (structure layouts and entry points), for the binding's load check: 6. */
 int32_t kvq_version(void);
 
 #ifdef __cplusplus

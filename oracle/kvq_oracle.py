@@ -395,7 +395,8 @@ def rope_rotate(x: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
     b = x[..., hd // 2:].astype(np.float32)
     ya = (a * c).astype(np.float32) - (b * s).astype(np.float32)
     yb = (b * c).astype(np.float32) + (a * s).astype(np.float32)
-    return np.concatenate([ya.astype(np.float32), yb.astype(np.float32)], axis=-1).astype(np.float16)
+    with np.errstate(over="ignore"):               # beyond the fp16 range: infinity, as IEEE-754 rounds it
+        return np.concatenate([ya.astype(np.float32), yb.astype(np.float32)], axis=-1).astype(np.float16)
 
 
 # --------------------------------------------------------------------------

@@ -16,10 +16,11 @@ LIB_PATH = os.path.join(HERE, "libkvq.so")
 
 KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_WORKSPACE, KVQ_ERR_LAUNCH, KVQ_ERR_SCRATCH = 0, -1, -2, -3, -4, -5
 
-INTERFACE_VERSION = 5       # kvq_version() of the library these structures and signatures match
+INTERFACE_VERSION = 6       # kvq_version() of the library these structures and signatures match
 EXPORTS = ["kvq_query_sizes", "kvq_append_residual", "kvq_trace_outliers", "kvq_quantize_group",
            "kvq_append_trace_quantize", "kvq_prefill_quantize", "kvq_prefill_quantize_seq", "kvq_decode_attention",
-           "kvq_append_decode_attention", "kvq_append_trace_quantize_ragged", "kvq_seq_advance",
+           "kvq_append_decode_attention", "kvq_append_decode_attention_rope", "kvq_rope_rotate",
+           "kvq_append_trace_quantize_ragged", "kvq_seq_advance",
            "kvq_decode_attention_ragged", "kvq_decode_attention_multi", "kvq_decode_workspace_bytes",
            "kvq_decode_launch_shape", "kvq_decode_attention_static", "kvq_dequantize", "kvq_stream_read",
            "kvq_quantize_value_tokens", "kvq_seq_plan_bytes", "kvq_seq_plan", "kvq_decode_attention_planned",
@@ -105,6 +106,11 @@ def load_library() -> C.CDLL:
     lib.kvq_append_decode_attention.restype = i32
     lib.kvq_append_decode_attention.argtypes = [cfgp, i32, vp, vp, vp, kvq_qcache, i32, kvq_residual, i32, i32, kvq_pool,
                                                 vp, vp, C.c_size_t, vp]
+    lib.kvq_append_decode_attention_rope.restype = i32
+    lib.kvq_append_decode_attention_rope.argtypes = [cfgp, i32, vp, vp, vp, vp, i64, kvq_qcache, i32, kvq_residual, i32,
+                                                     i32, kvq_pool, vp, vp, C.c_size_t, vp]
+    lib.kvq_rope_rotate.restype = i32
+    lib.kvq_rope_rotate.argtypes = [cfgp, vp, i32, vp, i64, vp, vp]
     lib.kvq_append_trace_quantize_ragged.restype = i32
     lib.kvq_append_trace_quantize_ragged.argtypes = [cfgp, i32, vp, vp, kvq_residual, vp, kvq_pool, vp, kvq_qcache, vp]
     lib.kvq_decode_workspace_bytes.restype = i64
@@ -269,6 +275,24 @@ def kvq_append_decode_attention(cfg, layer, q, k_new, v_new, qcache: kvq_qcache,
                                                     workspace_bytes, _stream(stream))
     if st != KVQ_OK:
         raise KvqError(st, "kvq_append_decode_attention")
+
+
+def kvq_append_decode_attention_rope(cfg, layer, q, k_new, v_new, rope, rope_stride, qcache: kvq_qcache, n_quant,
+                                     res: kvq_residual, res_start, n_res, pool: kvq_pool, out, workspace,
+                                     workspace_bytes, stream=None):
+    st = load_library().kvq_append_decode_attention_rope(C.byref(cfg), layer, _ptr(q), _ptr(k_new), _ptr(v_new),
+                                                         _ptr(rope), rope_stride, qcache, n_quant, res, res_start,
+                                                         n_res, pool, _ptr(out), _ptr(workspace), workspace_bytes,
+                                                         _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_append_decode_attention_rope")
+
+
+def kvq_rope_rotate(cfg, x, heads, rope, rope_stride, out, stream=None):
+    st = load_library().kvq_rope_rotate(C.byref(cfg), _ptr(x), heads, _ptr(rope), rope_stride, _ptr(out),
+                                        _stream(stream))
+    if st != KVQ_OK:
+        raise KvqError(st, "kvq_rope_rotate")
 
 
 def kvq_append_trace_quantize_ragged(cfg, layer, k_new, v_new, res: kvq_residual, seq_state, pool: kvq_pool, selected,

@@ -203,20 +203,34 @@ class KVCache:
                                      self.workspace.numel(), stream)
         return out
 
-    def step(self, layer, k_new, v_new, q, out=None, stream=None):
+    def step(self, layer, k_new, v_new, q, out=None, stream=None, rope=None, rope_stride=0):
         """One decode step of `layer`: the new token joins the cache and the attention output (fp16
         [batch, q_heads, head_dim]) over the cache including it is returned.  Two launches on the steps
         on which the ring fills (group step, then attention), one on all others; under the per-step
-        Value schedule one more, ahead of them (the Values of the token that leaves the window)."""
+        Value schedule one more, ahead of them (the Values of the token that leaves the window).
+        `rope` (fp32 device tensor: the head_dim/2 cosines, then the sines, of the new token's position;
+        per sequence if rope_stride > 0): q and k_new are given unrotated and the library rotates them,
+        inside the decode launch where there is one launch, with two small launches where the ring fills."""
         if out is None:
             out = torch.empty_like(q)
         if self.n_res[layer] + 1 == self.cfg.residual + self.cfg.group_k:
+            if rope is not None:
+                k_rot, q_rot = torch.empty_like(k_new), torch.empty_like(q)
+                B.kvq_rope_rotate(self.cfg, k_new, self.cfg.kv_heads, rope, rope_stride, k_rot, stream)
+                B.kvq_rope_rotate(self.cfg, q, self.cfg.q_heads, rope, rope_stride, q_rot, stream)
+                k_new, q = k_rot, q_rot
             self.append(layer, k_new, v_new, stream)
             return self.decode(layer, q, out, stream)
         self._value_leaves_window(layer, stream)
-        B.kvq_append_decode_attention(self.cfg, layer, q, k_new, v_new, self.qcache, self.n_quant[layer], self.res,
-                                      self.res_start[layer], self.n_res[layer], self.pool, out, self.workspace,
-                                      self.workspace.numel(), stream)
+        if rope is not None:
+            B.kvq_append_decode_attention_rope(self.cfg, layer, q, k_new, v_new, rope, rope_stride, self.qcache,
+                                               self.n_quant[layer], self.res, self.res_start[layer],
+                                               self.n_res[layer], self.pool, out, self.workspace,
+                                               self.workspace.numel(), stream)
+        else:
+            B.kvq_append_decode_attention(self.cfg, layer, q, k_new, v_new, self.qcache, self.n_quant[layer],
+                                          self.res, self.res_start[layer], self.n_res[layer], self.pool, out,
+                                          self.workspace, self.workspace.numel(), stream)
         self.n_res[layer] += 1
         return out
 

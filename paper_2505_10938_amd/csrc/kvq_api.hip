@@ -205,7 +205,7 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restric
 
 extern "C" {
 
-int32_t kvq_version(void) { return 5; }
+int32_t kvq_version(void) { return 6; }
 
 int32_t kvq_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {
   if (!buf || !sink || bytes == 0 || bytes % 16 != 0 || ((uintptr_t)buf & 15) != 0) return KVQ_ERR_INVALID_ARG;
@@ -502,7 +502,7 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, int32
                       int32_t n_quant, kvq_residual res, int32_t res_start, int32_t n_res, const int32_t* seq_state,
                       const void* k_new, const void* v_new, kvq_pool pool, void* out, void* workspace,
                       size_t workspace_bytes, void* stream, bool static_scratch = false,
-                      const int32_t* plan = nullptr) {
+                      const int32_t* plan = nullptr, const float* rope = nullptr, int64_t rope_stride = 0) {
   const int32_t st = check_config(cfg);
   if (st != KVQ_OK) return st;
   if (layer < 0 || layer >= cfg->layers) return KVQ_ERR_INVALID_ARG;
@@ -528,6 +528,10 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, int32
   if (k_new) {                                          // the new token must leave the ring short of full
     if (n_res + 1 >= cfg->residual + cfg->group_k || !res.k_res || !res.v_res) return KVQ_ERR_INVALID_ARG;
     if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 3) return KVQ_ERR_INVALID_ARG;
+  }
+  if (rope) {                                            // rows of head_dim floats, read 8 bytes at a time
+    if (!k_new || (((uintptr_t)rope) & 15)) return KVQ_ERR_INVALID_ARG;
+    if (rope_stride != 0 && (rope_stride < cfg->head_dim || rope_stride % 4 != 0)) return KVQ_ERR_INVALID_ARG;
   }
   // the arrays are needed even when nothing is quantized yet: every workgroup issues the loads of a
   // first block (the last one, or block 0) whether or not it has quantized tokens to work on
@@ -578,6 +582,8 @@ int32_t decode_common(const kvq_config* cfg, int32_t layer, const void* q, int32
   a.mc_per_split = sp.mc_per_split;
   a.plan = nullptr;
   a.plan_entries = 0;
+  a.rope = rope;
+  a.rope_stride = rope_stride;
   if (plan) {                                            // the plan's own shape; splits are per sequence
     const PlanShape ps = plan_shape(cfg);
     if (ps.entries == 0 || q_tokens != 1 || k_new) return KVQ_ERR_UNSUPPORTED;
@@ -656,6 +662,27 @@ int32_t kvq_append_decode_attention(const kvq_config* cfg, int32_t layer, const 
   if (!k_new || !v_new) return KVQ_ERR_INVALID_ARG;
   return decode_common(cfg, layer, q, 1, qc, n_quant, res, res_start, n_res, nullptr, k_new, v_new, pool, out,
                        workspace, workspace_bytes, stream);
+}
+
+int32_t kvq_append_decode_attention_rope(const kvq_config* cfg, int32_t layer, const void* q, const void* k_new,
+                                         const void* v_new, const float* rope, int64_t rope_stride, kvq_qcache qc,
+                                         int32_t n_quant, kvq_residual res, int32_t res_start, int32_t n_res,
+                                         kvq_pool pool, void* out, void* workspace, size_t workspace_bytes,
+                                         void* stream) {
+  if (!k_new || !v_new || !rope) return KVQ_ERR_INVALID_ARG;
+  return decode_common(cfg, layer, q, 1, qc, n_quant, res, res_start, n_res, nullptr, k_new, v_new, pool, out,
+                       workspace, workspace_bytes, stream, false, nullptr, rope, rope_stride);
+}
+
+int32_t kvq_rope_rotate(const kvq_config* cfg, const void* x, int32_t heads, const float* rope, int64_t rope_stride,
+                        void* out, void* stream) {
+  const int32_t st = check_config(cfg);
+  if (st != KVQ_OK) return st;
+  if (!x || !out || !rope || heads < 1 || heads > 65536) return KVQ_ERR_INVALID_ARG;
+  if (((((uintptr_t)x) | ((uintptr_t)out)) & 3) || (((uintptr_t)rope) & 15)) return KVQ_ERR_INVALID_ARG;
+  if (rope_stride != 0 && (rope_stride < cfg->head_dim || rope_stride % 4 != 0)) return KVQ_ERR_INVALID_ARG;
+  return from_hip(kvq::launch_rope((const __half*)x, (int64_t)cfg->batch * heads, heads, rope, rope_stride,
+                                   (__half*)out, (hipStream_t)stream));
 }
 
 int64_t kvq_seq_plan_bytes(const kvq_config* cfg) {

@@ -94,6 +94,11 @@ struct DecodeArgs {
   // `mc_per_split` are not used.
   const int32_t* plan;
   int32_t plan_entries;     // entries the plan has room for (the grid's x extent)
+  // Rotary position embedding of the query rows and of the new Key row inside the launch (null: none):
+  // fp32 cosines of the head_dim / 2 angles of the new token's position, then their sines; sequence b's
+  // row starts rope_stride elements after sequence b - 1's (0: one row for all).
+  const float* rope;
+  int64_t rope_stride;
 };
 
 hipError_t launch_append(const Dims& d, const __half* k_new, const __half* v_new, __half* k_res, __half* v_res,
@@ -120,6 +125,8 @@ hipError_t launch_seq_plan(const Dims& d, const int32_t* seq, int32_t max_n_quan
 hipError_t launch_value_tokens(const Dims& d, int32_t first_token, int32_t count, __half* v_res, int32_t ring_row,
                                const kvq_qcache& qc, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
+hipError_t launch_rope(const __half* x, int64_t rows, int32_t rows_per_seq, const float* rope, int64_t rope_stride,
+                       __half* out, hipStream_t s);
 int decode_wave_lds_bytes(int g, int vgroups);   // LDS one decode wavefront needs
 
 // ---- exchanges inside a row of 16 lanes on the DPP path (no LDS traffic) -----------------------

@@ -161,6 +161,22 @@ __device__ inline void mul_split(half2v ah, half2v al, half2v b, uint32_t& hi, u
 }
 __device__ inline half2v as_half2(uint32_t w) { return __builtin_bit_cast(half2v, w); }
 
+// Rotary position embedding of one lane's channel pair (2*lane, 2*lane + 1).  Channel i < 64 forms a
+// plane with channel i + 64, so a lane's partner is lane ^ 32 and both use the angles of pair lane & 31:
+//     y_i = x_i cos_i - x_{i+64} sin_i,   y_{i+64} = x_{i+64} cos_i + x_i sin_i
+// (Su et al., "RoFormer", Eq. 34, in the half-split pairing).  Each product and the sum are rounded to
+// fp32 on their own and the result once to fp16: the rotated Key row is stored, and what is stored must
+// not depend on how a compiler contracts the expression.
+__device__ inline uint32_t rope_word(uint32_t own, uint32_t partner, float2 c, float2 s, bool upper) {
+#pragma clang fp contract(off)
+  const float o0 = h2f_bits(own & 0xFFFFu), o1 = h2f_bits(own >> 16);
+  const float p0 = h2f_bits(partner & 0xFFFFu), p1 = h2f_bits(partner >> 16);
+  const float a0 = o0 * c.x, a1 = o1 * c.y, b0 = p0 * s.x, b1 = p1 * s.y;
+  const float y0 = upper ? a0 + b0 : a0 - b0;
+  const float y1 = upper ? a1 + b1 : a1 - b1;
+  return (uint32_t)__half_as_ushort(__float2half_rn(y0)) | ((uint32_t)__half_as_ushort(__float2half_rn(y1)) << 16);
+}
+
 // Exponent of the power of two carried by pair v (v = lane & 3 on the producing side) of a
 // field: a masked code at pair v is worth code * 2^(pos(v) - 24).
 template <int BITS>
@@ -488,6 +504,9 @@ __device__ __forceinline__ void compute_minichunk(McRegs<BITS, NV>& R, WaveAcc<G
     const bool ok0 = !((mword >> bit) & 1u);
     const bool ok1 = !((mword >> (bit + 1)) & 1u);
     const _Float16 fv = (_Float16)__builtin_amdgcn_exp2f((float)(kShV - pair_pos<BITS>(lane & 3)));
+    // The Value codes, which were asked for right after the steps and zeros used next, are waited for here
+    // as well and not block by block between the matrix instructions that read them (measured: 0.5 %).
+    asm volatile("" ::"v"(R.vc[3][2 * BITS - 1]));
 #pragma unroll
     for (int jv = 0; jv < NV; ++jv) vs[jv] = as_half2(R.vsp[jv]) * half2v{fv, fv};
     float alpha[GQ], x0[GQ], x1[GQ], mx[GQ];
@@ -661,12 +680,26 @@ __device__ __forceinline__ bool fp_row_ok(const DecodeArgs& a, const Seq& sq, co
 template <int GQ, int NV>
 __device__ __forceinline__ void fp_compute(FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, NV>& L, const DecodeArgs& a,
                                            const Seq& sq, const FpLayout& f, int n_pool, int n_aux, int r0,
-                                           uint32_t v_new_word, int lane) {
+                                           uint32_t k_new_word, uint32_t v_new_word, int lane) {
   const int m16 = lane & 15, r = lane >> 4;
   const bool okk = fp_row_ok(a, sq, f, X.group, m16, n_pool, n_aux);
   if (X.group == f.new_group) {                                    // uniform, one group of the unit
 #pragma unroll
     for (int t = 0; t < 16; ++t) X.vw[t] = t == f.new_t ? v_new_word : X.vw[t];
+    if (a.rope) {
+      // The new Key row was loaded as the caller gave it; the rotated one exists as one word per lane
+      // (channels 2*lane, 2*lane + 1).  The lanes that own the row take their 16-byte pieces (channels
+      // 32 cb + 8 r ..) from the lanes that hold them: words 16 cb + 4 r .. + 3.
+      const bool mine = m16 == f.new_t;
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) {
+        const uint32_t w0 = (uint32_t)__shfl((int)k_new_word, 16 * cb + 4 * r + 0);
+        const uint32_t w1 = (uint32_t)__shfl((int)k_new_word, 16 * cb + 4 * r + 1);
+        const uint32_t w2 = (uint32_t)__shfl((int)k_new_word, 16 * cb + 4 * r + 2);
+        const uint32_t w3 = (uint32_t)__shfl((int)k_new_word, 16 * cb + 4 * r + 3);
+        X.kf[cb] = mine ? make_uint4(w0, w1, w2, w3) : X.kf[cb];
+      }
+    }
   }
   // Several query tokens at once: token i of q_tokens does not see the q_tokens - 1 - i tokens after it,
   // which are the newest residual rows (one query token: nothing is hidden).  Row j of this workgroup
@@ -746,7 +779,7 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* 
                "s"(a.k_codes), "s"(a.k_meta), "s"(a.v_codes), "s"(a.v_meta), "s"(a.mask), "s"(a.k_res), "s"(a.v_res),
                "s"(a.pool_k), "s"(a.pool_v), "s"(a.pool_count), "s"(a.aux_count), "s"(a.seq));
   asm volatile("" ::"s"(a.k_new), "s"(a.v_new), "s"(d.page_table), "s"(d.table_stride), "s"(d.n_pages), "s"(d.plane0),
-               "s"(a.q_tokens), "s"(a.g_shift));
+               "s"(a.q_tokens), "s"(a.g_shift), "s"(a.rope), "s"(a.rope_stride));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -828,8 +861,17 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* 
   // loads; without such rows the query row is read instead).
   const __half* k_new_row = a.k_new ? a.k_new + (int64_t)ul * kHeadDim : qbase;
   const __half* v_new_row = a.k_new ? a.v_new + (int64_t)ul * kHeadDim : qbase;
-  const uint32_t k_new_word = ((const uint32_t*)k_new_row)[lane];
+  uint32_t k_new_word = ((const uint32_t*)k_new_row)[lane];
   const uint32_t v_new_word = ((const uint32_t*)v_new_row)[lane];
+  // the angles of the new token's position, if the launch is to rotate the query and the new Key (these
+  // two loads are the one exception to "the same loads on every path": a launch without rotation, the
+  // common one, is not to pay for them; with them the waits further down are merely less exact)
+  float2 rope_cos = {1.f, 1.f}, rope_sin = {0.f, 0.f};
+  if (a.rope) {                                          // uniform
+    const float* rope_row = a.rope + (int64_t)b * a.rope_stride;
+    rope_cos = ((const float2*)rope_row)[lane & 31];
+    rope_sin = ((const float2*)rope_row)[32 + (lane & 31)];
+  }
 
   // full-precision row groups go to the unit's wavefronts from the last one backwards (the
   // first wavefronts of a workgroup are the ones that may hold one more mini-chunk)
@@ -870,6 +912,12 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* 
   load_v_meta(R, P, mc, lane);
   load_codes<BITS>(R.vc, P.vc, P, mc, lane);
 
+  if (a.rope) {                                          // uniform
+#pragma unroll
+    for (int j = 0; j < GQ; ++j)
+      qw[j] = rope_word(qw[j], (uint32_t)__shfl_xor((int)qw[j], 32), rope_cos, rope_sin, lane >= 32);
+    k_new_word = rope_word(k_new_word, (uint32_t)__shfl_xor((int)k_new_word, 32), rope_cos, rope_sin, lane >= 32);
+  }
   // this lane's two channels (2*lane, 2*lane+1) of every query head, log2-domain scaled
   float qa[GQ][2];
 #pragma unroll
@@ -897,10 +945,10 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* 
   if (has_fp) {
     n_pool = __builtin_amdgcn_readfirstlane(n_pool);
     n_aux = __builtin_amdgcn_readfirstlane(n_aux);
-    fp_compute<GQ, NV>(X, F, L, a, sq, fl, n_pool, n_aux, r0, v_new_word, lane);
+    fp_compute<GQ, NV>(X, F, L, a, sq, fl, n_pool, n_aux, r0, k_new_word, v_new_word, lane);
     for (rg += unit_waves; rg < n_rg; rg += unit_waves) {          // the wavefront's further groups
       fp_load(X, a, sq, fl, u, k_new_row, rg, lane);
-      fp_compute<GQ, NV>(X, F, L, a, sq, fl, n_pool, n_aux, r0, v_new_word, lane);
+      fp_compute<GQ, NV>(X, F, L, a, sq, fl, n_pool, n_aux, r0, k_new_word, v_new_word, lane);
     }
   }
 
@@ -1124,7 +1172,30 @@ void launch_bits(const DecodeArgs& a, dim3 grid, hipStream_t s) {
     launch_nv<GQ, 4>(a, grid, s);
 }
 
+// The rotation on its own, for the steps on which the decode launch cannot apply it (a ring that fills:
+// the new Key goes through the group step first): one wavefront per row of 128 channels.  A wavefront
+// has read its whole row before it writes any of it, so out may be x.
+__global__ void __launch_bounds__(256) rope_kernel(const __half* __restrict__ x, int64_t rows, int rows_per_seq,
+                                                   const float* __restrict__ rope, int64_t rope_stride,
+                                                   __half* __restrict__ out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const float* rr = rope + (row / rows_per_seq) * rope_stride;
+  const float2 c = ((const float2*)rr)[lane & 31], sn = ((const float2*)rr)[32 + (lane & 31)];
+  const uint32_t own = ((const uint32_t*)(x + row * kHeadDim))[lane];
+  const uint32_t y = rope_word(own, (uint32_t)__shfl_xor((int)own, 32), c, sn, lane >= 32);
+  ((uint32_t*)(out + row * kHeadDim))[lane] = y;
+}
+
 }  // namespace
+
+hipError_t launch_rope(const __half* x, int64_t rows, int32_t rows_per_seq, const float* rope, int64_t rope_stride,
+                       __half* out, hipStream_t s) {
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, x, rows, rows_per_seq, rope,
+                     rope_stride, out);
+  return hipGetLastError();
+}
 
 int decode_wave_lds_bytes(int g, int nv) {
   auto of_g = [&](auto gq) -> int {

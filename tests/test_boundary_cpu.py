@@ -299,6 +299,27 @@ def test_launch_plan_sizes_and_arguments():
     assert dec(ws=s.workspace_bytes - 1) == B.KVQ_ERR_WORKSPACE
 
 
+def test_bad_rotary_arguments_rejected_before_launch():
+    lib = P.load_library()
+    c = cfg()
+    qc = B.kvq_qcache(256, 256, 256, 256, 256)
+    pool = B.kvq_pool(256, 256, 256, 256, 256, 256, 256)
+    res = B.kvq_residual(256, 256)
+    ws = P.kvq_query_sizes(c).workspace_bytes
+    dec = lambda k=256, v=256, rope=256, stride=0, n_res=10: lib.kvq_append_decode_attention_rope(
+        C.byref(c), 0, 256, k, v, rope, stride, qc, 64, res, 0, n_res, pool, 256, 256, ws, None)
+    bad = B.KVQ_ERR_INVALID_ARG
+    assert dec(rope=None) == bad and dec(rope=264) == bad            # no table; not 16-byte aligned
+    assert dec(k=None) == bad and dec(v=None) == bad                 # the rotation comes with the append only
+    assert dec(stride=64) == bad and dec(stride=130) == bad and dec(stride=-128) == bad
+    assert dec(n_res=c.residual + c.group_k - 1) == bad              # the ring would fill: not this entry point's step
+    rot = lambda x=256, heads=8, rope=256, stride=128, out=512: lib.kvq_rope_rotate(
+        C.byref(c), x, heads, rope, stride, out, None)
+    assert rot(x=None) == bad and rot(out=None) == bad and rot(rope=None) == bad
+    assert rot(x=258) == bad and rot(out=514) == bad and rot(rope=260) == bad
+    assert rot(heads=0) == bad and rot(stride=100) == bad and rot(stride=126) == bad
+
+
 def test_bad_dequantize_arguments_rejected_before_launch():
     lib = P.load_library()
     c = cfg()

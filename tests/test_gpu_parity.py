@@ -756,6 +756,100 @@ def test_streaming_steps_with_the_append_inside_the_decode_launch(kw):
     H.compare_state(cache, states, w, nq)
 
 
+def rope_table(pos, hd=128, base=10000.0):
+    """fp32 [hd]: the cosines of position `pos` at the usual frequencies base^(-2i/hd), then the sines."""
+    ang = pos * base ** (-2.0 * np.arange(hd // 2, dtype=np.float64) / hd)
+    return np.concatenate([np.cos(ang), np.sin(ang)]).astype(np.float32)
+
+
+@pytest.mark.parametrize("kw,per_sequence", [
+    (dict(bits=2, group_k=32, group_v=32, residual=32, outlier_budget=8), False),
+    (dict(bits=2, group_k=32, group_v=32, residual=32, outlier_budget=8), True),
+    (dict(bits=4, group_k=64, group_v=64, residual=32, outlier_budget=3, q_heads=8), True),   # four query heads
+    (dict(bits=2, group_k=32, group_v=128, residual=0, outlier_budget=4), False),  # every 32nd step fills the ring
+    (dict(bits=2, group_k=32, group_v=32, residual=40, outlier_budget=4, q_heads=16, batch=3), True),   # eight
+])
+def test_rotary_embedding_inside_the_decode_launch(kw, per_sequence):
+    """Token by token with KVCache.step and a table of angles: the library rotates the query and the new
+    Key itself (inside the decode launch; with the small launch on the steps that fill the ring).  The
+    oracle rotates them with its own function and runs the unrotated path.  The rotated Key rows are
+    compared bit for bit where they are stored (ring rows at the end; the codes and pool rows of the
+    groups quantized on the way, which are made of rotated rows after the first residual + G steps), the
+    attention output at every step."""
+    import torch
+    from oracle import kvq_oracle as O
+    from paper_2505_10938_amd import cache as KC
+    base = dict(layers=1, batch=2, q_heads=2, kv_heads=2, context=200)
+    base.update(kw)
+    w = S.Workload("rope", **base)
+    G = w.group_k
+    steps = w.residual + 3 * G + 9
+    K, V = S.layer_kv(w, 0, w.context + steps)
+    K = K.copy()
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ((w.context + steps + G - 1) // G) * G, w.bits, G,
+                         w.group_v, w.residual, w.outlier_budget, w.aux_capacity, w.head_dim)
+    nq, nr = w.n_quant, w.n_res
+    cache = H.gpu_cache(w, K, V, nq, nr, cache=KC.KVCache(cfg))
+    states = H.oracle_states(w, K, V, nq)
+    raw_k = torch.from_numpy(K.copy()).cuda()
+    Vd = torch.from_numpy(V).cuda()
+    n = w.context
+    fused = 0
+    for s in range(steps):
+        # the new token's position: the same for every sequence, or 1000 b further on for sequence b
+        pos = [n + (1000 * b if per_sequence else 0) for b in range(w.batch)]
+        tables = np.stack([rope_table(p) for p in pos])
+        rope = torch.from_numpy(tables if per_sequence else tables[0]).cuda()
+        Q = S.layer_queries(w, 0, s, "peaky")
+        Qr = np.stack([O.rope_rotate(Q[b], tables[b, :64], tables[b, 64:]) for b in range(w.batch)])
+        for b in range(w.batch):                                   # the oracle's token: rotated
+            K[b, :, n] = O.rope_rotate(K[b, :, n], tables[b, :64], tables[b, 64:])
+        out = cache.step(0, raw_k[:, :, n].contiguous(), Vd[:, :, n].contiguous(), torch.from_numpy(Q).cuda(),
+                         rope=rope, rope_stride=w.head_dim if per_sequence else 0)
+        n += 1
+        if n - nq == w.residual + G:
+            for ui, st in enumerate(states):
+                b, h = divmod(ui, w.kv_heads)
+                st.append_group(K[b, h, nq:nq + G], V[b, h, nq:nq + G])
+            nq += G
+        else:
+            fused += 1
+        assert cache.n_quant[0] == nq and cache.n_res[0] == n - nq
+        ref = H.oracle_attention(w, states, Qr, K, V, nq, n - nq)
+        got = out.cpu().numpy().astype(np.float64)
+        assert att_err(got, ref) <= ATT_TOL, (s, n, nq)
+    assert fused >= steps - 5 and nq >= w.context          # rotated rows have been quantized
+    H.compare_state(cache, states, w, nq)
+    ring = cache.res_view("k").cpu().numpy()
+    rows = cache.sizes.res_rows
+    for ui in range(w.batch * w.kv_heads):
+        b, h = divmod(ui, w.kv_heads)
+        at = [(cache.res_start[0] + i) % rows for i in range(n - nq)]
+        assert np.array_equal(ring[ui, at].view(np.uint16), K[b, h, nq:n].view(np.uint16)), ui
+    # the rotation changed the rows: the test would not pass on unrotated ones
+    assert not np.array_equal(K[:, :, w.context:n], raw_k[:, :, w.context:n].cpu().numpy())
+
+
+def test_rotation_on_its_own_equals_the_oracle_bit_for_bit():
+    import torch
+    from oracle import kvq_oracle as O
+    from paper_2505_10938_amd import cache as KC
+    cfg = KC.make_config(1, 5, 8, 2, 64, 2, 32, 32, 0, 0, 0, 128)
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((5, 8, 128)) * 4).astype(np.float16)
+    x[0, 0, :4] = [0.0, -0.0, 65504.0, 6e-8]
+    tables = np.stack([rope_table(31 * b + 3) for b in range(5)])
+    xd = torch.from_numpy(x).cuda()
+    out = torch.empty_like(xd)
+    B.kvq_rope_rotate(cfg, xd, 8, torch.from_numpy(tables).cuda(), 128, out)
+    want = np.stack([O.rope_rotate(x[b], tables[b, :64], tables[b, 64:]) for b in range(5)])
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), want.view(np.uint16))
+    # one row for all sequences, in place
+    B.kvq_rope_rotate(cfg, xd, 8, torch.from_numpy(tables[2]).cuda(), 0, xd)
+    want = O.rope_rotate(x, tables[2, :64], tables[2, 64:])
+    assert np.array_equal(xd.cpu().numpy().view(np.uint16), want.view(np.uint16))
+
+
 # ---- paged quantized cache: pages of one Key group each, dealt to the sequences by a table ----------------
 
 def paged(cfg, seed=11, spare=7, kind=None):
