@@ -554,6 +554,11 @@ def main():
         extras = []
         if stacked and w.bits == 2:                            # the same stack with 4-bit codes
             extras.append((w.with_(name=w.name + "_4bit", bits=4), w.layers))
+        if stacked and w.group_k == 32:
+            # the same stack under the hyper-parameters of the paper's main tables (Experiments, "Details":
+            # group size 128, residual length 32, 3 outlier tokens)
+            extras.append((w.with_(name=w.name + "_g128_r32_n3", group_k=128, group_v=128, residual=32,
+                                   outlier_budget=3), w.layers))
         if w.name == DEFAULT_WORKLOAD:                         # the single-layer MHA configuration, on copies
             w2 = S.WORKLOADS["llama2_7b_4k"]
             extras.append((w2, copies_for(w2)))
@@ -580,7 +585,8 @@ def main():
         for (we, le) in extras:
             r = run_stack(we, le, args.steps, args.warmup, [], None, 0.0, we.name)
             result.setdefault("other_workloads", {})[we.name] = {
-                "layers": le, "bits": we.bits, "ms_per_step": round(r["ms_per_step"], 5),
+                "layers": le, "bits": we.bits, "group_k": we.group_k, "group_v": we.group_v, "residual": we.residual,
+                "outlier_budget": we.outlier_budget, "ms_per_step": round(r["ms_per_step"], 5),
                 "value_GBps": round(r["value_GBps"], 2), "tokens_per_s": round(r["tokens_per_s"], 1),
                 "decode_us_per_launch": round(r["dec_us"], 3), "decode_algorithmic_bytes": int(r["dec_bytes"]),
                 "decode_frac_of_hbm_peak": round(r["dec_bytes"] / (r["dec_us"] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
