@@ -436,6 +436,9 @@ def main():
     ap.add_argument("--decode-only", type=int, default=0, metavar="N",
                     help="profiling aid: after set-up run N passes of plain decode-attention launches over the layers "
                          "and exit")
+    ap.add_argument("--prefill-only", type=int, default=0, metavar="N",
+                    help="profiling aid: quantize one layer's prompt (kvq_prefill_quantize) N times into caches taken "
+                         "in turn, print the time per call and exit")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="profiling aid: run 8 plain device copies of MIB MiB and exit (scales the HBM byte counters)")
     args = ap.parse_args()
@@ -451,7 +454,7 @@ def main():
     w = S.WORKLOADS[args.workload]
     cores = host_cores()
     pool = None
-    if not args.no_cpu and not args.decode_only and not args.copy_calibration:
+    if not args.no_cpu and not args.decode_only and not args.copy_calibration and not args.prefill_only:
         import multiprocessing as mp
         # forked here, before anything initialises the GPU in this process; the workers never touch it
         pool = mp.get_context("fork").Pool(cores, initializer=_oracle_worker_init)
@@ -473,6 +476,9 @@ def main():
     layers = w.layers if stacked else copies_for(w)
     if args.decode_only:
         decode_only(w, layers, args.decode_only)
+        return
+    if args.prefill_only:
+        prefill_only(w, args.prefill_only)
         return
 
     # units the oracle checks: three layers x three sequences x every kv head (fewer for a small workload)
@@ -620,6 +626,35 @@ def decode_only(w, layers, passes):
     torch.cuda.synchronize()
     print(json.dumps({"decode_only_passes": passes, "layers": layers, "workload": w.name,
                       "n_quant": cache.n_quant[0], "n_res": cache.n_res[0]}))
+
+
+def prefill_only(w, calls):
+    """Profiling aid: one layer's prompt of the workload (its full batch and context) quantized `calls` times
+    by kvq_prefill_quantize, each time into an empty cache of its own (the call expects empty pools); one
+    untimed call ahead; the time per call from events around the calls."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    dev = torch.device("cuda:0")
+    G = w.group_k
+    calls = min(calls, 64)
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ((w.context + G - 1) // G) * G, w.bits, G, w.group_v,
+                         w.residual, w.outlier_budget, w.aux_capacity, w.head_dim)
+    caches = [KC.KVCache(cfg, device=dev) for _ in range(calls + 1)]
+    K, V = DeviceSynth(w, dev).rows(0, w.context)
+    caches[0].prefill(0, K, V)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for c in caches[1:]:
+        c.prefill(0, K, V)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / calls
+    fp16_bytes = 2 * K.numel() * 2
+    print(json.dumps({"prefill_only_calls": calls, "workload": w.name, "units": w.batch * w.kv_heads,
+                      "tokens": w.context, "us_per_call": round(us, 1),
+                      "fp16_input_GBps": round(fp16_bytes / us / 1e3, 1),
+                      "n_quant": caches[0].n_quant[0], "n_res": caches[0].n_res[0]}))
 
 
 if __name__ == "__main__":
