@@ -3,6 +3,8 @@
 #include "kvq_common.h"
 #include "kvq_trace_core.h"
 
+#include <type_traits>
+
 // The integer code decisions must not depend on how the compiler fuses multiplies and adds.
 #pragma clang fp contract(off)
 
@@ -82,6 +84,7 @@ __device__ inline float lo_half(uint32_t w) { return __half2float(__ushort_as_ha
 __device__ inline float hi_half(uint32_t w) { return __half2float(__ushort_as_half((unsigned short)(w >> 16))); }
 
 constexpr int kQuantThreads = 1024;
+constexpr int64_t kPromptGroups = 1024;   // from this many groups in one launch on, prompt_quantize_kernel takes them
 
 // Minimum and maximum over groups of `n` adjacent lanes (n = 4, 8 or 16).
 __device__ inline void team_minmax(float& mn, float& mx, int n) {
@@ -349,6 +352,307 @@ __global__ void __launch_bounds__(kQuantThreads) quantize_kernel(
   quantize_body<BITS, G>(d, at.row, at.slot, L, flag, k_codes, k_meta, v_codes, v_meta, mask, tid);
 }
 
+// ---- many groups per launch (a prompt): one workgroup of two wavefronts per group -------------------------
+// The kernel above spreads one group over 1024 threads because a decode step waits for it.  A prompt has
+// thousands of groups, and what counts is the instructions spent per group.  Here wavefront 0 quantizes the
+// group's Keys and wavefront 1 its Values, each with a lane-to-element mapping in which the packed words fall
+// out of the lanes that computed the codes:
+//   Keys:   a lane owns one channel pair for all tokens, so minimum and maximum over the tokens are packed
+//           fp16 operations inside the lane (exact: they only select).  The 8 (2-bit) or 4 (4-bit) lanes
+//           whose codes share a packed word are adjacent (for 2-bit the lanes are numbered accordingly) and
+//           combine it with 3 or 2 cross-lane ORs; over 8 or 4 tokens each of them keeps one word, then all
+//           store.
+//   Values: minimum and maximum per (token, channel group) with 8 channels per lane and a butterfly over
+//           Gv / 8 lanes on the packed pair {min, -max}; the rows and their {zero, step / 2} then go through
+//           LDS into the mapping in which a lane owns the two channels of one packed word for 8 tokens.
+// Results are those of quantize_body bit for bit (same roundings in the same order; minimum, maximum and
+// the exact fp64 sums do not depend on the order they are taken in).
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ h2 as_h2(uint32_t w) { return __builtin_bit_cast(h2, w); }
+__device__ __forceinline__ uint32_t as_u32(h2 v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ __forceinline__ uint32_t rotl32(uint32_t w, int n) { return __builtin_amdgcn_alignbit(w, w, (32 - n) & 31); }
+__device__ __forceinline__ uint32_t half_bits(float x) { return (uint32_t)__half_as_ushort(__float2half_rn(x)); }
+__device__ __forceinline__ uint32_t mean_half_bits(double sum, int G) { return half_bits((float)(sum / (double)G)); }
+__device__ __forceinline__ void lds_order() {   // LDS traffic of one wavefront executes in order; this holds the compiler to it
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int BITS, int G>
+__global__ void __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(4, 8))) prompt_quantize_kernel(
+    Dims d, int32_t group_index, const __half* __restrict__ k_rows, const __half* __restrict__ v_rows,
+    int64_t unit_stride, const uint8_t* __restrict__ selected, int64_t selected_unit_stride,
+    uint8_t* __restrict__ k_codes, uint32_t* __restrict__ k_meta, uint8_t* __restrict__ v_codes,
+    uint32_t* __restrict__ v_meta, uint32_t* __restrict__ mask, int32_t n_groups, int32_t tail_n,
+    __half* __restrict__ k_res, __half* __restrict__ v_res) {
+  // grid (units, groups + tail blocks), as quantize_kernel's
+  __shared__ uint4 vrow[32 * 16];                      // 32 Value rows of 128 fp16 (mean-replaced where flagged)
+  __shared__ float2 vms[32 * 4];                       // their {zero, step / 2} per channel group
+  __shared__ uint32_t vpr[32 * 4];                     // and before that {minimum, -maximum} as an fp16 pair
+  const int tid = threadIdx.x;
+  const int ul = blockIdx.x, gy = blockIdx.y;
+  if (gy >= n_groups) {
+    const int i = (gy - n_groups) * 128 + tid;
+    if (i < tail_n * 16) {
+      const int64_t src = (int64_t)ul * unit_stride + (int64_t)n_groups * G * kHeadDim;
+      const int64_t dst = (d.unit0 + ul) * d.res_rows * kHeadDim;
+      ((uint4*)(k_res + dst))[i] = ((const uint4*)(k_rows + src))[i];
+      ((uint4*)(v_res + dst))[i] = ((const uint4*)(v_rows + src))[i];
+    }
+    return;
+  }
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t row0 = (int64_t)ul * unit_stride + (int64_t)gy * G * kHeadDim;
+  const GroupPlace at = place_of_group(d, ul, group_index + gy);
+  constexpr int nblk = G / kBlockTokens;
+  const int64_t block0 = at.row * d.blocks_per_unit + (int64_t)at.slot * nblk;   // the group's first packed block
+  // the flags of the group's tokens as bit masks (uniform)
+  constexpr int kSelWords = (G + 63) / 64;
+  unsigned long long sel[kSelWords];
+  bool any = false;
+#pragma unroll
+  for (int w = 0; w < kSelWords; ++w) {
+    const int t = 64 * w + lane;
+    const bool f = selected && t < G && selected[(int64_t)ul * selected_unit_stride + (int64_t)gy * G + t] != 0;
+    sel[w] = __ballot(f);
+    any |= sel[w] != 0;
+  }
+  auto is_sel = [&](int t) -> bool { return (sel[kSelWords == 1 ? 0 : t >> 6] >> (t & 63)) & 1ull; };
+
+  if (wave == 0) {
+    // ---- Keys ------------------------------------------------------------------------------------------
+    const int v = lane & 3;
+    int cp, r, hi = 0, p = 0, cb = 0;                  // cp: the lane's channel pair (channels 2 cp, 2 cp + 1)
+    if (BITS == 2) {
+      hi = lane >> 5, r = (lane >> 3) & 3, p = (lane >> 2) & 1;
+      cp = 16 * (2 * hi + p) + 4 * r + v;
+    } else {
+      cp = lane, cb = lane >> 4, r = (lane >> 2) & 3;
+    }
+    const uint32_t* kr = (const uint32_t*)(k_rows + row0) + cp;        // token t: kr[64 t]
+    // Where the lane's two codes of a token sit in the packed word: bit pos0 (channel 2 cp) and pos0 + 16
+    // (channel 2 cp + 1), the whole turned left by 8 for the odd fields of a 2-bit word.
+    const int pos0 = BITS == 2 ? 2 * (v + 1) : 2 + 4 * (v & 1) + 8 * (v >> 1);
+    const int turn = BITS == 2 ? 8 * p : 0;
+    const uint32_t bit_a0 = rotl32(1u << pos0, turn), bit_a1 = rotl32(2u << pos0, turn);         // 2-bit codes: their
+    const uint32_t bit_b0 = rotl32(1u << (pos0 + 16), turn), bit_b1 = rotl32(2u << (pos0 + 16), turn);   // two bits each
+    constexpr int J = BITS == 2 ? 8 : 4;               // lanes that share a word
+    const int j = lane & (J - 1);
+    auto keys = [&](auto any_c) {
+      constexpr bool ANY = decltype(any_c)::value;     // some token of the group is flagged (uniform)
+      uint32_t y[32];
+      h2 mn = {(_Float16)__builtin_inff(), (_Float16)__builtin_inff()};
+      h2 mx = {(_Float16)(-__builtin_inff()), (_Float16)(-__builtin_inff())};
+      double s0 = 0.0, s1 = 0.0;
+#pragma unroll 1
+      for (int blk = 0; blk < nblk; ++blk) {
+#pragma unroll
+        for (int t = 0; t < 32; ++t) y[t] = kr[(blk * 32 + t) * 64];
+#pragma unroll
+        for (int t = 0; t < 32; ++t) {
+          const h2 x = as_h2(y[t]);
+          if (ANY) {
+            const bool s = is_sel(blk * 32 + t);
+            mn = s ? mn : __builtin_elementwise_min(mn, x);
+            mx = s ? mx : __builtin_elementwise_max(mx, x);
+          } else {
+            mn = __builtin_elementwise_min(mn, x);
+            mx = __builtin_elementwise_max(mx, x);
+          }
+        }
+        if (ANY) {                                     // the exact sums of ALL rows as they came (two chains of
+#pragma unroll                                         // dependent additions: few conversions in flight at a time)
+          for (int t = 0; t < 32; ++t) {
+            s0 += (double)lo_half(y[t]);
+            asm volatile("" : "+v"(s0));
+            s1 += (double)hi_half(y[t]);
+            asm volatile("" : "+v"(s1));
+          }
+        }
+      }
+      uint32_t mean = 0;
+      if (ANY) {
+        mean = mean_half_bits(s0, G) | (mean_half_bits(s1, G) << 16);
+        mn = __builtin_elementwise_min(mn, as_h2(mean));
+        mx = __builtin_elementwise_max(mx, as_h2(mean));
+      }
+      const float mn0 = (float)mn[0] + 0.0f, mn1 = (float)mn[1] + 0.0f;   // a zero minimum is stored as +0
+      const __half st0 = step_of(mn0, (float)mx[0], BITS), st1 = step_of(mn1, (float)mx[1], BITS);
+      const float h0 = half_step_of(st0), h1 = half_step_of(st1);
+      {
+        uint32_t* gm = k_meta + (at.row * d.groups_per_unit + at.slot) * kHeadDim;   // fp16 step[128], then zero[128]
+        gm[cp] = (uint32_t)__half_as_ushort(st0) | ((uint32_t)__half_as_ushort(st1) << 16);
+        gm[64 + cp] = half_bits(mn0) | (half_bits(mn1) << 16);
+      }
+      // 2-bit: the thresholds (2k - 1) h themselves (exact: h has 11 bits)
+      const float h0x3 = 3.0f * h0, h0x5 = 5.0f * h0, h1x3 = 3.0f * h1, h1x5 = 5.0f * h1;
+#pragma unroll 1
+      for (int blk = 0; blk < nblk; ++blk) {
+        if (nblk > 1) {
+#pragma unroll
+          for (int t = 0; t < 32; ++t) y[t] = kr[(blk * 32 + t) * 64];
+        }
+        uint8_t* kb = k_codes + (block0 + blk) * (int64_t)d.block_bytes;
+        if (ANY) {                                     // the flagged rows become the mean row
+#pragma unroll
+          for (int t = 0; t < 32; ++t) y[t] = is_sel(blk * 32 + t) ? mean : y[t];
+        }
+        uint32_t keep = 0;
+#pragma unroll
+        for (int t = 0; t < 32; ++t) {
+          const uint32_t x = y[t];
+          uint32_t w;
+          if (BITS == 2) {
+            // code = [t >= 3h] * 2 + [t >= (5h if so, else h)]: the number of thresholds h, 3h, 5h reached
+            const float ta = lo_half(x) - mn0, tb = hi_half(x) - mn1;
+            const bool a1 = ta >= h0x3, b1 = tb >= h1x3;
+            const bool a0 = ta >= (a1 ? h0x5 : h0), b0 = tb >= (b1 ? h1x5 : h1);
+            w = (a1 ? bit_a1 : 0u) | (a0 ? bit_a0 : 0u) | (b1 ? bit_b1 : 0u) | (b0 ? bit_b0 : 0u);
+          } else {
+            const uint32_t ca = (uint32_t)quant_code_twice<BITS>(lo_half(x), mn0, h0);   // 2 * code
+            const uint32_t cb2 = (uint32_t)quant_code_twice<BITS>(hi_half(x), mn1, h1);
+            w = (ca << (pos0 - 1)) | rotl32(cb2 << (pos0 - 1), 16);
+          }
+          w |= row_partner_u32<0>(w);
+          w |= row_partner_u32<1>(w);
+          if (BITS == 2) w |= row_partner_u32<2>(w);
+          keep = (t & (J - 1)) == j ? w : keep;
+          if ((t & (J - 1)) == J - 1) {                // every lane now holds the word of token t - (J - 1) + j
+            const int tt = t - (J - 1) + j, m = tt & 15, th = tt >> 4;
+            const int byte = BITS == 2 ? 16 * (16 * r + m) + 4 * (2 * th + hi) : 1024 * th + 16 * (16 * r + m) + 4 * cb;
+            *(uint32_t*)(kb + byte) = keep;
+          }
+        }
+        if (lane == 0) {
+          const uint32_t mw = (uint32_t)(sel[kSelWords == 1 ? 0 : (blk * 32) >> 6] >> ((blk * 32) & 63));
+          mask[block0 + blk] = mw;
+        }
+      }
+    };
+    if (any) keys(std::true_type{});
+    else keys(std::false_type{});
+    return;
+  }
+
+  // ---- Values ----------------------------------------------------------------------------------------------
+  const int gv_shift = 31 - __clz(d.Gv);
+  const int lanes = d.Gv >> 3;                          // lanes per (token, channel group) in the first mapping
+  const int NV = d.vgroups;
+  const int nv_shift = NV == 4 ? 2 : NV == 2 ? 1 : 0;
+  const int t4 = lane >> 4, c16 = lane & 15;            // first mapping: token 4 i + t4, channels 8 c16 .. + 7
+  const __half* vr = v_rows + row0 + 8 * c16;
+  const int n = lane & 15, q = lane >> 4;               // second mapping: channels 32 q + n and 32 q + 16 + n
+  const int jq = (32 * q) >> gv_shift;                  // their channel group
+  auto values = [&](auto any_c) {
+    constexpr bool ANY = decltype(any_c)::value;
+    uint32_t mean4[4] = {0u, 0u, 0u, 0u};
+    if (ANY) {                                          // per-channel means of the group's Value rows, exact
+      double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll 4
+      for (int t = t4; t < G; t += 4) {
+        const uint4 w = *(const uint4*)(vr + t * kHeadDim);
+        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          acc[2 * k] += (double)lo_half(ww[k]);
+          acc[2 * k + 1] += (double)hi_half(ww[k]);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        acc[k] += __shfl_xor(acc[k], 16);
+        acc[k] += __shfl_xor(acc[k], 32);
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) mean4[k] = mean_half_bits(acc[2 * k], G) | (mean_half_bits(acc[2 * k + 1], G) << 16);
+    }
+#pragma unroll 1
+    for (int blk = 0; blk < nblk; ++blk) {
+      uint4 w[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) w[i] = *(const uint4*)(vr + (blk * 32 + 4 * i + t4) * kHeadDim);
+      lds_order();                                      // the previous block's reads are done
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int t = 4 * i + t4, T = blk * 32 + t;
+        if (ANY && ((sel[kSelWords == 1 ? 0 : T >> 6] >> (T & 63)) & 1ull))
+          w[i] = make_uint4(mean4[0], mean4[1], mean4[2], mean4[3]);
+        const h2 a = __builtin_elementwise_min(__builtin_elementwise_min(as_h2(w[i].x), as_h2(w[i].y)),
+                                               __builtin_elementwise_min(as_h2(w[i].z), as_h2(w[i].w)));
+        const h2 b = __builtin_elementwise_max(__builtin_elementwise_max(as_h2(w[i].x), as_h2(w[i].y)),
+                                               __builtin_elementwise_max(as_h2(w[i].z), as_h2(w[i].w)));
+        // the two halves against each other with the same instructions (they order -0 below +0, as the
+        // scalar minimum and maximum of the other kernel do; a comparison would not)
+        const h2 a2 = __builtin_elementwise_min(a, as_h2(rotl32(as_u32(a), 16)));
+        const h2 b2 = __builtin_elementwise_max(b, as_h2(rotl32(as_u32(b), 16)));
+        h2 pr = {a2[0], (_Float16)(-b2[0])};            // {min, -max}: one packed minimum reduces both
+        pr = __builtin_elementwise_min(pr, as_h2(row_partner_u32<0>(as_u32(pr))));
+        pr = __builtin_elementwise_min(pr, as_h2(row_partner_u32<1>(as_u32(pr))));
+        if (lanes > 4) pr = __builtin_elementwise_min(pr, as_h2(row_partner_u32<2>(as_u32(pr))));
+        if (lanes > 8) pr = __builtin_elementwise_min(pr, as_h2(row_partner_u32<3>(as_u32(pr))));
+        vrow[t * 16 + c16] = w[i];
+        if ((c16 & (lanes - 1)) == 0) vpr[t * 4 + ((8 * c16) >> gv_shift)] = as_u32(pr);
+      }
+      lds_order();
+      // steps and zeros of the block's 32 NV (token, channel group) pairs: one lane per (token pair, group),
+      // which is also one dword of each half of the block's meta (fp16 step[16 token pairs][NV][2], then
+      // fp16 zero[16 token pairs][NV][2])
+      if (lane < 16 * NV) {
+        const int tp = lane >> nv_shift, jv = lane & (NV - 1);
+        uint32_t stw = 0, zw = 0;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+          const h2 pr = as_h2(vpr[(2 * tp + k) * 4 + jv]);
+          const float mnf = (float)pr[0] + 0.0f, mxf = -(float)pr[1];
+          const __half st = step_of(mnf, mxf, BITS);
+          vms[(2 * tp + k) * 4 + jv] = make_float2(mnf, half_step_of(st));
+          stw |= (uint32_t)__half_as_ushort(st) << (16 * k);
+          zw |= half_bits(mnf) << (16 * k);
+        }
+        uint32_t* gm = v_meta + (block0 + blk) * 32 * NV;
+        gm[lane] = stw;
+        gm[16 * NV + lane] = zw;
+      }
+      lds_order();
+      uint8_t* vb = v_codes + (block0 + blk) * (int64_t)d.block_bytes;
+      const __half* rows = (const __half*)vrow;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        uint32_t wa = 0, wb = 0;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          const int t = 8 * r + x;
+          const float2 ms = vms[t * 4 + jq];
+          const _Float16 ha = ((const _Float16*)rows)[t * kHeadDim + 32 * q + n];
+          const _Float16 hb = ((const _Float16*)rows)[t * kHeadDim + 32 * q + 16 + n];
+          const float xa = (float)ha, xb = (float)hb;
+          if (BITS == 2) {
+            constexpr uint32_t one = 1u;
+            const int pos = code_bit(2, 0, x);          // at most 24: both bits fit
+            const float ta = xa - ms.x, tb = xb - ms.x, h3 = 3.0f * ms.y, h5 = 5.0f * ms.y;
+            const bool a1 = ta >= h3, b1 = tb >= h3;
+            const bool a0 = ta >= (a1 ? h5 : ms.y), b0 = tb >= (b1 ? h5 : ms.y);
+            wa |= (a1 ? one << (pos + 1) : 0u) | (a0 ? one << pos : 0u);
+            wb |= (b1 ? one << (pos + 1) : 0u) | (b0 ? one << pos : 0u);
+          } else {
+            wa |= place_twice<BITS>(quant_code_twice<BITS>(xa, ms.x, ms.y), code_bit(BITS, 0, x));
+            wb |= place_twice<BITS>(quant_code_twice<BITS>(xb, ms.x, ms.y), code_bit(BITS, 0, x));
+          }
+        }
+        if (BITS == 2) {                                // fields 2 q and 2 q + 1: word q of the packed lane, the odd field 8 bits up
+          ((uint32_t*)(vb + 16 * (16 * r + n)))[q] = wa | rotl32(wb, 8);
+        } else {                                        // words 2 (q & 1), 2 (q & 1) + 1 of half q >> 1
+          *(uint2*)(vb + 1024 * (q >> 1) + 16 * (16 * r + n) + 8 * (q & 1)) = make_uint2(wa, wb);
+        }
+      }
+    }
+  };
+  if (any) values(std::true_type{});
+  else values(std::false_type{});
+}
+
 // Rows n0 .. n0 + n - 1 of every unit's rows into ring rows 0 .. n - 1 (16 bytes per thread).
 __global__ void __launch_bounds__(256) tail_copy_kernel(Dims d, const __half* __restrict__ k_rows,
                                                         const __half* __restrict__ v_rows, int64_t unit_stride,
@@ -439,6 +743,16 @@ hipError_t launch_quantize_one(const Dims& d, int32_t group_index, int32_t n_gro
                                const __half* v_group, int64_t unit_stride, const uint8_t* selected,
                                int64_t selected_unit_stride, const kvq_qcache& qc, int32_t tail_n, __half* k_res,
                                __half* v_res, hipStream_t s) {
+  // many groups (a prompt): the kernel that spends the fewest instructions per group; few: the one that is
+  // done with a group soonest
+  if ((int64_t)d.units_per_layer * n_groups >= kPromptGroups && !d.keys_only) {
+    const int tail_blocks = (tail_n * 16 + 127) / 128;
+    hipLaunchKernelGGL((prompt_quantize_kernel<BITS, G>), dim3(d.units_per_layer, n_groups + tail_blocks), dim3(128), 0,
+                       s, d, group_index, k_group, v_group, unit_stride, selected, selected_unit_stride,
+                       (uint8_t*)qc.k_codes, (uint32_t*)qc.k_meta, (uint8_t*)qc.v_codes, (uint32_t*)qc.v_meta,
+                       (uint32_t*)qc.mask, n_groups, tail_n, k_res, v_res);
+    return hipGetLastError();
+  }
   const size_t smem = quant_lds_bytes<G>(d.vgroups);
   if (smem > 48 * 1024) {  // more than the default limit of dynamic LDS per workgroup
     hipError_t e = hipFuncSetAttribute((const void*)quantize_kernel<BITS, G>, hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -257,6 +257,37 @@ def test_batch_128_stack_layer_sampled_units(bits, context):
     assert not cache.pool_count.view(torch.int32)[:3 * w.units].any()
 
 
+@pytest.mark.parametrize("bits,G,Gv,N", [(2, 32, 32, 8), (4, 32, 128, 8), (2, 64, 64, 3), (4, 64, 32, 8),
+                                         (2, 128, 128, 3), (4, 128, 64, 40), (2, 32, 64, 0)])
+def test_prompts_of_many_groups_all_settings(bits, G, Gv, N):
+    """A prompt of 64 units x 16 groups in one call: from 1024 groups on the library quantizes with the kernel
+    that gives a group two wavefronts (Keys / Values) instead of 1024 threads.  Every bit width, group size and
+    value-group size; groups with and without flagged tokens (N = 40: most groups have several); sampled units
+    against the oracle, state bit for bit and the attention."""
+    import torch
+    from paper_2505_10938_amd import cache as KC
+    w = S.Workload("prompt", layers=1, batch=8, q_heads=8, kv_heads=8, context=32 + 16 * G + 5, bits=bits, group_k=G,
+                   group_v=Gv, residual=32, outlier_budget=N, aux_capacity=32 if N else 0, rho=0.04)
+    assert w.n_quant == 16 * G and w.batch * w.kv_heads * 16 >= 1024
+    units = [0, 9, 31, 63]
+    K, V = S.layer_kv(w, 0)
+    cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, w.n_quant, bits, G, Gv, w.residual, N, w.aux_capacity,
+                         w.head_dim)
+    cache = KC.KVCache(cfg)
+    cache.prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
+    torch.cuda.synchronize()
+    states = H.oracle_states(w, K, V, w.n_quant, units)
+    if N:
+        assert any(len(st.pool) + len(st.aux) > 0 for st in states)
+    H.compare_state(cache, states, w, w.n_quant, units=units)
+    Q = S.layer_queries(w, 0, 0, "peaky")
+    ref = H.oracle_attention(w, states, Q, K, V, w.n_quant, w.n_res, units)
+    got = cache.decode(0, torch.from_numpy(Q).cuda()).cpu().numpy().astype(np.float64)
+    for ui in units:
+        b, h = divmod(ui, w.kv_heads)
+        assert att_err(got[b, h:h + 1], ref[b, h:h + 1]) <= ATT_TOL, ui
+
+
 def test_four_bit_full_batch_sampled_units():
     w = S.WORKLOADS["llama2_7b_4k"].with_(name="llama2_7b_4k_4bit", bits=4, batch=4, context=2048 + 40)
     run_sampled(w, [3, 100])
