@@ -62,10 +62,13 @@ __device__ __forceinline__ double from_lane_below(double v) {
 __device__ inline bool key_less(double as, int ai, double bs, int bi) { return as < bs || (as == bs && ai < bi); }
 
 constexpr int kScoreChunk = 1024;                      // scores staged in LDS at a time
+// wavefronts per unit: one walks the groups, the others score ahead (8 or 16 instead of 4: 222 / 220 instead of
+// 232 us for 256 units, 822 / 865 instead of 810 us for 1024 units: the walk is what takes the time)
+constexpr int kTraceWaves = 4;
 
 // Requires empty pools on entry (a prompt starts a sequence).
 template <int G>
-__global__ void __launch_bounds__(256) prefill_trace_kernel(
+__global__ void __launch_bounds__(64 * kTraceWaves) prefill_trace_kernel(
     Dims d, int32_t n_groups, const __half* __restrict__ k_rows, const __half* __restrict__ v_rows,
     int64_t unit_stride, __half* pool_k, __half* pool_v, int32_t* pool_idx, double* pool_score, int32_t* pool_count,
     int32_t* aux_count, int32_t* frozen, uint8_t* __restrict__ selected) {
@@ -82,16 +85,16 @@ __global__ void __launch_bounds__(256) prefill_trace_kernel(
   uint8_t* sel = selected + (int64_t)ul * n_tok;
   const int N = d.N, A = d.A;
   if (N == 0) {                                        // no pool: nothing is ever selected
-    for (int i = tid; i < n_tok; i += 256) sel[i] = 0;
+    for (int i = tid; i < n_tok; i += 64 * kTraceWaves) sel[i] = 0;
     return;
   }
   constexpr int kRounds = (G + 63) / 64;               // a group is looked at 64 tokens at a time
   constexpr int kPer = kScoreChunk / 64;
-  // fp64 L1 scores of the chunk's tokens into `buf`, by the wavefronts w0 .. 3: 16 lanes per row, 4 rows
+  // fp64 L1 scores of the chunk's tokens into `buf`, by the wavefronts w0 .. kTraceWaves - 1: 16 lanes per row, 4 rows
   // per load instruction, eight of them in flight per wavefront
   const __half* rows = k_rows + (int64_t)ul * unit_stride;
   auto score_chunk = [&](int c0, double* buf, int w0) {
-    const int nw = 4 - w0;
+    const int nw = kTraceWaves - w0;
     const int n_here = min(kScoreChunk, n_tok - c0);
     const int team = lane >> 4, sub = lane & 15;
     for (int i0 = 0; ((wave - w0) + nw * i0) * 4 < n_here; i0 += 8) {
@@ -304,7 +307,7 @@ __global__ void __launch_bounds__(256) prefill_trace_kernel(
 hipError_t launch_prefill_trace(const Dims& d, int32_t n_groups, const __half* k_rows, const __half* v_rows,
                                 int64_t unit_stride, const kvq_pool& pool, uint8_t* selected, hipStream_t s) {
   auto go = [&](auto kern) {
-    hipLaunchKernelGGL(kern, dim3(d.units_per_layer), dim3(256), 0, s, d, n_groups, k_rows, v_rows, unit_stride,
+    hipLaunchKernelGGL(kern, dim3(d.units_per_layer), dim3(64 * kTraceWaves), 0, s, d, n_groups, k_rows, v_rows, unit_stride,
                        (__half*)pool.pool_k, (__half*)pool.pool_v, pool.pool_idx, pool.pool_score, pool.pool_count,
                        pool.aux_count, pool.frozen, selected);
   };
