@@ -493,7 +493,7 @@ def main():
 
     frac = main_res["dec_bytes"] / (main_res["dec_us"] * 1e-6) / 1e9 / HBM_PEAK_GBPS
     # template arguments: query rows per kv head, bits, Value groups per token, paged cache, blocks per Key group
-    kern = f"decode_kernel<{w.q_heads // w.kv_heads},{w.bits},{w.head_dim // w.group_v},false,{w.group_k // 32}>"
+    kern = f"decode_kernel<{w.q_heads // w.kv_heads},{w.bits},{w.head_dim // w.group_v},false,{w.group_k // 32},false>"
     what = (f"{w.name}: {layers} layers" if stacked else f"{w.name}: {layers} independent copies of the layer")
     result = {
         "metric": "decode_attention_kv_GBps_2bit_1xMI355X" if w.bits == 2 else "decode_attention_kv_GBps",

@@ -677,7 +677,7 @@ __device__ __forceinline__ bool fp_row_ok(const DecodeArgs& a, const Seq& sq, co
   return slot < a.d.N ? (slot < n_pool) : (slot < a.d.pool_slots && slot - a.d.N < n_aux);
 }
 
-template <int GQ, int NV>
+template <int GQ, int NV, bool ROPE>
 __device__ __forceinline__ void fp_compute(FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, NV>& L, const DecodeArgs& a,
                                            const Seq& sq, const FpLayout& f, int n_pool, int n_aux, int r0,
                                            uint32_t k_new_word, uint32_t v_new_word, int lane) {
@@ -686,7 +686,7 @@ __device__ __forceinline__ void fp_compute(FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, 
   if (X.group == f.new_group) {                                    // uniform, one group of the unit
 #pragma unroll
     for (int t = 0; t < 16; ++t) X.vw[t] = t == f.new_t ? v_new_word : X.vw[t];
-    if (a.rope) {
+    if constexpr (ROPE) {
       // The new Key row was loaded as the caller gave it; the rotated one exists as one word per lane
       // (channels 2*lane, 2*lane + 1).  The lanes that own the row take their 16-byte pieces (channels
       // 32 cb + 8 r ..) from the lanes that hold them: words 16 cb + 4 r .. + 3.
@@ -767,7 +767,9 @@ __device__ __forceinline__ void fp_compute(FpRegs& X, FpAcc<GQ>& F, WaveLds<GQ, 
 // otherwise entry `entry` of the launch plan does (a batch of sequences of different lengths dealt by
 // length).  The plan is device data: what is read from it is clamped to bounds the host has checked
 // against the buffers.
-template <int GQ, int BITS, int NV, bool PAGED, int SB>
+// (ROPE: the launch rotates the query rows and the new Key row - an instance of its own, so that the others
+// carry nothing of it: with a run-time test instead they measured 0.3 % slower)
+template <int GQ, int BITS, int NV, bool PAGED, int SB, bool ROPE>
 __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* smem, int& s_last, int entry) {
   const Dims& d = a.d;
   // Every argument the loads below depend on is fetched here, in one round trip (left to
@@ -779,7 +781,8 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* 
                "s"(a.k_codes), "s"(a.k_meta), "s"(a.v_codes), "s"(a.v_meta), "s"(a.mask), "s"(a.k_res), "s"(a.v_res),
                "s"(a.pool_k), "s"(a.pool_v), "s"(a.pool_count), "s"(a.aux_count), "s"(a.seq));
   asm volatile("" ::"s"(a.k_new), "s"(a.v_new), "s"(d.page_table), "s"(d.table_stride), "s"(d.n_pages), "s"(d.plane0),
-               "s"(a.q_tokens), "s"(a.g_shift), "s"(a.rope), "s"(a.rope_stride));
+               "s"(a.q_tokens), "s"(a.g_shift));
+  if constexpr (ROPE) asm volatile("" ::"s"(a.rope), "s"(a.rope_stride));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -863,11 +866,9 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* 
   const __half* v_new_row = a.k_new ? a.v_new + (int64_t)ul * kHeadDim : qbase;
   uint32_t k_new_word = ((const uint32_t*)k_new_row)[lane];
   const uint32_t v_new_word = ((const uint32_t*)v_new_row)[lane];
-  // the angles of the new token's position, if the launch is to rotate the query and the new Key (these
-  // two loads are the one exception to "the same loads on every path": a launch without rotation, the
-  // common one, is not to pay for them; with them the waits further down are merely less exact)
+  // the angles of the new token's position, if the launch is to rotate the query and the new Key
   float2 rope_cos = {1.f, 1.f}, rope_sin = {0.f, 0.f};
-  if (a.rope) {                                          // uniform
+  if constexpr (ROPE) {
     const float* rope_row = a.rope + (int64_t)b * a.rope_stride;
     rope_cos = ((const float2*)rope_row)[lane & 31];
     rope_sin = ((const float2*)rope_row)[32 + (lane & 31)];
@@ -912,7 +913,7 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* 
   load_v_meta(R, P, mc, lane);
   load_codes<BITS>(R.vc, P.vc, P, mc, lane);
 
-  if (a.rope) {                                          // uniform
+  if constexpr (ROPE) {
 #pragma unroll
     for (int j = 0; j < GQ; ++j)
       qw[j] = rope_word(qw[j], (uint32_t)__shfl_xor((int)qw[j], 32), rope_cos, rope_sin, lane >= 32);
@@ -945,10 +946,10 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* 
   if (has_fp) {
     n_pool = __builtin_amdgcn_readfirstlane(n_pool);
     n_aux = __builtin_amdgcn_readfirstlane(n_aux);
-    fp_compute<GQ, NV>(X, F, L, a, sq, fl, n_pool, n_aux, r0, k_new_word, v_new_word, lane);
+    fp_compute<GQ, NV, ROPE>(X, F, L, a, sq, fl, n_pool, n_aux, r0, k_new_word, v_new_word, lane);
     for (rg += unit_waves; rg < n_rg; rg += unit_waves) {          // the wavefront's further groups
       fp_load(X, a, sq, fl, u, k_new_row, rg, lane);
-      fp_compute<GQ, NV>(X, F, L, a, sq, fl, n_pool, n_aux, r0, k_new_word, v_new_word, lane);
+      fp_compute<GQ, NV, ROPE>(X, F, L, a, sq, fl, n_pool, n_aux, r0, k_new_word, v_new_word, lane);
     }
   }
 
@@ -1120,7 +1121,7 @@ __device__ __forceinline__ void decode_item(const DecodeArgs& a, unsigned char* 
 
 // grid (splits, kv_heads * head_parts, batch), or with a launch plan (entries, kv_heads, 1); 64 * a.nw threads
 // (a.nw at most what one compute unit holds of this instance), a.nw * sizeof(WaveLds) bytes of dynamic LDS.
-template <int GQ, int BITS, int NV, bool PAGED, int SB>
+template <int GQ, int BITS, int NV, bool PAGED, int SB, bool ROPE>
 __global__ void __launch_bounds__(64 * 4 * kDecodeWavesPerSimd) __attribute__((amdgpu_waves_per_eu(kDecodeWavesPerSimd)))
 decode_kernel(DecodeArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -1130,17 +1131,22 @@ decode_kernel(DecodeArgs a) {
     entry = blockIdx.x;
     if (entry >= min(a.plan[0], a.plan_entries)) return;
   }
-  decode_item<GQ, BITS, NV, PAGED, SB>(a, smem, s_last, entry);
+  decode_item<GQ, BITS, NV, PAGED, SB, ROPE>(a, smem, s_last, entry);
 }
 
-template <int GQ, int BITS, int NV, bool PAGED, int SB>
-void launch_shared(const DecodeArgs& a, dim3 grid, hipStream_t s) {
+template <int GQ, int BITS, int NV, bool PAGED, int SB, bool ROPE>
+void launch_instance(const DecodeArgs& a, dim3 grid, hipStream_t s) {
   const size_t lds = (size_t)a.nw * sizeof(WaveLds<GQ, NV>);
   static_assert(merge_bytes_per_wave<GQ, NV>() <= (int)sizeof(WaveLds<GQ, NV>), "merge view must fit");
   if (lds > 48 * 1024)     // more than the default limit of dynamic LDS: raise it (cheap, idempotent)
-    (void)hipFuncSetAttribute((const void*)decode_kernel<GQ, BITS, NV, PAGED, SB>,
+    (void)hipFuncSetAttribute((const void*)decode_kernel<GQ, BITS, NV, PAGED, SB, ROPE>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  hipLaunchKernelGGL((decode_kernel<GQ, BITS, NV, PAGED, SB>), grid, dim3(64 * a.nw), lds, s, a);
+  hipLaunchKernelGGL((decode_kernel<GQ, BITS, NV, PAGED, SB, ROPE>), grid, dim3(64 * a.nw), lds, s, a);
+}
+template <int GQ, int BITS, int NV, bool PAGED, int SB>
+void launch_shared(const DecodeArgs& a, dim3 grid, hipStream_t s) {
+  if (a.rope) launch_instance<GQ, BITS, NV, PAGED, SB, true>(a, grid, s);
+  else launch_instance<GQ, BITS, NV, PAGED, SB, false>(a, grid, s);
 }
 template <int GQ, int BITS, int NV, bool PAGED>
 void launch_paged(const DecodeArgs& a, dim3 grid, hipStream_t s) {
