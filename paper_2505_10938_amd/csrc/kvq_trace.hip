@@ -62,9 +62,11 @@ __device__ __forceinline__ double from_lane_below(double v) {
 __device__ inline bool key_less(double as, int ai, double bs, int bi) { return as < bs || (as == bs && ai < bi); }
 
 constexpr int kScoreChunk = 1024;                      // scores staged in LDS at a time
-// wavefronts per unit: one walks the groups, the others score ahead (8 or 16 instead of 4: 222 / 220 instead of
-// 232 us for 256 units, 822 / 865 instead of 810 us for 1024 units: the walk is what takes the time)
-constexpr int kTraceWaves = 4;
+// wavefronts per unit: one walks the groups, the others score ahead.  Measured on a 4096-token prompt: 4 / 8 / 16
+// wavefronts 91 / 80 / 79 us for 256 units (the whole prompt 233 / 218 / 220 us), 810 / 811 .. 822 / 865 us for the
+// whole prompt of 1024 units.  With 8 the scores are ready well ahead and the walk itself, about 75 us, is what
+// remains; a raised priority for the walking wavefront changes nothing.
+constexpr int kTraceWaves = 8;
 
 // Requires empty pools on entry (a prompt starts a sequence).
 template <int G>
