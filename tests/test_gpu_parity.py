@@ -799,6 +799,8 @@ def rope_table(pos, hd=128, base=10000.0):
     (dict(bits=4, group_k=64, group_v=64, residual=32, outlier_budget=3, q_heads=8), True),   # four query heads
     (dict(bits=2, group_k=32, group_v=128, residual=0, outlier_budget=4), False),  # every 32nd step fills the ring
     (dict(bits=2, group_k=32, group_v=32, residual=40, outlier_budget=4, q_heads=16, batch=3), True),   # eight
+    (dict(bits=2, group_k=128, group_v=128, residual=32, outlier_budget=3, context=300), False),  # four blocks per Key group
+    (dict(bits=2, group_k=32, group_v=32, residual=32, outlier_budget=8, q_heads=4, paged=True), True),  # behind a page table
 ])
 def test_rotary_embedding_inside_the_decode_launch(kw, per_sequence):
     """Token by token with KVCache.step and a table of angles: the library rotates the query and the new
@@ -812,6 +814,7 @@ def test_rotary_embedding_inside_the_decode_launch(kw, per_sequence):
     from paper_2505_10938_amd import cache as KC
     base = dict(layers=1, batch=2, q_heads=2, kv_heads=2, context=200)
     base.update(kw)
+    use_pages = base.pop("paged", False)
     w = S.Workload("rope", **base)
     G = w.group_k
     steps = w.residual + 3 * G + 9
@@ -820,7 +823,7 @@ def test_rotary_embedding_inside_the_decode_launch(kw, per_sequence):
     cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, ((w.context + steps + G - 1) // G) * G, w.bits, G,
                          w.group_v, w.residual, w.outlier_budget, w.aux_capacity, w.head_dim)
     nq, nr = w.n_quant, w.n_res
-    cache = H.gpu_cache(w, K, V, nq, nr, cache=KC.KVCache(cfg))
+    cache = H.gpu_cache(w, K, V, nq, nr, cache=paged(cfg) if use_pages else KC.KVCache(cfg))
     states = H.oracle_states(w, K, V, nq)
     raw_k = torch.from_numpy(K.copy()).cuda()
     Vd = torch.from_numpy(V).cuda()
