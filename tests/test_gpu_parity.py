@@ -257,9 +257,11 @@ def test_batch_128_stack_layer_sampled_units(bits, context):
     assert not cache.pool_count.view(torch.int32)[:3 * w.units].any()
 
 
-@pytest.mark.parametrize("bits,G,Gv,N", [(2, 32, 32, 8), (4, 32, 128, 8), (2, 64, 64, 3), (4, 64, 32, 8),
-                                         (2, 128, 128, 3), (4, 128, 64, 40), (2, 32, 64, 0)])
-def test_prompts_of_many_groups_all_settings(bits, G, Gv, N):
+@pytest.mark.parametrize("bits,G,Gv,N,use_pages", [
+    (2, 32, 32, 8, False), (4, 32, 128, 8, False), (2, 64, 64, 3, False), (4, 64, 32, 8, False),
+    (2, 128, 128, 3, False), (4, 128, 64, 40, False), (2, 32, 64, 0, False),
+    (2, 32, 32, 8, True), (4, 64, 64, 8, True)])                       # through a page table
+def test_prompts_of_many_groups_all_settings(bits, G, Gv, N, use_pages):
     """A prompt of 64 units x 16 groups in one call: from 1024 groups on the library quantizes with the kernel
     that gives a group two wavefronts (Keys / Values) instead of 1024 threads.  Every bit width, group size and
     value-group size; groups with and without flagged tokens (N = 40: most groups have several); sampled units
@@ -273,7 +275,7 @@ def test_prompts_of_many_groups_all_settings(bits, G, Gv, N):
     K, V = S.layer_kv(w, 0)
     cfg = KC.make_config(1, w.batch, w.q_heads, w.kv_heads, w.n_quant, bits, G, Gv, w.residual, N, w.aux_capacity,
                          w.head_dim)
-    cache = KC.KVCache(cfg)
+    cache = paged(cfg) if use_pages else KC.KVCache(cfg)
     cache.prefill(0, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
     torch.cuda.synchronize()
     states = H.oracle_states(w, K, V, w.n_quant, units)
