@@ -938,6 +938,13 @@ def test_paged_ragged_batch():
                make_cache=lambda cfg: paged(cfg, kind=KC.RaggedKVCache))
 
 
+def test_paged_ragged_batch_with_a_launch_plan():
+    """Sequences of different lengths behind a page table, the decode workgroups dealt by a launch plan."""
+    from paper_2505_10938_amd import cache as KC
+    run_ragged(dict(bits=2, group_k=64, group_v=32, residual=32, outlier_budget=4, q_heads=8), [45, 2100, 161, 700],
+               make_cache=lambda cfg: paged(cfg, kind=KC.RaggedKVCache), planned=True)
+
+
 def test_paged_equals_dense_bit_for_bit_second_layer():
     """Two layers, work on the second: a paged and a dense cache fed the same tokens hold the same
     bytes (pages gathered through the table) and give the same outputs, bit for bit; the pages of the
